@@ -1,0 +1,138 @@
+/*
+ * asi.h - C ABI of the MI355X (gfx950) library for the hot path of Activation
+ * Subspace Iteration (ASI, arxiv 2505.05086).
+ *
+ * Per training step and per fine-tuned layer the method
+ *   (1) runs one warm-started subspace-iteration step on every mode unfolding
+ *       of the stored activation and orthonormalises the result (Alg. 1),
+ *   (2) projects the activation onto those factors to get the Tucker core
+ *       (Alg. 1's core update; Eq. 3, Eq. 4),
+ *   (3) in the backward pass computes the conv2d / linear weight gradient from
+ *       core + factors without rebuilding the activation (App. A.3, Eq. 14).
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is caller-owned DEVICE memory on the current HIP
+ *     device.  The library allocates nothing, keeps no state between calls and
+ *     only enqueues kernels on `stream`; it never synchronises with the host.
+ *   - Activation `A` and output gradient `grad_out`: dense row-major, (B,C,H,W)
+ *     or (B,N,D); element type given by asi_tensor_desc.dtype (fp32, or bf16
+ *     with fp32 accumulation).
+ *   - Factor U_m: row-major (dims[m] x ranks[m]) fp32.  Core S: row-major
+ *     (ranks[0] x ... x ranks[ndim-1]) fp32.  dW: (Cout, C/groups, kh, kw) or
+ *     (Dout, Din) fp32.
+ *   - `ws` is scratch of at least asi_workspace_bytes() bytes, 256-byte aligned.
+ *     Calls that share one workspace must be ordered on one stream.
+ *   - Synchronous argument errors are returned as a status and enqueue nothing.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ */
+#ifndef ASI_H
+#define ASI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ASI_OK = 0,
+    ASI_ERR_INVALID_ARG = 1,   /* null pointer, bad ndim/dims/ranks, bad conv geometry */
+    ASI_ERR_UNSUPPORTED = 2,   /* unknown dtype, size beyond an implementation limit */
+    ASI_ERR_WORKSPACE = 3,     /* ws null, misaligned or smaller than asi_workspace_bytes() */
+    ASI_ERR_HIP = 4,           /* a HIP runtime call failed (launch error) */
+    ASI_ERR_NUMERIC = 5        /* reserved: numeric breakdown is reported through *info */
+} asi_status;
+
+typedef enum { ASI_F32 = 0, ASI_BF16 = 1 } asi_dtype;   /* element type of A and grad_out */
+
+/* One stored activation and its target ranks (Alg. 1 inputs).
+ * ndim = 4: dims = (B, C, H, W); ndim = 3: dims = (B, N, D).
+ * 1 <= ranks[m] <= min(dims[m], numel / dims[m]) (Alg. 1's rank range); ranks[m] <= 256. */
+typedef struct {
+    int32_t ndim;
+    int64_t dims[4];
+    int32_t ranks[4];
+    int32_t dtype;             /* asi_dtype */
+} asi_tensor_desc;
+
+/* Geometry of the convolution whose weight gradient is wanted (Sec. 3.1 notation:
+ * C' = cout, D = kh = kw in the paper; general stride / padding / dilation / groups here). */
+typedef struct {
+    int64_t cout;
+    int32_t kh, kw;
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;
+    int32_t dil_h, dil_w;
+    int32_t groups;            /* must divide both C and cout */
+} asi_conv2d_desc;
+
+typedef void* asi_stream_t;    /* hipStream_t */
+
+/* Scratch bytes that cover every entry point for this layer: asi_compress and
+ * asi_core_project always; asi_weight_grad_conv2d if conv != NULL;
+ * asi_weight_grad_linear if dout > 0.  Returns 0 if desc (or conv) is invalid. */
+size_t asi_workspace_bytes(const asi_tensor_desc* desc, const asi_conv2d_desc* conv, int64_t dout);
+
+/* Alg. 1, warm-start branch, for every mode m of A:
+ *     V = A_m^T U_prev[m];   P = A_m V;   U_out[m] = Orthogonalize(P)
+ * where A_m is the mode-m unfolding of the ORIGINAL activation (Sec. 3.2) and
+ * U_prev[m] is the factor kept from the previous training step.  Orthogonalize
+ * returns the Q factor of the thin QR of P with positive diagonal R (what
+ * Gram-Schmidt produces, App. A.1), so U_out^T U_out = I.
+ *   A          in  device, dims per desc, dtype per desc
+ *   U_prev[m]  in  device fp32 (dims[m] x ranks[m]), m < ndim; any full-rank matrix
+ *   U_out[m]   out device fp32 (dims[m] x ranks[m]); may alias U_prev[m]
+ *   info       out device int32 (nullable).  Set to 0 when the call starts executing;
+ *              if P of mode m (1-based) is numerically rank deficient at column
+ *              j (1-based) it becomes m*1000 + j and U_out[m] is unspecified.
+ *              Read it after synchronising the stream. */
+asi_status asi_compress(const asi_tensor_desc* desc, const void* A,
+                        const float* const* U_prev, float* const* U_out,
+                        void* ws, size_t ws_bytes, int32_t* info, asi_stream_t stream);
+
+/* Core tensor S = A x_1 U[0]^T x_2 U[1]^T ... x_d U[d-1]^T (Alg. 1's core update with
+ * Eq. 4's m-mode product; the order of the products does not change the result).
+ *   U[m]  in  device fp32 (dims[m] x ranks[m])
+ *   S     out device fp32, row-major (ranks[0] x ... x ranks[ndim-1]) */
+asi_status asi_core_project(const asi_tensor_desc* desc, const void* A,
+                            const float* const* U, float* S,
+                            void* ws, size_t ws_bytes, asi_stream_t stream);
+
+/* Weight gradient of a conv2d layer from the compressed activation, in the order
+ * the five terms of C_ASI describe (App. A.3, Eq. 14):
+ *     G1 = grad_out x_1 U1^T;  Z = S x_3 U3 x_4 U4;
+ *     T[o,j,kh,kw] = sum_{i,h',w'} G1[i,o,h',w'] * Zpad[i,j,h'*s-p+kh*dil, w'*s-p+kw*dil];
+ *     dW[o,c,kh,kw] = sum_j T[o,j,kh,kw] * U2[g(o)*C/groups + c, j].
+ * The result equals Eq. 1 applied to the reconstruction S x_1 U1 ... x_4 U4.
+ *   desc      4-mode descriptor of the activation that was compressed
+ *   grad_out  in  device (B, cout, H', W'), dtype per desc,
+ *             H' = floor((H + 2 pad_h - dil_h (kh-1) - 1) / stride_h) + 1
+ *   dW        out device fp32 (cout, C/groups, kh, kw); overwritten, or added to
+ *             when accumulate != 0 */
+asi_status asi_weight_grad_conv2d(const asi_tensor_desc* desc, const float* S,
+                                  const float* const* U, const void* grad_out,
+                                  const asi_conv2d_desc* conv, float* dW, int accumulate,
+                                  void* ws, size_t ws_bytes, asi_stream_t stream);
+
+/* Weight gradient of a linear layer (Sec. 3.1 footnote: the fully-connected case
+ * follows the same construction) for a 3-mode activation (B, N, Din):
+ *     G1 = grad_out x_1 U1^T;  G2 = G1 x_2 U2^T;
+ *     T[o,k] = sum_{i,j} G2[i,j,o] S[i,j,k];   dW[o,d] = sum_k T[o,k] U3[d,k].
+ *   grad_out  in  device (B, N, dout), dtype per desc
+ *   dW        out device fp32 (dout, Din); overwritten, or added to when accumulate != 0 */
+asi_status asi_weight_grad_linear(const asi_tensor_desc* desc, const float* S,
+                                  const float* const* U, const void* grad_out,
+                                  int64_t dout, float* dW, int accumulate,
+                                  void* ws, size_t ws_bytes, asi_stream_t stream);
+
+/* Static, human-readable name of a status code. */
+const char* asi_status_string(asi_status s);
+
+/* Library ABI version (major*1000 + minor). */
+int32_t asi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASI_H */

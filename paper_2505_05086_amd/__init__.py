@@ -1,0 +1,24 @@
+"""MI355X-native hot path of Activation Subspace Iteration (arxiv 2505.05086).
+
+Thin Python names over the C ABI of libasi_hip.so (see include/asi.h):
+asi_compress, asi_core_project, asi_weight_grad_conv2d, asi_weight_grad_linear.
+"""
+from .binding import (  # noqa: F401
+    ASI_BF16,
+    ASI_F32,
+    AsiError,
+    Conv2dDesc,
+    EXPORTS,
+    TensorDesc,
+    alloc_workspace,
+    asi_compress,
+    asi_core_project,
+    asi_status_string,
+    asi_version,
+    asi_weight_grad_conv2d,
+    asi_weight_grad_linear,
+    asi_workspace_bytes,
+    lib,
+    make_conv,
+    make_desc,
+)

@@ -1,0 +1,173 @@
+"""ctypes binding over the C ABI declared in include/asi.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+libasi_hip.so.  torch is used for device memory and the current stream.  There
+is no CPU fallback: a missing library raises at import of the first call.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+from .build import LIB_PATH
+
+ASI_OK = 0
+STATUS_NAMES = {0: "ASI_OK", 1: "ASI_ERR_INVALID_ARG", 2: "ASI_ERR_UNSUPPORTED",
+                3: "ASI_ERR_WORKSPACE", 4: "ASI_ERR_HIP", 5: "ASI_ERR_NUMERIC"}
+ASI_F32, ASI_BF16 = 0, 1
+
+EXPORTS = ["asi_workspace_bytes", "asi_compress", "asi_core_project", "asi_weight_grad_conv2d",
+           "asi_weight_grad_linear", "asi_status_string", "asi_version"]
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [("ndim", C.c_int32), ("dims", C.c_int64 * 4), ("ranks", C.c_int32 * 4), ("dtype", C.c_int32)]
+
+
+class Conv2dDesc(C.Structure):
+    _fields_ = [("cout", C.c_int64), ("kh", C.c_int32), ("kw", C.c_int32),
+                ("stride_h", C.c_int32), ("stride_w", C.c_int32), ("pad_h", C.c_int32), ("pad_w", C.c_int32),
+                ("dil_h", C.c_int32), ("dil_w", C.c_int32), ("groups", C.c_int32)]
+
+
+class AsiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_2505_05086_amd.build` "
+                               "(the ASI path has no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        pp = C.POINTER(C.c_void_p)
+        L.asi_workspace_bytes.restype = C.c_size_t
+        L.asi_workspace_bytes.argtypes = [C.POINTER(TensorDesc), C.POINTER(Conv2dDesc), C.c_int64]
+        L.asi_compress.restype = C.c_int
+        L.asi_compress.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, pp, C.c_void_p, C.c_size_t,
+                                   C.c_void_p, C.c_void_p]
+        L.asi_core_project.restype = C.c_int
+        L.asi_core_project.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, C.c_void_p, C.c_void_p,
+                                       C.c_size_t, C.c_void_p]
+        L.asi_weight_grad_conv2d.restype = C.c_int
+        L.asi_weight_grad_conv2d.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, C.c_void_p,
+                                             C.POINTER(Conv2dDesc), C.c_void_p, C.c_int, C.c_void_p,
+                                             C.c_size_t, C.c_void_p]
+        L.asi_weight_grad_linear.restype = C.c_int
+        L.asi_weight_grad_linear.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, C.c_void_p, C.c_int64,
+                                             C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.asi_status_string.restype = C.c_char_p
+        L.asi_status_string.argtypes = [C.c_int]
+        L.asi_version.restype = C.c_int32
+        L.asi_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def make_desc(dims: Sequence[int], ranks: Sequence[int], dtype: str = "f32") -> TensorDesc:
+    d = TensorDesc()
+    d.ndim = len(dims)
+    for i in range(4):
+        d.dims[i] = int(dims[i]) if i < len(dims) else 0
+        d.ranks[i] = int(ranks[i]) if i < len(ranks) else 0
+    d.dtype = {"f32": ASI_F32, "bf16": ASI_BF16}.get(dtype, 99) if isinstance(dtype, str) else int(dtype)
+    return d
+
+
+def make_conv(cout, kh, kw, stride=(1, 1), pad=(0, 0), dil=(1, 1), groups=1) -> Conv2dDesc:
+    c = Conv2dDesc()
+    c.cout, c.kh, c.kw = int(cout), int(kh), int(kw)
+    c.stride_h, c.stride_w = int(stride[0]), int(stride[1])
+    c.pad_h, c.pad_w = int(pad[0]), int(pad[1])
+    c.dil_h, c.dil_w = int(dil[0]), int(dil[1])
+    c.groups = int(groups)
+    return c
+
+
+def _ptr(t: Optional[torch.Tensor]) -> C.c_void_p:
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _ptr_array(ts: Sequence[torch.Tensor]):
+    arr = (C.c_void_p * 4)()
+    for i in range(4):
+        arr[i] = ts[i].data_ptr() if i < len(ts) and ts[i] is not None else None
+    return arr
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check_dev(*ts):
+    for t in ts:
+        if t is None:
+            continue
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("ASI binding needs contiguous device tensors")
+
+
+def _check(status: int, where: str):
+    if status != ASI_OK:
+        raise AsiError(status, where)
+
+
+def asi_workspace_bytes(desc: TensorDesc, conv: Optional[Conv2dDesc] = None, dout: int = 0) -> int:
+    return int(lib().asi_workspace_bytes(C.byref(desc), C.byref(conv) if conv is not None else None, int(dout)))
+
+
+def alloc_workspace(desc: TensorDesc, conv: Optional[Conv2dDesc] = None, dout: int = 0,
+                    device="cuda") -> torch.Tensor:
+    n = asi_workspace_bytes(desc, conv, dout)
+    if n == 0:
+        raise AsiError(1, "asi_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def asi_compress(desc: TensorDesc, A: torch.Tensor, U_prev: Sequence[torch.Tensor],
+                 U_out: Sequence[torch.Tensor], ws: torch.Tensor, info: Optional[torch.Tensor] = None) -> None:
+    _check_dev(A, ws, info, *U_prev, *U_out)
+    _check(lib().asi_compress(C.byref(desc), _ptr(A), _ptr_array(U_prev), _ptr_array(U_out), _ptr(ws),
+                              ws.numel(), _ptr(info), _stream()), "asi_compress")
+
+
+def asi_core_project(desc: TensorDesc, A: torch.Tensor, U: Sequence[torch.Tensor], S: torch.Tensor,
+                     ws: torch.Tensor) -> None:
+    _check_dev(A, ws, S, *U)
+    _check(lib().asi_core_project(C.byref(desc), _ptr(A), _ptr_array(U), _ptr(S), _ptr(ws), ws.numel(),
+                                  _stream()), "asi_core_project")
+
+
+def asi_weight_grad_conv2d(desc: TensorDesc, S: torch.Tensor, U: Sequence[torch.Tensor], grad_out: torch.Tensor,
+                           conv: Conv2dDesc, dW: torch.Tensor, accumulate: bool, ws: torch.Tensor) -> None:
+    _check_dev(S, grad_out, dW, ws, *U)
+    _check(lib().asi_weight_grad_conv2d(C.byref(desc), _ptr(S), _ptr_array(U), _ptr(grad_out), C.byref(conv),
+                                        _ptr(dW), int(bool(accumulate)), _ptr(ws), ws.numel(), _stream()),
+           "asi_weight_grad_conv2d")
+
+
+def asi_weight_grad_linear(desc: TensorDesc, S: torch.Tensor, U: Sequence[torch.Tensor], grad_out: torch.Tensor,
+                           dout: int, dW: torch.Tensor, accumulate: bool, ws: torch.Tensor) -> None:
+    _check_dev(S, grad_out, dW, ws, *U)
+    _check(lib().asi_weight_grad_linear(C.byref(desc), _ptr(S), _ptr_array(U), _ptr(grad_out), int(dout),
+                                        _ptr(dW), int(bool(accumulate)), _ptr(ws), ws.numel(), _stream()),
+           "asi_weight_grad_linear")
+
+
+def asi_status_string(status: int) -> str:
+    return lib().asi_status_string(int(status)).decode()
+
+
+def asi_version() -> int:
+    return int(lib().asi_version())

@@ -1,0 +1,374 @@
+// C ABI of the ASI library: argument validation, workspace carving and launch
+// sequencing.  No kernel code lives here.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+
+#include "../../include/asi.h"
+#include "asi_kernels.h"
+
+namespace {
+
+using namespace asi;
+
+constexpr size_t kAlign = 256;
+constexpr int kMaxRank = 1024;
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Carver {
+    char* base;
+    size_t off = 0;
+    explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+    template <typename T>
+    T* take(size_t count) {
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += align_up(count * sizeof(T));
+        return p;
+    }
+};
+
+struct Shape {
+    int d = 0;
+    long long n[4] = {1, 1, 1, 1};
+    int r[4] = {1, 1, 1, 1};
+    long long numel = 1;
+    DType dt = F32;
+    long long outer(int m) const { long long o = 1; for (int k = 0; k < m; ++k) o *= n[k]; return o; }
+    long long inner(int m) const { long long o = 1; for (int k = m + 1; k < d; ++k) o *= n[k]; return o; }
+};
+
+bool parse_desc(const asi_tensor_desc* desc, Shape* s, asi_status* why) {
+    if (!desc) { *why = ASI_ERR_INVALID_ARG; return false; }
+    if (desc->ndim != 3 && desc->ndim != 4) { *why = ASI_ERR_INVALID_ARG; return false; }
+    if (desc->dtype != ASI_F32 && desc->dtype != ASI_BF16) { *why = ASI_ERR_UNSUPPORTED; return false; }
+    s->d = desc->ndim;
+    s->dt = desc->dtype == ASI_F32 ? F32 : BF16;
+    s->numel = 1;
+    for (int m = 0; m < s->d; ++m) {
+        if (desc->dims[m] <= 0 || desc->dims[m] > (1LL << 30)) { *why = ASI_ERR_INVALID_ARG; return false; }
+        s->n[m] = desc->dims[m];
+        s->numel *= desc->dims[m];
+        if (s->numel > (1LL << 40)) { *why = ASI_ERR_UNSUPPORTED; return false; }
+    }
+    for (int m = 0; m < s->d; ++m) {
+        const long long b = s->numel / s->n[m];
+        const long long rmax = std::min(s->n[m], b);
+        if (desc->ranks[m] < 1 || desc->ranks[m] > rmax) { *why = ASI_ERR_INVALID_ARG; return false; }
+        if (desc->ranks[m] > kMaxRank) { *why = ASI_ERR_UNSUPPORTED; return false; }
+        s->r[m] = desc->ranks[m];
+    }
+    return true;
+}
+
+// ---- compress ---------------------------------------------------------------
+struct CompressPlan {
+    float* V = nullptr;
+    double* part[4] = {};
+    double* P64[4] = {};
+    double* G[4] = {};
+    int nsplit[4] = {};
+    size_t bytes = 0;
+};
+
+CompressPlan plan_compress(const Shape& s, void* ws) {
+    CompressPlan p;
+    Carver c(ws);
+    size_t vmax = 0;
+    for (int m = 0; m < s.d; ++m) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
+    p.V = c.take<float>(vmax);
+    for (int m = 0; m < s.d; ++m) {
+        p.nsplit[m] = pair_splits(s.outer(m), (int)s.n[m], s.inner(m), s.r[m]);
+        p.part[m] = c.take<double>((size_t)p.nsplit[m] * s.n[m] * s.r[m]);
+        p.P64[m] = c.take<double>((size_t)s.n[m] * s.r[m]);
+        p.G[m] = c.take<double>((size_t)s.r[m] * s.r[m]);
+    }
+    p.bytes = c.off;
+    return p;
+}
+
+// ---- core projection ----------------------------------------------------------
+struct CorePlan {
+    int order[4] = {0, 1, 2, 3};
+    float* buf[2] = {};
+    size_t bytes = 0;
+};
+
+CorePlan plan_core(const Shape& s, void* ws) {
+    CorePlan p;
+    int perm[4] = {0, 1, 2, 3};
+    double best = -1.0;
+    do {
+        long long cur[4];
+        for (int m = 0; m < 4; ++m) cur[m] = s.n[m];
+        double cost = 0.0;
+        for (int k = 0; k < s.d; ++k) {
+            const int m = perm[k];
+            double sz = 1.0;
+            for (int q = 0; q < s.d; ++q) sz *= (double)cur[q];
+            cost += sz * s.r[m];
+            cur[m] = s.r[m];
+        }
+        if (best < 0 || cost < best) { best = cost; std::memcpy(p.order, perm, sizeof(perm)); }
+    } while (std::next_permutation(perm, perm + s.d));
+    long long cur[4];
+    for (int m = 0; m < 4; ++m) cur[m] = s.n[m];
+    size_t need[2] = {0, 0};
+    for (int k = 0; k + 1 < s.d; ++k) {   // the last product writes S itself
+        cur[p.order[k]] = s.r[p.order[k]];
+        size_t sz = 1;
+        for (int q = 0; q < s.d; ++q) sz *= (size_t)cur[q];
+        need[k & 1] = std::max(need[k & 1], sz);
+    }
+    Carver c(ws);
+    p.buf[0] = c.take<float>(need[0]);
+    p.buf[1] = c.take<float>(need[1]);
+    p.bytes = c.off;
+    return p;
+}
+
+// ---- conv2d weight gradient ------------------------------------------------------
+struct ConvGeom {
+    CorrGeom g;
+    int C, B, groups;
+};
+
+bool parse_conv(const Shape& s, const asi_conv2d_desc* cv, ConvGeom* out) {
+    if (!cv || s.d != 4) return false;
+    if (cv->cout <= 0 || cv->cout > (1 << 24) || cv->kh <= 0 || cv->kw <= 0 || cv->kh > 64 || cv->kw > 64) return false;
+    if (cv->stride_h <= 0 || cv->stride_w <= 0 || cv->dil_h <= 0 || cv->dil_w <= 0) return false;
+    if (cv->pad_h < 0 || cv->pad_w < 0 || cv->groups <= 0) return false;
+    const long long C = s.n[1];
+    if (C % cv->groups != 0 || cv->cout % cv->groups != 0) return false;
+    const long long H = s.n[2], W = s.n[3];
+    const long long eh = H + 2LL * cv->pad_h - (long long)cv->dil_h * (cv->kh - 1) - 1;
+    const long long ew = W + 2LL * cv->pad_w - (long long)cv->dil_w * (cv->kw - 1) - 1;
+    if (eh < 0 || ew < 0) return false;
+    CorrGeom& g = out->g;
+    g.r1 = s.r[0]; g.r2 = s.r[1];
+    g.cout = (int)cv->cout;
+    g.H = (int)H; g.W = (int)W;
+    g.Ho = (int)(eh / cv->stride_h + 1); g.Wo = (int)(ew / cv->stride_w + 1);
+    g.kh = cv->kh; g.kw = cv->kw; g.sh = cv->stride_h; g.sw = cv->stride_w;
+    g.ph = cv->pad_h; g.pw = cv->pad_w; g.dh = cv->dil_h; g.dw = cv->dil_w;
+    out->C = (int)C; out->B = (int)s.n[0]; out->groups = cv->groups;
+    return true;
+}
+
+struct ConvPlan {
+    float *G1 = nullptr, *Z1 = nullptr, *Z = nullptr, *Tpart = nullptr, *T = nullptr;
+    int nsplit = 1;
+    size_t bytes = 0;
+};
+
+ConvPlan plan_conv(const Shape& s, const ConvGeom& cg, void* ws) {
+    ConvPlan p;
+    const CorrGeom& g = cg.g;
+    Carver c(ws);
+    p.G1 = c.take<float>((size_t)g.r1 * g.cout * g.Ho * g.Wo);
+    p.Z1 = c.take<float>((size_t)g.r1 * g.r2 * g.H * s.r[3]);
+    p.Z = c.take<float>((size_t)g.r1 * g.r2 * g.H * g.W);
+    p.nsplit = corr_splits(g);
+    const size_t tsz = (size_t)g.cout * g.r2 * g.kh * g.kw;
+    p.T = c.take<float>(tsz);
+    p.Tpart = p.nsplit > 1 ? c.take<float>(tsz * p.nsplit) : p.T;
+    p.bytes = c.off;
+    return p;
+}
+
+// ---- linear weight gradient --------------------------------------------------------
+struct LinPlan {
+    float *G1 = nullptr, *G2 = nullptr, *T = nullptr;
+    double* Tpart = nullptr;
+    int nsplit = 1;
+    size_t bytes = 0;
+};
+
+LinPlan plan_linear(const Shape& s, long long dout, void* ws) {
+    LinPlan p;
+    Carver c(ws);
+    p.G1 = c.take<float>((size_t)s.r[0] * s.n[1] * dout);
+    p.G2 = c.take<float>((size_t)s.r[0] * s.r[1] * dout);
+    p.nsplit = pair_splits((long long)s.r[0] * s.r[1], (int)dout, 1, s.r[2]);
+    p.T = c.take<float>((size_t)dout * s.r[2]);
+    p.Tpart = c.take<double>((size_t)p.nsplit * dout * s.r[2]);
+    p.bytes = c.off;
+    return p;
+}
+
+bool ws_ok(const void* ws, size_t have, size_t need) {
+    return ws && (reinterpret_cast<uintptr_t>(ws) % kAlign) == 0 && have >= need;
+}
+
+#define ASI_TRY(expr)                                  \
+    do {                                               \
+        hipError_t e__ = (expr);                       \
+        if (e__ != hipSuccess) return ASI_ERR_HIP;     \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int32_t asi_version(void) { return 1000; }
+
+const char* asi_status_string(asi_status s) {
+    switch (s) {
+        case ASI_OK: return "ASI_OK";
+        case ASI_ERR_INVALID_ARG: return "ASI_ERR_INVALID_ARG";
+        case ASI_ERR_UNSUPPORTED: return "ASI_ERR_UNSUPPORTED";
+        case ASI_ERR_WORKSPACE: return "ASI_ERR_WORKSPACE";
+        case ASI_ERR_HIP: return "ASI_ERR_HIP";
+        case ASI_ERR_NUMERIC: return "ASI_ERR_NUMERIC";
+    }
+    return "ASI_ERR_UNKNOWN";
+}
+
+size_t asi_workspace_bytes(const asi_tensor_desc* desc, const asi_conv2d_desc* conv, int64_t dout) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return 0;
+    size_t need = std::max(plan_compress(s, nullptr).bytes, plan_core(s, nullptr).bytes);
+    if (conv) {
+        ConvGeom cg;
+        if (!parse_conv(s, conv, &cg)) return 0;
+        need = std::max(need, plan_conv(s, cg, nullptr).bytes);
+    }
+    if (dout > 0) {
+        if (s.d != 3 || dout > (1 << 24)) return 0;
+        need = std::max(need, plan_linear(s, dout, nullptr).bytes);
+    }
+    return std::max(need, kAlign);
+}
+
+asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float* const* U_prev,
+                        float* const* U_out, void* ws, size_t ws_bytes, int32_t* info, asi_stream_t stream) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    if (!A || !U_prev || !U_out) return ASI_ERR_INVALID_ARG;
+    for (int m = 0; m < s.d; ++m)
+        if (!U_prev[m] || !U_out[m]) return ASI_ERR_INVALID_ARG;
+    CompressPlan p = plan_compress(s, ws);
+    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    if (info) ASI_TRY(launch_set_i32(info, 0, st));
+    OrthArgs oa;
+    std::memset(&oa, 0, sizeof(oa));
+    oa.njobs = s.d;
+    oa.info = info;
+    for (int m = 0; m < s.d; ++m) {
+        const long long outer = s.outer(m), inner = s.inner(m);
+        const int n = (int)s.n[m], r = s.r[m];
+        // V = A_m^T U_prev, kept as a tensor with mode m of size r
+        ASI_TRY(launch_ttm(s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0, st));
+        // P = A_m V, split over the unfolding's columns
+        ASI_TRY(launch_pair(s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], st));
+        OrthJob& j = oa.job[m];
+        j.part = p.part[m]; j.nsplit = p.nsplit[m]; j.n = n; j.r = r;
+        j.P64 = p.P64[m]; j.G = p.G[m]; j.Uout = U_out[m]; j.mode1 = m + 1;
+    }
+    ASI_TRY(launch_orth(oa, st));
+    return ASI_OK;
+}
+
+asi_status asi_core_project(const asi_tensor_desc* desc, const void* A, const float* const* U, float* S,
+                            void* ws, size_t ws_bytes, asi_stream_t stream) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    if (!A || !U || !S) return ASI_ERR_INVALID_ARG;
+    for (int m = 0; m < s.d; ++m)
+        if (!U[m]) return ASI_ERR_INVALID_ARG;
+    CorePlan p = plan_core(s, ws);
+    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    long long cur[4];
+    for (int m = 0; m < 4; ++m) cur[m] = s.n[m];
+    const void* src = A;
+    DType sdt = s.dt;
+    for (int k = 0; k < s.d; ++k) {
+        const int m = p.order[k];
+        long long outer = 1, inner = 1;
+        for (int q = 0; q < m; ++q) outer *= cur[q];
+        for (int q = m + 1; q < s.d; ++q) inner *= cur[q];
+        float* dst = (k + 1 == s.d) ? S : p.buf[k & 1];
+        ASI_TRY(launch_ttm(sdt, src, outer, (int)cur[m], inner, U[m], s.r[m], 1, s.r[m], dst, 0, st));
+        cur[m] = s.r[m];
+        src = dst;
+        sdt = F32;
+    }
+    return ASI_OK;
+}
+
+asi_status asi_weight_grad_conv2d(const asi_tensor_desc* desc, const float* S, const float* const* U,
+                                  const void* grad_out, const asi_conv2d_desc* conv, float* dW, int accumulate,
+                                  void* ws, size_t ws_bytes, asi_stream_t stream) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    if (s.d != 4 || !conv) return ASI_ERR_INVALID_ARG;
+    ConvGeom cg;
+    if (!parse_conv(s, conv, &cg)) return ASI_ERR_INVALID_ARG;
+    if (!S || !U || !grad_out || !dW) return ASI_ERR_INVALID_ARG;
+    for (int m = 0; m < 4; ++m)
+        if (!U[m]) return ASI_ERR_INVALID_ARG;
+    ConvPlan p = plan_conv(s, cg, ws);
+    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const CorrGeom& g = cg.g;
+    const int r3 = s.r[2], r4 = s.r[3];
+    const int taps = g.kh * g.kw;
+
+    // 1. G1 = grad_out x_1 U1^T                                   (r1, cout, Ho, Wo)
+    ASI_TRY(launch_ttm(s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0, st));
+    // 2. Z1 = S x_3 U3                                            (r1, r2, H, r4)
+    ASI_TRY(launch_ttm(F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0, st));
+    // 3. Z = Z1 x_4 U4                                            (r1, r2, H, W)
+    ASI_TRY(launch_ttm(F32, p.Z1, (long long)g.r1 * g.r2 * g.H, r4, 1, U[3], 1, r4, g.W, p.Z, 0, st));
+    // 4. T = correlation of Zpad with G1 over (r1, Ho, Wo)        (cout, r2, kh, kw)
+    ASI_TRY(launch_corr(p.G1, p.Z, p.Tpart, g, p.nsplit, st));
+    if (p.nsplit > 1) ASI_TRY(launch_sum_partials(p.Tpart, p.nsplit, (long long)g.cout * g.r2 * taps, p.T, 0, st));
+    // 5. dW = T x_(r2) U2, per group                              (cout, C/groups, kh, kw)
+    if (cg.groups == 1) {
+        ASI_TRY(launch_ttm(F32, p.T, g.cout, g.r2, taps, U[1], 1, g.r2, cg.C, dW, accumulate ? 1 : 0, st));
+    } else {
+        ASI_TRY(launch_expand_grouped(p.T, U[1], dW, g.cout, g.r2, taps, cg.C / cg.groups, g.cout / cg.groups,
+                                      accumulate ? 1 : 0, st));
+    }
+    return ASI_OK;
+}
+
+asi_status asi_weight_grad_linear(const asi_tensor_desc* desc, const float* S, const float* const* U,
+                                  const void* grad_out, int64_t dout, float* dW, int accumulate, void* ws,
+                                  size_t ws_bytes, asi_stream_t stream) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    if (s.d != 3 || dout <= 0 || dout > (1 << 24)) return ASI_ERR_INVALID_ARG;
+    if (!S || !U || !grad_out || !dW) return ASI_ERR_INVALID_ARG;
+    for (int m = 0; m < 3; ++m)
+        if (!U[m]) return ASI_ERR_INVALID_ARG;
+    LinPlan p = plan_linear(s, dout, ws);
+    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int B = (int)s.n[0], N = (int)s.n[1], D = (int)s.n[2];
+    const int r1 = s.r[0], r2 = s.r[1], r3 = s.r[2];
+
+    // 1. G1[i,n,o] = sum_b U1[b,i] dY[b,n,o]
+    ASI_TRY(launch_ttm(s.dt, grad_out, 1, B, (long long)N * dout, U[0], r1, 1, r1, p.G1, 0, st));
+    // 2. G2[i,j,o] = sum_n U2[n,j] G1[i,n,o]
+    ASI_TRY(launch_ttm(F32, p.G1, r1, N, dout, U[1], r2, 1, r2, p.G2, 0, st));
+    // 3. T[o,k] = sum_{i,j} G2[i,j,o] S[i,j,k]
+    ASI_TRY(launch_pair(F32, p.G2, (long long)r1 * r2, (int)dout, 1, S, r3, p.Tpart, p.nsplit, st));
+    ASI_TRY(launch_sum_partials_f64(p.Tpart, p.nsplit, (long long)dout * r3, p.T, 0, st));
+    // 4. dW[o,d] = sum_k T[o,k] U3[d,k]
+    ASI_TRY(launch_ttm(F32, p.T, dout, r3, 1, U[2], 1, r3, D, dW, accumulate ? 1 : 0, st));
+    return ASI_OK;
+}
+
+}  // extern "C"

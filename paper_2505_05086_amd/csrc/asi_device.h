@@ -1,0 +1,25 @@
+// Shared device-side helpers for the ASI kernels (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace asi {
+
+// bf16 storage is handled as raw 16-bit patterns: widening to fp32 is a shift.
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+
+template <typename T>
+__device__ __forceinline__ float ldf(const T* __restrict__ p, long long idx) { return to_f32(p[idx]); }
+
+// A tensor seen from one mode: X[o, i, j], o < outer, i < n (the mode), j < inner.
+// Column c of the mode unfolding (Sec. 3.2) is the pair (o, j) = (c / inner, c % inner).
+struct ModeView {
+    long long outer;
+    int n;
+    long long inner;
+};
+
+}  // namespace asi

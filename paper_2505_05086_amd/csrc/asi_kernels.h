@@ -1,0 +1,59 @@
+// Host-side launchers of the ASI kernels.  All pointers are device pointers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace asi {
+
+enum DType { F32 = 0, BF16 = 1 };
+
+// Y[o,q,j] = sum_i X[o,i,j] * M(i,q),  M(i,q) = Mp[i*ms_i + q*ms_q]   (Eq. 4 along one mode)
+// X: (outer, n, inner) of dtype xt;  Y: (outer, r, inner) fp32;  beta != 0 adds to Y.
+hipError_t launch_ttm(DType xt, const void* X, long long outer, int n, long long inner,
+                      const float* Mp, long long ms_i, long long ms_q, int r,
+                      float* Y, int beta, hipStream_t st);
+
+// part[s][i][q] = sum_{c in split s} X[i,c] * Y[q,c]  over unfolding columns c = (o,j)
+// X: (outer, n, inner) dtype xt;  Y: (outer, r, inner) fp32;  part: (nsplit, n, r) fp64
+// (products of fp32 values are exact in fp64 and the sums are carried in fp64).
+hipError_t launch_pair(DType xt, const void* X, long long outer, int n, long long inner,
+                       const float* Y, int r, double* part, int nsplit, hipStream_t st);
+int pair_splits(long long outer, int n, long long inner, int r);
+
+// out[e] = (beta ? out[e] : 0) + sum_s part[s*count + e]
+hipError_t launch_sum_partials(const float* part, int nsplit, long long count, float* out, int beta,
+                               hipStream_t st);
+hipError_t launch_sum_partials_f64(const double* part, int nsplit, long long count, float* out, int beta,
+                                   hipStream_t st);
+
+struct OrthJob {
+    const double* part;  // (nsplit, n, r) partial sums of P
+    int nsplit;
+    int n, r;
+    double* P64;         // (n, r) scratch
+    double* G;           // (r, r) scratch
+    float* Uout;         // (n, r)
+    int mode1;           // 1-based mode number for *info
+};
+struct OrthArgs {
+    OrthJob job[4];
+    int njobs;
+    int32_t* info;       // nullable
+};
+hipError_t launch_orth(const OrthArgs& a, hipStream_t st);
+hipError_t launch_set_i32(int32_t* p, int32_t v, hipStream_t st);
+
+// Step 4 of Eq. 14: T[o,j,kh,kw] = sum_{i,y,x} G1[i,o,y,x] * Zpad[i,j,y*s-p+kh*d, x*s-p+kw*d]
+// G1: (r1, cout, Ho, Wo);  Z: (r1, r2, H, W);  Tpart: (nsplit, cout, r2, kh, kw), split over i.
+struct CorrGeom {
+    int r1, r2, cout, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, dh, dw;
+};
+int corr_splits(const CorrGeom& g);
+hipError_t launch_corr(const float* G1, const float* Z, float* Tpart, const CorrGeom& g, int nsplit,
+                       hipStream_t st);
+
+// Step 5 of Eq. 14 with groups: dW[o,c,t] (+)= sum_j T[o,j,t] * U2[(o/og)*cg + c, j]
+hipError_t launch_expand_grouped(const float* T, const float* U2, float* dW, int cout, int r2, int taps,
+                                 int cg, int og, int beta, hipStream_t st);
+
+}  // namespace asi

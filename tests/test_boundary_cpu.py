@@ -1,0 +1,101 @@
+"""Boundary checks that need no GPU: the library loads, exports every symbol the
+header declares, sizes its workspace, and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2505_05086_amd as asi
+from paper_2505_05086_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = C.c_void_p(0x1000)          # non-null, 256-aligned, never dereferenced by validation
+
+
+def _declared():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            src = open(os.path.join(ROOT, "include", fn)).read()
+            src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+            names |= set(re.findall(r"\b(asi_[a-z0-9_]+)\s*\(", src))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    L = asi.lib()
+    declared = _declared()
+    assert {"asi_compress", "asi_core_project", "asi_weight_grad_conv2d", "asi_weight_grad_linear",
+            "asi_workspace_bytes", "asi_status_string", "asi_version"} <= declared
+    for name in declared:
+        assert hasattr(L, name), name
+    assert set(B.EXPORTS) == declared
+    assert asi.asi_version() >= 1000
+    assert asi.asi_status_string(0) == "ASI_OK" and asi.asi_status_string(3) == "ASI_ERR_WORKSPACE"
+
+
+def test_workspace_query():
+    d = asi.make_desc((64, 512, 7, 7), (16, 48, 5, 5))
+    base = asi.asi_workspace_bytes(d)
+    assert base > 0 and base % 256 == 0
+    assert asi.asi_workspace_bytes(d, asi.make_conv(512, 3, 3, pad=(1, 1))) >= base
+    assert asi.asi_workspace_bytes(asi.make_desc((64, 512, 7, 7), (16, 48, 5, 8))) == 0      # rank > dim
+    assert asi.asi_workspace_bytes(asi.make_desc((64, 512), (16, 48))) == 0                  # ndim
+    assert asi.asi_workspace_bytes(d, asi.make_conv(512, 3, 3, groups=3)) == 0               # groups
+    assert asi.asi_workspace_bytes(d, None, 100) == 0                                        # linear needs 3 modes
+    d3 = asi.make_desc((4, 5, 6), (2, 3, 4), "bf16")
+    assert asi.asi_workspace_bytes(d3, None, 7) > 0
+
+
+def _arr(n=4):
+    a = (C.c_void_p * 4)()
+    for i in range(n):
+        a[i] = 0x1000
+    return a
+
+
+def test_compress_rejects_bad_arguments_without_launching():
+    L = asi.lib()
+    good = asi.make_desc((8, 6, 5, 4), (2, 3, 2, 2))
+    need = asi.asi_workspace_bytes(good)
+    call = lambda d, A, up, uo, ws, n: L.asi_compress(C.byref(d), A, up, uo, ws, n, None, None)
+    assert call(asi.make_desc((8, 6, 5, 4), (2, 3, 2, 5)), FAKE, _arr(), _arr(), FAKE, need) == 1
+    assert call(asi.make_desc((8, 6, 5, 4), (0, 3, 2, 2)), FAKE, _arr(), _arr(), FAKE, need) == 1
+    assert call(asi.make_desc((8, 0, 5, 4), (2, 3, 2, 2)), FAKE, _arr(), _arr(), FAKE, need) == 1
+    assert call(asi.make_desc((8, 6, 5, 4), (2, 3, 2, 2), 7), FAKE, _arr(), _arr(), FAKE, need) == 2
+    assert call(good, None, _arr(), _arr(), FAKE, need) == 1
+    assert call(good, FAKE, _arr(3), _arr(), FAKE, need) == 1
+    assert call(good, FAKE, _arr(), _arr(), FAKE, need - 1) == 3
+    assert call(good, FAKE, _arr(), _arr(), None, need) == 3
+    assert call(good, FAKE, _arr(), _arr(), C.c_void_p(0x1010), need) == 3               # misaligned
+    # rank may not exceed the other side of the unfolding either (Alg. 1's range)
+    assert call(asi.make_desc((8, 1, 1, 1), (2, 1, 1, 1)), FAKE, _arr(), _arr(), FAKE, 1 << 20) == 1
+
+
+def test_other_entry_points_reject_bad_arguments():
+    L = asi.lib()
+    d4 = asi.make_desc((8, 6, 5, 4), (2, 3, 2, 2))
+    d3 = asi.make_desc((8, 6, 5), (2, 3, 2))
+    big = 1 << 24
+    assert L.asi_core_project(C.byref(d4), FAKE, _arr(), None, FAKE, big, None) == 1
+    assert L.asi_core_project(C.byref(d4), FAKE, _arr(), FAKE, FAKE, 0, None) == 3
+    cv = asi.make_conv(6, 3, 3, pad=(1, 1))
+    assert L.asi_weight_grad_conv2d(C.byref(d3), FAKE, _arr(), FAKE, C.byref(cv), FAKE, 0, FAKE, big, None) == 1
+    assert L.asi_weight_grad_conv2d(C.byref(d4), FAKE, _arr(), FAKE, None, FAKE, 0, FAKE, big, None) == 1
+    bad = asi.make_conv(6, 9, 9)            # kernel larger than the padded map
+    assert L.asi_weight_grad_conv2d(C.byref(d4), FAKE, _arr(), FAKE, C.byref(bad), FAKE, 0, FAKE, big, None) == 1
+    bad = asi.make_conv(6, 3, 3, stride=(0, 1))
+    assert L.asi_weight_grad_conv2d(C.byref(d4), FAKE, _arr(), FAKE, C.byref(bad), FAKE, 0, FAKE, big, None) == 1
+    assert L.asi_weight_grad_conv2d(C.byref(d4), FAKE, _arr(), FAKE, C.byref(cv), FAKE, 0, FAKE, 16, None) == 3
+    assert L.asi_weight_grad_linear(C.byref(d4), FAKE, _arr(), FAKE, 7, FAKE, 0, FAKE, big, None) == 1
+    assert L.asi_weight_grad_linear(C.byref(d3), FAKE, _arr(), FAKE, 0, FAKE, 0, FAKE, big, None) == 1
+    assert L.asi_weight_grad_linear(C.byref(d3), FAKE, _arr(), FAKE, 7, FAKE, 0, FAKE, 16, None) == 3
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    d = asi.make_desc((8, 6, 5, 4), (2, 3, 2, 2))
+    x = torch.zeros(8, 6, 5, 4)
+    with pytest.raises(ValueError):
+        asi.asi_core_project(d, x, [x] * 4, x, x)
