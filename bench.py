@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Throughput of the ASI hot path on one MI355X.
+
+One "step" = the whole path (asi_compress -> asi_core_project -> asi_weight_grad_*)
+for every layer of the workload on one batch of synthetic activations that are
+already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# dense peaks of the units each kernel uses (TFLOP/s)
+PEAK_TFLOPS = {"mfma_f32": 157.3, "mfma_f64": 78.6, "mfma_bf16": 2500.0, "valu_f32": 78.6, "valu_f64": 78.6}
+# which arithmetic unit each kernel symbol runs its contraction on
+KERNEL_UNIT = {"k_ttm": "valu_f32", "k_pair": "valu_f64", "k_corr": "valu_f32", "k_orth": "valu_f64",
+               "k_sum_partials": "valu_f64", "k_expand_grouped": "valu_f32"}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload (1-5), default the ResNet-18 tail")
+    ap.add_argument("--distinct", type=int, default=8, help="distinct input steps kept in HBM and cycled")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, streams, budget_s):
+    """The float64 oracle, as it stands, on the host cores: whole path per layer-step."""
+    import numpy as np
+    from oracle import asi_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    done_bytes, t_used, n_ls = 0, 0.0, 0
+    U = [[u.astype(np.float64) for u in st.u_prev0()] for st in streams]
+    step = 0
+    while t_used < budget_s and step < cfg.steps:
+        for li, (lay, st) in enumerate(zip(cfg.layers, streams)):
+            A = st.activation(step).astype(np.float64)
+            dY = st.grad_out(step).astype(np.float64)
+            t0 = time.perf_counter()
+            Un = O.compress(A, U[li])
+            S = O.core_project(A, Un)
+            if lay.kind == "conv2d":
+                cs = O.Conv2dSpec(lay.cout, lay.k, lay.k, (lay.stride,) * 2, (lay.pad,) * 2, (lay.dil,) * 2, lay.groups)
+                O.conv2d_weight_grad_lowrank(S, Un, dY, cs)
+            else:
+                O.linear_weight_grad_lowrank(S, Un, dY)
+            t_used += time.perf_counter() - t0
+            U[li] = Un
+            done_bytes += lay.act_bytes
+            n_ls += 1
+        step += 1
+    return {"value": done_bytes / t_used / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{step} step(s) x {len(cfg.layers)} layers of config {cfg.index} ({n_ls} layer-steps, "
+                      f"{t_used:.1f} s of float64 NumPy oracle time, input generation excluded)"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2505_05086_amd as asi
+    from asi_inputs import CONFIGS, LayerStream
+    from paper_2505_05086_amd.runner import LayerRunner
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[args.config]
+    streams = [LayerStream(cfg.index, li, lay, cfg.theta) for li, lay in enumerate(cfg.layers)]
+    runners = [LayerRunner(lay) for lay in cfg.layers]
+    ndist = max(1, min(args.distinct, cfg.steps if cfg.steps > 1 else args.distinct))
+
+    # inputs resident in HBM before any timing: `ndist` consecutive steps of the drifting sequence
+    A_dev, dY_dev = [], []
+    for t in range(ndist):
+        tt = t if cfg.steps > 1 else 0
+        A_dev.append([r.upload(st.activation(tt)) for r, st in zip(runners, streams)])
+        dY_dev.append([r.upload(st.grad_out(tt)) for r, st in zip(runners, streams)])
+    for r, st in zip(runners, streams):
+        r.set_factors(st.u_prev0())
+    act_bytes = sum(lay.act_bytes for lay in cfg.layers)
+
+    def one_step(k):
+        a, g = A_dev[k % ndist], dY_dev[k % ndist]
+        for r, at, gt in zip(runners, a, g):
+            r.step(at, gt)
+
+    for k in range(args.warmup):
+        one_step(k)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for k in range(args.steps):
+        one_step(args.warmup + k)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    for r in runners:
+        assert int(r.info.item()) == 0, "numeric breakdown during the benchmark"
+    value = act_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # per-kernel pass: same steps with every launch bracketed by HIP events on its stream
+    asi.asi_profile_enable(True)
+    nprof = min(args.steps, 10)
+    for k in range(nprof):
+        one_step(args.warmup + args.steps + k)
+    torch.cuda.synchronize()
+    rep = asi.asi_profile_report()
+    asi.asi_profile_enable(False)
+    per_kernel = {}
+    for site, v in rep.items():
+        sym = site.split(":")[0]
+        a = per_kernel.setdefault(sym, {"launches": 0, "ms": 0.0, "bytes": 0.0, "flops": 0.0})
+        for key in a:
+            a[key] += v[key]
+    dom = max(per_kernel, key=lambda s: per_kernel[s]["ms"])
+    d = per_kernel[dom]
+    avg_s = d["ms"] * 1e-3 / d["launches"]
+    bytes_per_launch, flops_per_launch = d["bytes"] / d["launches"], d["flops"] / d["launches"]
+    unit = KERNEL_UNIT.get(dom, "valu_f32")
+    t_mem, t_alu = bytes_per_launch / (HBM_PEAK_GBS * 1e9), flops_per_launch / (PEAK_TFLOPS[unit] * 1e12)
+    if t_mem >= t_alu:
+        roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma" if unit.startswith("mfma") else "alu", "achieved": flops_per_launch / avg_s / 1e12,
+                "peak": PEAK_TFLOPS[unit], "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = dom
+    roof["avg_launch_us"] = avg_s * 1e6
+    roof["launches_per_step"] = d["launches"] / nprof
+    roof["arith_unit"] = unit
+    tot_ms = sum(v["ms"] for v in per_kernel.values())
+    roof["kernel_time_share"] = d["ms"] / tot_ms
+    breakdown = {s: {"us_per_step": v["ms"] * 1e3 / nprof, "launches_per_step": v["launches"] / nprof,
+                     "GBps": v["bytes"] / (v["ms"] * 1e-3) / 1e9 if v["ms"] > 0 else None,
+                     "TFLOPs": v["flops"] / (v["ms"] * 1e-3) / 1e12 if v["ms"] > 0 else None}
+                 for s, v in sorted(rep.items(), key=lambda kv: -kv[1]["ms"])}
+
+    out = {
+        "metric": "ASI compress+dW throughput (GB/s raw activation), % of HBM/MFMA roofline",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.layers[0].dtype == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index} ({cfg.name}): " + ", ".join(
+            f"{'x'.join(map(str, l.dims))} r{'/'.join(map(str, l.ranks))}" for l in cfg.layers),
+            "layers": len(cfg.layers), "raw_activation_bytes_per_step": act_bytes,
+            "distinct_input_steps_in_hbm": ndist, "phases": "compress+core_project+weight_grad"},
+        "roofline": roof,
+        "kernel_breakdown": breakdown,
+        "gpu_ms_per_step_events": gpu_ms / args.steps,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, streams, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -48,7 +48,7 @@ typedef enum { ASI_F32 = 0, ASI_BF16 = 1 } asi_dtype;   /* element type of A and
 
 /* One stored activation and its target ranks (Alg. 1 inputs).
  * ndim = 4: dims = (B, C, H, W); ndim = 3: dims = (B, N, D).
- * 1 <= ranks[m] <= min(dims[m], numel / dims[m]) (Alg. 1's rank range); ranks[m] <= 256. */
+ * 1 <= ranks[m] <= min(dims[m], numel / dims[m]) (Alg. 1's rank range); ranks[m] <= 1024. */
 typedef struct {
     int32_t ndim;
     int64_t dims[4];
@@ -131,6 +131,18 @@ const char* asi_status_string(asi_status s);
 
 /* Library ABI version (major*1000 + minor). */
 int32_t asi_version(void);
+
+/* Benchmark aid, off by default, not thread-safe against concurrent launches.
+ * asi_profile_enable(on): drops earlier records; while on, every kernel launch of the
+ * entry points above is bracketed by two HIP events on its stream and tagged with the
+ * bytes and flops that step must move / compute by its definition.  Returns the previous
+ * setting.
+ * asi_profile_report(buf, buflen): waits for the recorded events and writes one text
+ * line per launch site, "site,launches,total_ms,total_bytes,total_flops\n", NUL-terminated
+ * and truncated to buflen (host memory).  Returns the bytes a full report needs, or -1
+ * if an event could not be read. */
+int32_t asi_profile_enable(int32_t on);
+int64_t asi_profile_report(char* buf, int64_t buflen);
 
 #ifdef __cplusplus
 }

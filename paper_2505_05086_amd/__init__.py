@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     alloc_workspace,
     asi_compress,
     asi_core_project,
+    asi_profile_enable,
+    asi_profile_report,
     asi_status_string,
     asi_version,
     asi_weight_grad_conv2d,

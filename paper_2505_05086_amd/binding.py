@@ -21,7 +21,8 @@ STATUS_NAMES = {0: "ASI_OK", 1: "ASI_ERR_INVALID_ARG", 2: "ASI_ERR_UNSUPPORTED",
 ASI_F32, ASI_BF16 = 0, 1
 
 EXPORTS = ["asi_workspace_bytes", "asi_compress", "asi_core_project", "asi_weight_grad_conv2d",
-           "asi_weight_grad_linear", "asi_status_string", "asi_version"]
+           "asi_weight_grad_linear", "asi_status_string", "asi_version", "asi_profile_enable",
+           "asi_profile_report"]
 
 
 class TensorDesc(C.Structure):
@@ -71,6 +72,10 @@ def lib() -> C.CDLL:
         L.asi_status_string.argtypes = [C.c_int]
         L.asi_version.restype = C.c_int32
         L.asi_version.argtypes = []
+        L.asi_profile_enable.restype = C.c_int32
+        L.asi_profile_enable.argtypes = [C.c_int32]
+        L.asi_profile_report.restype = C.c_int64
+        L.asi_profile_report.argtypes = [C.c_char_p, C.c_int64]
         _lib = L
     return _lib
 
@@ -171,3 +176,22 @@ def asi_status_string(status: int) -> str:
 
 def asi_version() -> int:
     return int(lib().asi_version())
+
+
+def asi_profile_enable(on: bool) -> bool:
+    return bool(lib().asi_profile_enable(1 if on else 0))
+
+
+def asi_profile_report() -> dict:
+    """{site: {"launches", "ms", "bytes", "flops"}} for the launches recorded since enable."""
+    need = int(lib().asi_profile_report(None, 0))
+    if need < 0:
+        raise AsiError(4, "asi_profile_report")
+    buf = C.create_string_buffer(max(need, 1))
+    if lib().asi_profile_report(buf, need) < 0:
+        raise AsiError(4, "asi_profile_report")
+    out = {}
+    for line in buf.value.decode().splitlines():
+        site, cnt, ms, by, fl = line.split(",")
+        out[site] = {"launches": int(cnt), "ms": float(ms), "bytes": float(by), "flops": float(fl)}
+    return out

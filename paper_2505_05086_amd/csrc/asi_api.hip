@@ -4,7 +4,12 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdio>
 #include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
 
 #include "../../include/asi.h"
 #include "asi_kernels.h"
@@ -202,6 +207,54 @@ bool ws_ok(const void* ws, size_t have, size_t need) {
     return ws && (reinterpret_cast<uintptr_t>(ws) % kAlign) == 0 && have >= need;
 }
 
+// ---- per-kernel timing for benchmarks (off by default) -----------------------------
+// When enabled, every launch is bracketed by two HIP events on the launch stream and
+// tagged with the bytes and flops the step must move / compute by its definition.
+struct ProfRec {
+    std::string site;
+    double bytes, flops;
+    hipEvent_t e0, e1;
+};
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+
+struct ProfScope {
+    bool on = false;
+    ProfRec rec;
+    hipStream_t st;
+    ProfScope(const char* site, double bytes, double flops, hipStream_t s) : st(s) {
+        if (!g_prof_on) return;
+        on = true;
+        rec.site = site; rec.bytes = bytes; rec.flops = flops;
+        if (hipEventCreate(&rec.e0) != hipSuccess || hipEventCreate(&rec.e1) != hipSuccess) { on = false; return; }
+        (void)hipEventRecord(rec.e0, st);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(rec.e1, st);
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof.push_back(rec);
+    }
+};
+
+inline double esize(DType t) { return t == F32 ? 4.0 : 2.0; }
+
+// mode product with its accounting: reads X and M once, writes (or updates) Y once
+hipError_t ttm(const char* site, DType xt, const void* X, long long outer, int n, long long inner, const float* Mp,
+               long long ms_i, long long ms_q, int r, float* Y, int beta, hipStream_t st) {
+    const double cols = (double)outer * (double)inner;
+    ProfScope ps(site, cols * n * esize(xt) + 4.0 * n * r + 4.0 * cols * r * (beta ? 2 : 1), 2.0 * cols * n * r, st);
+    return launch_ttm(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, st);
+}
+
+hipError_t pair(const char* site, DType xt, const void* X, long long outer, int n, long long inner, const float* Y,
+                int r, double* part, int nsplit, hipStream_t st) {
+    const double cols = (double)outer * (double)inner;
+    ProfScope ps(site, cols * n * esize(xt) + 4.0 * cols * r + 8.0 * n * r * nsplit, 2.0 * cols * n * r, st);
+    return launch_pair(xt, X, outer, n, inner, Y, r, part, nsplit, st);
+}
+
 #define ASI_TRY(expr)                                  \
     do {                                               \
         hipError_t e__ = (expr);                       \
@@ -213,6 +266,41 @@ bool ws_ok(const void* ws, size_t have, size_t need) {
 extern "C" {
 
 int32_t asi_version(void) { return 1000; }
+
+int32_t asi_profile_enable(int32_t on) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    const int32_t was = g_prof_on ? 1 : 0;
+    for (auto& r : g_prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+    g_prof.clear();
+    g_prof_on = on != 0;
+    return was;
+}
+
+int64_t asi_profile_report(char* buf, int64_t buflen) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    struct Agg { long long count = 0; double ms = 0, bytes = 0, flops = 0; };
+    std::map<std::string, Agg> agg;
+    for (auto& r : g_prof) {
+        if (hipEventSynchronize(r.e1) != hipSuccess) return -1;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) return -1;
+        Agg& a = agg[r.site];
+        a.count += 1; a.ms += ms; a.bytes += r.bytes; a.flops += r.flops;
+    }
+    std::string out;
+    char line[256];
+    for (auto& kv : agg) {
+        std::snprintf(line, sizeof(line), "%s,%lld,%.6f,%.1f,%.1f\n", kv.first.c_str(), kv.second.count, kv.second.ms,
+                      kv.second.bytes, kv.second.flops);
+        out += line;
+    }
+    if (buf && buflen > 0) {
+        const size_t ncopy = std::min((size_t)buflen - 1, out.size());
+        std::memcpy(buf, out.data(), ncopy);
+        buf[ncopy] = 0;
+    }
+    return (int64_t)out.size() + 1;
+}
 
 const char* asi_status_string(asi_status s) {
     switch (s) {
@@ -264,14 +352,23 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
         const long long outer = s.outer(m), inner = s.inner(m);
         const int n = (int)s.n[m], r = s.r[m];
         // V = A_m^T U_prev, kept as a tensor with mode m of size r
-        ASI_TRY(launch_ttm(s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0, st));
+        ASI_TRY(ttm("k_ttm:V", s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0, st));
         // P = A_m V, split over the unfolding's columns
-        ASI_TRY(launch_pair(s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], st));
+        ASI_TRY(pair("k_pair:P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], st));
         OrthJob& j = oa.job[m];
         j.part = p.part[m]; j.nsplit = p.nsplit[m]; j.n = n; j.r = r;
         j.P64 = p.P64[m]; j.G = p.G[m]; j.Uout = U_out[m]; j.mode1 = m + 1;
     }
-    ASI_TRY(launch_orth(oa, st));
+    {
+        double ob = 0, of = 0;
+        for (int m = 0; m < s.d; ++m) {
+            const double n = (double)s.n[m], r = s.r[m];
+            ob += 8.0 * n * r * p.nsplit[m] + 4.0 * n * r;
+            of += 3.0 * (3.0 * n * r * r + r * r * r / 3.0);
+        }
+        ProfScope ps("k_orth", ob, of, st);
+        ASI_TRY(launch_orth(oa, st));
+    }
     return ASI_OK;
 }
 
@@ -297,7 +394,7 @@ asi_status asi_core_project(const asi_tensor_desc* desc, const void* A, const fl
         for (int q = 0; q < m; ++q) outer *= cur[q];
         for (int q = m + 1; q < s.d; ++q) inner *= cur[q];
         float* dst = (k + 1 == s.d) ? S : p.buf[k & 1];
-        ASI_TRY(launch_ttm(sdt, src, outer, (int)cur[m], inner, U[m], s.r[m], 1, s.r[m], dst, 0, st));
+        ASI_TRY(ttm("k_ttm:core", sdt, src, outer, (int)cur[m], inner, U[m], s.r[m], 1, s.r[m], dst, 0, st));
         cur[m] = s.r[m];
         src = dst;
         sdt = F32;
@@ -325,18 +422,29 @@ asi_status asi_weight_grad_conv2d(const asi_tensor_desc* desc, const float* S, c
     const int taps = g.kh * g.kw;
 
     // 1. G1 = grad_out x_1 U1^T                                   (r1, cout, Ho, Wo)
-    ASI_TRY(launch_ttm(s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0, st));
+    ASI_TRY(ttm("k_ttm:G1", s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0, st));
     // 2. Z1 = S x_3 U3                                            (r1, r2, H, r4)
-    ASI_TRY(launch_ttm(F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0, st));
+    ASI_TRY(ttm("k_ttm:Z1", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0, st));
     // 3. Z = Z1 x_4 U4                                            (r1, r2, H, W)
-    ASI_TRY(launch_ttm(F32, p.Z1, (long long)g.r1 * g.r2 * g.H, r4, 1, U[3], 1, r4, g.W, p.Z, 0, st));
+    ASI_TRY(ttm("k_ttm:Z", F32, p.Z1, (long long)g.r1 * g.r2 * g.H, r4, 1, U[3], 1, r4, g.W, p.Z, 0, st));
     // 4. T = correlation of Zpad with G1 over (r1, Ho, Wo)        (cout, r2, kh, kw)
-    ASI_TRY(launch_corr(p.G1, p.Z, p.Tpart, g, p.nsplit, st));
-    if (p.nsplit > 1) ASI_TRY(launch_sum_partials(p.Tpart, p.nsplit, (long long)g.cout * g.r2 * taps, p.T, 0, st));
+    {
+        const double tsz = (double)g.cout * g.r2 * taps;
+        ProfScope ps("k_corr", 4.0 * ((double)g.r1 * g.cout * g.Ho * g.Wo + (double)g.r1 * g.r2 * g.H * g.W + tsz * p.nsplit),
+                     2.0 * g.r1 * g.Ho * g.Wo * tsz, st);
+        ASI_TRY(launch_corr(p.G1, p.Z, p.Tpart, g, p.nsplit, st));
+    }
+    if (p.nsplit > 1) {
+        const double tsz = (double)g.cout * g.r2 * taps;
+        ProfScope ps("k_sum_partials", 4.0 * tsz * (p.nsplit + 1), tsz * p.nsplit, st);
+        ASI_TRY(launch_sum_partials(p.Tpart, p.nsplit, (long long)g.cout * g.r2 * taps, p.T, 0, st));
+    }
     // 5. dW = T x_(r2) U2, per group                              (cout, C/groups, kh, kw)
     if (cg.groups == 1) {
-        ASI_TRY(launch_ttm(F32, p.T, g.cout, g.r2, taps, U[1], 1, g.r2, cg.C, dW, accumulate ? 1 : 0, st));
+        ASI_TRY(ttm("k_ttm:dW", F32, p.T, g.cout, g.r2, taps, U[1], 1, g.r2, cg.C, dW, accumulate ? 1 : 0, st));
     } else {
+        const double dwsz = (double)g.cout * (cg.C / cg.groups) * taps;
+        ProfScope ps("k_expand_grouped", 4.0 * ((double)g.cout * g.r2 * taps + (double)cg.C * g.r2 + dwsz), 2.0 * dwsz * g.r2, st);
         ASI_TRY(launch_expand_grouped(p.T, U[1], dW, g.cout, g.r2, taps, cg.C / cg.groups, g.cout / cg.groups,
                                       accumulate ? 1 : 0, st));
     }
@@ -360,14 +468,18 @@ asi_status asi_weight_grad_linear(const asi_tensor_desc* desc, const float* S, c
     const int r1 = s.r[0], r2 = s.r[1], r3 = s.r[2];
 
     // 1. G1[i,n,o] = sum_b U1[b,i] dY[b,n,o]
-    ASI_TRY(launch_ttm(s.dt, grad_out, 1, B, (long long)N * dout, U[0], r1, 1, r1, p.G1, 0, st));
+    ASI_TRY(ttm("k_ttm:G1", s.dt, grad_out, 1, B, (long long)N * dout, U[0], r1, 1, r1, p.G1, 0, st));
     // 2. G2[i,j,o] = sum_n U2[n,j] G1[i,n,o]
-    ASI_TRY(launch_ttm(F32, p.G1, r1, N, dout, U[1], r2, 1, r2, p.G2, 0, st));
+    ASI_TRY(ttm("k_ttm:G2", F32, p.G1, r1, N, dout, U[1], r2, 1, r2, p.G2, 0, st));
     // 3. T[o,k] = sum_{i,j} G2[i,j,o] S[i,j,k]
-    ASI_TRY(launch_pair(F32, p.G2, (long long)r1 * r2, (int)dout, 1, S, r3, p.Tpart, p.nsplit, st));
-    ASI_TRY(launch_sum_partials_f64(p.Tpart, p.nsplit, (long long)dout * r3, p.T, 0, st));
+    ASI_TRY(pair("k_pair:T", F32, p.G2, (long long)r1 * r2, (int)dout, 1, S, r3, p.Tpart, p.nsplit, st));
+    {
+        const double tsz = (double)dout * r3;
+        ProfScope ps("k_sum_partials", tsz * (8.0 * p.nsplit + 4.0), tsz * p.nsplit, st);
+        ASI_TRY(launch_sum_partials_f64(p.Tpart, p.nsplit, (long long)dout * r3, p.T, 0, st));
+    }
     // 4. dW[o,d] = sum_k T[o,k] U3[d,k]
-    ASI_TRY(launch_ttm(F32, p.T, dout, r3, 1, U[2], 1, r3, D, dW, accumulate ? 1 : 0, st));
+    ASI_TRY(ttm("k_ttm:dW", F32, p.T, dout, r3, 1, U[2], 1, r3, D, dW, accumulate ? 1 : 0, st));
     return ASI_OK;
 }
 
