@@ -75,6 +75,9 @@ struct CompressPlan {
     double* P64[4] = {};
     double* G[4] = {};
     int nsplit[4] = {};
+    int nred[4] = {};
+    int* ctrl = nullptr;
+    bool fused[4] = {};
     size_t bytes = 0;
 };
 
@@ -82,14 +85,20 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
     CompressPlan p;
     Carver c(ws);
     size_t vmax = 0;
-    for (int m = 0; m < s.d; ++m) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
+    for (int m = 0; m < s.d; ++m) {
+        p.fused[m] = subspace_small_supported((int)s.n[m], s.r[m]);
+        if (!p.fused[m]) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
+    }
     p.V = c.take<float>(vmax);
     for (int m = 0; m < s.d; ++m) {
-        p.nsplit[m] = pair_splits(s.outer(m), (int)s.n[m], s.inner(m), s.r[m]);
+        p.nsplit[m] = p.fused[m] ? subspace_small_nwg(s.outer(m), (int)s.n[m], s.inner(m))
+                                 : pair_splits(s.outer(m), (int)s.n[m], s.inner(m), s.r[m]);
         p.part[m] = c.take<double>((size_t)p.nsplit[m] * s.n[m] * s.r[m]);
         p.P64[m] = c.take<double>((size_t)s.n[m] * s.r[m]);
         p.G[m] = c.take<double>((size_t)s.r[m] * s.r[m]);
+        p.nred[m] = orth_reduce_blocks(p.nsplit[m], (int)s.n[m], s.r[m]);
     }
+    p.ctrl = c.take<int>(64);
     p.bytes = c.off;
     return p;
 }
@@ -343,7 +352,7 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
     if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    if (info) ASI_TRY(launch_set_i32(info, 0, st));
+    ASI_TRY(launch_init_ctrl(info, p.ctrl, 4, st));
     OrthArgs oa;
     std::memset(&oa, 0, sizeof(oa));
     oa.njobs = s.d;
@@ -351,13 +360,22 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
     for (int m = 0; m < s.d; ++m) {
         const long long outer = s.outer(m), inner = s.inner(m);
         const int n = (int)s.n[m], r = s.r[m];
-        // V = A_m^T U_prev, kept as a tensor with mode m of size r
-        ASI_TRY(ttm("k_ttm:V", s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0, st));
-        // P = A_m V, split over the unfolding's columns
-        ASI_TRY(pair("k_pair:P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], st));
+        if (p.fused[m]) {
+            // short fibres: V and P from one LDS tile of complete fibres, V never stored
+            const double cols = (double)outer * (double)inner;
+            ProfScope ps("k_subspace_small", cols * n * esize(s.dt) + 4.0 * n * r + 8.0 * n * r * p.nsplit[m],
+                         4.0 * cols * n * r, st);
+            ASI_TRY(launch_subspace_small(s.dt, A, outer, n, inner, U_prev[m], r, p.part[m], p.nsplit[m], st));
+        } else {
+            // V = A_m^T U_prev, kept as a tensor with mode m of size r
+            ASI_TRY(ttm("k_ttm:V", s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0, st));
+            // P = A_m V, split over the unfolding's columns
+            ASI_TRY(pair("k_pair:P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], st));
+        }
         OrthJob& j = oa.job[m];
         j.part = p.part[m]; j.nsplit = p.nsplit[m]; j.n = n; j.r = r;
         j.P64 = p.P64[m]; j.G = p.G[m]; j.Uout = U_out[m]; j.mode1 = m + 1;
+        j.nred = p.nred[m]; j.counter = p.ctrl + m;
     }
     {
         double ob = 0, of = 0;

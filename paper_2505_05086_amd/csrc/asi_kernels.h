@@ -26,6 +26,12 @@ hipError_t launch_sum_partials(const float* part, int nsplit, long long count, f
 hipError_t launch_sum_partials_f64(const double* part, int nsplit, long long count, float* out, int beta,
                                    hipStream_t st);
 
+// Fused V/P step for a mode with n <= 64 (asi_subspace.hip): part is (nwg, n, r) fp64.
+bool subspace_small_supported(int n, int r);
+int subspace_small_nwg(long long outer, int n, long long inner);
+hipError_t launch_subspace_small(DType xt, const void* X, long long outer, int n, long long inner, const float* U,
+                                 int r, double* part, int nwg, hipStream_t st);
+
 struct OrthJob {
     const double* part;  // (nsplit, n, r) partial sums of P
     int nsplit;
@@ -34,6 +40,8 @@ struct OrthJob {
     double* G;           // (r, r) scratch
     float* Uout;         // (n, r)
     int mode1;           // 1-based mode number for *info
+    int nred;            // workgroups that share the summation of the partials (>= 1)
+    int* counter;        // device counter, zero before the launch (needed if nred > 1)
 };
 struct OrthArgs {
     OrthJob job[4];
@@ -41,6 +49,9 @@ struct OrthArgs {
     int32_t* info;       // nullable
 };
 hipError_t launch_orth(const OrthArgs& a, hipStream_t st);
+int orth_reduce_blocks(int nsplit, int n, int r);
+// *info = 0 (if non-null) and counters[0..ncounters) = 0, ncounters <= 64
+hipError_t launch_init_ctrl(int32_t* info, int* counters, int ncounters, hipStream_t st);
 hipError_t launch_set_i32(int32_t* p, int32_t v, hipStream_t st);
 
 // Step 4 of Eq. 14: T[o,j,kh,kw] = sum_{i,y,x} G1[i,o,y,x] * Zpad[i,j,y*s-p+kh*d, x*s-p+kw*d]

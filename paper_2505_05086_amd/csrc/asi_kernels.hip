@@ -269,108 +269,6 @@ hipError_t launch_set_i32(int32_t* p, int32_t v, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------
-// Orthogonalize (Alg. 1): Q factor of the thin QR of P with positive diagonal R,
-// computed in fp64 by shifted Cholesky-QR followed by two plain Cholesky-QR passes
-// (one workgroup per mode):
-//   pass 0: G = P^T P + s I,  G = R^T R,  P <- P R^-1     (s makes the factorisation safe)
-//   pass 1, 2: the same with s = 0.
-// cond(P) reaches (sigma_1/sigma_r)^2 * cond(U^T U_prev) ~ 1e8 on the benchmark tensors, so
-// the Gram matrix of P itself is numerically singular in fp64; after the shifted pass the
-// condition number is ~1e3 and two further passes give orthogonality to rounding.
-// The product of the three upper-triangular factors has a positive diagonal, so the
-// result is the unique Q that Gram-Schmidt produces.  Its diagonal is also the norm each
-// column keeps after projecting out the earlier ones; a column that keeps less than
-// 1e-12 ||P||_F is reported through *info.
-// ---------------------------------------------------------------------------
-constexpr int ORTH_NT = 512;
-constexpr int ORTH_MAXR = 1024;
-
-__global__ __launch_bounds__(ORTH_NT) void k_orth(OrthArgs a) {
-    const OrthJob jb = a.job[blockIdx.x];
-    const int n = jb.n, r = jb.r, tid = threadIdx.x;
-    double* __restrict__ P = jb.P64;
-    double* __restrict__ G = jb.G;
-    __shared__ double s_inv;
-    __shared__ double s_trace;
-    __shared__ double s_rdiag[ORTH_MAXR];   // running product of the diagonals of the R factors
-
-    const long long cnt = (long long)n * r;
-    for (long long e = tid; e < cnt; e += ORTH_NT) {
-        double s = 0.0;
-        for (int sp = 0; sp < jb.nsplit; ++sp) s += jb.part[(long long)sp * cnt + e];
-        P[e] = s;
-    }
-    for (int k = tid; k < r; k += ORTH_NT) s_rdiag[k] = 1.0;
-    __syncthreads();
-
-    for (int pass = 0; pass < 3; ++pass) {
-        for (int e = tid; e < r * r; e += ORTH_NT) {
-            const int ca = e / r, cb = e - ca * r;
-            if (ca <= cb) {
-                double s = 0.0;
-                for (int i = 0; i < n; ++i) s = fma(P[(long long)i * r + ca], P[(long long)i * r + cb], s);
-                G[ca * r + cb] = s;
-            }
-        }
-        __syncthreads();
-        if (pass == 0) {
-            if (tid == 0) {
-                double tr = 0.0;
-                for (int k = 0; k < r; ++k) tr += G[k * r + k];
-                s_trace = tr;
-            }
-            __syncthreads();
-            const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * 1.1102230246251565e-16 * s_trace;
-            for (int k = tid; k < r; k += ORTH_NT) G[k * r + k] += shift;
-            __syncthreads();
-        }
-        for (int k = 0; k < r; ++k) {
-            if (tid == 0) {
-                double p = G[k * r + k];
-                if (!(p > 0.0)) {   // also true for NaN: zero or non-finite input
-                    if (a.info) atomicCAS(a.info, 0, jb.mode1 * 1000 + (k + 1));
-                    p = 1.0;
-                }
-                const double d = sqrt(p);
-                G[k * r + k] = d;
-                s_rdiag[k] *= d;
-                s_inv = 1.0 / d;
-            }
-            __syncthreads();
-            for (int j = k + 1 + tid; j < r; j += ORTH_NT) G[k * r + j] *= s_inv;
-            __syncthreads();
-            const int m = r - k - 1;
-            for (int e = tid; e < m * m; e += ORTH_NT) {
-                const int ca = k + 1 + e / m, cb = k + 1 + e % m;
-                if (ca <= cb) G[ca * r + cb] -= G[k * r + ca] * G[k * r + cb];
-            }
-            __syncthreads();
-        }
-        for (int i = tid; i < n; i += ORTH_NT) {
-            double* row = P + (long long)i * r;
-            for (int j = 0; j < r; ++j) {
-                double s = row[j];
-                for (int k = 0; k < j; ++k) s -= row[k] * G[k * r + j];
-                row[j] = s / G[j * r + j];
-            }
-        }
-        __syncthreads();
-    }
-    if (tid == 0 && a.info) {
-        const double floor_ = 1e-12 * sqrt(s_trace);
-        for (int k = 0; k < r; ++k)
-            if (!(s_rdiag[k] > floor_)) { atomicCAS(a.info, 0, jb.mode1 * 1000 + (k + 1)); break; }
-    }
-    for (long long e = tid; e < cnt; e += ORTH_NT) jb.Uout[e] = (float)P[e];
-}
-
-hipError_t launch_orth(const OrthArgs& a, hipStream_t st) {
-    if (a.njobs <= 0 || a.njobs > 4) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_orth, dim3(a.njobs), ORTH_NT, 0, st, a);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------
 // Step 4 of Eq. 14: one thread per T[o,j,kh,kw] and split of the r1 axis
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_corr(const float* __restrict__ G1, const float* __restrict__ Z,
