@@ -74,10 +74,14 @@ struct CompressPlan {
     double* part[4] = {};
     double* P64[4] = {};
     double* G[4] = {};
+    double* Gpart[4] = {};
+    double* R[4] = {};
+    double* Dinv[4] = {};
+    double* scal[4] = {};
     int nsplit[4] = {};
-    int nred[4] = {};
-    int* ctrl = nullptr;
+    int nblk[4] = {};
     bool fused[4] = {};
+    bool fast_orth[4] = {};
     size_t bytes = 0;
 };
 
@@ -91,14 +95,22 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
     }
     p.V = c.take<float>(vmax);
     for (int m = 0; m < s.d; ++m) {
-        p.nsplit[m] = p.fused[m] ? subspace_small_nwg(s.outer(m), (int)s.n[m], s.inner(m))
-                                 : pair_splits(s.outer(m), (int)s.n[m], s.inner(m), s.r[m]);
-        p.part[m] = c.take<double>((size_t)p.nsplit[m] * s.n[m] * s.r[m]);
-        p.P64[m] = c.take<double>((size_t)s.n[m] * s.r[m]);
-        p.G[m] = c.take<double>((size_t)s.r[m] * s.r[m]);
-        p.nred[m] = orth_reduce_blocks(p.nsplit[m], (int)s.n[m], s.r[m]);
+        const size_t n = (size_t)s.n[m], r = (size_t)s.r[m];
+        p.nsplit[m] = p.fused[m] ? subspace_small_nwg(s.outer(m), (int)n, s.inner(m))
+                                 : pair_splits(s.outer(m), (int)n, s.inner(m), (int)r);
+        p.part[m] = c.take<double>((size_t)p.nsplit[m] * n * r);
+        p.P64[m] = c.take<double>(n * r);
+        p.fast_orth[m] = orth_fast_supported((int)r);
+        if (p.fast_orth[m]) {
+            p.nblk[m] = orth_slices((int)n);
+            p.Gpart[m] = c.take<double>((size_t)p.nblk[m] * r * r);
+            p.R[m] = c.take<double>(r * r);
+            p.Dinv[m] = c.take<double>(((r + 15) / 16) * 256);
+            p.scal[m] = c.take<double>(66);
+        } else {
+            p.G[m] = c.take<double>(r * r);
+        }
     }
-    p.ctrl = c.take<int>(64);
     p.bytes = c.off;
     return p;
 }
@@ -352,11 +364,12 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
     if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    ASI_TRY(launch_init_ctrl(info, p.ctrl, 4, st));
-    OrthArgs oa;
-    std::memset(&oa, 0, sizeof(oa));
-    oa.njobs = s.d;
-    oa.info = info;
+    if (info) ASI_TRY(launch_init_ctrl(info, st));
+    OrthArgs fast, slow;
+    std::memset(&fast, 0, sizeof(fast));
+    std::memset(&slow, 0, sizeof(slow));
+    fast.info = slow.info = info;
+    double fast_b = 0, fast_f = 0, slow_b = 0, slow_f = 0;
     for (int m = 0; m < s.d; ++m) {
         const long long outer = s.outer(m), inner = s.inner(m);
         const int n = (int)s.n[m], r = s.r[m];
@@ -372,20 +385,26 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
             // P = A_m V, split over the unfolding's columns
             ASI_TRY(pair("k_pair:P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], st));
         }
-        OrthJob& j = oa.job[m];
+        OrthArgs& oa = p.fast_orth[m] ? fast : slow;
+        OrthJob& j = oa.job[oa.njobs++];
         j.part = p.part[m]; j.nsplit = p.nsplit[m]; j.n = n; j.r = r;
-        j.P64 = p.P64[m]; j.G = p.G[m]; j.Uout = U_out[m]; j.mode1 = m + 1;
-        j.nred = p.nred[m]; j.counter = p.ctrl + m;
+        j.P64 = p.P64[m]; j.Uout = U_out[m]; j.mode1 = m + 1;
+        j.nblk = p.nblk[m]; j.Gpart = p.Gpart[m]; j.R = p.R[m]; j.Dinv = p.Dinv[m]; j.scal = p.scal[m];
+        j.G = p.G[m];
+        (p.fast_orth[m] ? fast_b : slow_b) += 8.0 * n * r;
+        (p.fast_orth[m] ? fast_f : slow_f) += 2.0 * (double)n * r * r;
     }
-    {
-        double ob = 0, of = 0;
-        for (int m = 0; m < s.d; ++m) {
-            const double n = (double)s.n[m], r = s.r[m];
-            ob += 8.0 * n * r * p.nsplit[m] + 4.0 * n * r;
-            of += 3.0 * (3.0 * n * r * r + r * r * r / 3.0);
-        }
-        ProfScope ps("k_orth", ob, of, st);
-        ASI_TRY(launch_orth(oa, st));
+    if (fast.njobs) {
+        // Orthogonalize: shifted Cholesky-QR, then one plain Cholesky-QR pass
+        { ProfScope ps("k_orth_gram0", fast_b, fast_f, st); ASI_TRY(launch_orth_gram0(fast, st)); }
+        { ProfScope ps("k_orth_chol", 0, 0, st); ASI_TRY(launch_orth_chol(fast, 0, 0, st)); }
+        { ProfScope ps("k_orth_apply", 2 * fast_b, 2 * fast_f, st); ASI_TRY(launch_orth_apply(fast, 0, st)); }
+        { ProfScope ps("k_orth_chol", 0, 0, st); ASI_TRY(launch_orth_chol(fast, 1, 1, st)); }
+        { ProfScope ps("k_orth_apply", 1.5 * fast_b, fast_f, st); ASI_TRY(launch_orth_apply(fast, 1, st)); }
+    }
+    if (slow.njobs) {
+        ProfScope ps("k_orth_big", 6 * slow_b, 9 * slow_f, st);
+        ASI_TRY(launch_orth_big(slow, st));
     }
     return ASI_OK;
 }

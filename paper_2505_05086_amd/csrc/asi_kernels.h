@@ -37,21 +37,29 @@ struct OrthJob {
     int nsplit;
     int n, r;
     double* P64;         // (n, r) scratch
-    double* G;           // (r, r) scratch
     float* Uout;         // (n, r)
     int mode1;           // 1-based mode number for *info
-    int nred;            // workgroups that share the summation of the partials (>= 1)
-    int* counter;        // device counter, zero before the launch (needed if nred > 1)
+    // fast path (r <= 64)
+    int nblk;            // row slices = orth_slices(n)
+    double* Gpart;       // (nblk, r, r) slice Gram matrices
+    double* R;           // (r, r)
+    double* Dinv;        // (ceil(r/16), 16, 16) inverses of R's diagonal blocks
+    double* scal;        // 66 doubles of bookkeeping
+    // slow path (r > 64)
+    double* G;           // (r, r)
 };
 struct OrthArgs {
     OrthJob job[4];
     int njobs;
     int32_t* info;       // nullable
 };
-hipError_t launch_orth(const OrthArgs& a, hipStream_t st);
-int orth_reduce_blocks(int nsplit, int n, int r);
-// *info = 0 (if non-null) and counters[0..ncounters) = 0, ncounters <= 64
-hipError_t launch_init_ctrl(int32_t* info, int* counters, int ncounters, hipStream_t st);
+bool orth_fast_supported(int r);
+int orth_slices(int n);
+hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st);
+hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t st);
+hipError_t launch_orth_apply(const OrthArgs& a, int final_pass, hipStream_t st);
+hipError_t launch_orth_big(const OrthArgs& a, hipStream_t st);
+hipError_t launch_init_ctrl(int32_t* info, hipStream_t st);   // *info = 0 if non-null
 hipError_t launch_set_i32(int32_t* p, int32_t v, hipStream_t st);
 
 // Step 4 of Eq. 14: T[o,j,kh,kw] = sum_{i,y,x} G1[i,o,y,x] * Zpad[i,j,y*s-p+kh*d, x*s-p+kw*d]

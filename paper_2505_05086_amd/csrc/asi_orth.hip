@@ -1,19 +1,22 @@
-// Orthogonalize (Alg. 1): Q factor of the thin QR of P with positive diagonal R, computed
-// in fp64 by shifted Cholesky-QR followed by two plain Cholesky-QR passes:
-//   pass 0: G = P^T P + s I,  G = R^T R,  P <- P R^-1     (s makes the factorisation safe)
-//   pass 1, 2: the same with s = 0.
-// cond(P) reaches (sigma_1/sigma_r)^2 * cond(U^T U_prev) ~ 1e8 on the benchmark tensors, so
-// the Gram matrix of P itself is numerically singular in fp64; after the shifted pass the
-// condition number is ~1e3 and two further passes give orthogonality to rounding.  The
-// product of the three upper-triangular factors has a positive diagonal, so the result is
-// the unique Q that Gram-Schmidt produces.  That diagonal is also the norm each column keeps
-// after projecting out the earlier ones; a column that keeps less than 1e-12 ||P||_F is
-// reported through *info.
+// Orthogonalize (Alg. 1): Q factor of the thin QR of P with positive diagonal R, in fp64.
 //
-// One launch serves every mode of a tensor.  A mode gets `nred` workgroups: each sums a
-// slice of the split partial sums of P into P64; the last one to finish (device counter)
-// runs the three passes.  Ranks up to 64 keep the Gram matrix in LDS and use fp64 MFMA
-// for it; larger ranks take a plain global-memory path.
+// Method: Cholesky-QR with a diagonal shift on the first pass (safe for cond(P) up to
+// ~1e9, far beyond what a Gram matrix alone allows), followed by plain Cholesky-QR:
+//     pass 0: G = P^T P + s I = R0^T R0,  Q0 = P R0^-1        cond(Q0) ~ 1e3
+//     pass 1: G = Q0^T Q0     = R1^T R1,  Q  = Q0 R1^-1       |Q^T Q - I| ~ 1e-16 cond(Q0)^2
+// cond(P) reaches (sigma_1/sigma_r)^2 * cond(U^T U_prev) ~ 1e8 on the benchmark tensors.  Q
+// is handed back in fp32, so two passes are enough; the slow path below runs a third.  The
+// product R1 R0 is upper triangular with a positive diagonal, so Q is the unique factor
+// Gram-Schmidt produces.  Its diagonal is the norm each column keeps after the earlier ones
+// are projected out; a column keeping less than 1e-12 ||P||_F is reported through *info.
+//
+// Fast path (r <= 64), five launches that serve all modes of a tensor at once:
+//   gram0 : row slices of 32 rows: sum the split partial sums of P -> P64, slice Gram (fp64 MFMA)
+//   chol  : one workgroup per mode: sum slice Grams (+ shift), Cholesky in LDS, invert the
+//           16x16 diagonal blocks of R
+//   apply : row slices: Q = P R^-1 by block forward substitution (fp64 MFMA), next slice Gram
+//   chol, apply (final: writes fp32 U)
+// Slow path (r > 64): one workgroup per mode, everything in global memory.
 #include "asi_device.h"
 #include "asi_kernels.h"
 
@@ -21,181 +24,270 @@ namespace asi {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
-constexpr int ORTH_NT = 512;
-constexpr int ORTH_NW = ORTH_NT / 64;
-constexpr int ORTH_STAGE = 10;         // Gram work items (block pair x row slice) per pass
-constexpr int ORTH_RMAX = 64;          // LDS path
-constexpr int ORTH_LD = ORTH_RMAX + 1;
-constexpr int ORTH_MAXR = 1024;        // global path
-
-#ifdef ASI_DEBUG_TIMING
-__device__ long long g_orth_stamps[64];
-#define STAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 2) g_orth_stamps[i] = wall_clock64(); } while (0)
-#else
-#define STAMP(i) do {} while (0)
-#endif
+constexpr int OP_RS = 32;              // rows per slice
+constexpr int OP_RMAX = 64;
+constexpr int OP_LD = OP_RMAX + 1;
+constexpr double OP_EPS = 1.1102230246251565e-16;
 
 __device__ __forceinline__ void flag_info(int32_t* info, int mode1, int col1) {
     if (info) atomicCAS(info, 0, mode1 * 1000 + col1);
 }
 
-// ---- LDS path, r <= 64 -----------------------------------------------------------------
-// P <- P R^-1 by forward substitution, one row per thread, 16 columns at a time: the
-// finished columns of earlier blocks are re-read from the row itself, so only two 16-wide
-// register blocks are live.  Gs holds R above the diagonal, dinv the inverse diagonal.
-__device__ __attribute__((noinline)) void apply_rows(double* __restrict__ P, int n, int r, const double (*Gs)[ORTH_LD],
-                           const double* __restrict__ dinv) {
-    const int nb = (r + 15) / 16;
-    for (int i = threadIdx.x; i < n; i += ORTH_NT) {
-        double* row = P + (long long)i * r;
-        for (int jb = 0; jb < nb; ++jb) {
-            double cur[16];
+__device__ __forceinline__ void find_job(const OrthArgs& a, int* ji, int* blk) {
+    int j = 0, b = blockIdx.x;
+    while (j + 1 < a.njobs && b >= a.job[j].nblk) { b -= a.job[j].nblk; ++j; }
+    *ji = j; *blk = b;
+}
+
+// Gram of the 32 rows held in Ps (zero padded to 64 columns) -> upper triangle of Gout (r x r)
+__device__ void gram_from_lds(const double (*Ps)[OP_LD], int r, double* __restrict__ Gout) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lg = lane >> 4, ll = lane & 15;
+    const int nb = (r + 15) / 16, npairs = nb * (nb + 1) / 2;
+    for (int pr = wave; pr < npairs; pr += 2) {
+        int ab = 0, rem = pr;
+        while (rem >= nb - ab) { rem -= nb - ab; ++ab; }
+        const int bb = ab + rem;
+        v4d acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int j = 0; j < 16; ++j) cur[j] = (16 * jb + j < r) ? row[16 * jb + j] : 0.0;
-            for (int pb = 0; pb < jb; ++pb) {
-                double prev[16];
+        for (int ks = 0; ks < OP_RS / 4; ++ks)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[4 * ks + lg][16 * ab + ll], Ps[4 * ks + lg][16 * bb + ll], acc,
+                                                       0, 0, 0);
 #pragma unroll
-                for (int k = 0; k < 16; ++k) prev[k] = row[16 * pb + k];
-#pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    const double* grow = &Gs[16 * pb + k][16 * jb];
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) cur[j] = fma(-prev[k], grow[j], cur[j]);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                double s = cur[j];
-#pragma unroll
-                for (int k = 0; k < j; ++k) s = fma(-cur[k], Gs[16 * jb + k][16 * jb + j], s);
-                cur[j] = s * dinv[16 * jb + j];
-            }
-#pragma unroll
-            for (int j = 0; j < 16; ++j)
-                if (16 * jb + j < r) row[16 * jb + j] = cur[j];
+        for (int v = 0; v < 4; ++v) {
+            const int ga = 16 * ab + lg + 4 * v, gb = 16 * bb + ll;
+            if (ga < r && gb < r && ga <= gb) Gout[ga * r + gb] = acc[v];
         }
     }
 }
 
-__device__ __attribute__((noinline)) void orth_lds(const OrthJob& jb, int32_t* info, double (*Gs)[ORTH_LD], double* stage, double* dinv,
-                         double* rdiag) {
+// ---- gram0 ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void k_orth_gram0(OrthArgs a) {
+    __shared__ double Ps[OP_RS][OP_LD];
+    int ji, blk;
+    find_job(a, &ji, &blk);
+    const OrthJob jb = a.job[ji];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
-    double* __restrict__ P = jb.P64;
+    const int i0 = blk * OP_RS;
+    const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
+    const long long cnt = (long long)n * r;
+    for (int e = tid; e < OP_RS * OP_LD; e += 128) (&Ps[0][0])[e] = 0.0;
+    __syncthreads();
+    for (int idx = tid; idx < nrows * r; idx += 128) {
+        const long long e = (long long)i0 * r + idx;
+        double s = 0.0;
+        for (int sp0 = 0; sp0 < jb.nsplit; sp0 += 8) {          // 8 loads in flight
+            double t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = (sp0 + u < jb.nsplit) ? jb.part[(long long)(sp0 + u) * cnt + e] : 0.0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += t[u];
+        }
+        jb.P64[e] = s;
+        Ps[idx / r][idx % r] = s;
+    }
+    __syncthreads();
+    gram_from_lds(Ps, r, jb.Gpart + (long long)blk * r * r);
+}
+
+// ---- chol -----------------------------------------------------------------------------------
+// scal[0] = trace(P^T P), scal[1 + k] = running product of the R diagonals, scal[65] = first bad pivot
+__global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int last) {
+    __shared__ double Gs[OP_RMAX][OP_LD];
+    __shared__ double dinv[OP_RMAX];
+    __shared__ double rdiag[OP_RMAX];
     __shared__ double s_trace;
     __shared__ int s_bad;
-    const int nb = (r + 15) / 16;
-    const int npairs = nb * (nb + 1) / 2;          // <= 10 block pairs (ab <= bb)
-    const int nks = (ORTH_NW / npairs > 0) ? ORTH_NW / npairs : 1;   // row slices per pair; npairs*nks <= 10
-    for (int k = tid; k < r; k += ORTH_NT) rdiag[k] = 1.0;
+    const OrthJob jb = a.job[blockIdx.x];
+    const int n = jb.n, r = jb.r, tid = threadIdx.x;
     if (tid == 0) s_bad = 0;
-
-    for (int pass = 0; pass < 3; ++pass) {
-        STAMP(1 + pass * 5);
-        // ---- Gram with fp64 MFMA: wave -> (block pair, row slice)
-        for (int item = wave; item < npairs * nks; item += ORTH_NW) {
-            const int pr = item % npairs, ks = item / npairs;
-            int ab = 0, rem = pr;
-            while (rem >= nb - ab) { rem -= nb - ab; ++ab; }
-            const int bb = ab + rem;
-            const int rows_per = ((n + nks - 1) / nks + 3) / 4 * 4;
-            const int k_beg = ks * rows_per, k_end = (k_beg + rows_per < n) ? k_beg + rows_per : n;
-            v4d acc = {0.0, 0.0, 0.0, 0.0};
-            const int ca = 16 * ab + ll, cb = 16 * bb + ll;
-            for (int k0 = k_beg; k0 < k_end; k0 += 32) {        // 16 loads in flight per lane
-                double av[8], bv[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int row = k0 + 4 * u + lg;
-                    const bool ok = row < k_end;
-                    av[u] = (ok && ca < r) ? P[(long long)row * r + ca] : 0.0;
-                    bv[u] = (ok && cb < r) ? P[(long long)row * r + cb] : 0.0;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av[u], bv[u], acc, 0, 0, 0);
-            }
-#pragma unroll
-            for (int v = 0; v < 4; ++v) stage[item * 256 + (lg + 4 * v) * 16 + ll] = acc[v];
-        }
-        __syncthreads();
-        for (int e = tid; e < npairs * 256; e += ORTH_NT) {
-            const int pr = e >> 8, ij = e & 255;
-            int ab = 0, rem = pr;
-            while (rem >= nb - ab) { rem -= nb - ab; ++ab; }
-            const int bb = ab + rem;
+    for (int e = tid; e < r * r; e += 512) {
+        const int ga = e / r, gb = e - ga * r;
+        if (ga <= gb) {
             double s = 0.0;
-            for (int ks = 0; ks < nks; ++ks) s += stage[(ks * npairs + pr) * 256 + ij];
-            const int ga = 16 * ab + (ij >> 4), gb = 16 * bb + (ij & 15);
-            if (ga < r && gb < r && ga <= gb) Gs[ga][gb] = s;
-        }
-        __syncthreads();
-        if (pass == 0) {
-            if (tid == 0) {
-                double tr = 0.0;
-                for (int k = 0; k < r; ++k) tr += Gs[k][k];
-                s_trace = tr;
+            for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
+                double t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = (b0 + u < jb.nblk) ? jb.Gpart[(long long)(b0 + u) * r * r + e] : 0.0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) s += t[u];
             }
-            __syncthreads();
-            const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * 1.1102230246251565e-16 * s_trace;
-            if (tid < r) Gs[tid][tid] += shift;
-            __syncthreads();
+            Gs[ga][gb] = s;
         }
-        STAMP(2 + pass * 5);
-        // ---- Cholesky, right-looking; row k is left unscaled and scaled afterwards
-        for (int k = 0; k < r; ++k) {
-            double p = Gs[k][k];
-            if (!(p > 0.0)) {            // zero or non-finite input; every thread sees the same value
-                if (tid == 0 && s_bad == 0) s_bad = k + 1;
-                p = 1.0;
-            }
-            const double pinv = 1.0 / p;
-            const int m = r - k - 1;
-            for (int e = tid; e < m * m; e += ORTH_NT) {
-                const int ia = e / m, ib = e - ia * m;
-                if (ia <= ib) {
-                    const int ga = k + 1 + ia, gb = k + 1 + ib;
-                    Gs[ga][gb] = fma(-Gs[k][ga] * pinv, Gs[k][gb], Gs[ga][gb]);
-                }
-            }
-            __syncthreads();
-        }
-        STAMP(3 + pass * 5);
-        if (tid < r) {
-            double p = Gs[tid][tid];
-            if (!(p > 0.0)) p = 1.0;
-            const double d = sqrt(p);
-            dinv[tid] = 1.0 / d;
-            rdiag[tid] *= d;
-        }
-        __syncthreads();
-        for (int e = tid; e < r * r; e += ORTH_NT) {
-            const int ga = e / r, gb = e - ga * r;
-            if (ga < gb) Gs[ga][gb] *= dinv[ga];       // R[ga][gb]
-        }
-        __syncthreads();
-        // ---- P <- P R^-1, one row per thread
-        STAMP(4 + pass * 5);
-        apply_rows(P, n, r, Gs, dinv);
-        __syncthreads();
-        STAMP(5 + pass * 5);
     }
-    if (tid == 0 && info) {
-        if (s_bad) flag_info(info, jb.mode1, s_bad);
-        const double floor_ = 1e-12 * sqrt(s_trace);
-        for (int k = 0; k < r; ++k)
-            if (!(rdiag[k] > floor_)) { flag_info(info, jb.mode1, k + 1); break; }
+    __syncthreads();
+    if (pass == 0) {
+        if (tid == 0) {
+            double tr = 0.0;
+            for (int k = 0; k < r; ++k) tr += Gs[k][k];
+            s_trace = tr;
+            jb.scal[0] = tr;
+        }
+        __syncthreads();
+        const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * s_trace;
+        if (tid < r) Gs[tid][tid] += shift;
+        __syncthreads();
+    } else if (tid == 0) {
+        s_trace = jb.scal[0];
     }
-    const long long cnt = (long long)n * r;
-    for (long long e = tid; e < cnt; e += ORTH_NT) jb.Uout[e] = (float)P[e];
+    // right-looking Cholesky; thread (ty, tx) updates column tx, rows k+1+ty, +8, ...; row k stays unscaled
+    const int tx = tid & 63, ty = tid >> 6;
+    for (int k = 0; k < r; ++k) {
+        double p = Gs[k][k];
+        if (!(p > 0.0)) {                       // zero or non-finite input
+            if (tid == 0 && s_bad == 0) s_bad = k + 1;
+            p = 1.0;
+        }
+        if (tx > k && tx < r) {
+            const double f = Gs[k][tx] / p;
+            for (int ga = k + 1 + ty; ga <= tx; ga += 8) Gs[ga][tx] = fma(-Gs[k][ga], f, Gs[ga][tx]);
+        }
+        __syncthreads();
+    }
+    if (tid < r) {
+        double p = Gs[tid][tid];
+        if (!(p > 0.0)) p = 1.0;
+        const double d = sqrt(p);
+        dinv[tid] = 1.0 / d;
+        const double rd = (pass == 0 ? 1.0 : jb.scal[1 + tid]) * d;
+        rdiag[tid] = rd;
+        jb.scal[1 + tid] = rd;
+    }
+    __syncthreads();
+    for (int e = tid; e < r * r; e += 512) {
+        const int ga = e / r, gb = e - ga * r;
+        const double v = (ga < gb) ? Gs[ga][gb] * dinv[ga] : (ga == gb ? 1.0 / dinv[ga] : 0.0);
+        if (ga < gb) Gs[ga][gb] = v;
+        jb.R[e] = v;                              // R, zeros below the diagonal
+    }
+    __syncthreads();
+    // inverse of each 16x16 diagonal block: row i of X solves X R_bb = I
+    const int nb = (r + 15) / 16;
+    if (tid < nb * 16) {
+        const int b = tid >> 4, i = tid & 15, base = 16 * b;
+        double x[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            double s = (j == i) ? 1.0 : 0.0;
+#pragma unroll
+            for (int k = 0; k < j; ++k) s = fma(-x[k], (base + j < r) ? Gs[base + k][base + j] : 0.0, s);
+            x[j] = (j >= i && base + j < r && base + i < r) ? s * dinv[base + j] : 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) jb.Dinv[(b * 16 + i) * 16 + j] = x[j];
+    }
+    if (tid == 0) {
+        double bad = (pass == 0) ? 0.0 : jb.scal[65];
+        if (bad == 0.0 && s_bad) bad = (double)s_bad;
+        jb.scal[65] = bad;
+        if (last && a.info) {
+            if (bad != 0.0) flag_info(a.info, jb.mode1, (int)bad);
+            const double floor_ = 1e-12 * sqrt(s_trace);
+            for (int k = 0; k < r; ++k)
+                if (!(rdiag[k] > floor_)) { flag_info(a.info, jb.mode1, k + 1); break; }
+        }
+    }
 }
 
-// ---- global-memory path, any r <= 1024 ------------------------------------------------------
-__device__ __attribute__((noinline)) void orth_global(const OrthJob& jb, int32_t* info, double* rdiag) {
+// ---- apply ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void k_orth_apply(OrthArgs a, int final_pass) {
+    __shared__ double Ps[OP_RS][OP_LD];
+    __shared__ double Rs[OP_RMAX][OP_LD];
+    __shared__ double Ds[OP_RMAX / 16][16][17];
+    int ji, blk;
+    find_job(a, &ji, &blk);
+    const OrthJob jb = a.job[ji];
+    const int n = jb.n, r = jb.r, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
+    const int nb = (r + 15) / 16;
+    const int i0 = blk * OP_RS;
+    const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
+    for (int e = tid; e < OP_RS * OP_LD; e += 128) (&Ps[0][0])[e] = 0.0;
+    for (int e = tid; e < OP_RMAX * OP_LD; e += 128) (&Rs[0][0])[e] = 0.0;
+    __syncthreads();
+    for (int idx0 = 0; idx0 < nrows * r; idx0 += 128 * 8) {
+        double t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = idx0 + u * 128 + tid;
+            t[u] = (idx < nrows * r) ? jb.P64[(long long)i0 * r + idx] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = idx0 + u * 128 + tid;
+            if (idx < nrows * r) Ps[idx / r][idx % r] = t[u];
+        }
+    }
+    for (int e0 = 0; e0 < r * r; e0 += 128 * 8) {
+        double t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e = e0 + u * 128 + tid;
+            t[u] = (e < r * r) ? jb.R[e] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e = e0 + u * 128 + tid;
+            if (e < r * r) Rs[e / r][e % r] = t[u];
+        }
+    }
+    for (int e = tid; e < nb * 256; e += 128) Ds[e >> 8][(e >> 4) & 15][e & 15] = jb.Dinv[e];
+    __syncthreads();
+    // wave w owns rows 16w..16w+15 of the slice; block columns are solved left to right
+    const int rw = 16 * wave;
+    for (int b = 0; b < nb; ++b) {
+        // T = P_b - sum_{a<b} Q_a R_ab
+        v4d acc = {0.0, 0.0, 0.0, 0.0};
+        for (int ab = 0; ab < b; ++ab)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[rw + ll][16 * ab + 4 * ks + lg],
+                                                           Rs[16 * ab + 4 * ks + lg][16 * b + ll], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Ps[rw + lg + 4 * v][16 * b + ll] -= acc[v];
+        __syncthreads();
+        // Q_b = T R_bb^-1
+        v4d q = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            q = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[rw + ll][16 * b + 4 * ks + lg], Ds[b][4 * ks + lg][ll], q, 0, 0, 0);
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Ps[rw + lg + 4 * v][16 * b + ll] = q[v];
+        __syncthreads();
+    }
+    if (final_pass) {
+        for (int idx = tid; idx < nrows * r; idx += 128) jb.Uout[(long long)i0 * r + idx] = (float)Ps[idx / r][idx % r];
+    } else {
+        for (int idx = tid; idx < nrows * r; idx += 128) jb.P64[(long long)i0 * r + idx] = Ps[idx / r][idx % r];
+        gram_from_lds(Ps, r, jb.Gpart + (long long)blk * r * r);
+    }
+}
+
+// ---- slow path: one workgroup per mode, global memory, three passes ---------------------------
+constexpr int ORTH_NT = 512;
+constexpr int ORTH_MAXR = 1024;
+
+__global__ __launch_bounds__(ORTH_NT) void k_orth_big(OrthArgs a) {
+    __shared__ double rdiag[ORTH_MAXR];
+    __shared__ double s_inv;
+    __shared__ double s_trace2;
+    const OrthJob jb = a.job[blockIdx.x];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     double* __restrict__ P = jb.P64;
     double* __restrict__ G = jb.G;
-    __shared__ double s_inv;
-    __shared__ double s_trace2;
+    int32_t* info = a.info;
+    const long long cnt = (long long)n * r;
+    for (long long e = tid; e < cnt; e += ORTH_NT) {
+        double s = 0.0;
+        for (int sp0 = 0; sp0 < jb.nsplit; sp0 += 8) {
+            double t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = (sp0 + u < jb.nsplit) ? jb.part[(long long)(sp0 + u) * cnt + e] : 0.0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += t[u];
+        }
+        P[e] = s;
+    }
     for (int k = tid; k < r; k += ORTH_NT) rdiag[k] = 1.0;
     __syncthreads();
     for (int pass = 0; pass < 3; ++pass) {
@@ -215,7 +307,7 @@ __device__ __attribute__((noinline)) void orth_global(const OrthJob& jb, int32_t
                 s_trace2 = tr;
             }
             __syncthreads();
-            const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * 1.1102230246251565e-16 * s_trace2;
+            const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * s_trace2;
             for (int k = tid; k < r; k += ORTH_NT) G[k * r + k] += shift;
             __syncthreads();
         }
@@ -256,80 +348,55 @@ __device__ __attribute__((noinline)) void orth_global(const OrthJob& jb, int32_t
         for (int k = 0; k < r; ++k)
             if (!(rdiag[k] > floor_)) { flag_info(info, jb.mode1, k + 1); break; }
     }
-    const long long cnt = (long long)n * r;
     for (long long e = tid; e < cnt; e += ORTH_NT) jb.Uout[e] = (float)P[e];
 }
 
-__global__ __launch_bounds__(ORTH_NT) void k_orth(OrthArgs a) {
-    __shared__ double Gs[ORTH_RMAX][ORTH_LD];      // 33 KB
-    __shared__ double stage[ORTH_STAGE * 256];     // 20 KB: Gram blocks per work item
-    __shared__ double dinv[ORTH_RMAX];
-    __shared__ double rdiag[ORTH_MAXR];            // running product of the R diagonals
-    __shared__ int s_last;
-    int ji = 0, blk = blockIdx.x;
-    while (ji + 1 < a.njobs && blk >= a.job[ji].nred) { blk -= a.job[ji].nred; ++ji; }
-    const OrthJob jb = a.job[ji];
-    const int tid = threadIdx.x;
+// ---- host side -------------------------------------------------------------------------------
+bool orth_fast_supported(int r) { return r <= OP_RMAX; }
+int orth_slices(int n) { return (n + OP_RS - 1) / OP_RS; }
 
-    // sum this block's slice of the split partial sums
-    STAMP(0);
-    const long long cnt = (long long)jb.n * jb.r;
-    const long long per = (cnt + jb.nred - 1) / jb.nred;
-    const long long e0 = blk * per, e1 = (e0 + per < cnt) ? e0 + per : cnt;
-    for (long long e = e0 + tid; e < e1; e += ORTH_NT) {
-        double s = 0.0;
-        for (int sp = 0; sp < jb.nsplit; ++sp) s += jb.part[(long long)sp * cnt + e];
-        jb.P64[e] = s;
-    }
-    if (jb.nred > 1) {
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) s_last = (atomicAdd(jb.counter, 1) == jb.nred - 1);
-        __syncthreads();
-        if (!s_last) return;
-        __threadfence();
-    } else {
-        __syncthreads();
-    }
-    if (jb.r <= ORTH_RMAX) orth_lds(jb, a.info, Gs, stage, dinv, rdiag);
-    else orth_global(jb, a.info, rdiag);
+static int total_blocks(const OrthArgs& a) {
+    int t = 0;
+    for (int j = 0; j < a.njobs; ++j) t += a.job[j].nblk;
+    return t;
 }
-
-int orth_reduce_blocks(int nsplit, int n, int r) {
-    const long long work = (long long)nsplit * n * r;      // partial elements to read
-    long long nb = (work + (1 << 16) - 1) >> 16;           // ~64K elements per block
-    const long long cnt = (long long)n * r;
-    if (nb > (cnt + 255) / 256) nb = (cnt + 255) / 256;    // at least 256 outputs per block
-    if (nb > 64) nb = 64;
-    if (nb < 1) nb = 1;
-    return (int)nb;
-}
-
-hipError_t launch_orth(const OrthArgs& a, hipStream_t st) {
-    if (a.njobs <= 0 || a.njobs > 4) return hipErrorInvalidValue;
-    int total = 0;
+static bool fast_args_ok(const OrthArgs& a) {
+    if (a.njobs <= 0 || a.njobs > 4) return false;
     for (int j = 0; j < a.njobs; ++j) {
-        if (a.job[j].nred < 1 || a.job[j].r > ORTH_MAXR) return hipErrorInvalidValue;
-        if (a.job[j].nred > 1 && !a.job[j].counter) return hipErrorInvalidValue;
-        total += a.job[j].nred;
+        const OrthJob& jb = a.job[j];
+        if (jb.n <= 0 || jb.r <= 0 || jb.r > OP_RMAX || jb.nblk != orth_slices(jb.n)) return false;
+        if (!jb.Gpart || !jb.R || !jb.Dinv || !jb.scal || !jb.P64 || !jb.Uout || !jb.part) return false;
     }
-    hipLaunchKernelGGL(k_orth, dim3(total), ORTH_NT, 0, st, a);
+    return true;
+}
+hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st) {
+    if (!fast_args_ok(a)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_orth_gram0, dim3(total_blocks(a)), 128, 0, st, a);
+    return hipGetLastError();
+}
+hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t st) {
+    if (!fast_args_ok(a)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_orth_chol, dim3(a.njobs), 512, 0, st, a, pass, last);
+    return hipGetLastError();
+}
+hipError_t launch_orth_apply(const OrthArgs& a, int final_pass, hipStream_t st) {
+    if (!fast_args_ok(a)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_orth_apply, dim3(total_blocks(a)), 128, 0, st, a, final_pass);
+    return hipGetLastError();
+}
+hipError_t launch_orth_big(const OrthArgs& a, hipStream_t st) {
+    if (a.njobs <= 0 || a.njobs > 4) return hipErrorInvalidValue;
+    for (int j = 0; j < a.njobs; ++j)
+        if (a.job[j].r > ORTH_MAXR || !a.job[j].G || !a.job[j].P64) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_orth_big, dim3(a.njobs), ORTH_NT, 0, st, a);
     return hipGetLastError();
 }
 
-__global__ void k_init_ctrl(int32_t* info, int* counters, int ncounters) {
-    const int t = threadIdx.x;
-    if (t == 0 && info) *info = 0;
-    if (t < ncounters) counters[t] = 0;
+__global__ void k_init_ctrl(int32_t* info) {
+    if (threadIdx.x == 0 && info) *info = 0;
 }
-#ifdef ASI_DEBUG_TIMING
-extern "C" int asi_debug_orth_stamps(long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_orth_stamps), sizeof(long long) * 64);
-}
-#endif
-
-hipError_t launch_init_ctrl(int32_t* info, int* counters, int ncounters, hipStream_t st) {
-    hipLaunchKernelGGL(k_init_ctrl, 1, 64, 0, st, info, counters, ncounters);
+hipError_t launch_init_ctrl(int32_t* info, hipStream_t st) {
+    hipLaunchKernelGGL(k_init_ctrl, 1, 64, 0, st, info);
     return hipGetLastError();
 }
 
