@@ -43,7 +43,8 @@ __device__ __forceinline__ void find_job(const OrthArgs& a, int* ji, int* blk) {
 __device__ void gram_from_lds(const double (*Ps)[OP_LD], int r, double* __restrict__ Gout) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lg = lane >> 4, ll = lane & 15;
     const int nb = (r + 15) / 16, npairs = nb * (nb + 1) / 2;
-    for (int pr = wave; pr < npairs; pr += 2) {
+    const int nwaves = blockDim.x >> 6;
+    for (int pr = wave; pr < npairs; pr += nwaves) {
         int ab = 0, rem = pr;
         while (rem >= nb - ab) { rem -= nb - ab; ++ab; }
         const int bb = ab + rem;
@@ -61,8 +62,9 @@ __device__ void gram_from_lds(const double (*Ps)[OP_LD], int r, double* __restri
 }
 
 // ---- gram0 ----------------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void k_orth_gram0(OrthArgs a) {
+__global__ __launch_bounds__(256) void k_orth_gram0(OrthArgs a) {
     __shared__ double Ps[OP_RS][OP_LD];
+    __shared__ double red[256];
     int ji, blk;
     find_job(a, &ji, &blk);
     const OrthJob jb = a.job[ji];
@@ -70,20 +72,42 @@ __global__ __launch_bounds__(128) void k_orth_gram0(OrthArgs a) {
     const int i0 = blk * OP_RS;
     const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
     const long long cnt = (long long)n * r;
-    for (int e = tid; e < OP_RS * OP_LD; e += 128) (&Ps[0][0])[e] = 0.0;
+    const int E = nrows * r;
+    for (int e = tid; e < OP_RS * OP_LD; e += 256) (&Ps[0][0])[e] = 0.0;
     __syncthreads();
-    for (int idx = tid; idx < nrows * r; idx += 128) {
+    // sum of the split partial sums, 8 loads in flight; a small slice shares its splits among
+    // `nsg` thread groups whose results are added in group order
+    const int nsg = (E < 256) ? 256 / E : 1;
+    const int sg = (E < 256) ? tid / E : 0;
+    for (int idx0 = 0; idx0 < E; idx0 += 256) {
+        const int idx = (E < 256) ? tid - sg * E : idx0 + tid;
+        const bool act = idx < E && sg < nsg;
         const long long e = (long long)i0 * r + idx;
         double s = 0.0;
-        for (int sp0 = 0; sp0 < jb.nsplit; sp0 += 8) {          // 8 loads in flight
-            double t[8];
+        if (act) {
+            for (int sp0 = sg; sp0 < jb.nsplit; sp0 += 8 * nsg) {
+                double t[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) t[u] = (sp0 + u < jb.nsplit) ? jb.part[(long long)(sp0 + u) * cnt + e] : 0.0;
+                for (int u = 0; u < 8; ++u) {
+                    const int sp = sp0 + u * nsg;
+                    t[u] = (sp < jb.nsplit) ? jb.part[(long long)sp * cnt + e] : 0.0;
+                }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) s += t[u];
+                for (int u = 0; u < 8; ++u) s += t[u];
+            }
         }
-        jb.P64[e] = s;
-        Ps[idx / r][idx % r] = s;
+        if (nsg > 1) {
+            if (act) red[sg * E + idx] = s;
+            __syncthreads();
+            if (act && sg == 0) {
+                s = 0.0;
+                for (int g2 = 0; g2 < nsg; ++g2) s += red[g2 * E + idx];
+            }
+        }
+        if (act && sg == 0) {
+            jb.P64[e] = s;
+            Ps[idx / r][idx % r] = s;
+        }
     }
     __syncthreads();
     gram_from_lds(Ps, r, jb.Gpart + (long long)blk * r * r);
@@ -138,7 +162,10 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
             p = 1.0;
         }
         if (tx > k && tx < r) {
-            const double f = Gs[k][tx] / p;
+            double pinv = __builtin_amdgcn_rcp(p);
+            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);      // two Newton steps: full fp64 accuracy
+            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
+            const double f = Gs[k][tx] * pinv;
             for (int ga = k + 1 + ty; ga <= tx; ga += 8) Gs[ga][tx] = fma(-Gs[k][ga], f, Gs[ga][tx]);
         }
         __syncthreads();
@@ -371,7 +398,7 @@ static bool fast_args_ok(const OrthArgs& a) {
 }
 hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st) {
     if (!fast_args_ok(a)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_orth_gram0, dim3(total_blocks(a)), 128, 0, st, a);
+    hipLaunchKernelGGL(k_orth_gram0, dim3(total_blocks(a)), 256, 0, st, a);
     return hipGetLastError();
 }
 hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t st) {
