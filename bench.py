@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload (1-5), default the ResNet-18 tail")
     ap.add_argument("--distinct", type=int, default=8, help="distinct input steps kept in HBM and cycled")
+    ap.add_argument("--streams", type=int, default=0, help="HIP streams the layers are spread over (0 = one per layer)")
+    ap.add_argument("--graph", type=int, default=1, help="replay each step from a captured HIP graph (1) or launch eagerly (0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
@@ -94,6 +96,8 @@ def main():
     streams = [LayerStream(cfg.index, li, lay, cfg.theta) for li, lay in enumerate(cfg.layers)]
     runners = [LayerRunner(lay) for lay in cfg.layers]
     ndist = max(1, min(args.distinct, cfg.steps if cfg.steps > 1 else args.distinct))
+    if args.graph and ndist > 1:
+        ndist -= ndist % 2          # the captured steps alternate the two factor buffers
 
     # inputs resident in HBM before any timing: `ndist` consecutive steps of the drifting sequence
     A_dev, dY_dev = [], []
@@ -105,19 +109,55 @@ def main():
         r.set_factors(st.u_prev0())
     act_bytes = sum(lay.act_bytes for lay in cfg.layers)
 
+    # The layers of one step are independent jobs: each gets its own workspace and they are
+    # spread over side streams (default priority) that fork from / join the main stream.
+    nstreams = len(runners) if args.streams <= 0 else min(args.streams, len(runners))
+    main_stream = torch.cuda.current_stream()
+    side = [torch.cuda.Stream() for _ in range(nstreams)] if nstreams > 1 else [None]
+
     def one_step(k):
         a, g = A_dev[k % ndist], dY_dev[k % ndist]
-        for r, at, gt in zip(runners, a, g):
-            r.step(at, gt)
+        cur = torch.cuda.current_stream()
+        if nstreams > 1:
+            for s in side:
+                s.wait_stream(cur)
+        for li, (r, at, gt) in enumerate(zip(runners, a, g)):
+            with torch.cuda.stream(side[li % nstreams] if nstreams > 1 else cur):
+                r.step(at, gt)
+        if nstreams > 1:
+            for s in side:
+                cur.wait_stream(s)
+
+    # optional: one captured HIP graph per distinct input step, replayed in the timed loop
+    graphs = None
+    if args.graph:
+        one_step(0)
+        torch.cuda.synchronize()
+        graphs = []
+        cap = torch.cuda.Stream()
+        for k in range(ndist):
+            g_ = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(cap):
+                g_.capture_begin()
+                one_step(k)
+                g_.capture_end()
+            graphs.append(g_)
+        torch.cuda.synchronize()
+
+    def run_step(k):
+        if graphs is not None:
+            graphs[k % ndist].replay()
+        else:
+            one_step(k)
 
     for k in range(args.warmup):
-        one_step(k)
+        run_step(k)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for k in range(args.steps):
-        one_step(args.warmup + k)
+        run_step(args.warmup + k)
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -128,10 +168,13 @@ def main():
     value = act_bytes / (ms_per_step * 1e-3) / 1e9
 
     # per-kernel pass: same steps with every launch bracketed by HIP events on its stream
+    # (eager, one stream, so that no two kernels overlap and each duration is its own)
     asi.asi_profile_enable(True)
     nprof = min(args.steps, 10)
     for k in range(nprof):
-        one_step(args.warmup + args.steps + k)
+        a_, g_ = A_dev[k % ndist], dY_dev[k % ndist]
+        for r, at, gt in zip(runners, a_, g_):
+            r.step(at, gt)
     torch.cuda.synchronize()
     rep = asi.asi_profile_report()
     asi.asi_profile_enable(False)
@@ -173,7 +216,8 @@ def main():
         "config": {"workload": f"config {cfg.index} ({cfg.name}): " + ", ".join(
             f"{'x'.join(map(str, l.dims))} r{'/'.join(map(str, l.ranks))}" for l in cfg.layers),
             "layers": len(cfg.layers), "raw_activation_bytes_per_step": act_bytes,
-            "distinct_input_steps_in_hbm": ndist, "phases": "compress+core_project+weight_grad"},
+            "distinct_input_steps_in_hbm": ndist, "phases": "compress+core_project+weight_grad",
+            "streams": nstreams, "hip_graph": bool(args.graph)},
         "roofline": roof,
         "kernel_breakdown": breakdown,
         "gpu_ms_per_step_events": gpu_ms / args.steps,

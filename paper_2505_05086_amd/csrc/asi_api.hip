@@ -72,6 +72,8 @@ bool parse_desc(const asi_tensor_desc* desc, Shape* s, asi_status* why) {
 struct CompressPlan {
     float* V = nullptr;
     double* part[4] = {};
+    double* part2[4] = {};          // first level of the partial-sum tree (nsplit > 32)
+    int nsplit2[4] = {};
     double* P64[4] = {};
     double* G[4] = {};
     double* Gpart[4] = {};
@@ -81,6 +83,7 @@ struct CompressPlan {
     int nsplit[4] = {};
     int nblk[4] = {};
     bool fused[4] = {};
+    bool paired = false;             // the last two modes of a 4-mode tensor share one kernel
     bool fast_orth[4] = {};
     size_t bytes = 0;
 };
@@ -94,11 +97,17 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
         if (!p.fused[m]) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
     }
     p.V = c.take<float>(vmax);
+    p.paired = s.d == 4 && subspace_pair_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
     for (int m = 0; m < s.d; ++m) {
         const size_t n = (size_t)s.n[m], r = (size_t)s.r[m];
-        p.nsplit[m] = p.fused[m] ? subspace_small_nwg(s.outer(m), (int)n, s.inner(m))
-                                 : pair_splits(s.outer(m), (int)n, s.inner(m), (int)r);
+        if (p.paired && m >= 2) p.nsplit[m] = subspace_pair_nwg(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3]);
+        else p.nsplit[m] = p.fused[m] ? subspace_small_nwg(s.outer(m), (int)n, s.inner(m))
+                                      : pair_splits(s.outer(m), (int)n, s.inner(m), (int)r);
         p.part[m] = c.take<double>((size_t)p.nsplit[m] * n * r);
+        if (p.nsplit[m] > 32) {
+            p.nsplit2[m] = (p.nsplit[m] + 31) / 32;
+            p.part2[m] = c.take<double>((size_t)p.nsplit2[m] * n * r);
+        }
         p.P64[m] = c.take<double>(n * r);
         p.fast_orth[m] = orth_fast_supported((int)r);
         if (p.fast_orth[m]) {
@@ -369,11 +378,22 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
     std::memset(&fast, 0, sizeof(fast));
     std::memset(&slow, 0, sizeof(slow));
     fast.info = slow.info = info;
-    double fast_b = 0, fast_f = 0, slow_b = 0, slow_f = 0;
+    PresumArgs pre;
+    std::memset(&pre, 0, sizeof(pre));
+    double fast_b = 0, fast_f = 0, slow_b = 0, slow_f = 0, pre_b = 0;
     for (int m = 0; m < s.d; ++m) {
         const long long outer = s.outer(m), inner = s.inner(m);
         const int n = (int)s.n[m], r = s.r[m];
-        if (p.fused[m]) {
+        if (p.paired && m == 2) {
+            // H and W modes: both subspace steps from one read of the activation's planes
+            const double tot = (double)s.numel;
+            ProfScope ps("k_subspace_small", tot * esize(s.dt) + 8.0 * (n * r + (double)s.n[3] * s.r[3]) * p.nsplit[m],
+                         4.0 * tot * (r + s.r[3]), st);
+            ASI_TRY(launch_subspace_pair(s.dt, A, s.n[0] * s.n[1], n, (int)s.n[3], U_prev[2], r, p.part[2], U_prev[3],
+                                         s.r[3], p.part[3], p.nsplit[m], st));
+        } else if (p.paired && m == 3) {
+            // done together with mode 3
+        } else if (p.fused[m]) {
             // short fibres: V and P from one LDS tile of complete fibres, V never stored
             const double cols = (double)outer * (double)inner;
             ProfScope ps("k_subspace_small", cols * n * esize(s.dt) + 4.0 * n * r + 8.0 * n * r * p.nsplit[m],
@@ -388,11 +408,22 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
         OrthArgs& oa = p.fast_orth[m] ? fast : slow;
         OrthJob& j = oa.job[oa.njobs++];
         j.part = p.part[m]; j.nsplit = p.nsplit[m]; j.n = n; j.r = r;
+        if (p.part2[m]) {
+            PresumJob& pj = pre.job[pre.njobs++];
+            pj.in = p.part[m]; pj.out = p.part2[m]; pj.cnt = (long long)n * r; pj.nsplit = p.nsplit[m];
+            pj.nchunks = (int)((pj.cnt + 255) / 256); pj.ngroups = p.nsplit2[m];
+            pre_b += 8.0 * n * r * (p.nsplit[m] + p.nsplit2[m]);
+            j.part = p.part2[m]; j.nsplit = p.nsplit2[m];
+        }
         j.P64 = p.P64[m]; j.Uout = U_out[m]; j.mode1 = m + 1;
         j.nblk = p.nblk[m]; j.Gpart = p.Gpart[m]; j.R = p.R[m]; j.Dinv = p.Dinv[m]; j.scal = p.scal[m];
         j.G = p.G[m];
         (p.fast_orth[m] ? fast_b : slow_b) += 8.0 * n * r;
         (p.fast_orth[m] ? fast_f : slow_f) += 2.0 * (double)n * r * r;
+    }
+    if (pre.njobs) {
+        ProfScope ps("k_orth_presum", pre_b, pre_b / 8.0, st);
+        ASI_TRY(launch_orth_presum(pre, st));
     }
     if (fast.njobs) {
         // Orthogonalize: shifted Cholesky-QR, then one plain Cholesky-QR pass

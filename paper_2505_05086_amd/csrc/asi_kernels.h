@@ -31,6 +31,12 @@ bool subspace_small_supported(int n, int r);
 int subspace_small_nwg(long long outer, int n, long long inner);
 hipError_t launch_subspace_small(DType xt, const void* X, long long outer, int n, long long inner, const float* U,
                                  int r, double* part, int nwg, hipStream_t st);
+// The last two modes of X seen as (planes, rows, cols), both from one read of X.
+bool subspace_pair_supported(int rows, int cols, int r_rows, int r_cols);
+int subspace_pair_nwg(long long planes, int rows, int cols);
+hipError_t launch_subspace_pair(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows,
+                                int r_rows, double* part_rows, const float* U_cols, int r_cols, double* part_cols,
+                                int nwg, hipStream_t st);
 
 struct OrthJob {
     const double* part;  // (nsplit, n, r) partial sums of P
@@ -53,6 +59,17 @@ struct OrthArgs {
     int njobs;
     int32_t* info;       // nullable
 };
+struct PresumJob {
+    const double* in;    // (nsplit, cnt)
+    double* out;         // (ngroups, cnt), ngroups = ceil(nsplit / 32)
+    long long cnt;
+    int nsplit, nchunks, ngroups;   // nchunks = ceil(cnt / 256)
+};
+struct PresumArgs {
+    PresumJob job[4];
+    int njobs;
+};
+hipError_t launch_orth_presum(const PresumArgs& a, hipStream_t st);
 bool orth_fast_supported(int r);
 int orth_slices(int n);
 hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st);

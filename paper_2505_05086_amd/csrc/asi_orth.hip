@@ -29,6 +29,16 @@ constexpr int OP_RMAX = 64;
 constexpr int OP_LD = OP_RMAX + 1;
 constexpr double OP_EPS = 1.1102230246251565e-16;
 
+#ifdef ASI_DEBUG_TIMING
+__device__ long long g_orth_stamps[64];
+#define STAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 2 && pass == 0) g_orth_stamps[i] = wall_clock64(); } while (0)
+extern "C" int asi_debug_orth_stamps(long long* out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_orth_stamps), sizeof(long long) * 64);
+}
+#else
+#define STAMP(i) do {} while (0)
+#endif
+
 __device__ __forceinline__ void flag_info(int32_t* info, int mode1, int col1) {
     if (info) atomicCAS(info, 0, mode1 * 1000 + col1);
 }
@@ -61,6 +71,39 @@ __device__ void gram_from_lds(const double (*Ps)[OP_LD], int r, double* __restri
     }
 }
 
+// ---- first level of the partial-sum tree -----------------------------------------------------
+// When a mode arrives with more than 32 split partial sums, groups of 32 are added first
+// (fixed order inside a group), so that no workgroup of gram0 has to walk hundreds of them.
+__global__ __launch_bounds__(256) void k_orth_presum(PresumArgs a) {
+    int j = 0, b = blockIdx.x;
+    while (j + 1 < a.njobs && b >= a.job[j].nchunks * a.job[j].ngroups) { b -= a.job[j].nchunks * a.job[j].ngroups; ++j; }
+    const PresumJob jb = a.job[j];
+    const int g = b / jb.nchunks, chunk = b - g * jb.nchunks;
+    const long long e = (long long)chunk * 256 + threadIdx.x;
+    if (e >= jb.cnt) return;
+    const int s0 = g * 32;
+    double t[32];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) t[u] = (s0 + u < jb.nsplit) ? jb.in[(long long)(s0 + u) * jb.cnt + e] : 0.0;
+    double s = 0.0;
+#pragma unroll
+    for (int u = 0; u < 32; ++u) s += t[u];
+    jb.out[(long long)g * jb.cnt + e] = s;
+}
+
+hipError_t launch_orth_presum(const PresumArgs& a, hipStream_t st) {
+    if (a.njobs <= 0 || a.njobs > 4) return hipErrorInvalidValue;
+    long long blocks = 0;
+    for (int j = 0; j < a.njobs; ++j) {
+        const PresumJob& jb = a.job[j];
+        if (!jb.in || !jb.out || jb.cnt <= 0 || jb.nsplit <= 0) return hipErrorInvalidValue;
+        if (jb.nchunks != (int)((jb.cnt + 255) / 256) || jb.ngroups != (jb.nsplit + 31) / 32) return hipErrorInvalidValue;
+        blocks += (long long)jb.nchunks * jb.ngroups;
+    }
+    hipLaunchKernelGGL(k_orth_presum, dim3((unsigned)blocks), 256, 0, st, a);
+    return hipGetLastError();
+}
+
 // ---- gram0 ----------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_orth_gram0(OrthArgs a) {
     __shared__ double Ps[OP_RS][OP_LD];
@@ -85,15 +128,15 @@ __global__ __launch_bounds__(256) void k_orth_gram0(OrthArgs a) {
         const long long e = (long long)i0 * r + idx;
         double s = 0.0;
         if (act) {
-            for (int sp0 = sg; sp0 < jb.nsplit; sp0 += 8 * nsg) {
-                double t[8];
+            for (int sp0 = sg; sp0 < jb.nsplit; sp0 += 16 * nsg) {      // 16 loads in flight
+                double t[16];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < 16; ++u) {
                     const int sp = sp0 + u * nsg;
                     t[u] = (sp < jb.nsplit) ? jb.part[(long long)sp * cnt + e] : 0.0;
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) s += t[u];
+                for (int u = 0; u < 16; ++u) s += t[u];
             }
         }
         if (nsg > 1) {
@@ -124,6 +167,7 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
     const OrthJob jb = a.job[blockIdx.x];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     if (tid == 0) s_bad = 0;
+    STAMP(0);
     for (int e = tid; e < r * r; e += 512) {
         const int ga = e / r, gb = e - ga * r;
         if (ga <= gb) {
@@ -139,6 +183,7 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
         }
     }
     __syncthreads();
+    STAMP(1);
     if (pass == 0) {
         if (tid == 0) {
             double tr = 0.0;
@@ -153,6 +198,7 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
     } else if (tid == 0) {
         s_trace = jb.scal[0];
     }
+    STAMP(2);
     // right-looking Cholesky; thread (ty, tx) updates column tx, rows k+1+ty, +8, ...; row k stays unscaled
     const int tx = tid & 63, ty = tid >> 6;
     for (int k = 0; k < r; ++k) {
@@ -166,10 +212,24 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
             pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);      // two Newton steps: full fp64 accuracy
             pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
             const double f = Gs[k][tx] * pinv;
-            for (int ga = k + 1 + ty; ga <= tx; ga += 8) Gs[ga][tx] = fma(-Gs[k][ga], f, Gs[ga][tx]);
+            // rows k+1+ty, +8, ... <= tx (at most 8): all loads first, then the updates
+            double gk[8], gg[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int ga = k + 1 + ty + 8 * u;
+                const bool ok = ga <= tx;
+                gk[u] = ok ? Gs[k][ga] : 0.0;
+                gg[u] = ok ? Gs[ga][tx] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int ga = k + 1 + ty + 8 * u;
+                if (ga <= tx) Gs[ga][tx] = fma(-gk[u], f, gg[u]);
+            }
         }
         __syncthreads();
     }
+    STAMP(3);
     if (tid < r) {
         double p = Gs[tid][tid];
         if (!(p > 0.0)) p = 1.0;
@@ -187,6 +247,7 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
         jb.R[e] = v;                              // R, zeros below the diagonal
     }
     __syncthreads();
+    STAMP(4);
     // inverse of each 16x16 diagonal block: row i of X solves X R_bb = I
     const int nb = (r + 15) / 16;
     if (tid < nb * 16) {
@@ -202,6 +263,7 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
 #pragma unroll
         for (int j = 0; j < 16; ++j) jb.Dinv[(b * 16 + i) * 16 + j] = x[j];
     }
+    STAMP(5);
     if (tid == 0) {
         double bad = (pass == 0) ? 0.0 : jb.scal[65];
         if (bad == 0.0 && s_bad) bad = (double)s_bad;
