@@ -85,6 +85,7 @@ struct CompressPlan {
     bool fused[4] = {};
     bool paired = false;             // the last two modes of a 4-mode tensor share one kernel
     bool fast_orth[4] = {};
+    bool wide_orth[4] = {};
     size_t bytes = 0;
 };
 
@@ -116,6 +117,13 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
             p.R[m] = c.take<double>(r * r);
             p.Dinv[m] = c.take<double>(((r + 15) / 16) * 256);
             p.scal[m] = c.take<double>(66);
+        } else if (orth_wide_supported((int)r)) {
+            p.wide_orth[m] = true;
+            p.nblk[m] = orth_wide_gram_blocks((int)n);
+            p.Gpart[m] = c.take<double>((size_t)p.nblk[m] * r * r);
+            p.R[m] = c.take<double>(r * r);
+            p.Dinv[m] = c.take<double>(((r + 15) / 16) * 256);
+            p.scal[m] = c.take<double>(200);
         } else {
             p.G[m] = c.take<double>(r * r);
         }
@@ -374,10 +382,14 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     if (info) ASI_TRY(launch_init_ctrl(info, st));
-    OrthArgs fast, slow;
+    OrthArgs fast, wide, slow;
     std::memset(&fast, 0, sizeof(fast));
+    std::memset(&wide, 0, sizeof(wide));
     std::memset(&slow, 0, sizeof(slow));
-    fast.info = slow.info = info;
+    fast.info = wide.info = slow.info = info;
+    PresumArgs pre2;                 // second tree level: wide modes need the finished sum in P64
+    std::memset(&pre2, 0, sizeof(pre2));
+    double wide_b = 0, wide_f = 0, pre2_b = 0;
     PresumArgs pre;
     std::memset(&pre, 0, sizeof(pre));
     double fast_b = 0, fast_f = 0, slow_b = 0, slow_f = 0, pre_b = 0;
@@ -405,7 +417,7 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
             // P = A_m V, split over the unfolding's columns
             ASI_TRY(pair("k_pair:P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], st));
         }
-        OrthArgs& oa = p.fast_orth[m] ? fast : slow;
+        OrthArgs& oa = p.fast_orth[m] ? fast : (p.wide_orth[m] ? wide : slow);
         OrthJob& j = oa.job[oa.njobs++];
         j.part = p.part[m]; j.nsplit = p.nsplit[m]; j.n = n; j.r = r;
         if (p.part2[m]) {
@@ -418,8 +430,14 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
         j.P64 = p.P64[m]; j.Uout = U_out[m]; j.mode1 = m + 1;
         j.nblk = p.nblk[m]; j.Gpart = p.Gpart[m]; j.R = p.R[m]; j.Dinv = p.Dinv[m]; j.scal = p.scal[m];
         j.G = p.G[m];
-        (p.fast_orth[m] ? fast_b : slow_b) += 8.0 * n * r;
-        (p.fast_orth[m] ? fast_f : slow_f) += 2.0 * (double)n * r * r;
+        if (p.wide_orth[m]) {
+            PresumJob& pj = pre2.job[pre2.njobs++];
+            pj.in = j.part; pj.out = p.P64[m]; pj.cnt = (long long)n * r; pj.nsplit = j.nsplit;
+            pj.nchunks = (int)((pj.cnt + 255) / 256); pj.ngroups = 1;
+            pre2_b += 8.0 * n * r * (j.nsplit + 1);
+        }
+        (p.fast_orth[m] ? fast_b : (p.wide_orth[m] ? wide_b : slow_b)) += 8.0 * n * r;
+        (p.fast_orth[m] ? fast_f : (p.wide_orth[m] ? wide_f : slow_f)) += 2.0 * (double)n * r * r;
     }
     if (pre.njobs) {
         ProfScope ps("k_orth_presum", pre_b, pre_b / 8.0, st);
@@ -432,6 +450,15 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
         { ProfScope ps("k_orth_apply", 2 * fast_b, 2 * fast_f, st); ASI_TRY(launch_orth_apply(fast, 0, st)); }
         { ProfScope ps("k_orth_chol", 0, 0, st); ASI_TRY(launch_orth_chol(fast, 1, 1, st)); }
         { ProfScope ps("k_orth_apply", 1.5 * fast_b, fast_f, st); ASI_TRY(launch_orth_apply(fast, 1, st)); }
+    }
+    if (wide.njobs) {
+        { ProfScope ps("k_orth_presum", pre2_b, pre2_b / 8.0, st); ASI_TRY(launch_orth_presum(pre2, st)); }
+        { ProfScope ps("k_orthw_gram", wide_b, wide_f, st); ASI_TRY(launch_orthw_gram(wide, st)); }
+        { ProfScope ps("k_orthw_chol", 0, 0, st); ASI_TRY(launch_orthw_chol(wide, 0, 0, st)); }
+        { ProfScope ps("k_orthw_apply", 2 * wide_b, wide_f, st); ASI_TRY(launch_orthw_apply(wide, 0, st)); }
+        { ProfScope ps("k_orthw_gram", wide_b, wide_f, st); ASI_TRY(launch_orthw_gram(wide, st)); }
+        { ProfScope ps("k_orthw_chol", 0, 0, st); ASI_TRY(launch_orthw_chol(wide, 1, 1, st)); }
+        { ProfScope ps("k_orthw_apply", 1.5 * wide_b, wide_f, st); ASI_TRY(launch_orthw_apply(wide, 1, st)); }
     }
     if (slow.njobs) {
         ProfScope ps("k_orth_big", 6 * slow_b, 9 * slow_f, st);

@@ -75,6 +75,13 @@ int orth_slices(int n);
 hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st);
 hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t st);
 hipError_t launch_orth_apply(const OrthArgs& a, int final_pass, hipStream_t st);
+// wide path, 64 < r <= 192: nblk = orth_wide_gram_blocks(n), scal holds 2 + 192 doubles,
+// P64 must already hold the summed P (launch_orth_presum with a single group does that)
+bool orth_wide_supported(int r);
+int orth_wide_gram_blocks(int n);
+hipError_t launch_orthw_gram(const OrthArgs& a, hipStream_t st);
+hipError_t launch_orthw_chol(const OrthArgs& a, int pass, int last, hipStream_t st);
+hipError_t launch_orthw_apply(const OrthArgs& a, int final_pass, hipStream_t st);
 hipError_t launch_orth_big(const OrthArgs& a, hipStream_t st);
 hipError_t launch_init_ctrl(int32_t* info, hipStream_t st);   // *info = 0 if non-null
 hipError_t launch_set_i32(int32_t* p, int32_t v, hipStream_t st);

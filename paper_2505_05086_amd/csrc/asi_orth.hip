@@ -352,6 +352,273 @@ __global__ __launch_bounds__(128) void k_orth_apply(OrthArgs a, int final_pass) 
     }
 }
 
+// ---- wide path, 64 < r <= 192 -----------------------------------------------------------------
+// Same two passes.  The Gram matrix no longer fits the statically sized LDS arrays, so
+//   gramw : 128-row blocks read P64 in 32-row sub-slices and keep their block pairs in registers
+//   cholw : one workgroup per mode, Gram matrix packed (upper triangle) in up to 150 KB of
+//           dynamic LDS, same right-looking factorisation
+//   applyw: 32-row blocks, R's off-diagonal blocks are read straight from global memory
+constexpr int OW_RMAX = 192;
+constexpr int OW_LD = OW_RMAX + 1;
+constexpr int OW_ROWS = 128;            // rows per gramw block
+constexpr int OW_MAXPAIR = 20;          // block pairs per wave: ceil(78 / 4)
+
+__global__ __launch_bounds__(256) void k_orthw_gram(OrthArgs a) {
+    __shared__ double Ps[OP_RS][OW_LD];
+    int ji, blk;
+    find_job(a, &ji, &blk);
+    const OrthJob jb = a.job[ji];
+    const int n = jb.n, r = jb.r, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
+    const int nb = (r + 15) / 16, npairs = nb * (nb + 1) / 2;
+    v4d acc[OW_MAXPAIR];
+#pragma unroll
+    for (int s = 0; s < OW_MAXPAIR; ++s) acc[s] = (v4d){0.0, 0.0, 0.0, 0.0};
+    for (int e = tid; e < OP_RS * OW_LD; e += 256) (&Ps[0][0])[e] = 0.0;
+    const int row_beg = blk * OW_ROWS;
+    const int row_end = (row_beg + OW_ROWS < n) ? row_beg + OW_ROWS : n;
+    for (int i0 = row_beg; i0 < row_end; i0 += OP_RS) {
+        const int nrows = (row_end - i0 < OP_RS) ? row_end - i0 : OP_RS;
+        __syncthreads();
+        for (int idx0 = 0; idx0 < OP_RS * r; idx0 += 256 * 8) {
+            double t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = idx0 + u * 256 + tid;
+                t[u] = (idx < nrows * r) ? jb.P64[(long long)i0 * r + idx] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = idx0 + u * 256 + tid;
+                if (idx < OP_RS * r) Ps[idx / r][idx % r] = t[u];      // rows past nrows become zero
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < OW_MAXPAIR; ++s) {
+            const int pr = wave + 4 * s;
+            if (pr < npairs) {
+                int ab = 0, rem = pr;
+                while (rem >= nb - ab) { rem -= nb - ab; ++ab; }
+                const int bb = ab + rem;
+#pragma unroll
+                for (int ks = 0; ks < OP_RS / 4; ++ks)
+                    acc[s] = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[4 * ks + lg][16 * ab + ll], Ps[4 * ks + lg][16 * bb + ll],
+                                                                  acc[s], 0, 0, 0);
+            }
+        }
+    }
+    double* Gout = jb.Gpart + (long long)blk * r * r;
+#pragma unroll
+    for (int s = 0; s < OW_MAXPAIR; ++s) {
+        const int pr = wave + 4 * s;
+        if (pr < npairs) {
+            int ab = 0, rem = pr;
+            while (rem >= nb - ab) { rem -= nb - ab; ++ab; }
+            const int bb = ab + rem;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int ga = 16 * ab + lg + 4 * v, gb = 16 * bb + ll;
+                if (ga < r && gb < r && ga <= gb) Gout[ga * r + gb] = acc[s][v];
+            }
+        }
+    }
+}
+
+extern __shared__ double ow_dyn[];
+
+__global__ __launch_bounds__(1024) void k_orthw_chol(OrthArgs a, int pass, int last) {
+    const OrthJob jb = a.job[blockIdx.x];
+    const int n = jb.n, r = jb.r, tid = threadIdx.x;
+    double* Gp = ow_dyn;                              // packed upper triangle, r (r + 1) / 2
+    double* dinv = ow_dyn + (r * (r + 1)) / 2;
+    double* rdiag = dinv + r;
+    __shared__ double s_trace;
+    __shared__ int s_bad;
+    auto pidx = [r](int ga, int gb) { return ga * r - (ga * (ga - 1)) / 2 + (gb - ga); };
+    if (tid == 0) s_bad = 0;
+    for (int e = tid; e < r * r; e += 1024) {
+        const int ga = e / r, gb = e - ga * r;
+        if (ga <= gb) {
+            double s = 0.0;
+            for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
+                double t[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) t[u] = (b0 + u < jb.nblk) ? jb.Gpart[(long long)(b0 + u) * r * r + e] : 0.0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) s += t[u];
+            }
+            Gp[pidx(ga, gb)] = s;
+        }
+    }
+    __syncthreads();
+    if (pass == 0) {
+        if (tid == 0) {
+            double tr = 0.0;
+            for (int k = 0; k < r; ++k) tr += Gp[pidx(k, k)];
+            s_trace = tr;
+            jb.scal[0] = tr;
+        }
+        __syncthreads();
+        const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * s_trace;
+        if (tid < r) Gp[pidx(tid, tid)] += shift;
+        __syncthreads();
+    } else if (tid == 0) {
+        s_trace = jb.scal[0];
+    }
+    const int tx = tid & 255, ty = tid >> 8;
+    for (int k = 0; k < r; ++k) {
+        double p = Gp[pidx(k, k)];
+        if (!(p > 0.0)) {
+            if (tid == 0 && s_bad == 0) s_bad = k + 1;
+            p = 1.0;
+        }
+        if (tx > k && tx < r) {
+            double pinv = __builtin_amdgcn_rcp(p);
+            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
+            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
+            const double f = Gp[pidx(k, tx)] * pinv;
+            const int rowk = pidx(k, k) - k;          // Gp[rowk + ga] = G[k][ga]
+            for (int ga0 = k + 1 + ty; ga0 <= tx; ga0 += 32) {
+                double gk[8], gg[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int ga = ga0 + 4 * u;
+                    const bool ok = ga <= tx;
+                    gk[u] = ok ? Gp[rowk + ga] : 0.0;
+                    gg[u] = ok ? Gp[pidx(ga, tx)] : 0.0;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int ga = ga0 + 4 * u;
+                    if (ga <= tx) Gp[pidx(ga, tx)] = fma(-gk[u], f, gg[u]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (tid < r) {
+        double p = Gp[pidx(tid, tid)];
+        if (!(p > 0.0)) p = 1.0;
+        const double d = sqrt(p);
+        dinv[tid] = 1.0 / d;
+        const double rd = (pass == 0 ? 1.0 : jb.scal[1 + tid]) * d;
+        rdiag[tid] = rd;
+        jb.scal[1 + tid] = rd;
+    }
+    __syncthreads();
+    for (int e = tid; e < r * r; e += 1024) {
+        const int ga = e / r, gb = e - ga * r;
+        double v = 0.0;
+        if (ga < gb) { v = Gp[pidx(ga, gb)] * dinv[ga]; }
+        else if (ga == gb) v = 1.0 / dinv[ga];
+        jb.R[e] = v;
+    }
+    __syncthreads();
+    for (int e = tid; e < r * r; e += 1024) {      // scale in place after everyone has read the unscaled rows
+        const int ga = e / r, gb = e - ga * r;
+        if (ga < gb) Gp[pidx(ga, gb)] *= dinv[ga];
+    }
+    __syncthreads();
+    const int nb = (r + 15) / 16;
+    if (tid < nb * 16) {
+        const int b = tid >> 4, i = tid & 15, base = 16 * b;
+        double x[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            double s = (j == i) ? 1.0 : 0.0;
+#pragma unroll
+            for (int k = 0; k < j; ++k) s = fma(-x[k], (base + j < r) ? Gp[pidx(base + k, base + j)] : 0.0, s);
+            x[j] = (j >= i && base + j < r && base + i < r) ? s * dinv[base + j] : 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) jb.Dinv[(b * 16 + i) * 16 + j] = x[j];
+    }
+    if (tid == 0) {
+        double bad = (pass == 0) ? 0.0 : jb.scal[1 + OW_RMAX];
+        if (bad == 0.0 && s_bad) bad = (double)s_bad;
+        jb.scal[1 + OW_RMAX] = bad;
+        if (last && a.info) {
+            if (bad != 0.0) flag_info(a.info, jb.mode1, (int)bad);
+            const double floor_ = 1e-12 * sqrt(s_trace);
+            for (int k = 0; k < r; ++k)
+                if (!(rdiag[k] > floor_)) { flag_info(a.info, jb.mode1, k + 1); break; }
+        }
+    }
+}
+
+__global__ __launch_bounds__(128) void k_orthw_apply(OrthArgs a, int final_pass) {
+    __shared__ double Ps[OP_RS][OW_LD];
+    int ji, blk;
+    find_job(a, &ji, &blk);
+    const OrthJob jb = a.job[ji];
+    const int n = jb.n, r = jb.r, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
+    const int nb = (r + 15) / 16;
+    const int i0 = blk * OP_RS;
+    const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
+    for (int idx0 = 0; idx0 < OP_RS * OW_LD; idx0 += 128) {
+        const int e = idx0 + tid;
+        if (e < OP_RS * OW_LD) (&Ps[0][0])[e] = 0.0;
+    }
+    __syncthreads();
+    for (int idx0 = 0; idx0 < nrows * r; idx0 += 128 * 8) {
+        double t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = idx0 + u * 128 + tid;
+            t[u] = (idx < nrows * r) ? jb.P64[(long long)i0 * r + idx] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = idx0 + u * 128 + tid;
+            if (idx < nrows * r) Ps[idx / r][idx % r] = t[u];
+        }
+    }
+    __syncthreads();
+    const int rw = 16 * wave;
+    const double* __restrict__ R = jb.R;
+    for (int b = 0; b < nb; ++b) {
+        v4d acc = {0.0, 0.0, 0.0, 0.0};
+        const int cb = 16 * b + ll;
+        double dv[4];                                   // B operands of R_bb^-1
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) dv[ks] = jb.Dinv[(b * 16 + 4 * ks + lg) * 16 + ll];
+        for (int ab0 = 0; ab0 < b; ab0 += 4) {          // 16 global loads in flight
+            double rv[4][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const int row = 16 * (ab0 + u) + 4 * ks + lg;
+                    rv[u][ks] = (ab0 + u < b && cb < r) ? R[(long long)row * r + cb] : 0.0;
+                }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (ab0 + u < b)
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[rw + ll][16 * (ab0 + u) + 4 * ks + lg], rv[u][ks], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Ps[rw + lg + 4 * v][16 * b + ll] -= acc[v];
+        __syncthreads();
+        v4d q = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            q = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[rw + ll][16 * b + 4 * ks + lg], dv[ks], q, 0, 0, 0);
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Ps[rw + lg + 4 * v][16 * b + ll] = q[v];
+        __syncthreads();
+    }
+    if (final_pass) {
+        for (int idx = tid; idx < nrows * r; idx += 128) jb.Uout[(long long)i0 * r + idx] = (float)Ps[idx / r][idx % r];
+    } else {
+        for (int idx = tid; idx < nrows * r; idx += 128) jb.P64[(long long)i0 * r + idx] = Ps[idx / r][idx % r];
+    }
+}
+
 // ---- slow path: one workgroup per mode, global memory, three passes ---------------------------
 constexpr int ORTH_NT = 512;
 constexpr int ORTH_MAXR = 1024;
@@ -471,6 +738,46 @@ hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t s
 hipError_t launch_orth_apply(const OrthArgs& a, int final_pass, hipStream_t st) {
     if (!fast_args_ok(a)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_orth_apply, dim3(total_blocks(a)), 128, 0, st, a, final_pass);
+    return hipGetLastError();
+}
+bool orth_wide_supported(int r) { return r > OP_RMAX && r <= OW_RMAX; }
+int orth_wide_gram_blocks(int n) { return (n + OW_ROWS - 1) / OW_ROWS; }
+static bool wide_args_ok(const OrthArgs& a) {
+    if (a.njobs <= 0 || a.njobs > 4) return false;
+    for (int j = 0; j < a.njobs; ++j) {
+        const OrthJob& jb = a.job[j];
+        if (jb.n <= 0 || !orth_wide_supported(jb.r) || jb.nblk != orth_wide_gram_blocks(jb.n)) return false;
+        if (!jb.Gpart || !jb.R || !jb.Dinv || !jb.scal || !jb.P64 || !jb.Uout) return false;
+    }
+    return true;
+}
+hipError_t launch_orthw_gram(const OrthArgs& a, hipStream_t st) {
+    if (!wide_args_ok(a)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_orthw_gram, dim3(total_blocks(a)), 256, 0, st, a);
+    return hipGetLastError();
+}
+hipError_t launch_orthw_chol(const OrthArgs& a, int pass, int last, hipStream_t st) {
+    if (!wide_args_ok(a)) return hipErrorInvalidValue;
+    int rmax = 0;
+    for (int j = 0; j < a.njobs; ++j) rmax = a.job[j].r > rmax ? a.job[j].r : rmax;
+    const size_t lds = sizeof(double) * ((size_t)rmax * (rmax + 1) / 2 + 2 * (size_t)rmax);
+    static size_t lds_allowed = 0;                 // the attribute only ever needs to grow
+    if (lds > lds_allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_orthw_chol),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        lds_allowed = lds;
+    }
+    hipLaunchKernelGGL(k_orthw_chol, dim3(a.njobs), 1024, lds, st, a, pass, last);
+    return hipGetLastError();
+}
+hipError_t launch_orthw_apply(const OrthArgs& a, int final_pass, hipStream_t st) {
+    if (!wide_args_ok(a)) return hipErrorInvalidValue;
+    int blocks = 0;
+    for (int j = 0; j < a.njobs; ++j) blocks += orth_slices(a.job[j].n);
+    OrthArgs b = a;                                // apply walks 32-row slices
+    for (int j = 0; j < b.njobs; ++j) b.job[j].nblk = orth_slices(b.job[j].n);
+    hipLaunchKernelGGL(k_orthw_apply, dim3(blocks), 128, 0, st, b, final_pass);
     return hipGetLastError();
 }
 hipError_t launch_orth_big(const OrthArgs& a, hipStream_t st) {
