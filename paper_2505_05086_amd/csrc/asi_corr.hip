@@ -16,7 +16,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int CR_TO = 64;            // output channels per workgroup
 constexpr int CR_KC = 64;            // output positions per chunk
-constexpr int CR_ZMAX = 8192;        // floats of LDS for the Z slab
+constexpr int CR_ZMAX = 4096;        // floats of LDS for the Z slab
 
 struct CorrPlan {
     int ry;          // output rows per chunk
@@ -32,6 +32,8 @@ struct CorrPlan {
 static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
     const int taps = g.kh * g.kw;
     if (g.Wo > CR_KC || taps > 25) return false;
+    // the kernel indexes G1 and Z with 32-bit offsets
+    if ((long long)g.r1 * g.cout * g.Ho * g.Wo >= (1LL << 31) || (long long)g.r1 * g.r2 * g.H * g.W >= (1LL << 31)) return false;
     p->ry = CR_KC / g.Wo;
     if (p->ry > g.Ho) p->ry = g.Ho;
     p->nyc = (g.Ho + p->ry - 1) / p->ry;
@@ -49,22 +51,26 @@ static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
     return true;
 }
 
-template <int MAXT>
-__global__ __launch_bounds__(256) void k_corr_mfma(const float* __restrict__ G1, const float* __restrict__ Z,
+#ifdef ASI_DEBUG_TIMING
+__device__ long long g_corr_stamps[64];
+#define CSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && (i) < 64) g_corr_stamps[i] = wall_clock64(); } while (0)
+extern "C" int asi_debug_corr_stamps(long long* out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_corr_stamps), sizeof(long long) * 64);
+}
+#else
+#define CSTAMP(i) do {} while (0)
+#endif
+
+template <int MAXT, bool EXACT>
+__global__ __launch_bounds__(256, 2) void k_corr_mfma(const float* __restrict__ G1, const float* __restrict__ Z,
                                                    float* __restrict__ Tpart, CorrGeom g, CorrPlan pl) {
     __shared__ float As[CR_KC][CR_TO + 1];
     __shared__ float Zs[CR_ZMAX];
-    __shared__ int zoff[CR_KC];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     const int taps = g.kh * g.kw;
     const int o0 = blockIdx.x * CR_TO, j0 = blockIdx.y * 16, z = blockIdx.z;
     const int HoWo = g.Ho * g.Wo;
 
-    // chunk-local position k -> offset of its window origin inside the slab (same for every chunk)
-    for (int k = tid; k < CR_KC; k += 256) {
-        const int yl = k / g.Wo, x = k - yl * g.Wo;
-        zoff[k] = (yl < pl.ry) ? yl * g.sh * pl.wp + x * g.sw : 0;
-    }
     int tapofs[MAXT];
 #pragma unroll
     for (int t = 0; t < MAXT; ++t) {
@@ -77,61 +83,73 @@ __global__ __launch_bounds__(256) void k_corr_mfma(const float* __restrict__ G1,
 
     const int ch_beg = z * pl.cps;
     const int ch_end = (ch_beg + pl.cps < pl.nchunks) ? ch_beg + pl.cps : pl.nchunks;
+    const int ztotal = 16 * pl.slab;
+    const float inv_slab = 1.0f / (float)pl.slab, inv_wp = 1.0f / (float)pl.wp, inv_wo = 1.0f / (float)g.Wo;
+    const int row_step = g.sh * pl.wp;
+    float a_t[16], z_t[CR_ZMAX / 256];
+    // loads of one chunk into registers: the G1 tile (64 channels x kcv positions, contiguous
+    // along k) and the Z slab with its zero halo (rows ylo.., columns -pw..)
+    auto fetch = [&](int ch) {
+        const int i = ch / pl.nyc, yc = ch - i * pl.nyc;
+        const int y0 = yc * pl.ry;
+        const int rows = (g.Ho - y0 < pl.ry) ? g.Ho - y0 : pl.ry;
+        const int kcv = rows * g.Wo;
+        const int k = tid & 63;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int o = o0 + (tid >> 6) + 4 * u;
+            a_t[u] = ldg_f32(G1, (i * g.cout + o) * HoWo + y0 * g.Wo + k, k < kcv && o < g.cout);
+        }
+        const int ylo = y0 * g.sh - g.ph;
+#pragma unroll
+        for (int u = 0; u < CR_ZMAX / 256; ++u) {
+            const int e = u * 256 + tid;
+            // e < 4096: the rounded float quotient is exact, no integer division needed
+            const int jl = (int)(((float)e + 0.5f) * inv_slab), rem = e - jl * pl.slab;
+            const int rr = (int)(((float)rem + 0.5f) * inv_wp), cc = rem - rr * pl.wp;
+            const int row = ylo + rr, col = cc - g.pw, j = j0 + jl;
+            const bool ok = e < ztotal && j < g.r2 && row >= 0 && row < g.H && col >= 0 && col < g.W;
+            const float v = ldg_f32(Z, ((i * g.r2 + j) * g.H + row) * g.W + col, ok);
+            z_t[u] = v;
+        }
+    };
+    CSTAMP(0);
+    if (ch_beg < ch_end) fetch(ch_beg);
     for (int ch = ch_beg; ch < ch_end; ++ch) {
+        CSTAMP(1 + 4 * (ch - ch_beg));
         const int i = ch / pl.nyc, yc = ch - i * pl.nyc;
         const int y0 = yc * pl.ry;
         const int rows = (g.Ho - y0 < pl.ry) ? g.Ho - y0 : pl.ry;
         const int kcv = rows * g.Wo;                       // valid positions in this chunk
         __syncthreads();                                   // previous chunk consumed
-        // G1 tile: 64 channels x kcv positions, contiguous along k
-        {
-            const int k = tid & 63;
-            float t[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int o = o0 + (tid >> 6) + 4 * u;
-                t[u] = (k < kcv && o < g.cout) ? G1[((long long)i * g.cout + o) * HoWo + (long long)y0 * g.Wo + k] : 0.f;
-            }
+        for (int u = 0; u < 16; ++u) As[tid & 63][(tid >> 6) + 4 * u] = a_t[u];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) As[k][(tid >> 6) + 4 * u] = t[u];
-        }
-        // Z slab with zero halo: rows ylo .. ylo + rows_in - 1, columns -pw .. -pw + wp - 1
-        {
-            const int ylo = y0 * g.sh - g.ph;
-            const int total = 16 * pl.slab;
-            for (int e0 = 0; e0 < total; e0 += 256 * 8) {
-                float t[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int e = e0 + u * 256 + tid;
-                    float v = 0.f;
-                    if (e < total) {
-                        const int jl = e / pl.slab, rem = e - jl * pl.slab;
-                        const int rr = rem / pl.wp, cc = rem - rr * pl.wp;
-                        const int row = ylo + rr, col = cc - g.pw, j = j0 + jl;
-                        if (j < g.r2 && row >= 0 && row < g.H && col >= 0 && col < g.W)
-                            v = Z[(((long long)i * g.r2 + j) * g.H + row) * g.W + col];
-                    }
-                    t[u] = v;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int e = e0 + u * 256 + tid;
-                    if (e < total) Zs[e] = t[u];
-                }
-            }
+        for (int u = 0; u < CR_ZMAX / 256; ++u) {
+            const int e = u * 256 + tid;
+            if (e < ztotal) Zs[e] = z_t[u];
         }
         __syncthreads();
+        CSTAMP(2 + 4 * (ch - ch_beg));
+        if (ch + 1 < ch_end) fetch(ch + 1);                // in flight while this chunk is multiplied
+        CSTAMP(3 + 4 * (ch - ch_beg));
         const float* zrow = Zs + ll * pl.slab;
-        for (int ks = 0; 4 * ks < kcv; ++ks) {
-            const int k = 4 * ks + lg;
-            const float a = As[k][16 * wave + ll];
-            const float* zp = zrow + zoff[k];
+#pragma unroll 4
+        for (int ks = 0; ks < CR_KC / 4; ++ks) {
+            if (4 * ks < kcv) {
+                const int k = 4 * ks + lg;
+                // window origin of position k inside the slab: (k / Wo) * sh * wp + (k % Wo) * sw
+                const int yl = (int)(((float)k + 0.5f) * inv_wo), x = k - yl * g.Wo;
+                const float a = As[k][16 * wave + ll];
+                const float* zp = zrow + ((yl < pl.ry) ? yl * row_step + x * g.sw : 0);
 #pragma unroll
-            for (int t = 0; t < MAXT; ++t)
-                if (t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, zp[tapofs[t]], acc[t], 0, 0, 0);
+                for (int t = 0; t < MAXT; ++t)
+                    if (EXACT || t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, zp[tapofs[t]], acc[t], 0, 0, 0);
+            }
         }
+        CSTAMP(4 + 4 * (ch - ch_beg));
     }
+    CSTAMP(62);
     // lane holds o = o0 + 16w + 4*lg + v, j = j0 + ll
     const long long total = (long long)g.cout * g.r2 * taps;
 #pragma unroll
@@ -196,9 +214,10 @@ hipError_t launch_corr(const float* G1, const float* Z, float* Tpart, const Corr
         if (nsplit != pl.nsplit) return hipErrorInvalidValue;
         dim3 grid((unsigned)((g.cout + CR_TO - 1) / CR_TO), (unsigned)((g.r2 + 15) / 16), (unsigned)pl.nsplit);
         const int taps = g.kh * g.kw;
-        if (taps == 1) hipLaunchKernelGGL((k_corr_mfma<1>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
-        else if (taps <= 9) hipLaunchKernelGGL((k_corr_mfma<9>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
-        else hipLaunchKernelGGL((k_corr_mfma<25>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
+        if (taps == 1) hipLaunchKernelGGL((k_corr_mfma<1, true>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
+        else if (taps == 9) hipLaunchKernelGGL((k_corr_mfma<9, true>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
+        else if (taps < 9) hipLaunchKernelGGL((k_corr_mfma<9, false>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
+        else hipLaunchKernelGGL((k_corr_mfma<25, false>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
         return hipGetLastError();
     }
     const int ips = (g.r1 + nsplit - 1) / nsplit;

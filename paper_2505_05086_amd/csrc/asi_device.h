@@ -14,6 +14,19 @@ __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uin
 template <typename T>
 __device__ __forceinline__ float ldf(const T* __restrict__ p, long long idx) { return to_f32(p[idx]); }
 
+// Guarded loads without a branch: the index is clamped to element 0 (always valid) and the
+// value is selected afterwards, so that many loads stay in flight instead of each waiting
+// inside its own conditional block.
+template <typename T>
+__device__ __forceinline__ float ldg_f32(const T* __restrict__ p, long long idx, bool ok) {
+    const T v = p[ok ? idx : 0];
+    return ok ? to_f32(v) : 0.f;
+}
+__device__ __forceinline__ double ldg_f64(const double* __restrict__ p, long long idx, bool ok) {
+    const double v = p[ok ? idx : 0];
+    return ok ? v : 0.0;
+}
+
 // A tensor seen from one mode: X[o, i, j], o < outer, i < n (the mode), j < inner.
 // Column c of the mode unfolding (Sec. 3.2) is the pair (o, j) = (c / inner, c % inner).
 struct ModeView {

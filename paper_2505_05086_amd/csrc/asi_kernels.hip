@@ -45,25 +45,25 @@ __global__ __launch_bounds__(256) void k_pair(const T* __restrict__ X, long long
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const int i = i0 + (tid >> 5) + 8 * t;
-                xr[t] = (valid && i < n) ? ldf(X, xbase + (long long)i * inner) : 0.f;
+                xr[t] = ldg_f32(X, xbase + (long long)i * inner, valid && i < n);
             }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int q = q0 + (tid >> 5) + 8 * t;
-                yr[t] = (valid && q < r) ? Y[ybase + (long long)q * inner] : 0.f;
+                yr[t] = ldg_f32(Y, ybase + (long long)q * inner, valid && q < r);
             }
         } else {  // inner == 1
             const int i = i0 + (tid & 63);
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const long long c = c0 + (tid >> 6) + 4 * t;
-                xr[t] = (c < cend && i < n) ? ldf(X, c * (long long)n + i) : 0.f;
+                xr[t] = ldg_f32(X, c * (long long)n + i, c < cend && i < n);
             }
             const int q = q0 + (tid & 31);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const long long c = c0 + (tid >> 5) + 8 * t;
-                yr[t] = (c < cend && q < r) ? Y[c * (long long)r + q] : 0.f;
+                yr[t] = ldg_f32(Y, c * (long long)r + q, c < cend && q < r);
             }
         }
     };

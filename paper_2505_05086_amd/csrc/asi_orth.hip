@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void k_orth_presum(PresumArgs a) {
     const int s0 = g * 32;
     double t[32];
 #pragma unroll
-    for (int u = 0; u < 32; ++u) t[u] = (s0 + u < jb.nsplit) ? jb.in[(long long)(s0 + u) * jb.cnt + e] : 0.0;
+    for (int u = 0; u < 32; ++u) t[u] = ldg_f64(jb.in, (long long)(s0 + u) * jb.cnt + e, s0 + u < jb.nsplit);
     double s = 0.0;
 #pragma unroll
     for (int u = 0; u < 32; ++u) s += t[u];
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void k_orth_gram0(OrthArgs a) {
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
                     const int sp = sp0 + u * nsg;
-                    t[u] = (sp < jb.nsplit) ? jb.part[(long long)sp * cnt + e] : 0.0;
+                    t[u] = ldg_f64(jb.part, (long long)sp * cnt + e, sp < jb.nsplit);
                 }
 #pragma unroll
                 for (int u = 0; u < 16; ++u) s += t[u];
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
             for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
                 double t[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) t[u] = (b0 + u < jb.nblk) ? jb.Gpart[(long long)(b0 + u) * r * r + e] : 0.0;
+                for (int u = 0; u < 8; ++u) t[u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, b0 + u < jb.nblk);
 #pragma unroll
                 for (int u = 0; u < 8; ++u) s += t[u];
             }
@@ -298,7 +298,7 @@ __global__ __launch_bounds__(128) void k_orth_apply(OrthArgs a, int final_pass) 
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int idx = idx0 + u * 128 + tid;
-            t[u] = (idx < nrows * r) ? jb.P64[(long long)i0 * r + idx] : 0.0;
+            t[u] = ldg_f64(jb.P64, (long long)i0 * r + idx, idx < nrows * r);
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(128) void k_orth_apply(OrthArgs a, int final_pass) 
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int e = e0 + u * 128 + tid;
-            t[u] = (e < r * r) ? jb.R[e] : 0.0;
+            t[u] = ldg_f64(jb.R, e, e < r * r);
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -385,7 +385,7 @@ __global__ __launch_bounds__(256) void k_orthw_gram(OrthArgs a) {
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int idx = idx0 + u * 256 + tid;
-                t[u] = (idx < nrows * r) ? jb.P64[(long long)i0 * r + idx] : 0.0;
+                t[u] = ldg_f64(jb.P64, (long long)i0 * r + idx, idx < nrows * r);
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthArgs a, int pass, int l
             for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
                 double t[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) t[u] = (b0 + u < jb.nblk) ? jb.Gpart[(long long)(b0 + u) * r * r + e] : 0.0;
+                for (int u = 0; u < 8; ++u) t[u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, b0 + u < jb.nblk);
 #pragma unroll
                 for (int u = 0; u < 8; ++u) s += t[u];
             }
@@ -567,7 +567,7 @@ __global__ __launch_bounds__(128) void k_orthw_apply(OrthArgs a, int final_pass)
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int idx = idx0 + u * 128 + tid;
-            t[u] = (idx < nrows * r) ? jb.P64[(long long)i0 * r + idx] : 0.0;
+            t[u] = ldg_f64(jb.P64, (long long)i0 * r + idx, idx < nrows * r);
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -591,7 +591,7 @@ __global__ __launch_bounds__(128) void k_orthw_apply(OrthArgs a, int final_pass)
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
                     const int row = 16 * (ab0 + u) + 4 * ks + lg;
-                    rv[u][ks] = (ab0 + u < b && cb < r) ? R[(long long)row * r + cb] : 0.0;
+                    rv[u][ks] = ldg_f64(R, (long long)row * r + cb, ab0 + u < b && cb < r);
                 }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
@@ -638,7 +638,7 @@ __global__ __launch_bounds__(ORTH_NT) void k_orth_big(OrthArgs a) {
         for (int sp0 = 0; sp0 < jb.nsplit; sp0 += 8) {
             double t[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) t[u] = (sp0 + u < jb.nsplit) ? jb.part[(long long)(sp0 + u) * cnt + e] : 0.0;
+            for (int u = 0; u < 8; ++u) t[u] = ldg_f64(jb.part, (long long)(sp0 + u) * cnt + e, sp0 + u < jb.nsplit);
 #pragma unroll
             for (int u = 0; u < 8; ++u) s += t[u];
         }

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
         const int vi = e / (NBM * 16 * NBR * 16), rem = e - vi * (NBM * 16 * NBR * 16);
         const int i = rem / (NBR * 16), q = rem - i * (NBR * 16);
         const SmallView& sv = jb.v[vi];
-        Us[vi][i][q] = (i < sv.n && q < sv.r) ? sv.U[(long long)i * sv.r + q] : 0.f;
+        Us[vi][i][q] = ldg_f32(sv.U, (long long)i * sv.r + q, i < sv.n && q < sv.r);
     }
     for (int e = tid; e < NV * SS_TC; e += 256) {
         const int vi = e / SS_TC, c = e - vi * SS_TC;
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
 #pragma unroll
             for (int u = 0; u < SS_PRE; ++u) {
                 const int e = u * 256 + tid;
-                if (e < count) pre[u] = src[e];
+                pre[u] = src[e < count ? e : 0];          // clamped, not branched: all loads stay in flight
             }
 #pragma unroll
             for (int u = 0; u < SS_PRE; ++u) {
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
 #pragma unroll
             for (int u = 0; u < 32; ++u) {
                 const int i = (tid >> 7) + 2 * u;
-                if (c < vc && i < n0) pre[u] = src[(long long)i * jb.inner];
+                pre[u] = src[(c < vc && i < n0) ? (long long)i * jb.inner : 0];
             }
 #pragma unroll
             for (int u = 0; u < 32; ++u) {
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
                 for (int ks = 0; ks < NBM * 4; ++ks) {
                     if (4 * ks < n) {
                         const int i = 4 * ks + lg;
-                        const float a = (okA && i < n) ? smem[ofsA + i * sI] : 0.f;
+                        const float a = ldg_f32(smem, ofsA + i * sI, okA && i < n);
 #pragma unroll
                         for (int nb = 0; nb < NBR; ++nb)
                             vacc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Us[vi][i][16 * nb + ll], vacc[nb], 0, 0, 0);

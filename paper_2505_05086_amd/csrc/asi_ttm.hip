@@ -50,14 +50,14 @@ __global__ __launch_bounds__(256) void k_ttm_mfma(const T* __restrict__ X, long 
         for (int t = 0; t < 8; ++t) {
             if (!LASTMODE) {
                 const int i = k0 + l_i + 4 * t;
-                xr[t] = (ld_base >= 0 && i < n) ? ldf(X, ld_base + (long long)i * inner) : 0.f;
+                xr[t] = ldg_f32(X, ld_base + (long long)i * inner, ld_base >= 0 && i < n);
             } else {
                 const long long c = c0 + l_c + 8 * t;
                 const int i = k0 + l_i;
-                xr[t] = (c < ncols && i < n) ? ldf(X, c * (long long)n + i) : 0.f;
+                xr[t] = ldg_f32(X, c * (long long)n + i, c < ncols && i < n);
             }
             const int i = k0 + m_i + 4 * t, q = q0 + m_q;
-            mr[t] = (i < n && q < r) ? Mp[(long long)i * ms_i + (long long)q * ms_q] : 0.f;
+            mr[t] = ldg_f32(Mp, (long long)i * ms_i + (long long)q * ms_q, i < n && q < r);
         }
     };
     auto stash = [&]() {
