@@ -157,29 +157,71 @@ __global__ __launch_bounds__(256) void k_orth_gram0(OrthArgs a) {
 }
 
 // ---- chol -----------------------------------------------------------------------------------
+// Right-looking Cholesky of the symmetric matrix in Gs (order r <= RM) by ONE wave.  Lane j keeps
+// column j in registers; at step k every lane publishes its G[k][j] in `rowbuf`, reads the
+// pivot and the rest of row k back (LDS serves one wave's accesses in order, so no barrier is
+// needed), and updates its rows k+1.. with the rank-one term.  Row k is left unscaled:
+// on return Gs[k][j], k <= j, holds R[k][j] * R[k][k] and Gs[k][k] the pivot R[k][k]^2.
+template <int RM>
+__device__ void chol_wave(double (*Gs)[OP_LD], double* rowbuf, int r, int* s_bad) {
+    const int j = threadIdx.x;          // 0..63
+    double col[RM];
+#pragma unroll
+    for (int a2 = 0; a2 < RM; ++a2) col[a2] = (j < r && a2 < r) ? Gs[a2][j] : 0.0;
+#pragma unroll
+    for (int k = 0; k < RM; ++k) {
+        if (k < r) {
+            rowbuf[j] = col[k];
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            double p = rowbuf[k];
+            if (!(p > 0.0)) {                       // zero or non-finite input
+                if (j == 0 && *s_bad == 0) *s_bad = k + 1;
+                p = 1.0;
+            }
+            double pinv = __builtin_amdgcn_rcp(p);
+            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);      // two Newton steps: full fp64 accuracy
+            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
+            const double f = col[k] * pinv;
+#pragma unroll
+            for (int a2 = k + 1; a2 < RM; ++a2) {
+                col[a2] = fma(-rowbuf[a2], f, col[a2]);
+                if (((a2 - k) & 15) == 0) __builtin_amdgcn_sched_barrier(0);   // keep at most 16 row values live
+            }
+            if (j == k) col[k] = p;                 // the pivot actually used
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < RM; ++k)
+        if (k < r && j < r && k <= j) Gs[k][j] = col[k];
+}
+
 // scal[0] = trace(P^T P), scal[1 + k] = running product of the R diagonals, scal[65] = first bad pivot
-__global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int last) {
+template <int RM>
+__global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int last) {
     __shared__ double Gs[OP_RMAX][OP_LD];
     __shared__ double dinv[OP_RMAX];
     __shared__ double rdiag[OP_RMAX];
+    __shared__ double rowbuf[64];
     __shared__ double s_trace;
     __shared__ int s_bad;
     const OrthJob jb = a.job[blockIdx.x];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     if (tid == 0) s_bad = 0;
     STAMP(0);
-    for (int e = tid; e < r * r; e += 512) {
+    for (int e = tid; e < r * r; e += 256) {
         const int ga = e / r, gb = e - ga * r;
         if (ga <= gb) {
             double s = 0.0;
-            for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
-                double t[8];
+            for (int b0 = 0; b0 < jb.nblk; b0 += 16) {        // 16 loads in flight
+                double t[16];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) t[u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, b0 + u < jb.nblk);
+                for (int u = 0; u < 16; ++u) t[u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, b0 + u < jb.nblk);
 #pragma unroll
-                for (int u = 0; u < 8; ++u) s += t[u];
+                for (int u = 0; u < 16; ++u) s += t[u];
             }
             Gs[ga][gb] = s;
+            Gs[gb][ga] = s;
         }
     }
     __syncthreads();
@@ -199,36 +241,11 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
         s_trace = jb.scal[0];
     }
     STAMP(2);
-    // right-looking Cholesky; thread (ty, tx) updates column tx, rows k+1+ty, +8, ...; row k stays unscaled
-    const int tx = tid & 63, ty = tid >> 6;
-    for (int k = 0; k < r; ++k) {
-        double p = Gs[k][k];
-        if (!(p > 0.0)) {                       // zero or non-finite input
-            if (tid == 0 && s_bad == 0) s_bad = k + 1;
-            p = 1.0;
-        }
-        if (tx > k && tx < r) {
-            double pinv = __builtin_amdgcn_rcp(p);
-            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);      // two Newton steps: full fp64 accuracy
-            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
-            const double f = Gs[k][tx] * pinv;
-            // rows k+1+ty, +8, ... <= tx (at most 8): all loads first, then the updates
-            double gk[8], gg[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int ga = k + 1 + ty + 8 * u;
-                const bool ok = ga <= tx;
-                gk[u] = ok ? Gs[k][ga] : 0.0;
-                gg[u] = ok ? Gs[ga][tx] : 0.0;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int ga = k + 1 + ty + 8 * u;
-                if (ga <= tx) Gs[ga][tx] = fma(-gk[u], f, gg[u]);
-            }
-        }
-        __syncthreads();
+    // right-looking Cholesky by wave 0 alone, lane j holding column j in registers (see chol_wave)
+    if (tid < 64) {
+        chol_wave<RM>(Gs, rowbuf, r, &s_bad);      // RM >= r for every mode of the launch
     }
+    __syncthreads();
     STAMP(3);
     if (tid < r) {
         double p = Gs[tid][tid];
@@ -240,7 +257,7 @@ __global__ __launch_bounds__(512) void k_orth_chol(OrthArgs a, int pass, int las
         jb.scal[1 + tid] = rd;
     }
     __syncthreads();
-    for (int e = tid; e < r * r; e += 512) {
+    for (int e = tid; e < r * r; e += 256) {
         const int ga = e / r, gb = e - ga * r;
         const double v = (ga < gb) ? Gs[ga][gb] * dinv[ga] : (ga == gb ? 1.0 / dinv[ga] : 0.0);
         if (ga < gb) Gs[ga][gb] = v;
@@ -732,7 +749,12 @@ hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st) {
 }
 hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t st) {
     if (!fast_args_ok(a)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_orth_chol, dim3(a.njobs), 512, 0, st, a, pass, last);
+    int rmax = 0;
+    for (int j = 0; j < a.njobs; ++j) rmax = a.job[j].r > rmax ? a.job[j].r : rmax;
+    if (rmax <= 16) hipLaunchKernelGGL(k_orth_chol<16>, dim3(a.njobs), 256, 0, st, a, pass, last);
+    else if (rmax <= 32) hipLaunchKernelGGL(k_orth_chol<32>, dim3(a.njobs), 256, 0, st, a, pass, last);
+    else if (rmax <= 48) hipLaunchKernelGGL(k_orth_chol<48>, dim3(a.njobs), 256, 0, st, a, pass, last);
+    else hipLaunchKernelGGL(k_orth_chol<64>, dim3(a.njobs), 256, 0, st, a, pass, last);
     return hipGetLastError();
 }
 hipError_t launch_orth_apply(const OrthArgs& a, int final_pass, hipStream_t st) {
