@@ -25,11 +25,28 @@ HBM_PEAK_GBS = 8000.0
 PEAK_TFLOPS = {"mfma_f32": 157.3, "mfma_f64": 78.6, "mfma_bf16": 2500.0, "valu_f32": 78.6, "valu_f64": 78.6,
                "mfma_f32+f64": 2.0 / (1.0 / 157.3 + 1.0 / 78.6)}
 # which arithmetic unit each kernel symbol runs its contraction on
-KERNEL_UNIT = {"k_subspace_small": "mfma_f32+f64", "k_ttm": "mfma_f32", "k_pair": "mfma_f64", "k_corr": "mfma_f32",
+KERNEL_UNIT = {"k_subspace_small": "mfma_f32+f64", "k_ttm_mfma": "mfma_f32", "k_pair": "mfma_f64",
+               "k_corr_mfma": "mfma_f32", "k_corr": "valu_f32",
                "k_orth_gram0": "mfma_f64", "k_orth_apply": "mfma_f64", "k_orth_chol": "valu_f64",
                "k_orthw_gram": "mfma_f64", "k_orthw_apply": "mfma_f64", "k_orthw_chol": "valu_f64",
                "k_orth_big": "valu_f64", "k_orth_presum": "valu_f64", "k_sum_partials": "valu_f64",
                "k_expand_grouped": "valu_f32"}
+
+
+def unit_of(symbol: str) -> str:
+    base = symbol.split("<")[0]
+    return KERNEL_UNIT.get(base, "valu_f32")
+
+
+def measured_traffic(cfg_index: int, symbol: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"config{cfg_index}_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            rec = json.load(f).get("kernels", {}).get(symbol)
+        return None if rec is None else float(rec["fetch_bytes_per_launch"]) + float(rec["write_bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
+        return None
 
 
 def parse_args():
@@ -41,6 +58,8 @@ def parse_args():
     ap.add_argument("--distinct", type=int, default=8, help="distinct input steps kept in HBM and cycled")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams the layers are spread over (0 = one per layer)")
     ap.add_argument("--graph", type=int, default=1, help="replay each step from a captured HIP graph (1) or launch eagerly (0)")
+    ap.add_argument("--copy-calib-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB ten times (calibrates rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
@@ -155,6 +174,14 @@ def main():
         else:
             one_step(k)
 
+    if args.copy_calib_mib > 0:
+        src = torch.empty(args.copy_calib_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for k in range(args.warmup):
         run_step(k)
     torch.cuda.synchronize()
@@ -193,7 +220,7 @@ def main():
     d = per_kernel[dom]
     avg_s = d["ms"] * 1e-3 / d["launches"]
     bytes_per_launch, flops_per_launch = d["bytes"] / d["launches"], d["flops"] / d["launches"]
-    unit = KERNEL_UNIT.get(dom, "valu_f32")
+    unit = unit_of(dom)
     t_mem, t_alu = bytes_per_launch / (HBM_PEAK_GBS * 1e9), flops_per_launch / (PEAK_TFLOPS[unit] * 1e12)
     if t_mem >= t_alu:
         roof = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
@@ -201,7 +228,7 @@ def main():
         roof = {"bound": "mfma" if unit.startswith("mfma") else "alu", "achieved": flops_per_launch / avg_s / 1e12,
                 "peak": PEAK_TFLOPS[unit], "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = measured_traffic(cfg.index, dom)
     roof["kernel"] = dom
     roof["avg_launch_us"] = avg_s * 1e6
     roof["launches_per_step"] = d["launches"] / nprof

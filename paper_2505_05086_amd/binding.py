@@ -192,6 +192,6 @@ def asi_profile_report() -> dict:
         raise AsiError(4, "asi_profile_report")
     out = {}
     for line in buf.value.decode().splitlines():
-        site, cnt, ms, by, fl = line.split(",")
+        site, cnt, ms, by, fl = line.rsplit(",", 4)      # the site itself may contain commas
         out[site] = {"launches": int(cnt), "ms": float(ms), "bytes": float(by), "flops": float(fl)}
     return out

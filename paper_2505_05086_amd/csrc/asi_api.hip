@@ -271,6 +271,9 @@ struct ProfScope {
     ~ProfScope() {
         if (!on) return;
         (void)hipEventRecord(rec.e1, st);
+        // "kernel instantiation:role", e.g. "k_ttm_mfma<float, false, 3>:core"
+        const size_t colon = rec.site.find(':');
+        rec.site = std::string(last_label()) + (colon == std::string::npos ? "" : rec.site.substr(colon));
         std::lock_guard<std::mutex> lk(g_prof_mu);
         g_prof.push_back(rec);
     }
@@ -389,7 +392,7 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
     fast.info = wide.info = slow.info = info;
     PresumArgs pre2;                 // second tree level: wide modes need the finished sum in P64
     std::memset(&pre2, 0, sizeof(pre2));
-    double wide_b = 0, wide_f = 0, pre2_b = 0;
+    double wide_b = 0, wide_f = 0, pre2_b = 0, chol_b = 0, chol_f = 0;
     PresumArgs pre;
     std::memset(&pre, 0, sizeof(pre));
     double fast_b = 0, fast_f = 0, slow_b = 0, slow_f = 0, pre_b = 0;
@@ -436,6 +439,11 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
             pj.nchunks = (int)((pj.cnt + 255) / 256); pj.ngroups = 1;
             pre2_b += 8.0 * n * r * (j.nsplit + 1);
         }
+        if (p.fast_orth[m] || p.wide_orth[m]) {
+            // Cholesky launches: read the slice Grams, write R and the diagonal-block inverses; r^3/3 flops
+            chol_b += 8.0 * ((double)p.nblk[m] * r * r + (double)r * r + 256.0 * ((r + 15) / 16));
+            chol_f += (double)r * r * r / 3.0;
+        }
         (p.fast_orth[m] ? fast_b : (p.wide_orth[m] ? wide_b : slow_b)) += 8.0 * n * r;
         (p.fast_orth[m] ? fast_f : (p.wide_orth[m] ? wide_f : slow_f)) += 2.0 * (double)n * r * r;
     }
@@ -446,18 +454,18 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
     if (fast.njobs) {
         // Orthogonalize: shifted Cholesky-QR, then one plain Cholesky-QR pass
         { ProfScope ps("k_orth_gram0", fast_b, fast_f, st); ASI_TRY(launch_orth_gram0(fast, st)); }
-        { ProfScope ps("k_orth_chol", 0, 0, st); ASI_TRY(launch_orth_chol(fast, 0, 0, st)); }
+        { ProfScope ps("k_orth_chol", chol_b, chol_f, st); ASI_TRY(launch_orth_chol(fast, 0, 0, st)); }
         { ProfScope ps("k_orth_apply", 2 * fast_b, 2 * fast_f, st); ASI_TRY(launch_orth_apply(fast, 0, st)); }
-        { ProfScope ps("k_orth_chol", 0, 0, st); ASI_TRY(launch_orth_chol(fast, 1, 1, st)); }
+        { ProfScope ps("k_orth_chol", chol_b, chol_f, st); ASI_TRY(launch_orth_chol(fast, 1, 1, st)); }
         { ProfScope ps("k_orth_apply", 1.5 * fast_b, fast_f, st); ASI_TRY(launch_orth_apply(fast, 1, st)); }
     }
     if (wide.njobs) {
         { ProfScope ps("k_orth_presum", pre2_b, pre2_b / 8.0, st); ASI_TRY(launch_orth_presum(pre2, st)); }
         { ProfScope ps("k_orthw_gram", wide_b, wide_f, st); ASI_TRY(launch_orthw_gram(wide, st)); }
-        { ProfScope ps("k_orthw_chol", 0, 0, st); ASI_TRY(launch_orthw_chol(wide, 0, 0, st)); }
+        { ProfScope ps("k_orthw_chol", chol_b, chol_f, st); ASI_TRY(launch_orthw_chol(wide, 0, 0, st)); }
         { ProfScope ps("k_orthw_apply", 2 * wide_b, wide_f, st); ASI_TRY(launch_orthw_apply(wide, 0, st)); }
         { ProfScope ps("k_orthw_gram", wide_b, wide_f, st); ASI_TRY(launch_orthw_gram(wide, st)); }
-        { ProfScope ps("k_orthw_chol", 0, 0, st); ASI_TRY(launch_orthw_chol(wide, 1, 1, st)); }
+        { ProfScope ps("k_orthw_chol", chol_b, chol_f, st); ASI_TRY(launch_orthw_chol(wide, 1, 1, st)); }
         { ProfScope ps("k_orthw_apply", 1.5 * wide_b, wide_f, st); ASI_TRY(launch_orthw_apply(wide, 1, st)); }
     }
     if (slow.njobs) {

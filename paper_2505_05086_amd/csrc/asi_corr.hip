@@ -214,6 +214,7 @@ hipError_t launch_corr(const float* G1, const float* Z, float* Tpart, const Corr
         if (nsplit != pl.nsplit) return hipErrorInvalidValue;
         dim3 grid((unsigned)((g.cout + CR_TO - 1) / CR_TO), (unsigned)((g.r2 + 15) / 16), (unsigned)pl.nsplit);
         const int taps = g.kh * g.kw;
+        set_last_label("k_corr_mfma<%d, %s>", taps == 1 ? 1 : (taps <= 9 ? 9 : 25), (taps == 1 || taps == 9) ? "true" : "false");
         if (taps == 1) hipLaunchKernelGGL((k_corr_mfma<1, true>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
         else if (taps == 9) hipLaunchKernelGGL((k_corr_mfma<9, true>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
         else if (taps < 9) hipLaunchKernelGGL((k_corr_mfma<9, false>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
@@ -222,6 +223,7 @@ hipError_t launch_corr(const float* G1, const float* Z, float* Tpart, const Corr
     }
     const int ips = (g.r1 + nsplit - 1) / nsplit;
     dim3 grid((unsigned)((total + 255) / 256), (unsigned)nsplit);
+    set_last_label("k_corr");
     hipLaunchKernelGGL(k_corr, grid, 256, 0, st, G1, Z, Tpart, g, ips);
     return hipGetLastError();
 }

@@ -7,6 +7,11 @@ namespace asi {
 
 enum DType { F32 = 0, BF16 = 1 };
 
+// Name of the kernel instantiation the last launcher call on this thread picked, written the
+// way a profiler prints it (e.g. "k_ttm_mfma<float, false, 3>"); used to tag timing records.
+void set_last_label(const char* fmt, ...);
+const char* last_label();
+
 // Y[o,q,j] = sum_i X[o,i,j] * M(i,q),  M(i,q) = Mp[i*ms_i + q*ms_q]   (Eq. 4 along one mode)
 // X: (outer, n, inner) of dtype xt;  Y: (outer, r, inner) fp32;  beta != 0 adds to Y.
 hipError_t launch_ttm(DType xt, const void* X, long long outer, int n, long long inner,

@@ -6,7 +6,19 @@
 #include "asi_device.h"
 #include "asi_kernels.h"
 
+#include <cstdarg>
+#include <cstdio>
+
 namespace asi {
+
+static thread_local char g_last_label[160] = "";
+void set_last_label(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_last_label, sizeof(g_last_label), fmt, ap);
+    va_end(ap);
+}
+const char* last_label() { return g_last_label; }
 
 // ---------------------------------------------------------------------------
 // pair: P[i,q] = sum_c X[i,c] Y[q,c] on fp64 MFMA.  A workgroup owns 64 rows i x 32 outputs q
@@ -132,6 +144,7 @@ hipError_t launch_pair(DType xt, const void* X, long long outer, int n, long lon
     const long long cps = pair_cols_per_split(ncols, nsplit);
     dim3 grid((unsigned)((n + PR_TI - 1) / PR_TI), (unsigned)((r + PR_TQ - 1) / PR_TQ), (unsigned)nsplit);
     const bool last = (inner == 1);
+    set_last_label("k_pair<%s, %s>", xt == F32 ? "float" : "asi::bf16_t", last ? "true" : "false");
     if (xt == F32) {
         if (last) hipLaunchKernelGGL((k_pair<float, true>), grid, 256, 0, st, (const float*)X, outer, n, inner, Y, r, part, cps);
         else      hipLaunchKernelGGL((k_pair<float, false>), grid, 256, 0, st, (const float*)X, outer, n, inner, Y, r, part, cps);
@@ -158,6 +171,7 @@ __global__ __launch_bounds__(256) void k_sum_partials(const PT* __restrict__ par
 hipError_t launch_sum_partials(const float* part, int nsplit, long long count, float* out, int beta, hipStream_t st) {
     if (count <= 0) return hipErrorInvalidValue;
     const long long gx = (count + 255) / 256;
+    set_last_label("k_sum_partials<float>");
     hipLaunchKernelGGL(k_sum_partials<float>, dim3((unsigned)gx), 256, 0, st, part, nsplit, count, out, beta);
     return hipGetLastError();
 }
@@ -165,6 +179,7 @@ hipError_t launch_sum_partials_f64(const double* part, int nsplit, long long cou
                                    hipStream_t st) {
     if (count <= 0) return hipErrorInvalidValue;
     const long long gx = (count + 255) / 256;
+    set_last_label("k_sum_partials<double>");
     hipLaunchKernelGGL(k_sum_partials<double>, dim3((unsigned)gx), 256, 0, st, part, nsplit, count, out, beta);
     return hipGetLastError();
 }
@@ -198,6 +213,7 @@ hipError_t launch_expand_grouped(const float* T, const float* U2, float* dW, int
                                  int og, int beta, hipStream_t st) {
     const long long total = (long long)cout * cg * taps;
     if (total <= 0) return hipErrorInvalidValue;
+    set_last_label("k_expand_grouped");
     hipLaunchKernelGGL(k_expand_grouped, dim3((unsigned)((total + 255) / 256)), 256, 0, st, T, U2, dW, cout, r2,
                        taps, cg, og, beta);
     return hipGetLastError();

@@ -100,6 +100,7 @@ hipError_t launch_orth_presum(const PresumArgs& a, hipStream_t st) {
         if (jb.nchunks != (int)((jb.cnt + 255) / 256) || jb.ngroups != (jb.nsplit + 31) / 32) return hipErrorInvalidValue;
         blocks += (long long)jb.nchunks * jb.ngroups;
     }
+    set_last_label("k_orth_presum");
     hipLaunchKernelGGL(k_orth_presum, dim3((unsigned)blocks), 256, 0, st, a);
     return hipGetLastError();
 }
@@ -744,6 +745,7 @@ static bool fast_args_ok(const OrthArgs& a) {
 }
 hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st) {
     if (!fast_args_ok(a)) return hipErrorInvalidValue;
+    set_last_label("k_orth_gram0");
     hipLaunchKernelGGL(k_orth_gram0, dim3(total_blocks(a)), 256, 0, st, a);
     return hipGetLastError();
 }
@@ -751,6 +753,7 @@ hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t s
     if (!fast_args_ok(a)) return hipErrorInvalidValue;
     int rmax = 0;
     for (int j = 0; j < a.njobs; ++j) rmax = a.job[j].r > rmax ? a.job[j].r : rmax;
+    set_last_label("k_orth_chol<%d>", rmax <= 16 ? 16 : (rmax <= 32 ? 32 : (rmax <= 48 ? 48 : 64)));
     if (rmax <= 16) hipLaunchKernelGGL(k_orth_chol<16>, dim3(a.njobs), 256, 0, st, a, pass, last);
     else if (rmax <= 32) hipLaunchKernelGGL(k_orth_chol<32>, dim3(a.njobs), 256, 0, st, a, pass, last);
     else if (rmax <= 48) hipLaunchKernelGGL(k_orth_chol<48>, dim3(a.njobs), 256, 0, st, a, pass, last);
@@ -759,6 +762,7 @@ hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t s
 }
 hipError_t launch_orth_apply(const OrthArgs& a, int final_pass, hipStream_t st) {
     if (!fast_args_ok(a)) return hipErrorInvalidValue;
+    set_last_label("k_orth_apply");
     hipLaunchKernelGGL(k_orth_apply, dim3(total_blocks(a)), 128, 0, st, a, final_pass);
     return hipGetLastError();
 }
@@ -775,6 +779,7 @@ static bool wide_args_ok(const OrthArgs& a) {
 }
 hipError_t launch_orthw_gram(const OrthArgs& a, hipStream_t st) {
     if (!wide_args_ok(a)) return hipErrorInvalidValue;
+    set_last_label("k_orthw_gram");
     hipLaunchKernelGGL(k_orthw_gram, dim3(total_blocks(a)), 256, 0, st, a);
     return hipGetLastError();
 }
@@ -790,6 +795,7 @@ hipError_t launch_orthw_chol(const OrthArgs& a, int pass, int last, hipStream_t 
         if (e != hipSuccess) return e;
         lds_allowed = lds;
     }
+    set_last_label("k_orthw_chol");
     hipLaunchKernelGGL(k_orthw_chol, dim3(a.njobs), 1024, lds, st, a, pass, last);
     return hipGetLastError();
 }
@@ -799,6 +805,7 @@ hipError_t launch_orthw_apply(const OrthArgs& a, int final_pass, hipStream_t st)
     for (int j = 0; j < a.njobs; ++j) blocks += orth_slices(a.job[j].n);
     OrthArgs b = a;                                // apply walks 32-row slices
     for (int j = 0; j < b.njobs; ++j) b.job[j].nblk = orth_slices(b.job[j].n);
+    set_last_label("k_orthw_apply");
     hipLaunchKernelGGL(k_orthw_apply, dim3(blocks), 128, 0, st, b, final_pass);
     return hipGetLastError();
 }
@@ -806,6 +813,7 @@ hipError_t launch_orth_big(const OrthArgs& a, hipStream_t st) {
     if (a.njobs <= 0 || a.njobs > 4) return hipErrorInvalidValue;
     for (int j = 0; j < a.njobs; ++j)
         if (a.job[j].r > ORTH_MAXR || !a.job[j].G || !a.job[j].P64) return hipErrorInvalidValue;
+    set_last_label("k_orth_big");
     hipLaunchKernelGGL(k_orth_big, dim3(a.njobs), ORTH_NT, 0, st, a);
     return hipGetLastError();
 }

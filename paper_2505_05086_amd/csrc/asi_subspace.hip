@@ -249,6 +249,8 @@ template <typename T, int NV>
 static hipError_t launch_small_t(const SmallJob& jb, int nbm, int nbr, int nwg, hipStream_t st) {
 #define ASI_SS_CASE(M, R)                                                                       \
     if (nbm == M && nbr == R) {                                                                 \
+        set_last_label("k_subspace_small<%s, %d, %d, %d, %s>", sizeof(T) == 4 ? "float" : "asi::bf16_t", M, R, NV,   \
+                       jb.whole_o ? "true" : "false");                                                          \
         if (jb.whole_o) hipLaunchKernelGGL((k_subspace_small<T, M, R, NV, true>), dim3(nwg), 256, 0, st, jb);   \
         else if constexpr (NV == 1) hipLaunchKernelGGL((k_subspace_small<T, M, R, NV, false>), dim3(nwg), 256, 0, st, jb); \
         return hipGetLastError();                                                               \

@@ -128,6 +128,7 @@ static hipError_t launch_ttm_t(const T* X, long long outer, int n, long long inn
     dim3 grid((unsigned)gx, (unsigned)((r + TM_TQ - 1) / TM_TQ));
     const int rr = r < TM_TQ ? r : TM_TQ;
     const int nbr = (rr + 15) / 16;
+    set_last_label("k_ttm_mfma<%s, %s, %d>", sizeof(T) == 4 ? "float" : "asi::bf16_t", LAST ? "true" : "false", nbr > 4 ? 4 : nbr);
     switch (nbr) {
         case 1: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 1>), grid, 256, 0, st, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta); break;
         case 2: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 2>), grid, 256, 0, st, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta); break;
