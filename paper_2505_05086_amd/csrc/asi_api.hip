@@ -133,36 +133,53 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
 }
 
 // ---- core projection ----------------------------------------------------------
+// The products are ordered to minimise multiply-adds.  For small spatial extents the H and W
+// modes are contracted together by one pass with the Kronecker product of their factors, so
+// the tensor is treated as (B, C, H*W) with three "super modes".
+constexpr int kKronMaxN = 256, kKronMaxR = 64;
+
 struct CorePlan {
+    int d = 0;                       // super modes
+    long long n[4] = {1, 1, 1, 1};
+    int r[4] = {1, 1, 1, 1};
+    bool kron = false;               // the last super mode is (H, W) merged
     int order[4] = {0, 1, 2, 3};
     float* buf[2] = {};
     size_t bytes = 0;
 };
 
+bool kron_ok(long long n_a, long long n_b, int r_a, int r_b) {
+    return n_a * n_b <= kKronMaxN && (long long)r_a * r_b <= kKronMaxR;
+}
+
 CorePlan plan_core(const Shape& s, void* ws) {
     CorePlan p;
+    p.kron = s.d == 4 && kron_ok(s.n[2], s.n[3], s.r[2], s.r[3]);
+    p.d = p.kron ? 3 : s.d;
+    for (int m = 0; m < p.d; ++m) { p.n[m] = s.n[m]; p.r[m] = s.r[m]; }
+    if (p.kron) { p.n[2] = s.n[2] * s.n[3]; p.r[2] = s.r[2] * s.r[3]; }
     int perm[4] = {0, 1, 2, 3};
     double best = -1.0;
     do {
         long long cur[4];
-        for (int m = 0; m < 4; ++m) cur[m] = s.n[m];
+        for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
         double cost = 0.0;
-        for (int k = 0; k < s.d; ++k) {
+        for (int k = 0; k < p.d; ++k) {
             const int m = perm[k];
             double sz = 1.0;
-            for (int q = 0; q < s.d; ++q) sz *= (double)cur[q];
-            cost += sz * s.r[m];
-            cur[m] = s.r[m];
+            for (int q = 0; q < p.d; ++q) sz *= (double)cur[q];
+            cost += sz * p.r[m];
+            cur[m] = p.r[m];
         }
         if (best < 0 || cost < best) { best = cost; std::memcpy(p.order, perm, sizeof(perm)); }
-    } while (std::next_permutation(perm, perm + s.d));
+    } while (std::next_permutation(perm, perm + p.d));
     long long cur[4];
-    for (int m = 0; m < 4; ++m) cur[m] = s.n[m];
+    for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
     size_t need[2] = {0, 0};
-    for (int k = 0; k + 1 < s.d; ++k) {   // the last product writes S itself
-        cur[p.order[k]] = s.r[p.order[k]];
+    for (int k = 0; k + 1 < p.d; ++k) {   // the last product writes S itself
+        cur[p.order[k]] = p.r[p.order[k]];
         size_t sz = 1;
-        for (int q = 0; q < s.d; ++q) sz *= (size_t)cur[q];
+        for (int q = 0; q < p.d; ++q) sz *= (size_t)cur[q];
         need[k & 1] = std::max(need[k & 1], sz);
     }
     Carver c(ws);
@@ -211,7 +228,8 @@ ConvPlan plan_conv(const Shape& s, const ConvGeom& cg, void* ws) {
     const CorrGeom& g = cg.g;
     Carver c(ws);
     p.G1 = c.take<float>((size_t)g.r1 * g.cout * g.Ho * g.Wo);
-    p.Z1 = c.take<float>((size_t)g.r1 * g.r2 * g.H * s.r[3]);
+    if ((long long)s.r[2] * s.r[3] > kKronMaxN || (long long)g.H * g.W > kKronMaxN)
+        p.Z1 = c.take<float>((size_t)g.r1 * g.r2 * g.H * s.r[3]);      // else Z comes from one merged pass
     p.Z = c.take<float>((size_t)g.r1 * g.r2 * g.H * g.W);
     p.nsplit = corr_splits(g);
     const size_t tsz = (size_t)g.cout * g.r2 * g.kh * g.kw;
@@ -287,6 +305,15 @@ hipError_t ttm(const char* site, DType xt, const void* X, long long outer, int n
     const double cols = (double)outer * (double)inner;
     ProfScope ps(site, cols * n * esize(xt) + 4.0 * n * r + 4.0 * cols * r * (beta ? 2 : 1), 2.0 * cols * n * r, st);
     return launch_ttm(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, st);
+}
+
+// two trailing modes at once (Kronecker product of their matrices)
+hipError_t ttm_kron(const char* site, DType xt, const void* X, long long cols, int n1, int n2, const float* M1,
+                    long long ms1_i, long long ms1_q, int r1, const float* M2, long long ms2_i, long long ms2_q, int r2,
+                    float* Y, hipStream_t st) {
+    const double n = (double)n1 * n2, r = (double)r1 * r2;
+    ProfScope ps(site, cols * n * esize(xt) + 4.0 * (n1 * r1 + n2 * r2) + 4.0 * cols * r, 2.0 * cols * n * r, st);
+    return launch_ttm_kron(xt, X, cols, n1, n2, M1, ms1_i, ms1_q, r1, M2, ms2_i, ms2_q, r2, Y, 0, st);
 }
 
 hipError_t pair(const char* site, DType xt, const void* X, long long outer, int n, long long inner, const float* Y,
@@ -384,7 +411,6 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
     if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    if (info) ASI_TRY(launch_init_ctrl(info, st));
     OrthArgs fast, wide, slow;
     std::memset(&fast, 0, sizeof(fast));
     std::memset(&wide, 0, sizeof(wide));
@@ -447,6 +473,7 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
         (p.fast_orth[m] ? fast_b : (p.wide_orth[m] ? wide_b : slow_b)) += 8.0 * n * r;
         (p.fast_orth[m] ? fast_f : (p.wide_orth[m] ? wide_f : slow_f)) += 2.0 * (double)n * r * r;
     }
+    if (info && !fast.njobs) ASI_TRY(launch_init_ctrl(info, st));     // otherwise gram0 clears it
     if (pre.njobs) {
         ProfScope ps("k_orth_presum", pre_b, pre_b / 8.0, st);
         ASI_TRY(launch_orth_presum(pre, st));
@@ -488,17 +515,23 @@ asi_status asi_core_project(const asi_tensor_desc* desc, const void* A, const fl
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     long long cur[4];
-    for (int m = 0; m < 4; ++m) cur[m] = s.n[m];
+    for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
     const void* src = A;
     DType sdt = s.dt;
-    for (int k = 0; k < s.d; ++k) {
+    for (int k = 0; k < p.d; ++k) {
         const int m = p.order[k];
         long long outer = 1, inner = 1;
         for (int q = 0; q < m; ++q) outer *= cur[q];
-        for (int q = m + 1; q < s.d; ++q) inner *= cur[q];
-        float* dst = (k + 1 == s.d) ? S : p.buf[k & 1];
-        ASI_TRY(ttm("k_ttm:core", sdt, src, outer, (int)cur[m], inner, U[m], s.r[m], 1, s.r[m], dst, 0, st));
-        cur[m] = s.r[m];
+        for (int q = m + 1; q < p.d; ++q) inner *= cur[q];
+        float* dst = (k + 1 == p.d) ? S : p.buf[k & 1];
+        if (p.kron && m == 2) {
+            // (.., H, W) -> (.., r3, r4):  M(h*W + w, a*r4 + b) = U3[h,a] * U4[w,b]
+            ASI_TRY(ttm_kron("k_ttm:core", sdt, src, outer, (int)s.n[2], (int)s.n[3], U[2], s.r[2], 1, s.r[2], U[3],
+                             s.r[3], 1, s.r[3], dst, st));
+        } else {
+            ASI_TRY(ttm("k_ttm:core", sdt, src, outer, (int)cur[m], inner, U[m], p.r[m], 1, p.r[m], dst, 0, st));
+        }
+        cur[m] = p.r[m];
         src = dst;
         sdt = F32;
     }
@@ -526,10 +559,15 @@ asi_status asi_weight_grad_conv2d(const asi_tensor_desc* desc, const float* S, c
 
     // 1. G1 = grad_out x_1 U1^T                                   (r1, cout, Ho, Wo)
     ASI_TRY(ttm("k_ttm:G1", s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0, st));
-    // 2. Z1 = S x_3 U3                                            (r1, r2, H, r4)
-    ASI_TRY(ttm("k_ttm:Z1", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0, st));
-    // 3. Z = Z1 x_4 U4                                            (r1, r2, H, W)
-    ASI_TRY(ttm("k_ttm:Z", F32, p.Z1, (long long)g.r1 * g.r2 * g.H, r4, 1, U[3], 1, r4, g.W, p.Z, 0, st));
+    if (!p.Z1) {
+        // 2+3. Z = S x_3 U3 x_4 U4 in one pass:  M(a*r4 + b, h*W + w) = U3[h,a] * U4[w,b]   (r1, r2, H, W)
+        ASI_TRY(ttm_kron("k_ttm:Z", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, U[3], 1, r4, g.W, p.Z, st));
+    } else {
+        // 2. Z1 = S x_3 U3                                        (r1, r2, H, r4)
+        ASI_TRY(ttm("k_ttm:Z1", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0, st));
+        // 3. Z = Z1 x_4 U4                                        (r1, r2, H, W)
+        ASI_TRY(ttm("k_ttm:Z", F32, p.Z1, (long long)g.r1 * g.r2 * g.H, r4, 1, U[3], 1, r4, g.W, p.Z, 0, st));
+    }
     // 4. T = correlation of Zpad with G1 over (r1, Ho, Wo)        (cout, r2, kh, kw)
     {
         const double tsz = (double)g.cout * g.r2 * taps;

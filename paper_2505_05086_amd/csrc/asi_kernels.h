@@ -18,6 +18,12 @@ hipError_t launch_ttm(DType xt, const void* X, long long outer, int n, long long
                       const float* Mp, long long ms_i, long long ms_q, int r,
                       float* Y, int beta, hipStream_t st);
 
+// Two adjacent trailing modes in one pass (small extents): X is (cols, n1*n2) row-major,
+//   Y[c, q1*r2 + q2] (+)= sum_{i1,i2} X[c, i1*n2 + i2] * M1(i1,q1) * M2(i2,q2),  Mk(i,q) = Mk[i*msk_i + q*msk_q]
+hipError_t launch_ttm_kron(DType xt, const void* X, long long cols, int n1, int n2, const float* M1,
+                           long long ms1_i, long long ms1_q, int r1, const float* M2, long long ms2_i,
+                           long long ms2_q, int r2, float* Y, int beta, hipStream_t st);
+
 // part[s][i][q] = sum_{c in split s} X[i,c] * Y[q,c]  over unfolding columns c = (o,j)
 // X: (outer, n, inner) dtype xt;  Y: (outer, r, inner) fp32;  part: (nsplit, n, r) fp64
 // (products of fp32 values are exact in fp64 and the sums are carried in fp64).

@@ -49,7 +49,10 @@ __device__ __forceinline__ void find_job(const OrthArgs& a, int* ji, int* blk) {
     *ji = j; *blk = b;
 }
 
-// Gram of the 32 rows held in Ps (zero padded to 64 columns) -> upper triangle of Gout (r x r)
+// Packed upper triangle: element (ga <= gb) of an r x r symmetric matrix
+__device__ __forceinline__ int tri_idx(int r, int ga, int gb) { return ga * r - (ga * (ga - 1)) / 2 + (gb - ga); }
+
+// Gram of the 32 rows held in Ps (zero padded to 64 columns) -> packed upper triangle Gout (r (r+1) / 2)
 __device__ void gram_from_lds(const double (*Ps)[OP_LD], int r, double* __restrict__ Gout) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lg = lane >> 4, ll = lane & 15;
     const int nb = (r + 15) / 16, npairs = nb * (nb + 1) / 2;
@@ -66,7 +69,7 @@ __device__ void gram_from_lds(const double (*Ps)[OP_LD], int r, double* __restri
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int ga = 16 * ab + lg + 4 * v, gb = 16 * bb + ll;
-            if (ga < r && gb < r && ga <= gb) Gout[ga * r + gb] = acc[v];
+            if (ga < r && gb < r && ga <= gb) Gout[tri_idx(r, ga, gb)] = acc[v];
         }
     }
 }
@@ -106,6 +109,8 @@ hipError_t launch_orth_presum(const PresumArgs& a, hipStream_t st) {
 }
 
 // ---- gram0 ----------------------------------------------------------------------------------
+// RM bounds the ranks of the launch's modes: a slice has at most 32 * RM elements, ITS per thread.
+template <int RM>
 __global__ __launch_bounds__(256) void k_orth_gram0(OrthArgs a) {
     __shared__ double Ps[OP_RS][OP_LD];
     __shared__ double red[256];
@@ -113,83 +118,123 @@ __global__ __launch_bounds__(256) void k_orth_gram0(OrthArgs a) {
     find_job(a, &ji, &blk);
     const OrthJob jb = a.job[ji];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
+    if (blockIdx.x == 0 && tid == 0 && a.info) *a.info = 0;      // nothing has reported yet
     const int i0 = blk * OP_RS;
     const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
     const long long cnt = (long long)n * r;
     const int E = nrows * r;
     for (int e = tid; e < OP_RS * OP_LD; e += 256) (&Ps[0][0])[e] = 0.0;
-    __syncthreads();
-    // sum of the split partial sums, 8 loads in flight; a small slice shares its splits among
-    // `nsg` thread groups whose results are added in group order
-    const int nsg = (E < 256) ? 256 / E : 1;
-    const int sg = (E < 256) ? tid / E : 0;
-    for (int idx0 = 0; idx0 < E; idx0 += 256) {
-        const int idx = (E < 256) ? tid - sg * E : idx0 + tid;
-        const bool act = idx < E && sg < nsg;
-        const long long e = (long long)i0 * r + idx;
-        double s = 0.0;
-        if (act) {
-            for (int sp0 = sg; sp0 < jb.nsplit; sp0 += 16 * nsg) {      // 16 loads in flight
-                double t[16];
+    // Sum of the split partial sums.  A slice of 256 or more elements gives every thread ITS
+    // elements and SB splits per round; a smaller one shares its splits among `nsg` thread
+    // groups whose results are added in group order.  All loads of a round are in flight together.
+    constexpr int ITS = RM / 8, SB = 32 / ITS;
+    const bool small = E < 256;
+    const int nsg = small ? 256 / E : 1;
+    const int sg = small ? tid / E : 0;
+    const int idx0 = small ? tid - sg * E : tid;
+    const bool act0 = sg < nsg;
+    double sum[ITS];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    const int sp = sp0 + u * nsg;
-                    t[u] = ldg_f64(jb.part, (long long)sp * cnt + e, sp < jb.nsplit);
-                }
+    for (int it = 0; it < ITS; ++it) sum[it] = 0.0;
+    for (int sp0 = sg; sp0 < jb.nsplit; sp0 += SB * nsg) {
+        double t[SB][ITS];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) s += t[u];
+        for (int u = 0; u < SB; ++u)
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) {
+                const int sp = sp0 + u * nsg, idx = idx0 + 256 * it;
+                const bool ok = act0 && idx < E && (it == 0 || !small) && sp < jb.nsplit;
+                t[u][it] = ldg_f64(jb.part, (long long)sp * cnt + (long long)i0 * r + idx, ok);
             }
+#pragma unroll
+        for (int u = 0; u < SB; ++u)
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) sum[it] += t[u][it];
+    }
+    if (small && nsg > 1) {
+        if (act0) red[sg * E + idx0] = sum[0];
+        __syncthreads();
+        if (act0 && sg == 0) {
+            double s2 = 0.0;
+            for (int g2 = 0; g2 < nsg; ++g2) s2 += red[g2 * E + idx0];
+            sum[0] = s2;
         }
-        if (nsg > 1) {
-            if (act) red[sg * E + idx] = s;
-            __syncthreads();
-            if (act && sg == 0) {
-                s = 0.0;
-                for (int g2 = 0; g2 < nsg; ++g2) s += red[g2 * E + idx];
+    } else {
+        __syncthreads();      // the zero fill above is complete
+    }
+    if (act0 && sg == 0) {
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const int idx = idx0 + 256 * it;
+            if (idx < E && (it == 0 || !small)) {
+                jb.P64[(long long)i0 * r + idx] = sum[it];
+                Ps[idx / r][idx % r] = sum[it];
             }
-        }
-        if (act && sg == 0) {
-            jb.P64[e] = s;
-            Ps[idx / r][idx % r] = s;
         }
     }
     __syncthreads();
-    gram_from_lds(Ps, r, jb.Gpart + (long long)blk * r * r);
+    gram_from_lds(Ps, r, jb.Gpart + (long long)blk * ((r * (r + 1)) / 2));
 }
 
 // ---- chol -----------------------------------------------------------------------------------
-// Right-looking Cholesky of the symmetric matrix in Gs (order r <= RM) by ONE wave.  Lane j keeps
-// column j in registers; at step k every lane publishes its G[k][j] in `rowbuf`, reads the
-// pivot and the rest of row k back (LDS serves one wave's accesses in order, so no barrier is
-// needed), and updates its rows k+1.. with the rank-one term.  Row k is left unscaled:
-// on return Gs[k][j], k <= j, holds R[k][j] * R[k][k] and Gs[k][k] the pivot R[k][k]^2.
+__device__ __forceinline__ double bcast_lane(double x, int src) {      // src uniform
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), src);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), src);
+    return __hiloint2double(hi, lo);
+}
+
+// Right-looking Cholesky of the symmetric matrix in Gs (order r <= RM) by ONE wave, four pivots
+// per round.  Lane j keeps column j of the (symmetric) trailing matrix in registers, so row k of
+// the trailing matrix is lane k's column.  A round first eliminates its four pivots inside the
+// 4-row panel, fetching the few values it needs from their lanes, then every lane publishes its
+// four finished row entries in `rowbuf` (LDS serves one wave's accesses in order, so no barrier
+// is needed) and applies the rank-4 update to its rows below the panel.  Rows are left
+// unscaled: on return Gs[k][j], k <= j, holds R[k][j] * R[k][k] and Gs[k][k] the pivot R[k][k]^2.
+// `shift` is added to the diagonal on load.
 template <int RM>
-__device__ void chol_wave(double (*Gs)[OP_LD], double* rowbuf, int r, int* s_bad) {
+__device__ void chol_wave(double (*Gs)[OP_LD], double (*rowbuf)[4], int r, double shift, int* s_bad) {
     const int j = threadIdx.x;          // 0..63
     double col[RM];
 #pragma unroll
-    for (int a2 = 0; a2 < RM; ++a2) col[a2] = (j < r && a2 < r) ? Gs[a2][j] : 0.0;
+    for (int a2 = 0; a2 < RM; ++a2) {
+        double v = (a2 == j) ? 1.0 : 0.0;                 // identity padding beyond r
+        if (j < r && a2 < r) v = Gs[a2][j] + ((a2 == j) ? shift : 0.0);
+        col[a2] = v;
+    }
 #pragma unroll
-    for (int k = 0; k < RM; ++k) {
-        if (k < r) {
-            rowbuf[j] = col[k];
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-            double p = rowbuf[k];
-            if (!(p > 0.0)) {                       // zero or non-finite input
-                if (j == 0 && *s_bad == 0) *s_bad = k + 1;
-                p = 1.0;
-            }
-            double pinv = __builtin_amdgcn_rcp(p);
-            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);      // two Newton steps: full fp64 accuracy
-            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
-            const double f = col[k] * pinv;
+    for (int k0 = 0; k0 < RM; k0 += 4) {
+        if (k0 < r) {
+            double f[4];
 #pragma unroll
-            for (int a2 = k + 1; a2 < RM; ++a2) {
-                col[a2] = fma(-rowbuf[a2], f, col[a2]);
-                if (((a2 - k) & 15) == 0) __builtin_amdgcn_sched_barrier(0);   // keep at most 16 row values live
+            for (int kk = 0; kk < 4; ++kk) {
+                const int k = k0 + kk;
+                double p = bcast_lane(col[k], k);
+                if (!(p > 0.0)) {                       // zero or non-finite input
+                    if (j == 0 && *s_bad == 0) *s_bad = k + 1;
+                    p = 1.0;
+                }
+                double pinv = __builtin_amdgcn_rcp(p);
+                pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);      // two Newton steps: full fp64 accuracy
+                pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
+                f[kk] = col[k] * pinv;
+#pragma unroll
+                for (int a2 = k + 1; a2 < k0 + 4; ++a2) col[a2] = fma(-bcast_lane(col[a2], k), f[kk], col[a2]);
+                if (j == k) col[k] = p;                 // the pivot actually used
             }
-            if (j == k) col[k] = p;                 // the pivot actually used
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            if (k0 + 4 < RM) {
+                rowbuf[j][0] = col[k0]; rowbuf[j][1] = col[k0 + 1]; rowbuf[j][2] = col[k0 + 2]; rowbuf[j][3] = col[k0 + 3];
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+#pragma unroll
+                for (int a2 = k0 + 4; a2 < RM; ++a2) {
+                    double t = col[a2];
+                    t = fma(-rowbuf[a2][0], f[0], t);
+                    t = fma(-rowbuf[a2][1], f[1], t);
+                    t = fma(-rowbuf[a2][2], f[2], t);
+                    t = fma(-rowbuf[a2][3], f[3], t);
+                    col[a2] = t;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            }
         }
     }
 #pragma unroll
@@ -203,48 +248,65 @@ __global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int las
     __shared__ double Gs[OP_RMAX][OP_LD];
     __shared__ double dinv[OP_RMAX];
     __shared__ double rdiag[OP_RMAX];
-    __shared__ double rowbuf[64];
+    __shared__ double rowbuf[64][4];
     __shared__ double s_trace;
     __shared__ int s_bad;
     const OrthJob jb = a.job[blockIdx.x];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     if (tid == 0) s_bad = 0;
     STAMP(0);
-    for (int e = tid; e < r * r; e += 256) {
-        const int ga = e / r, gb = e - ga * r;
-        if (ga <= gb) {
-            double s = 0.0;
-            for (int b0 = 0; b0 < jb.nblk; b0 += 16) {        // 16 loads in flight
-                double t[16];
+    // sum of the slice Grams (packed upper triangles): ITS elements per thread, SB slices per
+    // round, all ITS * SB loads of a round in flight together
+    constexpr int ITS = (RM * (RM + 1) / 2 + 255) / 256;
+    constexpr int SB = (32 / ITS) < 1 ? 1 : (32 / ITS);
+    const int T = (r * (r + 1)) / 2;
+    double sum[ITS];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) t[u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, b0 + u < jb.nblk);
+    for (int it = 0; it < ITS; ++it) sum[it] = 0.0;
+    for (int b0 = 0; b0 < jb.nblk; b0 += SB) {
+        double t[SB][ITS];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) s += t[u];
+        for (int u = 0; u < SB; ++u)
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) {
+                const int e = tid + 256 * it;
+                t[u][it] = ldg_f64(jb.Gpart, (long long)(b0 + u) * T + e, e < T && b0 + u < jb.nblk);
             }
-            Gs[ga][gb] = s;
-            Gs[gb][ga] = s;
+#pragma unroll
+        for (int u = 0; u < SB; ++u)
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) sum[it] += t[u][it];
+    }
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+        const int e = tid + 256 * it;
+        if (e < T) {
+            // row ga of the packed triangle: largest ga with tri_idx(r, ga, ga) <= e
+            int ga = (int)(((2 * r + 1) - sqrtf((float)((2 * r + 1) * (2 * r + 1) - 8 * e))) * 0.5f);
+            ga = ga < 0 ? 0 : (ga > r - 1 ? r - 1 : ga);
+            while (ga > 0 && tri_idx(r, ga, ga) > e) --ga;
+            while (ga + 1 < r && tri_idx(r, ga + 1, ga + 1) <= e) ++ga;
+            const int gb = ga + (e - tri_idx(r, ga, ga));
+            Gs[ga][gb] = sum[it];
+            Gs[gb][ga] = sum[it];
         }
     }
     __syncthreads();
     STAMP(1);
-    if (pass == 0) {
-        if (tid == 0) {
-            double tr = 0.0;
-            for (int k = 0; k < r; ++k) tr += Gs[k][k];
-            s_trace = tr;
-            jb.scal[0] = tr;
-        }
-        __syncthreads();
-        const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * s_trace;
-        if (tid < r) Gs[tid][tid] += shift;
-        __syncthreads();
-    } else if (tid == 0) {
-        s_trace = jb.scal[0];
-    }
-    STAMP(2);
-    // right-looking Cholesky by wave 0 alone, lane j holding column j in registers (see chol_wave)
+    // wave 0: trace, shift (first pass), factorisation
     if (tid < 64) {
-        chol_wave<RM>(Gs, rowbuf, r, &s_bad);      // RM >= r for every mode of the launch
+        double shift = 0.0;
+        if (pass == 0) {
+            double tr = (tid < r) ? Gs[tid][tid] : 0.0;
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) tr += __shfl_xor(tr, m);
+            if (tid == 0) { s_trace = tr; jb.scal[0] = tr; }
+            shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * tr;
+        } else if (tid == 0) {
+            s_trace = jb.scal[0];
+        }
+        STAMP(2);
+        chol_wave<RM>(Gs, rowbuf, r, shift, &s_bad);      // RM >= r for every mode of the launch
     }
     __syncthreads();
     STAMP(3);
@@ -282,21 +344,28 @@ __global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int las
         for (int j = 0; j < 16; ++j) jb.Dinv[(b * 16 + i) * 16 + j] = x[j];
     }
     STAMP(5);
-    if (tid == 0) {
-        double bad = (pass == 0) ? 0.0 : jb.scal[65];
-        if (bad == 0.0 && s_bad) bad = (double)s_bad;
-        jb.scal[65] = bad;
-        if (last && a.info) {
-            if (bad != 0.0) flag_info(a.info, jb.mode1, (int)bad);
-            const double floor_ = 1e-12 * sqrt(s_trace);
-            for (int k = 0; k < r; ++k)
-                if (!(rdiag[k] > floor_)) { flag_info(a.info, jb.mode1, k + 1); break; }
+    if (tid < 64) {
+        // first column (if any) whose accumulated R diagonal fell to the noise floor
+        const double floor_ = 1e-12 * sqrt(s_trace);
+        const bool low = tid < r && !(rdiag[tid] > floor_);
+        const unsigned long long mask = __ballot(low);
+        if (tid == 0) {
+            double bad = (pass == 0) ? 0.0 : jb.scal[65];
+            if (bad == 0.0 && s_bad) bad = (double)s_bad;
+            jb.scal[65] = bad;
+            if (last && a.info) {
+                if (bad != 0.0) flag_info(a.info, jb.mode1, (int)bad);
+                if (mask) flag_info(a.info, jb.mode1, __ffsll((long long)mask));
+            }
         }
     }
 }
 
 // ---- apply ----------------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void k_orth_apply(OrthArgs a, int final_pass) {
+// 256 threads load the slice, R and the diagonal-block inverses in one round of loads; waves 0 and 1
+// then solve 16 rows each.
+template <int RM>
+__global__ __launch_bounds__(256) void k_orth_apply(OrthArgs a, int final_pass) {
     __shared__ double Ps[OP_RS][OP_LD];
     __shared__ double Rs[OP_RMAX][OP_LD];
     __shared__ double Ds[OP_RMAX / 16][16][17];
@@ -308,65 +377,76 @@ __global__ __launch_bounds__(128) void k_orth_apply(OrthArgs a, int final_pass) 
     const int nb = (r + 15) / 16;
     const int i0 = blk * OP_RS;
     const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
-    for (int e = tid; e < OP_RS * OP_LD; e += 128) (&Ps[0][0])[e] = 0.0;
-    for (int e = tid; e < OP_RMAX * OP_LD; e += 128) (&Rs[0][0])[e] = 0.0;
-    __syncthreads();
-    for (int idx0 = 0; idx0 < nrows * r; idx0 += 128 * 8) {
-        double t[8];
+    constexpr int PI = RM / 8, RI = RM * RM / 256, DI = RM / 16;
+    double tp[PI], tr[RI], td[DI];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int idx = idx0 + u * 128 + tid;
-            t[u] = ldg_f64(jb.P64, (long long)i0 * r + idx, idx < nrows * r);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int idx = idx0 + u * 128 + tid;
-            if (idx < nrows * r) Ps[idx / r][idx % r] = t[u];
-        }
+    for (int u = 0; u < PI; ++u) {
+        const int idx = u * 256 + tid;
+        tp[u] = ldg_f64(jb.P64, (long long)i0 * r + idx, idx < nrows * r);
     }
-    for (int e0 = 0; e0 < r * r; e0 += 128 * 8) {
-        double t[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int e = e0 + u * 128 + tid;
-            t[u] = ldg_f64(jb.R, e, e < r * r);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int e = e0 + u * 128 + tid;
-            if (e < r * r) Rs[e / r][e % r] = t[u];
-        }
+    for (int u = 0; u < RI; ++u) {
+        const int e = u * 256 + tid;
+        tr[u] = ldg_f64(jb.R, e, e < r * r);
     }
-    for (int e = tid; e < nb * 256; e += 128) Ds[e >> 8][(e >> 4) & 15][e & 15] = jb.Dinv[e];
+#pragma unroll
+    for (int u = 0; u < DI; ++u) {
+        const int e = u * 256 + tid;
+        td[u] = ldg_f64(jb.Dinv, e, e < nb * 256);
+    }
+    for (int e = tid; e < OP_RS * OP_LD; e += 256) (&Ps[0][0])[e] = 0.0;
+    for (int e = tid; e < OP_RMAX * OP_LD; e += 256) (&Rs[0][0])[e] = 0.0;
     __syncthreads();
-    // wave w owns rows 16w..16w+15 of the slice; block columns are solved left to right
-    const int rw = 16 * wave;
+#pragma unroll
+    for (int u = 0; u < PI; ++u) {
+        const int idx = u * 256 + tid;
+        if (idx < nrows * r) Ps[idx / r][idx % r] = tp[u];
+    }
+#pragma unroll
+    for (int u = 0; u < RI; ++u) {
+        const int e = u * 256 + tid;
+        if (e < r * r) Rs[e / r][e % r] = tr[u];
+    }
+#pragma unroll
+    for (int u = 0; u < DI; ++u) {
+        const int e = u * 256 + tid;
+        if (e < nb * 256) Ds[e >> 8][(e >> 4) & 15][e & 15] = td[u];
+    }
+    __syncthreads();
+    // wave w < 2 owns rows 16w..16w+15 of the slice; block columns are solved left to right
+    const int rw = 16 * (wave & 1);
     for (int b = 0; b < nb; ++b) {
-        // T = P_b - sum_{a<b} Q_a R_ab
-        v4d acc = {0.0, 0.0, 0.0, 0.0};
-        for (int ab = 0; ab < b; ++ab)
+        if (wave < 2) {
+            // T = P_b - sum_{a<b} Q_a R_ab
+            v4d acc = {0.0, 0.0, 0.0, 0.0};
+            for (int ab = 0; ab < b; ++ab)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[rw + ll][16 * ab + 4 * ks + lg],
+                                                               Rs[16 * ab + 4 * ks + lg][16 * b + ll], acc, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Ps[rw + lg + 4 * v][16 * b + ll] -= acc[v];
+        }
+        __syncthreads();
+        v4d q = {0.0, 0.0, 0.0, 0.0};
+        if (wave < 2) {
+            // Q_b = T R_bb^-1
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
-                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[rw + ll][16 * ab + 4 * ks + lg],
-                                                           Rs[16 * ab + 4 * ks + lg][16 * b + ll], acc, 0, 0, 0);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) Ps[rw + lg + 4 * v][16 * b + ll] -= acc[v];
+                q = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[rw + ll][16 * b + 4 * ks + lg], Ds[b][4 * ks + lg][ll], q, 0, 0, 0);
+        }
         __syncthreads();
-        // Q_b = T R_bb^-1
-        v4d q = {0.0, 0.0, 0.0, 0.0};
+        if (wave < 2) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            q = __builtin_amdgcn_mfma_f64_16x16x4f64(Ps[rw + ll][16 * b + 4 * ks + lg], Ds[b][4 * ks + lg][ll], q, 0, 0, 0);
-        __syncthreads();
-#pragma unroll
-        for (int v = 0; v < 4; ++v) Ps[rw + lg + 4 * v][16 * b + ll] = q[v];
+            for (int v = 0; v < 4; ++v) Ps[rw + lg + 4 * v][16 * b + ll] = q[v];
+        }
         __syncthreads();
     }
     if (final_pass) {
-        for (int idx = tid; idx < nrows * r; idx += 128) jb.Uout[(long long)i0 * r + idx] = (float)Ps[idx / r][idx % r];
+        for (int idx = tid; idx < nrows * r; idx += 256) jb.Uout[(long long)i0 * r + idx] = (float)Ps[idx / r][idx % r];
     } else {
-        for (int idx = tid; idx < nrows * r; idx += 128) jb.P64[(long long)i0 * r + idx] = Ps[idx / r][idx % r];
-        gram_from_lds(Ps, r, jb.Gpart + (long long)blk * r * r);
+        for (int idx = tid; idx < nrows * r; idx += 256) jb.P64[(long long)i0 * r + idx] = Ps[idx / r][idx % r];
+        gram_from_lds(Ps, r, jb.Gpart + (long long)blk * ((r * (r + 1)) / 2));
     }
 }
 
@@ -743,27 +823,42 @@ static bool fast_args_ok(const OrthArgs& a) {
     }
     return true;
 }
+// register shape of a launch: the largest rank among its modes, rounded up to 16
+static int rank_class(const OrthArgs& a) {
+    int rmax = 0;
+    for (int j = 0; j < a.njobs; ++j) rmax = a.job[j].r > rmax ? a.job[j].r : rmax;
+    return rmax <= 16 ? 16 : (rmax <= 32 ? 32 : (rmax <= 48 ? 48 : 64));
+}
 hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st) {
     if (!fast_args_ok(a)) return hipErrorInvalidValue;
-    set_last_label("k_orth_gram0");
-    hipLaunchKernelGGL(k_orth_gram0, dim3(total_blocks(a)), 256, 0, st, a);
+    const int rm = rank_class(a);
+    set_last_label("k_orth_gram0<%d>", rm);
+    const dim3 grid(total_blocks(a));
+    if (rm == 16) hipLaunchKernelGGL(k_orth_gram0<16>, grid, 256, 0, st, a);
+    else if (rm == 32) hipLaunchKernelGGL(k_orth_gram0<32>, grid, 256, 0, st, a);
+    else if (rm == 48) hipLaunchKernelGGL(k_orth_gram0<48>, grid, 256, 0, st, a);
+    else hipLaunchKernelGGL(k_orth_gram0<64>, grid, 256, 0, st, a);
     return hipGetLastError();
 }
 hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t st) {
     if (!fast_args_ok(a)) return hipErrorInvalidValue;
-    int rmax = 0;
-    for (int j = 0; j < a.njobs; ++j) rmax = a.job[j].r > rmax ? a.job[j].r : rmax;
-    set_last_label("k_orth_chol<%d>", rmax <= 16 ? 16 : (rmax <= 32 ? 32 : (rmax <= 48 ? 48 : 64)));
-    if (rmax <= 16) hipLaunchKernelGGL(k_orth_chol<16>, dim3(a.njobs), 256, 0, st, a, pass, last);
-    else if (rmax <= 32) hipLaunchKernelGGL(k_orth_chol<32>, dim3(a.njobs), 256, 0, st, a, pass, last);
-    else if (rmax <= 48) hipLaunchKernelGGL(k_orth_chol<48>, dim3(a.njobs), 256, 0, st, a, pass, last);
+    const int rm = rank_class(a);
+    set_last_label("k_orth_chol<%d>", rm);
+    if (rm == 16) hipLaunchKernelGGL(k_orth_chol<16>, dim3(a.njobs), 256, 0, st, a, pass, last);
+    else if (rm == 32) hipLaunchKernelGGL(k_orth_chol<32>, dim3(a.njobs), 256, 0, st, a, pass, last);
+    else if (rm == 48) hipLaunchKernelGGL(k_orth_chol<48>, dim3(a.njobs), 256, 0, st, a, pass, last);
     else hipLaunchKernelGGL(k_orth_chol<64>, dim3(a.njobs), 256, 0, st, a, pass, last);
     return hipGetLastError();
 }
 hipError_t launch_orth_apply(const OrthArgs& a, int final_pass, hipStream_t st) {
     if (!fast_args_ok(a)) return hipErrorInvalidValue;
-    set_last_label("k_orth_apply");
-    hipLaunchKernelGGL(k_orth_apply, dim3(total_blocks(a)), 128, 0, st, a, final_pass);
+    const int rm = rank_class(a);
+    set_last_label("k_orth_apply<%d>", rm);
+    const dim3 grid(total_blocks(a));
+    if (rm == 16) hipLaunchKernelGGL(k_orth_apply<16>, grid, 256, 0, st, a, final_pass);
+    else if (rm == 32) hipLaunchKernelGGL(k_orth_apply<32>, grid, 256, 0, st, a, final_pass);
+    else if (rm == 48) hipLaunchKernelGGL(k_orth_apply<48>, grid, 256, 0, st, a, final_pass);
+    else hipLaunchKernelGGL(k_orth_apply<64>, grid, 256, 0, st, a, final_pass);
     return hipGetLastError();
 }
 bool orth_wide_supported(int r) { return r > OP_RMAX && r <= OW_RMAX; }
