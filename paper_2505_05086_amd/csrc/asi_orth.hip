@@ -183,82 +183,121 @@ __device__ __forceinline__ double bcast_lane(double x, int src) {      // src un
     return __hiloint2double(hi, lo);
 }
 
-// Right-looking Cholesky of the symmetric matrix in Gs (order r <= RM) by ONE wave, four pivots
-// per round.  Lane j keeps column j of the (symmetric) trailing matrix in registers, so row k of
-// the trailing matrix is lane k's column.  A round first eliminates its four pivots inside the
-// 4-row panel, fetching the few values it needs from their lanes, then every lane publishes its
-// four finished row entries in `rowbuf` (LDS serves one wave's accesses in order, so no barrier
-// is needed) and applies the rank-4 update to its rows below the panel.  Rows are left
-// unscaled: on return Gs[k][j], k <= j, holds R[k][j] * R[k][k] and Gs[k][k] the pivot R[k][k]^2.
-// `shift` is added to the diagonal on load.
-template <int RM>
-__device__ void chol_wave(double (*Gs)[OP_LD], double (*rowbuf)[4], int r, double shift, int* s_bad) {
+// Cholesky of the 16x16 diagonal block of Gs at `base` by ONE wave, four pivots per round.
+// Lane j < 16 keeps column j of the (symmetric) trailing block in registers, so row k of the
+// trailing block is lane k's column.  A round eliminates its four pivots inside the 4-row
+// panel, fetching the few values it needs from their lanes; every lane then publishes its four
+// finished row entries in `rowbuf` (LDS serves one wave's accesses in order, so no barrier is
+// needed) and applies the rank-4 update to its rows below the panel.  The rows of the next
+// panel are updated first, so that the next panel's chain of reciprocals is independent of the
+// rest of the update and the two are interleaved.  The code is branch free; a non-positive
+// pivot is replaced by 1 and reported through `bad` (1-based index, first one wins).
+// Rows are left unscaled: on return Gs[base+k][base+j], k <= j, holds R[k][j] * R[k][k], the
+// diagonal the pivots R[k][k]^2, and pinvs[base+k] their reciprocals.
+// Lanes 48..63 carry the columns of an identity block through the same row operations, which
+// leaves the inverse of the block's unit lower triangular factor in Xb[i][j] = (L^-1)[j][i].
+#ifdef ASI_DEBUG_TIMING
+#define BSTAMP(i) do { if (dbg && threadIdx.x == 0) g_orth_stamps[i] = wall_clock64(); } while (0)
+#else
+#define BSTAMP(i) do {} while (0)
+#endif
+__device__ void chol_block16(double (*Gs)[OP_LD], double (*rowbuf)[64][4], double (*Xb)[17], double* pinvs, int base,
+                             int* bad_io, bool dbg = false) {
     const int j = threadIdx.x;          // 0..63
-    double col[RM];
+    BSTAMP(20);
+    const bool xl = j >= 48;            // identity lane
+    double col[16];
 #pragma unroll
-    for (int a2 = 0; a2 < RM; ++a2) {
-        double v = (a2 == j) ? 1.0 : 0.0;                 // identity padding beyond r
-        if (j < r && a2 < r) v = Gs[a2][j] + ((a2 == j) ? shift : 0.0);
-        col[a2] = v;
+    for (int a2 = 0; a2 < 16; ++a2) {
+        const double g = Gs[base + a2][base + (j & 15)];
+        col[a2] = xl ? ((a2 == j - 48) ? 1.0 : 0.0) : (j < 16 ? g : 0.0);
     }
-#pragma unroll
-    for (int k0 = 0; k0 < RM; k0 += 4) {
-        if (k0 < r) {
-            double f[4];
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int k = k0 + kk;
-                double p = bcast_lane(col[k], k);
-                if (!(p > 0.0)) {                       // zero or non-finite input
-                    if (j == 0 && *s_bad == 0) *s_bad = k + 1;
-                    p = 1.0;
-                }
-                double pinv = __builtin_amdgcn_rcp(p);
-                pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);      // two Newton steps: full fp64 accuracy
-                pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
-                f[kk] = col[k] * pinv;
-#pragma unroll
-                for (int a2 = k + 1; a2 < k0 + 4; ++a2) col[a2] = fma(-bcast_lane(col[a2], k), f[kk], col[a2]);
-                if (j == k) col[k] = p;                 // the pivot actually used
-            }
-            if (k0 + 4 < RM) {
-                rowbuf[j][0] = col[k0]; rowbuf[j][1] = col[k0 + 1]; rowbuf[j][2] = col[k0 + 2]; rowbuf[j][3] = col[k0 + 3];
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-#pragma unroll
-                for (int a2 = k0 + 4; a2 < RM; ++a2) {
-                    double t = col[a2];
-                    t = fma(-rowbuf[a2][0], f[0], t);
-                    t = fma(-rowbuf[a2][1], f[1], t);
-                    t = fma(-rowbuf[a2][2], f[2], t);
-                    t = fma(-rowbuf[a2][3], f[3], t);
-                    col[a2] = t;
-                }
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-            }
-        }
+    int bad = *bad_io;
+    double f[4];
+    BSTAMP(21);
+#define ASI_CHOL_PANEL(K0, F)                                                                       \
+    {                                                                                               \
+        _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                          \
+            const int k = (K0) + kk;                                                                \
+            double p = bcast_lane(col[k], k);                                                       \
+            const bool okp = p > 0.0;                /* false for zero, negative, NaN */            \
+            bad = (!okp && bad == 0) ? base + k + 1 : bad;                                          \
+            p = okp ? p : 1.0;                                                                      \
+            double pinv = __builtin_amdgcn_rcp(p);                                                  \
+            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);   /* two Newton steps: full accuracy */     \
+            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);                                             \
+            F[kk] = col[k] * pinv;                                                                  \
+            _Pragma("unroll") for (int a2 = k + 1; a2 < (K0) + 4; ++a2)                             \
+                col[a2] = fma(-bcast_lane(col[a2], k), F[kk], col[a2]);                             \
+            if (j == k) { col[k] = p; pinvs[base + k] = pinv; }   /* the pivot actually used */     \
+        }                                                                                           \
     }
+#define ASI_CHOL_UPDATE(A_LO, A_HI, RB)                                                             \
+    {                                                                                               \
+        _Pragma("unroll") for (int a0 = (A_LO); a0 < (A_HI); a0 += 4) {                             \
+            double w[4][4];                                                                         \
+            _Pragma("unroll") for (int g = 0; g < 4; ++g)                                           \
+                _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) w[g][kk] = RB[a0 + g][kk];         \
+            _Pragma("unroll") for (int kk = 0; kk < 4; ++kk)                                        \
+                _Pragma("unroll") for (int g = 0; g < 4; ++g)                                       \
+                    col[a0 + g] = fma(-w[g][kk], f[kk], col[a0 + g]);                               \
+        }                                                                                           \
+    }
+    ASI_CHOL_PANEL(0, f)
+    BSTAMP(22);
 #pragma unroll
-    for (int k = 0; k < RM; ++k)
-        if (k < r && j < r && k <= j) Gs[k][j] = col[k];
+    for (int k0 = 0; k0 + 4 < 16; k0 += 4) {
+        BSTAMP(23 + (k0 >> 2));
+        double (*rb)[4] = rowbuf[(k0 >> 2) & 1];
+        rb[j][0] = col[k0]; rb[j][1] = col[k0 + 1]; rb[j][2] = col[k0 + 2]; rb[j][3] = col[k0 + 3];
+        ASI_CHOL_UPDATE(k0 + 4, k0 + 8, rb)
+        double fn[4];
+        ASI_CHOL_PANEL(k0 + 4, fn)
+        ASI_CHOL_UPDATE(k0 + 8, 16, rb)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) f[kk] = fn[kk];
+    }
+#undef ASI_CHOL_PANEL
+#undef ASI_CHOL_UPDATE
+    BSTAMP(26);
+    *bad_io = bad;
+    if (xl) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) Xb[j - 48][q] = col[q];
+    }
+    if (j < 16) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (k <= j) Gs[base + k][base + j] = col[k];
+    }
+    BSTAMP(27);
 }
 
-// scal[0] = trace(P^T P), scal[1 + k] = running product of the R diagonals, scal[65] = first bad pivot
+// Blocked right-looking Cholesky of the matrix in Gs (identity padded to a multiple of 16):
+// wave 0 factors a diagonal block, then the four waves solve that block row and update the
+// trailing blocks with fp64 MFMA.  scal[0] = trace(P^T P), scal[1 + k] = running product of the
+// R diagonals, scal[65] = first bad pivot.
 template <int RM>
 __global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int last) {
     __shared__ double Gs[OP_RMAX][OP_LD];
     __shared__ double dinv[OP_RMAX];
     __shared__ double rdiag[OP_RMAX];
-    __shared__ double rowbuf[64][4];
+    __shared__ double pinvs[OP_RMAX];
+    __shared__ double rowbuf[2][64][4];
+    __shared__ double Xs[OP_RMAX / 16][16][17];
     __shared__ double s_trace;
     __shared__ int s_bad;
     const OrthJob jb = a.job[blockIdx.x];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
-    if (tid == 0) s_bad = 0;
+    const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
+    const int nb = (r + 15) / 16;
     STAMP(0);
+    // identity everywhere first, so that the padding up to a multiple of 16 needs no special case
+    for (int e = tid; e < OP_RMAX * 64; e += 256) Gs[e >> 6][e & 63] = ((e >> 6) == (e & 63)) ? 1.0 : 0.0;
     // sum of the slice Grams (packed upper triangles): ITS elements per thread, SB slices per
     // round, all ITS * SB loads of a round in flight together
     constexpr int ITS = (RM * (RM + 1) / 2 + 255) / 256;
-    constexpr int SB = (32 / ITS) < 1 ? 1 : (32 / ITS);
+    constexpr int SB = (96 / ITS) > 16 ? 16 : (96 / ITS);
     const int T = (r * (r + 1)) / 2;
     double sum[ITS];
 #pragma unroll
@@ -277,6 +316,7 @@ __global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int las
 #pragma unroll
             for (int it = 0; it < ITS; ++it) sum[it] += t[u][it];
     }
+    __syncthreads();
 #pragma unroll
     for (int it = 0; it < ITS; ++it) {
         const int e = tid + 256 * it;
@@ -293,22 +333,67 @@ __global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int las
     }
     __syncthreads();
     STAMP(1);
-    // wave 0: trace, shift (first pass), factorisation
-    if (tid < 64) {
-        double shift = 0.0;
+    int bad = 0;
+    if (wave == 0) {
+        // trace and diagonal shift (first pass)
         if (pass == 0) {
-            double tr = (tid < r) ? Gs[tid][tid] : 0.0;
+            const double g = (lane < r) ? Gs[lane][lane] : 0.0;
+            double tr = g;
 #pragma unroll
             for (int m = 32; m >= 1; m >>= 1) tr += __shfl_xor(tr, m);
-            if (tid == 0) { s_trace = tr; jb.scal[0] = tr; }
-            shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * tr;
-        } else if (tid == 0) {
+            if (lane == 0) { s_trace = tr; jb.scal[0] = tr; }
+            const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * tr;
+            if (lane < r) Gs[lane][lane] = g + shift;
+        } else if (lane == 0) {
             s_trace = jb.scal[0];
         }
-        STAMP(2);
-        chol_wave<RM>(Gs, rowbuf, r, shift, &s_bad);      // RM >= r for every mode of the launch
     }
-    __syncthreads();
+    STAMP(2);
+    for (int P = 0; P < nb; ++P) {
+#ifdef ASI_DEBUG_TIMING
+        if (wave == 0) chol_block16(Gs, rowbuf, Xs[P], pinvs, 16 * P, &bad, P == 0 && jb.mode1 == 2 && pass == 0);
+#else
+        if (wave == 0) chol_block16(Gs, rowbuf, Xs[P], pinvs, 16 * P, &bad);
+#endif
+        if (P == 0) STAMP(6);
+        __syncthreads();
+        if (P == 0) STAMP(7);
+        if (P + 1 < nb) {
+            // block row P right of the diagonal:  U_PJ = L_PP^-1 G_PJ   (unscaled rows, like the diagonal block)
+            for (int J = P + 1 + wave; J < nb; J += 4) {
+                double bv[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) bv[ks] = Gs[16 * P + 4 * ks + lg][16 * J + ll];
+                v4d acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)      // A[i][k] = (L^-1)[i][k] = Xs[P][k][i]
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Xs[P][4 * ks + lg][ll], bv[ks], acc, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) Gs[16 * P + lg + 4 * v][16 * J + ll] = acc[v];
+            }
+            __syncthreads();
+            if (P == 0) STAMP(8);
+            // trailing blocks:  G_IJ -= U_PI^T diag(1/pivot) U_PJ,  P < I <= J
+            int cnt = 0;
+            for (int I = P + 1; I < nb; ++I)
+                for (int J = I; J < nb; ++J, ++cnt) {
+                    if ((cnt & 3) != wave) continue;
+                    v4d acc;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[v] = Gs[16 * I + lg + 4 * v][16 * J + ll];
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) {
+                        const int k = 16 * P + 4 * ks + lg;
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-Gs[k][16 * I + ll], Gs[k][16 * J + ll] * pinvs[k], acc, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Gs[16 * I + lg + 4 * v][16 * J + ll] = acc[v];
+                }
+            __syncthreads();
+            if (P == 0) STAMP(9);
+        }
+    }
+    if (tid == 0) s_bad = bad;
     STAMP(3);
     if (tid < r) {
         double p = Gs[tid][tid];
@@ -320,28 +405,21 @@ __global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int las
         jb.scal[1 + tid] = rd;
     }
     __syncthreads();
-    for (int e = tid; e < r * r; e += 256) {
-        const int ga = e / r, gb = e - ga * r;
-        const double v = (ga < gb) ? Gs[ga][gb] * dinv[ga] : (ga == gb ? 1.0 / dinv[ga] : 0.0);
-        if (ga < gb) Gs[ga][gb] = v;
-        jb.R[e] = v;                              // R, zeros below the diagonal
-    }
-    __syncthreads();
-    STAMP(4);
-    // inverse of each 16x16 diagonal block: row i of X solves X R_bb = I
-    const int nb = (r + 15) / 16;
-    if (tid < nb * 16) {
-        const int b = tid >> 4, i = tid & 15, base = 16 * b;
-        double x[16];
+    {   // R = rows scaled by 1 / R[k][k], zeros below the diagonal
+        const int gb = tid & 63;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            double s = (j == i) ? 1.0 : 0.0;
-#pragma unroll
-            for (int k = 0; k < j; ++k) s = fma(-x[k], (base + j < r) ? Gs[base + k][base + j] : 0.0, s);
-            x[j] = (j >= i && base + j < r && base + i < r) ? s * dinv[base + j] : 0.0;
+        for (int it = 0; it < RM / 4; ++it) {
+            const int ga = (tid >> 6) + 4 * it;
+            if (ga < r && gb < r)
+                jb.R[ga * r + gb] = (ga < gb) ? Gs[ga][gb] * dinv[ga] : (ga == gb ? 1.0 / dinv[ga] : 0.0);
         }
-#pragma unroll
-        for (int j = 0; j < 16; ++j) jb.Dinv[(b * 16 + i) * 16 + j] = x[j];
+    }
+    STAMP(4);
+    // inverse of each 16x16 diagonal block of R:  (R_bb^-1)[i][j] = (L_bb^-1)[j][i] / R[j][j]
+    for (int e = tid; e < nb * 256; e += 256) {
+        const int b = e >> 8, i = (e >> 4) & 15, jj = e & 15, base = 16 * b;
+        const bool in = base + i < r && base + jj < r && jj >= i;
+        jb.Dinv[e] = in ? Xs[b][i][jj] * dinv[base + jj] : 0.0;
     }
     STAMP(5);
     if (tid < 64) {
@@ -350,11 +428,11 @@ __global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int las
         const bool low = tid < r && !(rdiag[tid] > floor_);
         const unsigned long long mask = __ballot(low);
         if (tid == 0) {
-            double bad = (pass == 0) ? 0.0 : jb.scal[65];
-            if (bad == 0.0 && s_bad) bad = (double)s_bad;
-            jb.scal[65] = bad;
+            double badv = (pass == 0) ? 0.0 : jb.scal[65];
+            if (badv == 0.0 && s_bad) badv = (double)s_bad;
+            jb.scal[65] = badv;
             if (last && a.info) {
-                if (bad != 0.0) flag_info(a.info, jb.mode1, (int)bad);
+                if (badv != 0.0) flag_info(a.info, jb.mode1, (int)badv);
                 if (mask) flag_info(a.info, jb.mode1, __ffsll((long long)mask));
             }
         }
