@@ -57,6 +57,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, help="workload (1-5), default the ResNet-18 tail")
     ap.add_argument("--distinct", type=int, default=8, help="distinct input steps kept in HBM and cycled")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams the layers are spread over (0 = one per layer)")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="1: all layers of a step go through the batched entry points (every launch serves all layers); "
+                         "0: one call chain per layer, spread over --streams")
     ap.add_argument("--graph", type=int, default=1, help="replay each step from a captured HIP graph (1) or launch eagerly (0)")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB ten times (calibrates rocprofv3 byte counters)")
@@ -110,7 +113,7 @@ def main():
 
     import paper_2505_05086_amd as asi
     from asi_inputs import CONFIGS, LayerStream
-    from paper_2505_05086_amd.runner import LayerRunner
+    from paper_2505_05086_amd.runner import BatchRunner, LayerRunner
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -118,7 +121,13 @@ def main():
     torch.cuda.set_device(0)
     cfg = CONFIGS[args.config]
     streams = [LayerStream(cfg.index, li, lay, cfg.theta) for li, lay in enumerate(cfg.layers)]
-    runners = [LayerRunner(lay) for lay in cfg.layers]
+    batches = None
+    if args.batch:
+        mb = asi.binding.MAX_BATCH
+        batches = [BatchRunner(cfg.layers[i:i + mb]) for i in range(0, len(cfg.layers), mb)]
+        runners = [r for b in batches for r in b.runs]
+    else:
+        runners = [LayerRunner(lay) for lay in cfg.layers]
     ndist = max(1, min(args.distinct, cfg.steps if cfg.steps > 1 else args.distinct))
     if args.graph and ndist > 1:
         ndist -= ndist % 2          # the captured steps alternate the two factor buffers
@@ -136,11 +145,23 @@ def main():
     # The layers of one step are independent jobs: each gets its own workspace and they are
     # spread over side streams (default priority) that fork from / join the main stream.
     nstreams = len(runners) if args.streams <= 0 else min(args.streams, len(runners))
+    if batches is not None:
+        nstreams = 1
     main_stream = torch.cuda.current_stream()
     side = [torch.cuda.Stream() for _ in range(nstreams)] if nstreams > 1 else [None]
 
+    def batched_step(a, g):
+        i = 0
+        for b in batches:
+            n = len(b.runs)
+            b.step(a[i:i + n], g[i:i + n])
+            i += n
+
     def one_step(k):
         a, g = A_dev[k % ndist], dY_dev[k % ndist]
+        if batches is not None:
+            batched_step(a, g)
+            return
         cur = torch.cuda.current_stream()
         if nstreams > 1:
             for s in side:
@@ -205,8 +226,11 @@ def main():
     nprof = min(args.steps, 10)
     for k in range(nprof):
         a_, g_ = A_dev[k % ndist], dY_dev[k % ndist]
-        for r, at, gt in zip(runners, a_, g_):
-            r.step(at, gt)
+        if batches is not None:
+            batched_step(a_, g_)
+        else:
+            for r, at, gt in zip(runners, a_, g_):
+                r.step(at, gt)
     torch.cuda.synchronize()
     rep = asi.asi_profile_report()
     asi.asi_profile_enable(False)
@@ -249,7 +273,7 @@ def main():
             f"{'x'.join(map(str, l.dims))} r{'/'.join(map(str, l.ranks))}" for l in cfg.layers),
             "layers": len(cfg.layers), "raw_activation_bytes_per_step": act_bytes,
             "distinct_input_steps_in_hbm": ndist, "phases": "compress+core_project+weight_grad",
-            "streams": nstreams, "hip_graph": bool(args.graph)},
+            "batched_launches": bool(args.batch), "streams": nstreams, "hip_graph": bool(args.graph)},
         "roofline": roof,
         "kernel_breakdown": breakdown,
         "gpu_ms_per_step_events": gpu_ms / args.steps,

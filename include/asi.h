@@ -126,6 +126,37 @@ asi_status asi_weight_grad_linear(const asi_tensor_desc* desc, const float* S,
                                   int64_t dout, float* dW, int accumulate,
                                   void* ws, size_t ws_bytes, asi_stream_t stream);
 
+/* Batched forms of the four operations above: the same computation for `count` layers
+ * (1 <= count <= 8) in as many kernel launches as ONE layer needs, because every kernel
+ * serves the argument blocks of all layers side by side (launches of different layers are
+ * merged when they use the same kernel; layers of one network stage usually do).  Per-step
+ * cost on MI355X is dominated by the number of dependent launches, not by their size.
+ * Every array argument is a HOST array of length count whose element l holds what the
+ * single-layer call takes for layer l (descs and convs are arrays of structs; accumulate may
+ * be NULL = all zero; info may be NULL or hold NULL entries).  Each layer has its own
+ * workspace.  The factors are bit-identical to those of `count` single-layer calls; the core
+ * projection may take its m-mode products in another order (one order for the whole batch, so
+ * that the layers' products share launches), which changes S and dW at rounding level only.
+ * If any layer's arguments are rejected nothing is enqueued and that status is returned;
+ * count outside the range gives ASI_ERR_UNSUPPORTED. */
+asi_status asi_compress_batch(int32_t count, const asi_tensor_desc* descs, const void* const* A,
+                              const float* const* const* U_prev, float* const* const* U_out,
+                              void* const* ws, const size_t* ws_bytes, int32_t* const* info,
+                              asi_stream_t stream);
+asi_status asi_core_project_batch(int32_t count, const asi_tensor_desc* descs, const void* const* A,
+                                  const float* const* const* U, float* const* S,
+                                  void* const* ws, const size_t* ws_bytes, asi_stream_t stream);
+asi_status asi_weight_grad_conv2d_batch(int32_t count, const asi_tensor_desc* descs, const float* const* S,
+                                        const float* const* const* U, const void* const* grad_out,
+                                        const asi_conv2d_desc* convs, float* const* dW,
+                                        const int32_t* accumulate, void* const* ws, const size_t* ws_bytes,
+                                        asi_stream_t stream);
+asi_status asi_weight_grad_linear_batch(int32_t count, const asi_tensor_desc* descs, const float* const* S,
+                                        const float* const* const* U, const void* const* grad_out,
+                                        const int64_t* dout, float* const* dW,
+                                        const int32_t* accumulate, void* const* ws, const size_t* ws_bytes,
+                                        asi_stream_t stream);
+
 /* Static, human-readable name of a status code. */
 const char* asi_status_string(asi_status s);
 

@@ -1,7 +1,8 @@
 """MI355X-native hot path of Activation Subspace Iteration (arxiv 2505.05086).
 
 Thin Python names over the C ABI of libasi_hip.so (see include/asi.h):
-asi_compress, asi_core_project, asi_weight_grad_conv2d, asi_weight_grad_linear.
+asi_compress, asi_core_project, asi_weight_grad_conv2d, asi_weight_grad_linear and their
+*_batch forms, which serve several layers with every kernel launch.
 """
 from .binding import (  # noqa: F401
     ASI_BF16,
@@ -12,13 +13,17 @@ from .binding import (  # noqa: F401
     TensorDesc,
     alloc_workspace,
     asi_compress,
+    asi_compress_batch,
     asi_core_project,
+    asi_core_project_batch,
     asi_profile_enable,
     asi_profile_report,
     asi_status_string,
     asi_version,
     asi_weight_grad_conv2d,
+    asi_weight_grad_conv2d_batch,
     asi_weight_grad_linear,
+    asi_weight_grad_linear_batch,
     asi_workspace_bytes,
     lib,
     make_conv,

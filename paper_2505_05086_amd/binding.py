@@ -21,8 +21,10 @@ STATUS_NAMES = {0: "ASI_OK", 1: "ASI_ERR_INVALID_ARG", 2: "ASI_ERR_UNSUPPORTED",
 ASI_F32, ASI_BF16 = 0, 1
 
 EXPORTS = ["asi_workspace_bytes", "asi_compress", "asi_core_project", "asi_weight_grad_conv2d",
-           "asi_weight_grad_linear", "asi_status_string", "asi_version", "asi_profile_enable",
-           "asi_profile_report"]
+           "asi_weight_grad_linear", "asi_compress_batch", "asi_core_project_batch",
+           "asi_weight_grad_conv2d_batch", "asi_weight_grad_linear_batch", "asi_status_string", "asi_version",
+           "asi_profile_enable", "asi_profile_report"]
+MAX_BATCH = 8
 
 
 class TensorDesc(C.Structure):
@@ -68,6 +70,15 @@ def lib() -> C.CDLL:
         L.asi_weight_grad_linear.restype = C.c_int
         L.asi_weight_grad_linear.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, C.c_void_p, C.c_int64,
                                              C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
+        vp = C.c_void_p
+        L.asi_compress_batch.restype = C.c_int
+        L.asi_compress_batch.argtypes = [C.c_int32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.asi_core_project_batch.restype = C.c_int
+        L.asi_core_project_batch.argtypes = [C.c_int32, vp, vp, vp, vp, vp, vp, vp]
+        L.asi_weight_grad_conv2d_batch.restype = C.c_int
+        L.asi_weight_grad_conv2d_batch.argtypes = [C.c_int32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.asi_weight_grad_linear_batch.restype = C.c_int
+        L.asi_weight_grad_linear_batch.argtypes = [C.c_int32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.asi_status_string.restype = C.c_char_p
         L.asi_status_string.argtypes = [C.c_int]
         L.asi_version.restype = C.c_int32
@@ -168,6 +179,88 @@ def asi_weight_grad_linear(desc: TensorDesc, S: torch.Tensor, U: Sequence[torch.
     _check(lib().asi_weight_grad_linear(C.byref(desc), _ptr(S), _ptr_array(U), _ptr(grad_out), int(dout),
                                         _ptr(dW), int(bool(accumulate)), _ptr(ws), ws.numel(), _stream()),
            "asi_weight_grad_linear")
+
+
+# ---- batched forms: host arrays of per-layer arguments ---------------------------------------
+def _desc_array(descs: Sequence[TensorDesc]):
+    arr = (TensorDesc * len(descs))()
+    for i, d in enumerate(descs):
+        arr[i] = d
+    return arr
+
+
+def _pp(ts: Sequence[Optional[torch.Tensor]]):
+    """Host array of device pointers, one per layer."""
+    arr = (C.c_void_p * len(ts))()
+    for i, t in enumerate(ts):
+        arr[i] = None if t is None else t.data_ptr()
+    return arr
+
+
+def _ppp(tss: Sequence[Sequence[torch.Tensor]]):
+    """Host array of host arrays of device pointers (per layer, per mode); returns (outer, keepalive)."""
+    inner = [_ptr_array(ts) for ts in tss]
+    outer = (C.c_void_p * len(tss))()
+    for i, a in enumerate(inner):
+        outer[i] = C.addressof(a)
+    return outer, inner
+
+
+def _sizes(ws: Sequence[torch.Tensor]):
+    arr = (C.c_size_t * len(ws))()
+    for i, w in enumerate(ws):
+        arr[i] = w.numel()
+    return arr
+
+
+def _ints(vals: Sequence[int], ctype):
+    arr = (ctype * len(vals))()
+    for i, v in enumerate(vals):
+        arr[i] = int(v)
+    return arr
+
+
+def asi_compress_batch(descs, A, U_prev, U_out, ws, info=None) -> None:
+    n = len(descs)
+    for l in range(n):
+        _check_dev(A[l], ws[l], None if info is None else info[l], *U_prev[l], *U_out[l])
+    up, k1 = _ppp(U_prev)
+    uo, k2 = _ppp(U_out)
+    _check(lib().asi_compress_batch(n, _desc_array(descs), _pp(A), up, uo, _pp(ws), _sizes(ws),
+                                    None if info is None else _pp(info), _stream()), "asi_compress_batch")
+
+
+def asi_core_project_batch(descs, A, U, S, ws) -> None:
+    n = len(descs)
+    for l in range(n):
+        _check_dev(A[l], ws[l], S[l], *U[l])
+    u, keep = _ppp(U)
+    _check(lib().asi_core_project_batch(n, _desc_array(descs), _pp(A), u, _pp(S), _pp(ws), _sizes(ws), _stream()),
+           "asi_core_project_batch")
+
+
+def asi_weight_grad_conv2d_batch(descs, S, U, grad_out, convs, dW, accumulate, ws) -> None:
+    n = len(descs)
+    for l in range(n):
+        _check_dev(S[l], grad_out[l], dW[l], ws[l], *U[l])
+    u, keep = _ppp(U)
+    carr = (Conv2dDesc * n)()
+    for i, c in enumerate(convs):
+        carr[i] = c
+    _check(lib().asi_weight_grad_conv2d_batch(n, _desc_array(descs), _pp(S), u, _pp(grad_out), carr, _pp(dW),
+                                              _ints([int(bool(a)) for a in accumulate], C.c_int32), _pp(ws),
+                                              _sizes(ws), _stream()), "asi_weight_grad_conv2d_batch")
+
+
+def asi_weight_grad_linear_batch(descs, S, U, grad_out, dout, dW, accumulate, ws) -> None:
+    n = len(descs)
+    for l in range(n):
+        _check_dev(S[l], grad_out[l], dW[l], ws[l], *U[l])
+    u, keep = _ppp(U)
+    _check(lib().asi_weight_grad_linear_batch(n, _desc_array(descs), _pp(S), u, _pp(grad_out),
+                                              _ints(dout, C.c_int64), _pp(dW),
+                                              _ints([int(bool(a)) for a in accumulate], C.c_int32), _pp(ws),
+                                              _sizes(ws), _stream()), "asi_weight_grad_linear_batch")
 
 
 def asi_status_string(status: int) -> str:

@@ -75,15 +75,16 @@ struct CompressPlan {
     double* part2[4] = {};          // first level of the partial-sum tree (nsplit > 32)
     int nsplit2[4] = {};
     double* P64[4] = {};
-    double* G[4] = {};
     double* Gpart[4] = {};
     double* R[4] = {};
     double* Dinv[4] = {};
     double* scal[4] = {};
+    int32_t* ctr8 = nullptr;         // arrival counters, two per mode
     int nsplit[4] = {};
     int nblk[4] = {};
     bool fused[4] = {};
     bool paired = false;             // the last two modes of a 4-mode tensor share one kernel
+    bool tiny = false;               // ... the vector-ALU kernel for tiny planes
     bool fast_orth[4] = {};
     bool wide_orth[4] = {};
     size_t bytes = 0;
@@ -98,10 +99,13 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
         if (!p.fused[m]) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
     }
     p.V = c.take<float>(vmax);
-    p.paired = s.d == 4 && subspace_pair_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
+    p.ctr8 = c.take<int32_t>(8);
+    p.tiny = s.d == 4 && subspace_tiny_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
+    p.paired = p.tiny || (s.d == 4 && subspace_pair_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]));
     for (int m = 0; m < s.d; ++m) {
         const size_t n = (size_t)s.n[m], r = (size_t)s.r[m];
-        if (p.paired && m >= 2) p.nsplit[m] = subspace_pair_nwg(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3]);
+        if (p.tiny && m >= 2) p.nsplit[m] = subspace_tiny_nwg(s.n[0] * s.n[1]);
+        else if (p.paired && m >= 2) p.nsplit[m] = subspace_pair_nwg(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3]);
         else p.nsplit[m] = p.fused[m] ? subspace_small_nwg(s.outer(m), (int)n, s.inner(m))
                                       : pair_splits(s.outer(m), (int)n, s.inner(m), (int)r);
         p.part[m] = c.take<double>((size_t)p.nsplit[m] * n * r);
@@ -125,7 +129,7 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
             p.Dinv[m] = c.take<double>(((r + 15) / 16) * 256);
             p.scal[m] = c.take<double>(200);
         } else {
-            p.G[m] = c.take<double>(r * r);
+            p.Gpart[m] = c.take<double>(r * r);      // slow path: the Gram matrix itself
         }
     }
     p.bytes = c.off;
@@ -152,36 +156,49 @@ bool kron_ok(long long n_a, long long n_b, int r_a, int r_b) {
     return n_a * n_b <= kKronMaxN && (long long)r_a * r_b <= kKronMaxR;
 }
 
-CorePlan plan_core(const Shape& s, void* ws) {
-    CorePlan p;
-    p.kron = s.d == 4 && kron_ok(s.n[2], s.n[3], s.r[2], s.r[3]);
-    p.d = p.kron ? 3 : s.d;
-    for (int m = 0; m < p.d; ++m) { p.n[m] = s.n[m]; p.r[m] = s.r[m]; }
-    if (p.kron) { p.n[2] = s.n[2] * s.n[3]; p.r[2] = s.r[2] * s.r[3]; }
-    int perm[4] = {0, 1, 2, 3};
-    double best = -1.0;
-    do {
-        long long cur[4];
-        for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
-        double cost = 0.0;
-        for (int k = 0; k < p.d; ++k) {
-            const int m = perm[k];
-            double sz = 1.0;
-            for (int q = 0; q < p.d; ++q) sz *= (double)cur[q];
-            cost += sz * p.r[m];
-            cur[m] = p.r[m];
-        }
-        if (best < 0 || cost < best) { best = cost; std::memcpy(p.order, perm, sizeof(perm)); }
-    } while (std::next_permutation(perm, perm + p.d));
+// multiply-adds of the products taken in the order perm
+double core_cost(const CorePlan& p, const int* perm) {
     long long cur[4];
     for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
-    size_t need[2] = {0, 0};
-    for (int k = 0; k + 1 < p.d; ++k) {   // the last product writes S itself
-        cur[p.order[k]] = p.r[p.order[k]];
-        size_t sz = 1;
-        for (int q = 0; q < p.d; ++q) sz *= (size_t)cur[q];
-        need[k & 1] = std::max(need[k & 1], sz);
+    double cost = 0.0;
+    for (int k = 0; k < p.d; ++k) {
+        const int m = perm[k];
+        double sz = 1.0;
+        for (int q = 0; q < p.d; ++q) sz *= (double)cur[q];
+        cost += sz * p.r[m];
+        cur[m] = p.r[m];
     }
+    return cost;
+}
+
+void core_shape(const Shape& s, CorePlan* p) {
+    p->kron = s.d == 4 && kron_ok(s.n[2], s.n[3], s.r[2], s.r[3]);
+    p->d = p->kron ? 3 : s.d;
+    for (int m = 0; m < p->d; ++m) { p->n[m] = s.n[m]; p->r[m] = s.r[m]; }
+    if (p->kron) { p->n[2] = s.n[2] * s.n[3]; p->r[2] = s.r[2] * s.r[3]; }
+}
+
+// order: the order of the products, or null for the cheapest.  The two intermediate buffers are
+// sized for any order, so that a batch may impose a common one.
+CorePlan plan_core(const Shape& s, void* ws, const int* order = nullptr) {
+    CorePlan p;
+    core_shape(s, &p);
+    int perm[4] = {0, 1, 2, 3};
+    double best = -1.0;
+    size_t need[2] = {0, 0};
+    do {
+        const double cost = core_cost(p, perm);
+        if (!order && (best < 0 || cost < best)) { best = cost; std::memcpy(p.order, perm, sizeof(perm)); }
+        long long cur[4];
+        for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
+        for (int k = 0; k + 1 < p.d; ++k) {   // the last product writes S itself
+            cur[perm[k]] = p.r[perm[k]];
+            size_t sz = 1;
+            for (int q = 0; q < p.d; ++q) sz *= (size_t)cur[q];
+            need[k & 1] = std::max(need[k & 1], sz);
+        }
+    } while (std::next_permutation(perm, perm + p.d));
+    if (order) std::memcpy(p.order, order, sizeof(int) * 4);
     Carver c(ws);
     p.buf[0] = c.take<float>(need[0]);
     p.buf[1] = c.take<float>(need[1]);
@@ -275,65 +292,315 @@ std::mutex g_prof_mu;
 bool g_prof_on = false;
 std::vector<ProfRec> g_prof;
 
-struct ProfScope {
-    bool on = false;
-    ProfRec rec;
-    hipStream_t st;
-    ProfScope(const char* site, double bytes, double flops, hipStream_t s) : st(s) {
-        if (!g_prof_on) return;
-        on = true;
-        rec.site = site; rec.bytes = bytes; rec.flops = flops;
-        if (hipEventCreate(&rec.e0) != hipSuccess || hipEventCreate(&rec.e1) != hipSuccess) { on = false; return; }
-        (void)hipEventRecord(rec.e0, st);
-    }
-    ~ProfScope() {
-        if (!on) return;
-        (void)hipEventRecord(rec.e1, st);
-        // "kernel instantiation:role", e.g. "k_ttm_mfma<float, false, 3>:core"
-        const size_t colon = rec.site.find(':');
-        rec.site = std::string(last_label()) + (colon == std::string::npos ? "" : rec.site.substr(colon));
-        std::lock_guard<std::mutex> lk(g_prof_mu);
-        g_prof.push_back(rec);
-    }
-};
-
 inline double esize(DType t) { return t == F32 ? 4.0 : 2.0; }
 
-// mode product with its accounting: reads X and M once, writes (or updates) Y once
-hipError_t ttm(const char* site, DType xt, const void* X, long long outer, int n, long long inner, const float* Mp,
-               long long ms_i, long long ms_q, int r, float* Y, int beta, hipStream_t st) {
-    const double cols = (double)outer * (double)inner;
-    ProfScope ps(site, cols * n * esize(xt) + 4.0 * n * r + 4.0 * cols * r * (beta ? 2 : 1), 2.0 * cols * n * r, st);
-    return launch_ttm(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, st);
+// ---- the launches of one layer, in order --------------------------------------------
+struct Program {
+    std::vector<Item> items;
+    Item* add(const char* role, double bytes, double flops) {
+        items.emplace_back();
+        return &items.back();
+    }
+};
+// finishes the item appended last
+inline void tag(Program& pg, const char* role, double bytes, double flops) {
+    Item& it = pg.items.back();
+    std::snprintf(it.role, sizeof(it.role), "%s", role);
+    it.bytes = bytes; it.flops = flops;
 }
-
-// two trailing modes at once (Kronecker product of their matrices)
-hipError_t ttm_kron(const char* site, DType xt, const void* X, long long cols, int n1, int n2, const float* M1,
-                    long long ms1_i, long long ms1_q, int r1, const float* M2, long long ms2_i, long long ms2_q, int r2,
-                    float* Y, hipStream_t st) {
-    const double n = (double)n1 * n2, r = (double)r1 * r2;
-    ProfScope ps(site, cols * n * esize(xt) + 4.0 * (n1 * r1 + n2 * r2) + 4.0 * cols * r, 2.0 * cols * n * r, st);
-    return launch_ttm_kron(xt, X, cols, n1, n2, M1, ms1_i, ms1_q, r1, M2, ms2_i, ms2_q, r2, Y, 0, st);
-}
-
-hipError_t pair(const char* site, DType xt, const void* X, long long outer, int n, long long inner, const float* Y,
-                int r, double* part, int nsplit, hipStream_t st) {
-    const double cols = (double)outer * (double)inner;
-    ProfScope ps(site, cols * n * esize(xt) + 4.0 * cols * r + 8.0 * n * r * nsplit, 2.0 * cols * n * r, st);
-    return launch_pair(xt, X, outer, n, inner, Y, r, part, nsplit, st);
-}
-
-#define ASI_TRY(expr)                                  \
-    do {                                               \
-        hipError_t e__ = (expr);                       \
-        if (e__ != hipSuccess) return ASI_ERR_HIP;     \
+#define ASI_ADD(pg, role, bytes, flops, make_call)         \
+    do {                                                   \
+        (pg).items.emplace_back();                         \
+        Item* it__ = &(pg).items.back();                   \
+        if (!(make_call)) return ASI_ERR_UNSUPPORTED;      \
+        tag((pg), (role), (bytes), (flops));               \
     } while (0)
+
+// mode product with its accounting: reads X and M once, writes (or updates) Y once
+asi_status add_ttm(Program& pg, const char* role, DType xt, const void* X, long long outer, int n, long long inner,
+                   const float* Mp, long long ms_i, long long ms_q, int r, float* Y, int beta) {
+    const double cols = (double)outer * (double)inner;
+    ASI_ADD(pg, role, cols * n * esize(xt) + 4.0 * n * r + 4.0 * cols * r * (beta ? 2 : 1), 2.0 * cols * n * r,
+            make_ttm(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, it__));
+    return ASI_OK;
+}
+// two trailing modes at once (Kronecker product of their matrices)
+asi_status add_ttm_kron(Program& pg, const char* role, DType xt, const void* X, long long cols, int n1, int n2,
+                        const float* M1, long long ms1_i, long long ms1_q, int r1, const float* M2, long long ms2_i,
+                        long long ms2_q, int r2, float* Y) {
+    const double n = (double)n1 * n2, r = (double)r1 * r2;
+    ASI_ADD(pg, role, cols * n * esize(xt) + 4.0 * (n1 * r1 + n2 * r2) + 4.0 * cols * r, 2.0 * cols * n * r,
+            make_ttm_kron(xt, X, cols, n1, n2, M1, ms1_i, ms1_q, r1, M2, ms2_i, ms2_q, r2, Y, 0, it__));
+    return ASI_OK;
+}
+asi_status add_pair(Program& pg, const char* role, DType xt, const void* X, long long outer, int n, long long inner,
+                    const float* Y, int r, double* part, int nsplit, int32_t* zero, int nzero) {
+    const double cols = (double)outer * (double)inner;
+    ASI_ADD(pg, role, cols * n * esize(xt) + 4.0 * cols * r + 8.0 * n * r * nsplit, 2.0 * cols * n * r,
+            make_pair(xt, X, outer, n, inner, Y, r, part, nsplit, zero, nzero, it__));
+    return ASI_OK;
+}
+#define ASI_TRYS(expr)                                 \
+    do {                                               \
+        asi_status s__ = (expr);                       \
+        if (s__ != ASI_OK) return s__;                 \
+    } while (0)
+
+// Runs the programs of `count` layers: position by position, the items that can share a
+// launch (same kernel instantiation up to size bounds) go out together.
+asi_status flush(std::vector<Program>& progs, hipStream_t st) {
+    size_t maxlen = 0;
+    for (auto& pg : progs) maxlen = std::max(maxlen, pg.items.size());
+    for (size_t pos = 0; pos < maxlen; ++pos) {
+        std::vector<const Item*> pending;
+        for (auto& pg : progs)
+            if (pos < pg.items.size()) pending.push_back(&pg.items[pos]);
+        while (!pending.empty()) {
+            const Item* group[kMaxBatch];
+            int n = 0;
+            std::vector<const Item*> rest;
+            for (const Item* it : pending) {
+                if (n < kMaxBatch && (n == 0 || same_launch(*group[0], *it))) group[n++] = it;
+                else rest.push_back(it);
+            }
+            ProfRec rec;
+            const bool prof = g_prof_on;
+            if (prof) {
+                if (hipEventCreate(&rec.e0) != hipSuccess || hipEventCreate(&rec.e1) != hipSuccess) return ASI_ERR_HIP;
+                (void)hipEventRecord(rec.e0, st);
+            }
+            char label[96];
+            if (launch_items(group, n, st, label) != hipSuccess) return ASI_ERR_HIP;
+            if (prof) {
+                (void)hipEventRecord(rec.e1, st);
+                // "kernel instantiation:role", e.g. "k_ttm_mfma<float, false, 3, false>:core"
+                rec.site = std::string(label) + (group[0]->role[0] ? std::string(":") + group[0]->role : std::string());
+                rec.bytes = rec.flops = 0;
+                for (int j = 0; j < n; ++j) { rec.bytes += group[j]->bytes; rec.flops += group[j]->flops; }
+                std::lock_guard<std::mutex> lk(g_prof_mu);
+                g_prof.push_back(rec);
+            }
+            pending.swap(rest);
+        }
+    }
+    return ASI_OK;
+}
+
+// ---- builders: validate one layer's arguments and append its launches -----------------------------
+asi_status build_compress(const asi_tensor_desc* desc, const void* A, const float* const* U_prev, float* const* U_out,
+                          void* ws, size_t ws_bytes, int32_t* info, Program& pg) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    if (!A || !U_prev || !U_out) return ASI_ERR_INVALID_ARG;
+    for (int m = 0; m < s.d; ++m)
+        if (!U_prev[m] || !U_out[m]) return ASI_ERR_INVALID_ARG;
+    CompressPlan p = plan_compress(s, ws);
+    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
+
+    OrthArgs fast, wide, slow;
+    std::memset(&fast, 0, sizeof(fast));
+    std::memset(&wide, 0, sizeof(wide));
+    std::memset(&slow, 0, sizeof(slow));
+    PresumArgs pre, pre2;            // pre2, second tree level: wide modes need the finished sum in P64
+    std::memset(&pre, 0, sizeof(pre));
+    std::memset(&pre2, 0, sizeof(pre2));
+    double wide_b = 0, wide_f = 0, pre2_b = 0, chol_b = 0, chol_f = 0, wchol_b = 0, wchol_f = 0;
+    double fast_b = 0, fast_f = 0, slow_b = 0, slow_f = 0, pre_b = 0;
+    for (int m = 0; m < s.d; ++m) {
+        const long long outer = s.outer(m), inner = s.inner(m);
+        const int n = (int)s.n[m], r = s.r[m];
+        int32_t* zero = (m == 0) ? p.ctr8 : nullptr;     // the first mode's kernel clears the arrival counters
+        if (p.paired && m == 2) {
+            // H and W modes: both subspace steps from one read of the activation's planes
+            const double tot = (double)s.numel;
+            if (p.tiny)
+                ASI_ADD(pg, "", tot * esize(s.dt) + 8.0 * (n * r + (double)s.n[3] * s.r[3]) * p.nsplit[m], 4.0 * tot * (r + s.r[3]),
+                        make_subspace_tiny(s.dt, A, s.n[0] * s.n[1], n, (int)s.n[3], U_prev[2], r, p.part[2], U_prev[3], s.r[3],
+                                           p.part[3], p.nsplit[m], it__));
+            else
+                ASI_ADD(pg, "", tot * esize(s.dt) + 8.0 * (n * r + (double)s.n[3] * s.r[3]) * p.nsplit[m], 4.0 * tot * (r + s.r[3]),
+                        make_subspace_pair(s.dt, A, s.n[0] * s.n[1], n, (int)s.n[3], U_prev[2], r, p.part[2], U_prev[3], s.r[3],
+                                           p.part[3], p.nsplit[m], it__));
+        } else if (p.paired && m == 3) {
+            // done together with mode 3
+        } else if (p.fused[m]) {
+            // short fibres: V and P from one LDS tile of complete fibres, V never stored
+            const double cols = (double)outer * (double)inner;
+            ASI_ADD(pg, "", cols * n * esize(s.dt) + 4.0 * n * r + 8.0 * n * r * p.nsplit[m], 4.0 * cols * n * r,
+                    make_subspace_small(s.dt, A, outer, n, inner, U_prev[m], r, p.part[m], p.nsplit[m], zero, 8, it__));
+        } else {
+            // V = A_m^T U_prev, kept as a tensor with mode m of size r
+            ASI_TRYS(add_ttm(pg, "V", s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0));
+            // P = A_m V, split over the unfolding's columns
+            ASI_TRYS(add_pair(pg, "P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], zero, 8));
+        }
+        OrthArgs& oa = p.fast_orth[m] ? fast : (p.wide_orth[m] ? wide : slow);
+        OrthJob& j = oa.job[oa.njobs++];
+        j.part = p.part[m]; j.nsplit = p.nsplit[m]; j.n = n; j.r = r;
+        if (p.part2[m]) {
+            PresumJob& pj = pre.job[pre.njobs++];
+            pj.in = p.part[m]; pj.out = p.part2[m]; pj.cnt = (long long)n * r; pj.nsplit = p.nsplit[m];
+            pj.nchunks = (int)((pj.cnt + 255) / 256); pj.ngroups = p.nsplit2[m];
+            pre_b += 8.0 * n * r * (p.nsplit[m] + p.nsplit2[m]);
+            j.part = p.part2[m]; j.nsplit = p.nsplit2[m];
+        }
+        j.P64 = p.P64[m]; j.Uout = U_out[m]; j.mode1 = m + 1; j.info = info;
+        j.nblk = p.nblk[m]; j.Gpart = p.Gpart[m]; j.R = p.R[m]; j.Dinv = p.Dinv[m]; j.scal = p.scal[m];
+        j.ctr = p.ctr8 + 2 * m;
+        if (p.wide_orth[m]) {
+            PresumJob& pj = pre2.job[pre2.njobs++];
+            pj.in = j.part; pj.out = p.P64[m]; pj.cnt = (long long)n * r; pj.nsplit = j.nsplit;
+            pj.nchunks = (int)((pj.cnt + 255) / 256); pj.ngroups = 1;
+            pre2_b += 8.0 * n * r * (j.nsplit + 1);
+        }
+        // Cholesky: reads the slice Grams, writes R and the diagonal-block inverses; r^3/3 flops
+        const double cb = 8.0 * ((double)p.nblk[m] * r * r + (double)r * r + 256.0 * ((r + 15) / 16));
+        const double cf = (double)r * r * r / 3.0;
+        if (p.fast_orth[m]) { chol_b += cb; chol_f += cf; }
+        if (p.wide_orth[m]) { wchol_b += cb; wchol_f += cf; }
+        (p.fast_orth[m] ? fast_b : (p.wide_orth[m] ? wide_b : slow_b)) += 8.0 * n * r;
+        (p.fast_orth[m] ? fast_f : (p.wide_orth[m] ? wide_f : slow_f)) += 2.0 * (double)n * r * r;
+    }
+    if (info && !fast.njobs) ASI_ADD(pg, "", 4.0, 0.0, make_init_ctrl(info, it__));     // otherwise gram0 clears it
+    if (pre.njobs) ASI_ADD(pg, "", pre_b, pre_b / 8.0, make_orth_presum(pre, it__));
+    if (fast.njobs) {
+        // Orthogonalize: shifted Cholesky-QR, then one plain Cholesky-QR pass
+        // (each of the first two launches ends with the Cholesky factorisation of its Gram matrices)
+        ASI_ADD(pg, "", fast_b + chol_b, fast_f + chol_f, make_orth_gram0(fast, it__));
+        ASI_ADD(pg, "", 2 * fast_b + chol_b, 2 * fast_f + chol_f, make_orth_apply(fast, 0, it__));
+        ASI_ADD(pg, "", 1.5 * fast_b, fast_f, make_orth_apply(fast, 1, it__));
+    }
+    if (wide.njobs) {
+        ASI_ADD(pg, "", pre2_b, pre2_b / 8.0, make_orth_presum(pre2, it__));
+        ASI_ADD(pg, "", wide_b, wide_f, make_orthw_gram(wide, it__));
+        ASI_ADD(pg, "", wchol_b, wchol_f, make_orthw_chol(wide, 0, 0, it__));
+        ASI_ADD(pg, "", 2 * wide_b, wide_f, make_orthw_apply(wide, 0, it__));
+        ASI_ADD(pg, "", wide_b, wide_f, make_orthw_gram(wide, it__));
+        ASI_ADD(pg, "", wchol_b, wchol_f, make_orthw_chol(wide, 1, 1, it__));
+        ASI_ADD(pg, "", 1.5 * wide_b, wide_f, make_orthw_apply(wide, 1, it__));
+    }
+    if (slow.njobs) ASI_ADD(pg, "", 6 * slow_b, 9 * slow_f, make_orth_big(slow, it__));
+    return ASI_OK;
+}
+
+asi_status build_core(const asi_tensor_desc* desc, const void* A, const float* const* U, float* S, void* ws,
+                      size_t ws_bytes, const int* order, Program& pg) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    if (!A || !U || !S) return ASI_ERR_INVALID_ARG;
+    for (int m = 0; m < s.d; ++m)
+        if (!U[m]) return ASI_ERR_INVALID_ARG;
+    CorePlan p = plan_core(s, ws, order);
+    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
+
+    long long cur[4];
+    for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
+    const void* src = A;
+    DType sdt = s.dt;
+    for (int k = 0; k < p.d; ++k) {
+        const int m = p.order[k];
+        long long outer = 1, inner = 1;
+        for (int q = 0; q < m; ++q) outer *= cur[q];
+        for (int q = m + 1; q < p.d; ++q) inner *= cur[q];
+        float* dst = (k + 1 == p.d) ? S : p.buf[k & 1];
+        if (p.kron && m == 2) {
+            // (.., H, W) -> (.., r3, r4):  M(h*W + w, a*r4 + b) = U3[h,a] * U4[w,b]
+            ASI_TRYS(add_ttm_kron(pg, "core", sdt, src, outer, (int)s.n[2], (int)s.n[3], U[2], s.r[2], 1, s.r[2], U[3],
+                                  s.r[3], 1, s.r[3], dst));
+        } else {
+            ASI_TRYS(add_ttm(pg, "core", sdt, src, outer, (int)cur[m], inner, U[m], p.r[m], 1, p.r[m], dst, 0));
+        }
+        cur[m] = p.r[m];
+        src = dst;
+        sdt = F32;
+    }
+    return ASI_OK;
+}
+
+asi_status build_conv(const asi_tensor_desc* desc, const float* S, const float* const* U, const void* grad_out,
+                      const asi_conv2d_desc* conv, float* dW, int accumulate, void* ws, size_t ws_bytes, Program& pg) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    if (s.d != 4 || !conv) return ASI_ERR_INVALID_ARG;
+    ConvGeom cg;
+    if (!parse_conv(s, conv, &cg)) return ASI_ERR_INVALID_ARG;
+    if (!S || !U || !grad_out || !dW) return ASI_ERR_INVALID_ARG;
+    for (int m = 0; m < 4; ++m)
+        if (!U[m]) return ASI_ERR_INVALID_ARG;
+    ConvPlan p = plan_conv(s, cg, ws);
+    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
+    const CorrGeom& g = cg.g;
+    const int r3 = s.r[2], r4 = s.r[3];
+    const int taps = g.kh * g.kw;
+
+    // 1. G1 = grad_out x_1 U1^T                                   (r1, cout, Ho, Wo)
+    ASI_TRYS(add_ttm(pg, "G1", s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0));
+    if (!p.Z1) {
+        // 2+3. Z = S x_3 U3 x_4 U4 in one pass:  M(a*r4 + b, h*W + w) = U3[h,a] * U4[w,b]   (r1, r2, H, W)
+        ASI_TRYS(add_ttm_kron(pg, "Z", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, U[3], 1, r4, g.W, p.Z));
+    } else {
+        // 2. Z1 = S x_3 U3                                        (r1, r2, H, r4)
+        ASI_TRYS(add_ttm(pg, "Z1", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0));
+        // 3. Z = Z1 x_4 U4                                        (r1, r2, H, W)
+        ASI_TRYS(add_ttm(pg, "Z", F32, p.Z1, (long long)g.r1 * g.r2 * g.H, r4, 1, U[3], 1, r4, g.W, p.Z, 0));
+    }
+    // 4. T = correlation of Zpad with G1 over (r1, Ho, Wo)        (cout, r2, kh, kw)
+    const double tsz = (double)g.cout * g.r2 * taps;
+    ASI_ADD(pg, "", 4.0 * ((double)g.r1 * g.cout * g.Ho * g.Wo + (double)g.r1 * g.r2 * g.H * g.W + tsz * p.nsplit),
+            2.0 * g.r1 * g.Ho * g.Wo * tsz, make_corr(p.G1, p.Z, p.Tpart, g, p.nsplit, it__));
+    if (p.nsplit > 1)
+        ASI_ADD(pg, "", 4.0 * tsz * (p.nsplit + 1), tsz * p.nsplit,
+                make_sum_partials(p.Tpart, p.nsplit, (long long)g.cout * g.r2 * taps, p.T, 0, it__));
+    // 5. dW = T x_(r2) U2, per group                              (cout, C/groups, kh, kw)
+    if (cg.groups == 1) {
+        ASI_TRYS(add_ttm(pg, "dW", F32, p.T, g.cout, g.r2, taps, U[1], 1, g.r2, cg.C, dW, accumulate ? 1 : 0));
+    } else {
+        const double dwsz = (double)g.cout * (cg.C / cg.groups) * taps;
+        ASI_ADD(pg, "", 4.0 * ((double)g.cout * g.r2 * taps + (double)cg.C * g.r2 + dwsz), 2.0 * dwsz * g.r2,
+                make_expand_grouped(p.T, U[1], dW, g.cout, g.r2, taps, cg.C / cg.groups, g.cout / cg.groups,
+                                    accumulate ? 1 : 0, it__));
+    }
+    return ASI_OK;
+}
+
+asi_status build_linear(const asi_tensor_desc* desc, const float* S, const float* const* U, const void* grad_out,
+                        int64_t dout, float* dW, int accumulate, void* ws, size_t ws_bytes, Program& pg) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    if (s.d != 3 || dout <= 0 || dout > (1 << 24)) return ASI_ERR_INVALID_ARG;
+    if (!S || !U || !grad_out || !dW) return ASI_ERR_INVALID_ARG;
+    for (int m = 0; m < 3; ++m)
+        if (!U[m]) return ASI_ERR_INVALID_ARG;
+    LinPlan p = plan_linear(s, dout, ws);
+    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
+    const int B = (int)s.n[0], N = (int)s.n[1], D = (int)s.n[2];
+    const int r1 = s.r[0], r2 = s.r[1], r3 = s.r[2];
+
+    // 1. G1[i,n,o] = sum_b U1[b,i] dY[b,n,o]
+    ASI_TRYS(add_ttm(pg, "G1", s.dt, grad_out, 1, B, (long long)N * dout, U[0], r1, 1, r1, p.G1, 0));
+    // 2. G2[i,j,o] = sum_n U2[n,j] G1[i,n,o]
+    ASI_TRYS(add_ttm(pg, "G2", F32, p.G1, r1, N, dout, U[1], r2, 1, r2, p.G2, 0));
+    // 3. T[o,k] = sum_{i,j} G2[i,j,o] S[i,j,k]
+    ASI_TRYS(add_pair(pg, "T", F32, p.G2, (long long)r1 * r2, (int)dout, 1, S, r3, p.Tpart, p.nsplit, nullptr, 0));
+    const double tsz = (double)dout * r3;
+    ASI_ADD(pg, "", tsz * (8.0 * p.nsplit + 4.0), tsz * p.nsplit,
+            make_sum_partials_f64(p.Tpart, p.nsplit, (long long)dout * r3, p.T, 0, it__));
+    // 4. dW[o,d] = sum_k T[o,k] U3[d,k]
+    ASI_TRYS(add_ttm(pg, "dW", F32, p.T, dout, r3, 1, U[2], 1, r3, D, dW, accumulate ? 1 : 0));
+    return ASI_OK;
+}
+
+bool batch_count_ok(int32_t count) { return count >= 1 && count <= kMaxBatch; }
 
 }  // namespace
 
 extern "C" {
 
-int32_t asi_version(void) { return 1000; }
+int32_t asi_version(void) { return 1001; }
 
 int32_t asi_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
@@ -399,229 +666,102 @@ size_t asi_workspace_bytes(const asi_tensor_desc* desc, const asi_conv2d_desc* c
     return std::max(need, kAlign);
 }
 
+asi_status asi_compress_batch(int32_t count, const asi_tensor_desc* descs, const void* const* A,
+                              const float* const* const* U_prev, float* const* const* U_out, void* const* ws,
+                              const size_t* ws_bytes, int32_t* const* info, asi_stream_t stream) {
+    if (!batch_count_ok(count)) return ASI_ERR_UNSUPPORTED;
+    if (!descs || !A || !U_prev || !U_out || !ws || !ws_bytes) return ASI_ERR_INVALID_ARG;
+    std::vector<Program> progs(count);
+    for (int l = 0; l < count; ++l)
+        ASI_TRYS(build_compress(&descs[l], A[l], U_prev[l], U_out[l], ws[l], ws_bytes[l], info ? info[l] : nullptr, progs[l]));
+    return flush(progs, static_cast<hipStream_t>(stream));
+}
+
+asi_status asi_core_project_batch(int32_t count, const asi_tensor_desc* descs, const void* const* A,
+                                  const float* const* const* U, float* const* S, void* const* ws,
+                                  const size_t* ws_bytes, asi_stream_t stream) {
+    if (!batch_count_ok(count)) return ASI_ERR_UNSUPPORTED;
+    if (!descs || !A || !U || !S || !ws || !ws_bytes) return ASI_ERR_INVALID_ARG;
+    // Layers with the same mode structure take their products in one common order (the cheapest in
+    // total), so that product k of every layer can share a launch.
+    int common[4] = {0, 1, 2, 3};
+    bool have_common = count > 1;
+    CorePlan first;
+    std::vector<CorePlan> shapes(count);
+    for (int l = 0; l < count && have_common; ++l) {
+        Shape s;
+        asi_status why;
+        if (!parse_desc(&descs[l], &s, &why)) { have_common = false; break; }
+        core_shape(s, &shapes[l]);
+        if (shapes[l].d != shapes[0].d || shapes[l].kron != shapes[0].kron) have_common = false;
+    }
+    if (have_common) {
+        int perm[4] = {0, 1, 2, 3};
+        double best = -1.0;
+        do {
+            double cost = 0.0;
+            for (int l = 0; l < count; ++l) cost += core_cost(shapes[l], perm);
+            if (best < 0 || cost < best) { best = cost; std::memcpy(common, perm, sizeof(perm)); }
+        } while (std::next_permutation(perm, perm + shapes[0].d));
+    }
+    std::vector<Program> progs(count);
+    for (int l = 0; l < count; ++l)
+        ASI_TRYS(build_core(&descs[l], A[l], U[l], S[l], ws[l], ws_bytes[l], have_common ? common : nullptr, progs[l]));
+    return flush(progs, static_cast<hipStream_t>(stream));
+}
+
+asi_status asi_weight_grad_conv2d_batch(int32_t count, const asi_tensor_desc* descs, const float* const* S,
+                                        const float* const* const* U, const void* const* grad_out,
+                                        const asi_conv2d_desc* convs, float* const* dW, const int32_t* accumulate,
+                                        void* const* ws, const size_t* ws_bytes, asi_stream_t stream) {
+    if (!batch_count_ok(count)) return ASI_ERR_UNSUPPORTED;
+    if (!descs || !S || !U || !grad_out || !convs || !dW || !ws || !ws_bytes) return ASI_ERR_INVALID_ARG;
+    std::vector<Program> progs(count);
+    for (int l = 0; l < count; ++l)
+        ASI_TRYS(build_conv(&descs[l], S[l], U[l], grad_out[l], &convs[l], dW[l], accumulate ? accumulate[l] : 0, ws[l],
+                            ws_bytes[l], progs[l]));
+    return flush(progs, static_cast<hipStream_t>(stream));
+}
+
+asi_status asi_weight_grad_linear_batch(int32_t count, const asi_tensor_desc* descs, const float* const* S,
+                                        const float* const* const* U, const void* const* grad_out, const int64_t* dout,
+                                        float* const* dW, const int32_t* accumulate, void* const* ws,
+                                        const size_t* ws_bytes, asi_stream_t stream) {
+    if (!batch_count_ok(count)) return ASI_ERR_UNSUPPORTED;
+    if (!descs || !S || !U || !grad_out || !dout || !dW || !ws || !ws_bytes) return ASI_ERR_INVALID_ARG;
+    std::vector<Program> progs(count);
+    for (int l = 0; l < count; ++l)
+        ASI_TRYS(build_linear(&descs[l], S[l], U[l], grad_out[l], dout[l], dW[l], accumulate ? accumulate[l] : 0, ws[l],
+                              ws_bytes[l], progs[l]));
+    return flush(progs, static_cast<hipStream_t>(stream));
+}
+
 asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float* const* U_prev,
                         float* const* U_out, void* ws, size_t ws_bytes, int32_t* info, asi_stream_t stream) {
-    Shape s;
-    asi_status why;
-    if (!parse_desc(desc, &s, &why)) return why;
-    if (!A || !U_prev || !U_out) return ASI_ERR_INVALID_ARG;
-    for (int m = 0; m < s.d; ++m)
-        if (!U_prev[m] || !U_out[m]) return ASI_ERR_INVALID_ARG;
-    CompressPlan p = plan_compress(s, ws);
-    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-
-    OrthArgs fast, wide, slow;
-    std::memset(&fast, 0, sizeof(fast));
-    std::memset(&wide, 0, sizeof(wide));
-    std::memset(&slow, 0, sizeof(slow));
-    fast.info = wide.info = slow.info = info;
-    PresumArgs pre2;                 // second tree level: wide modes need the finished sum in P64
-    std::memset(&pre2, 0, sizeof(pre2));
-    double wide_b = 0, wide_f = 0, pre2_b = 0, chol_b = 0, chol_f = 0;
-    PresumArgs pre;
-    std::memset(&pre, 0, sizeof(pre));
-    double fast_b = 0, fast_f = 0, slow_b = 0, slow_f = 0, pre_b = 0;
-    for (int m = 0; m < s.d; ++m) {
-        const long long outer = s.outer(m), inner = s.inner(m);
-        const int n = (int)s.n[m], r = s.r[m];
-        if (p.paired && m == 2) {
-            // H and W modes: both subspace steps from one read of the activation's planes
-            const double tot = (double)s.numel;
-            ProfScope ps("k_subspace_small", tot * esize(s.dt) + 8.0 * (n * r + (double)s.n[3] * s.r[3]) * p.nsplit[m],
-                         4.0 * tot * (r + s.r[3]), st);
-            ASI_TRY(launch_subspace_pair(s.dt, A, s.n[0] * s.n[1], n, (int)s.n[3], U_prev[2], r, p.part[2], U_prev[3],
-                                         s.r[3], p.part[3], p.nsplit[m], st));
-        } else if (p.paired && m == 3) {
-            // done together with mode 3
-        } else if (p.fused[m]) {
-            // short fibres: V and P from one LDS tile of complete fibres, V never stored
-            const double cols = (double)outer * (double)inner;
-            ProfScope ps("k_subspace_small", cols * n * esize(s.dt) + 4.0 * n * r + 8.0 * n * r * p.nsplit[m],
-                         4.0 * cols * n * r, st);
-            ASI_TRY(launch_subspace_small(s.dt, A, outer, n, inner, U_prev[m], r, p.part[m], p.nsplit[m], st));
-        } else {
-            // V = A_m^T U_prev, kept as a tensor with mode m of size r
-            ASI_TRY(ttm("k_ttm:V", s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0, st));
-            // P = A_m V, split over the unfolding's columns
-            ASI_TRY(pair("k_pair:P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], st));
-        }
-        OrthArgs& oa = p.fast_orth[m] ? fast : (p.wide_orth[m] ? wide : slow);
-        OrthJob& j = oa.job[oa.njobs++];
-        j.part = p.part[m]; j.nsplit = p.nsplit[m]; j.n = n; j.r = r;
-        if (p.part2[m]) {
-            PresumJob& pj = pre.job[pre.njobs++];
-            pj.in = p.part[m]; pj.out = p.part2[m]; pj.cnt = (long long)n * r; pj.nsplit = p.nsplit[m];
-            pj.nchunks = (int)((pj.cnt + 255) / 256); pj.ngroups = p.nsplit2[m];
-            pre_b += 8.0 * n * r * (p.nsplit[m] + p.nsplit2[m]);
-            j.part = p.part2[m]; j.nsplit = p.nsplit2[m];
-        }
-        j.P64 = p.P64[m]; j.Uout = U_out[m]; j.mode1 = m + 1;
-        j.nblk = p.nblk[m]; j.Gpart = p.Gpart[m]; j.R = p.R[m]; j.Dinv = p.Dinv[m]; j.scal = p.scal[m];
-        j.G = p.G[m];
-        if (p.wide_orth[m]) {
-            PresumJob& pj = pre2.job[pre2.njobs++];
-            pj.in = j.part; pj.out = p.P64[m]; pj.cnt = (long long)n * r; pj.nsplit = j.nsplit;
-            pj.nchunks = (int)((pj.cnt + 255) / 256); pj.ngroups = 1;
-            pre2_b += 8.0 * n * r * (j.nsplit + 1);
-        }
-        if (p.fast_orth[m] || p.wide_orth[m]) {
-            // Cholesky launches: read the slice Grams, write R and the diagonal-block inverses; r^3/3 flops
-            chol_b += 8.0 * ((double)p.nblk[m] * r * r + (double)r * r + 256.0 * ((r + 15) / 16));
-            chol_f += (double)r * r * r / 3.0;
-        }
-        (p.fast_orth[m] ? fast_b : (p.wide_orth[m] ? wide_b : slow_b)) += 8.0 * n * r;
-        (p.fast_orth[m] ? fast_f : (p.wide_orth[m] ? wide_f : slow_f)) += 2.0 * (double)n * r * r;
-    }
-    if (info && !fast.njobs) ASI_TRY(launch_init_ctrl(info, st));     // otherwise gram0 clears it
-    if (pre.njobs) {
-        ProfScope ps("k_orth_presum", pre_b, pre_b / 8.0, st);
-        ASI_TRY(launch_orth_presum(pre, st));
-    }
-    if (fast.njobs) {
-        // Orthogonalize: shifted Cholesky-QR, then one plain Cholesky-QR pass
-        { ProfScope ps("k_orth_gram0", fast_b, fast_f, st); ASI_TRY(launch_orth_gram0(fast, st)); }
-        { ProfScope ps("k_orth_chol", chol_b, chol_f, st); ASI_TRY(launch_orth_chol(fast, 0, 0, st)); }
-        { ProfScope ps("k_orth_apply", 2 * fast_b, 2 * fast_f, st); ASI_TRY(launch_orth_apply(fast, 0, st)); }
-        { ProfScope ps("k_orth_chol", chol_b, chol_f, st); ASI_TRY(launch_orth_chol(fast, 1, 1, st)); }
-        { ProfScope ps("k_orth_apply", 1.5 * fast_b, fast_f, st); ASI_TRY(launch_orth_apply(fast, 1, st)); }
-    }
-    if (wide.njobs) {
-        { ProfScope ps("k_orth_presum", pre2_b, pre2_b / 8.0, st); ASI_TRY(launch_orth_presum(pre2, st)); }
-        { ProfScope ps("k_orthw_gram", wide_b, wide_f, st); ASI_TRY(launch_orthw_gram(wide, st)); }
-        { ProfScope ps("k_orthw_chol", chol_b, chol_f, st); ASI_TRY(launch_orthw_chol(wide, 0, 0, st)); }
-        { ProfScope ps("k_orthw_apply", 2 * wide_b, wide_f, st); ASI_TRY(launch_orthw_apply(wide, 0, st)); }
-        { ProfScope ps("k_orthw_gram", wide_b, wide_f, st); ASI_TRY(launch_orthw_gram(wide, st)); }
-        { ProfScope ps("k_orthw_chol", chol_b, chol_f, st); ASI_TRY(launch_orthw_chol(wide, 1, 1, st)); }
-        { ProfScope ps("k_orthw_apply", 1.5 * wide_b, wide_f, st); ASI_TRY(launch_orthw_apply(wide, 1, st)); }
-    }
-    if (slow.njobs) {
-        ProfScope ps("k_orth_big", 6 * slow_b, 9 * slow_f, st);
-        ASI_TRY(launch_orth_big(slow, st));
-    }
-    return ASI_OK;
+    if (!desc) return ASI_ERR_INVALID_ARG;
+    return asi_compress_batch(1, desc, &A, &U_prev, &U_out, &ws, &ws_bytes, &info, stream);
 }
 
 asi_status asi_core_project(const asi_tensor_desc* desc, const void* A, const float* const* U, float* S,
                             void* ws, size_t ws_bytes, asi_stream_t stream) {
-    Shape s;
-    asi_status why;
-    if (!parse_desc(desc, &s, &why)) return why;
-    if (!A || !U || !S) return ASI_ERR_INVALID_ARG;
-    for (int m = 0; m < s.d; ++m)
-        if (!U[m]) return ASI_ERR_INVALID_ARG;
-    CorePlan p = plan_core(s, ws);
-    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-
-    long long cur[4];
-    for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
-    const void* src = A;
-    DType sdt = s.dt;
-    for (int k = 0; k < p.d; ++k) {
-        const int m = p.order[k];
-        long long outer = 1, inner = 1;
-        for (int q = 0; q < m; ++q) outer *= cur[q];
-        for (int q = m + 1; q < p.d; ++q) inner *= cur[q];
-        float* dst = (k + 1 == p.d) ? S : p.buf[k & 1];
-        if (p.kron && m == 2) {
-            // (.., H, W) -> (.., r3, r4):  M(h*W + w, a*r4 + b) = U3[h,a] * U4[w,b]
-            ASI_TRY(ttm_kron("k_ttm:core", sdt, src, outer, (int)s.n[2], (int)s.n[3], U[2], s.r[2], 1, s.r[2], U[3],
-                             s.r[3], 1, s.r[3], dst, st));
-        } else {
-            ASI_TRY(ttm("k_ttm:core", sdt, src, outer, (int)cur[m], inner, U[m], p.r[m], 1, p.r[m], dst, 0, st));
-        }
-        cur[m] = p.r[m];
-        src = dst;
-        sdt = F32;
-    }
-    return ASI_OK;
+    if (!desc) return ASI_ERR_INVALID_ARG;
+    return asi_core_project_batch(1, desc, &A, &U, &S, &ws, &ws_bytes, stream);
 }
 
 asi_status asi_weight_grad_conv2d(const asi_tensor_desc* desc, const float* S, const float* const* U,
                                   const void* grad_out, const asi_conv2d_desc* conv, float* dW, int accumulate,
                                   void* ws, size_t ws_bytes, asi_stream_t stream) {
-    Shape s;
-    asi_status why;
-    if (!parse_desc(desc, &s, &why)) return why;
-    if (s.d != 4 || !conv) return ASI_ERR_INVALID_ARG;
-    ConvGeom cg;
-    if (!parse_conv(s, conv, &cg)) return ASI_ERR_INVALID_ARG;
-    if (!S || !U || !grad_out || !dW) return ASI_ERR_INVALID_ARG;
-    for (int m = 0; m < 4; ++m)
-        if (!U[m]) return ASI_ERR_INVALID_ARG;
-    ConvPlan p = plan_conv(s, cg, ws);
-    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const CorrGeom& g = cg.g;
-    const int r3 = s.r[2], r4 = s.r[3];
-    const int taps = g.kh * g.kw;
-
-    // 1. G1 = grad_out x_1 U1^T                                   (r1, cout, Ho, Wo)
-    ASI_TRY(ttm("k_ttm:G1", s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0, st));
-    if (!p.Z1) {
-        // 2+3. Z = S x_3 U3 x_4 U4 in one pass:  M(a*r4 + b, h*W + w) = U3[h,a] * U4[w,b]   (r1, r2, H, W)
-        ASI_TRY(ttm_kron("k_ttm:Z", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, U[3], 1, r4, g.W, p.Z, st));
-    } else {
-        // 2. Z1 = S x_3 U3                                        (r1, r2, H, r4)
-        ASI_TRY(ttm("k_ttm:Z1", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0, st));
-        // 3. Z = Z1 x_4 U4                                        (r1, r2, H, W)
-        ASI_TRY(ttm("k_ttm:Z", F32, p.Z1, (long long)g.r1 * g.r2 * g.H, r4, 1, U[3], 1, r4, g.W, p.Z, 0, st));
-    }
-    // 4. T = correlation of Zpad with G1 over (r1, Ho, Wo)        (cout, r2, kh, kw)
-    {
-        const double tsz = (double)g.cout * g.r2 * taps;
-        ProfScope ps("k_corr", 4.0 * ((double)g.r1 * g.cout * g.Ho * g.Wo + (double)g.r1 * g.r2 * g.H * g.W + tsz * p.nsplit),
-                     2.0 * g.r1 * g.Ho * g.Wo * tsz, st);
-        ASI_TRY(launch_corr(p.G1, p.Z, p.Tpart, g, p.nsplit, st));
-    }
-    if (p.nsplit > 1) {
-        const double tsz = (double)g.cout * g.r2 * taps;
-        ProfScope ps("k_sum_partials", 4.0 * tsz * (p.nsplit + 1), tsz * p.nsplit, st);
-        ASI_TRY(launch_sum_partials(p.Tpart, p.nsplit, (long long)g.cout * g.r2 * taps, p.T, 0, st));
-    }
-    // 5. dW = T x_(r2) U2, per group                              (cout, C/groups, kh, kw)
-    if (cg.groups == 1) {
-        ASI_TRY(ttm("k_ttm:dW", F32, p.T, g.cout, g.r2, taps, U[1], 1, g.r2, cg.C, dW, accumulate ? 1 : 0, st));
-    } else {
-        const double dwsz = (double)g.cout * (cg.C / cg.groups) * taps;
-        ProfScope ps("k_expand_grouped", 4.0 * ((double)g.cout * g.r2 * taps + (double)cg.C * g.r2 + dwsz), 2.0 * dwsz * g.r2, st);
-        ASI_TRY(launch_expand_grouped(p.T, U[1], dW, g.cout, g.r2, taps, cg.C / cg.groups, g.cout / cg.groups,
-                                      accumulate ? 1 : 0, st));
-    }
-    return ASI_OK;
+    if (!desc || !conv) return ASI_ERR_INVALID_ARG;
+    const int32_t acc = accumulate;
+    return asi_weight_grad_conv2d_batch(1, desc, &S, &U, &grad_out, conv, &dW, &acc, &ws, &ws_bytes, stream);
 }
 
 asi_status asi_weight_grad_linear(const asi_tensor_desc* desc, const float* S, const float* const* U,
                                   const void* grad_out, int64_t dout, float* dW, int accumulate, void* ws,
                                   size_t ws_bytes, asi_stream_t stream) {
-    Shape s;
-    asi_status why;
-    if (!parse_desc(desc, &s, &why)) return why;
-    if (s.d != 3 || dout <= 0 || dout > (1 << 24)) return ASI_ERR_INVALID_ARG;
-    if (!S || !U || !grad_out || !dW) return ASI_ERR_INVALID_ARG;
-    for (int m = 0; m < 3; ++m)
-        if (!U[m]) return ASI_ERR_INVALID_ARG;
-    LinPlan p = plan_linear(s, dout, ws);
-    if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int B = (int)s.n[0], N = (int)s.n[1], D = (int)s.n[2];
-    const int r1 = s.r[0], r2 = s.r[1], r3 = s.r[2];
-
-    // 1. G1[i,n,o] = sum_b U1[b,i] dY[b,n,o]
-    ASI_TRY(ttm("k_ttm:G1", s.dt, grad_out, 1, B, (long long)N * dout, U[0], r1, 1, r1, p.G1, 0, st));
-    // 2. G2[i,j,o] = sum_n U2[n,j] G1[i,n,o]
-    ASI_TRY(ttm("k_ttm:G2", F32, p.G1, r1, N, dout, U[1], r2, 1, r2, p.G2, 0, st));
-    // 3. T[o,k] = sum_{i,j} G2[i,j,o] S[i,j,k]
-    ASI_TRY(pair("k_pair:T", F32, p.G2, (long long)r1 * r2, (int)dout, 1, S, r3, p.Tpart, p.nsplit, st));
-    {
-        const double tsz = (double)dout * r3;
-        ProfScope ps("k_sum_partials", tsz * (8.0 * p.nsplit + 4.0), tsz * p.nsplit, st);
-        ASI_TRY(launch_sum_partials_f64(p.Tpart, p.nsplit, (long long)dout * r3, p.T, 0, st));
-    }
-    // 4. dW[o,d] = sum_k T[o,k] U3[d,k]
-    ASI_TRY(ttm("k_ttm:dW", F32, p.T, dout, r3, 1, U[2], 1, r3, D, dW, accumulate ? 1 : 0, st));
-    return ASI_OK;
+    if (!desc) return ASI_ERR_INVALID_ARG;
+    const int32_t acc = accumulate;
+    return asi_weight_grad_linear_batch(1, desc, &S, &U, &grad_out, &dout, &dW, &acc, &ws, &ws_bytes, stream);
 }
 
 }  // extern "C"

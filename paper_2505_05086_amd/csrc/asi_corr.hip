@@ -5,10 +5,14 @@
 // core channel i and up to 64 output positions (whole output rows).  Per chunk it stages
 //   As[k][o]           the G1 tile, so that lane (o = l%16, k = l/16) reads its A operand
 //   Zs[j][row][col]    the slab of Z rows the chunk touches, with a zero halo for the padding
-// and for every tap the B operand of lane (k = l/16, j = l%16) is Zs[j][zoff[k] + tapofs].
+// and for every tap the B operand of lane (k = l/16, j = l%16) is the slab entry of core channel j
+// at the window origin of position k plus the tap's offset.
 // Splits of K write partial T's that a reduction kernel sums in fixed order.
 #include "asi_device.h"
 #include "asi_kernels.h"
+
+#include <cstdio>
+#include <cstring>
 
 namespace asi {
 
@@ -27,6 +31,16 @@ struct CorrPlan {
     int nchunks;     // r1 * nyc
     int cps;         // chunks per split
     int nsplit;
+};
+
+struct CorrJob {
+    const float* G1;
+    const float* Z;
+    float* Tpart;
+    CorrGeom g;
+    CorrPlan pl;
+    int gx, gy, gz;      // channel tiles x core-channel tiles x splits (fallback kernel: blocks x splits x 1)
+    int ips;             // fallback kernel: core channels i per split
 };
 
 static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
@@ -53,7 +67,7 @@ static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
 
 #ifdef ASI_DEBUG_TIMING
 __device__ long long g_corr_stamps[64];
-#define CSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && (i) < 64) g_corr_stamps[i] = wall_clock64(); } while (0)
+#define CSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && (i) < 64) g_corr_stamps[i] = wall_clock64(); } while (0)
 extern "C" int asi_debug_corr_stamps(long long* out) {
     return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_corr_stamps), sizeof(long long) * 64);
 }
@@ -62,13 +76,20 @@ extern "C" int asi_debug_corr_stamps(long long* out) {
 #endif
 
 template <int MAXT, bool EXACT>
-__global__ __launch_bounds__(256, 2) void k_corr_mfma(const float* __restrict__ G1, const float* __restrict__ Z,
-                                                   float* __restrict__ Tpart, CorrGeom g, CorrPlan pl) {
+__global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
     __shared__ float As[CR_KC][CR_TO + 1];
     __shared__ float Zs[CR_ZMAX];
+    int lb;
+    const CorrJob& jb = bt.job[locate(bt, &lb)];
+    const float* __restrict__ G1 = jb.G1;
+    const float* __restrict__ Z = jb.Z;
+    float* __restrict__ Tpart = jb.Tpart;
+    const CorrGeom g = jb.g;
+    const CorrPlan pl = jb.pl;
+    const int bz = lb / (jb.gx * jb.gy), brem = lb - bz * (jb.gx * jb.gy), by = brem / jb.gx, bx = brem - by * jb.gx;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     const int taps = g.kh * g.kw;
-    const int o0 = blockIdx.x * CR_TO, j0 = blockIdx.y * 16, z = blockIdx.z;
+    const int o0 = bx * CR_TO, j0 = by * 16, z = bz;
     const int HoWo = g.Ho * g.Wo;
 
     int tapofs[MAXT];
@@ -165,17 +186,24 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(const float* __restrict__ 
 }
 
 // one thread per T[o,j,kh,kw] and split of the r1 axis: any geometry
-__global__ __launch_bounds__(256) void k_corr(const float* __restrict__ G1, const float* __restrict__ Z,
-                                              float* __restrict__ Tpart, CorrGeom g, int i_per_split) {
+__global__ __launch_bounds__(256) void k_corr(Batch<CorrJob> bt) {
+    int lb;
+    const CorrJob& jb = bt.job[locate(bt, &lb)];
+    const float* __restrict__ G1 = jb.G1;
+    const float* __restrict__ Z = jb.Z;
+    float* __restrict__ Tpart = jb.Tpart;
+    const CorrGeom g = jb.g;
+    const int i_per_split = jb.ips;
+    const int bsplit = lb / jb.gx, bx = lb - bsplit * jb.gx;
     const int taps = g.kh * g.kw;
     const long long total = (long long)g.cout * g.r2 * taps;
-    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long e = (long long)bx * 256 + threadIdx.x;
     if (e >= total) return;
     const int t = (int)(e % taps);
     const int j = (int)((e / taps) % g.r2);
     const int o = (int)(e / ((long long)taps * g.r2));
     const int kh = t / g.kw, kw = t - kh * g.kw;
-    const int ibeg = blockIdx.y * i_per_split;
+    const int ibeg = bsplit * i_per_split;
     const int iend = (ibeg + i_per_split < g.r1) ? ibeg + i_per_split : g.r1;
     const int hoff = kh * g.dh - g.ph, woff = kw * g.dw - g.pw;
     float acc = 0.f;
@@ -191,7 +219,7 @@ __global__ __launch_bounds__(256) void k_corr(const float* __restrict__ G1, cons
             }
         }
     }
-    Tpart[(long long)blockIdx.y * total + e] = acc;
+    Tpart[(long long)bsplit * total + e] = acc;
 }
 
 int corr_splits(const CorrGeom& g) {
@@ -206,25 +234,50 @@ int corr_splits(const CorrGeom& g) {
     return (g.r1 + ips - 1) / ips;
 }
 
-hipError_t launch_corr(const float* G1, const float* Z, float* Tpart, const CorrGeom& g, int nsplit, hipStream_t st) {
+// key: 0 = k_corr_mfma<1,true>, 1 = <9,true>, 2 = <9,false>, 3 = <25,false>; the fallback kernel has kind IT_CORR
+bool make_corr(const float* G1, const float* Z, float* Tpart, const CorrGeom& g, int nsplit, Item* out) {
     const long long total = (long long)g.cout * g.r2 * g.kh * g.kw;
-    if (total <= 0 || nsplit <= 0) return hipErrorInvalidValue;
-    CorrPlan pl;
-    if (corr_plan(g, &pl)) {
-        if (nsplit != pl.nsplit) return hipErrorInvalidValue;
-        dim3 grid((unsigned)((g.cout + CR_TO - 1) / CR_TO), (unsigned)((g.r2 + 15) / 16), (unsigned)pl.nsplit);
+    if (total <= 0 || nsplit <= 0 || !G1 || !Z || !Tpart) return false;
+    CorrJob jb;
+    std::memset(&jb, 0, sizeof(jb));
+    jb.G1 = G1; jb.Z = Z; jb.Tpart = Tpart; jb.g = g;
+    *out = Item();
+    if (corr_plan(g, &jb.pl)) {
+        if (nsplit != jb.pl.nsplit) return false;
+        jb.gx = (g.cout + CR_TO - 1) / CR_TO; jb.gy = (g.r2 + 15) / 16; jb.gz = jb.pl.nsplit;
         const int taps = g.kh * g.kw;
-        set_last_label("k_corr_mfma<%d, %s>", taps == 1 ? 1 : (taps <= 9 ? 9 : 25), (taps == 1 || taps == 9) ? "true" : "false");
-        if (taps == 1) hipLaunchKernelGGL((k_corr_mfma<1, true>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
-        else if (taps == 9) hipLaunchKernelGGL((k_corr_mfma<9, true>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
-        else if (taps < 9) hipLaunchKernelGGL((k_corr_mfma<9, false>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
-        else hipLaunchKernelGGL((k_corr_mfma<25, false>), grid, 256, 0, st, G1, Z, Tpart, g, pl);
+        out->kind = IT_CORR_MFMA;
+        out->key = taps == 1 ? 0u : (taps == 9 ? 1u : (taps < 9 ? 2u : 3u));
+        std::snprintf(out->label, sizeof(out->label), "k_corr_mfma<%d, %s>", taps == 1 ? 1 : (taps <= 9 ? 9 : 25),
+                      (taps == 1 || taps == 9) ? "true" : "false");
+    } else {
+        jb.ips = (g.r1 + nsplit - 1) / nsplit;
+        if ((total + 255) / 256 > 0x3fffffLL) return false;
+        jb.gx = (int)((total + 255) / 256); jb.gy = nsplit; jb.gz = 1;
+        out->kind = IT_CORR;
+        std::snprintf(out->label, sizeof(out->label), "k_corr");
+    }
+    if ((long long)jb.gx * jb.gy * jb.gz > 0x3fffffffLL) return false;
+    out->nblocks = jb.gx * jb.gy * jb.gz;
+    static_assert(sizeof(CorrJob) <= kItemArgMax, "argument block");
+    std::memcpy(out->arg, &jb, sizeof(jb));
+    return true;
+}
+
+hipError_t launch_corr_items(const Item* const* items, int n, hipStream_t st) {
+    Batch<CorrJob> b;
+    dim3 grid;
+    if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
+    if (items[0]->kind == IT_CORR) {
+        hipLaunchKernelGGL(k_corr, grid, 256, 0, st, b);
         return hipGetLastError();
     }
-    const int ips = (g.r1 + nsplit - 1) / nsplit;
-    dim3 grid((unsigned)((total + 255) / 256), (unsigned)nsplit);
-    set_last_label("k_corr");
-    hipLaunchKernelGGL(k_corr, grid, 256, 0, st, G1, Z, Tpart, g, ips);
+    switch (items[0]->key) {
+        case 0: hipLaunchKernelGGL((k_corr_mfma<1, true>), grid, 256, 0, st, b); break;
+        case 1: hipLaunchKernelGGL((k_corr_mfma<9, true>), grid, 256, 0, st, b); break;
+        case 2: hipLaunchKernelGGL((k_corr_mfma<9, false>), grid, 256, 0, st, b); break;
+        default: hipLaunchKernelGGL((k_corr_mfma<25, false>), grid, 256, 0, st, b); break;
+    }
     return hipGetLastError();
 }
 

@@ -1,74 +1,173 @@
-// Host-side launchers of the ASI kernels.  All pointers are device pointers.
+// Host-side interface of the ASI kernels.  All data pointers are device pointers.
+//
+// Every kernel launch is prepared as an Item: the kernel instantiation (kind, key), its grid and its
+// argument block for ONE layer.  Items of several layers that name the same instantiation are
+// launched together (launch_items): the kernel receives the argument blocks side by side and
+// each workgroup finds its layer from its block index.  A step over L layers therefore costs as
+// many launches as a step over one.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 namespace asi {
 
 enum DType { F32 = 0, BF16 = 1 };
 
-// Name of the kernel instantiation the last launcher call on this thread picked, written the
-// way a profiler prints it (e.g. "k_ttm_mfma<float, false, 3>"); used to tag timing records.
-void set_last_label(const char* fmt, ...);
-const char* last_label();
+constexpr int kMaxBatch = 8;         // layers one launch can serve
+constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument block
 
-// Y[o,q,j] = sum_i X[o,i,j] * M(i,q),  M(i,q) = Mp[i*ms_i + q*ms_q]   (Eq. 4 along one mode)
-// X: (outer, n, inner) of dtype xt;  Y: (outer, r, inner) fp32;  beta != 0 adds to Y.
-hipError_t launch_ttm(DType xt, const void* X, long long outer, int n, long long inner,
-                      const float* Mp, long long ms_i, long long ms_q, int r,
-                      float* Y, int beta, hipStream_t st);
+enum ItemKind {
+    IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
+    IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY
+};
 
-// Two adjacent trailing modes in one pass (small extents): X is (cols, n1*n2) row-major,
-//   Y[c, q1*r2 + q2] (+)= sum_{i1,i2} X[c, i1*n2 + i2] * M1(i1,q1) * M2(i2,q2),  Mk(i,q) = Mk[i*msk_i + q*msk_q]
-hipError_t launch_ttm_kron(DType xt, const void* X, long long cols, int n1, int n2, const float* M1,
-                           long long ms1_i, long long ms1_q, int r1, const float* M2, long long ms2_i,
-                           long long ms2_q, int r2, float* Y, int beta, hipStream_t st);
+struct Item {
+    int kind = 0;
+    unsigned key = 0;        // instantiation within the kind
+    int nblocks = 0;         // workgroups of this layer
+    int aux = 0;             // kind specific (orth: final pass / pass number)
+    char label[96];          // kernel instantiation the way a profiler prints it
+    char role[16];           // what the launch computes ("V", "core", "dW", ...), for timing reports
+    double bytes = 0, flops = 0;   // what this launch must move / compute by its definition
+    alignas(16) unsigned char arg[kItemArgMax];
+};
 
-// part[s][i][q] = sum_{c in split s} X[i,c] * Y[q,c]  over unfolding columns c = (o,j)
+// Launches items[0..n) as ONE kernel launch, n <= kMaxBatch; they must be mergeable (same_launch).
+// label_out (nullable, 96 bytes) receives the name of the instantiation that ran.
+hipError_t launch_items(const Item* const* items, int n, hipStream_t st, char* label_out);
+// Items of the same kernel whose instantiations differ only in size bounds (column blocks, steps)
+// share the launch of the largest.
+bool same_launch(const Item& a, const Item& b);
+
+// Argument blocks side by side; workgroup `blockIdx.x` belongs to the job j with first[j] <= blockIdx.x < first[j+1].
+template <typename J>
+struct Batch {
+    int njobs;
+    int first[kMaxBatch + 1];
+    J job[kMaxBatch];
+};
+
+// device side: index of the job this workgroup belongs to, and its block index inside that job
+template <typename J>
+__device__ __forceinline__ int locate(const Batch<J>& b, int* local) {
+    int j = 0;
+    const int bid = blockIdx.x;
+    while (j + 1 < b.njobs && bid >= b.first[j + 1]) ++j;
+    *local = bid - b.first[j];
+    return j;
+}
+// host side: argument blocks of items[0..n) side by side, grid = all their workgroups
+template <typename J>
+inline bool gather(const Item* const* items, int n, Batch<J>* b, dim3* grid) {
+    if (n <= 0 || n > kMaxBatch) return false;
+    long long total = 0;
+    b->njobs = n;
+    for (int j = 0; j < n; ++j) {
+        b->first[j] = (int)total;
+        memcpy(&b->job[j], items[j]->arg, sizeof(J));
+        total += items[j]->nblocks;
+        if (items[j]->nblocks <= 0 || total > 0x7fffffffLL) return false;
+    }
+    for (int j = n; j <= kMaxBatch; ++j) b->first[j] = (int)total;
+    *grid = dim3((unsigned)total);
+    return true;
+}
+
+// ---- m-mode product (Eq. 4 along one mode) -------------------------------------------------------
+// Y[o,q,j] (+)= sum_i X[o,i,j] * M(i,q),  M(i,q) = Mp[i*ms_i + q*ms_q];  X: (outer, n, inner) of dtype xt,
+// Y: (outer, r, inner) fp32.  With a second factor (kron) the matrix is the Kronecker product
+// M(i,q) = M1(i / n2, q / r2) * M2(i % n2, q % r2), which contracts two adjacent trailing modes at once
+// (inner must be 1).
+struct KronSpec {
+    const float* M2;       // second factor; element (i2, q2) at M2[i2 * ms_i + q2 * ms_q]; null = none
+    long long ms_i, ms_q;
+    int n2, r2;            // i = i1 * n2 + i2,  q = q1 * r2 + q2
+};
+struct TtmJob {
+    const void* X;
+    long long outer, inner;
+    const float* Mp;
+    long long ms_i, ms_q;
+    float* Y;
+    KronSpec kr;
+    int n, r, beta;
+    int gx, gy;            // grid of this job: column tiles x output tiles
+    int tile_cols;         // tiled kernel: unfolding columns per tile (64, or whole outer indices for a short inner)
+    int32_t* zero;         // nullable: `nzero` int32 the kernel clears (arrival counters of later launches)
+    int nzero;
+};
+bool make_ttm(DType xt, const void* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
+              long long ms_q, int r, float* Y, int beta, Item* out);
+bool make_ttm_kron(DType xt, const void* X, long long cols, int n1, int n2, const float* M1, long long ms1_i,
+                   long long ms1_q, int r1, const float* M2, long long ms2_i, long long ms2_q, int r2, float* Y,
+                   int beta, Item* out);
+
+// ---- pair: part[s][i][q] = sum_{c in split s} X[i,c] * Y[q,c]  over unfolding columns c = (o,j) -----
 // X: (outer, n, inner) dtype xt;  Y: (outer, r, inner) fp32;  part: (nsplit, n, r) fp64
 // (products of fp32 values are exact in fp64 and the sums are carried in fp64).
-hipError_t launch_pair(DType xt, const void* X, long long outer, int n, long long inner,
-                       const float* Y, int r, double* part, int nsplit, hipStream_t st);
+struct PairJob {
+    const void* X;
+    long long outer, inner, cols_per_split;
+    const float* Y;
+    double* part;
+    int n, r;
+    int gx, gy, gz;        // row tiles x output tiles x splits
+    int32_t* zero;         // nullable: `nzero` int32 the kernel clears
+    int nzero;
+};
 int pair_splits(long long outer, int n, long long inner, int r);
+bool make_pair(DType xt, const void* X, long long outer, int n, long long inner, const float* Y, int r, double* part,
+               int nsplit, int32_t* zero, int nzero, Item* out);
 
-// out[e] = (beta ? out[e] : 0) + sum_s part[s*count + e]
-hipError_t launch_sum_partials(const float* part, int nsplit, long long count, float* out, int beta,
-                               hipStream_t st);
-hipError_t launch_sum_partials_f64(const double* part, int nsplit, long long count, float* out, int beta,
-                                   hipStream_t st);
+// ---- out[e] = (beta ? out[e] : 0) + sum_s part[s*count + e] ---------------------------------------------
+struct SumJob {
+    const void* part;
+    float* out;
+    long long count;
+    int nsplit, beta;
+};
+bool make_sum_partials(const float* part, int nsplit, long long count, float* out, int beta, Item* it);
+bool make_sum_partials_f64(const double* part, int nsplit, long long count, float* out, int beta, Item* it);
 
-// Fused V/P step for a mode with n <= 64 (asi_subspace.hip): part is (nwg, n, r) fp64.
+// ---- fused V/P step for modes with n <= 64 (asi_subspace.hip): part is (nwg, n, r) fp64 ---------------
 bool subspace_small_supported(int n, int r);
 int subspace_small_nwg(long long outer, int n, long long inner);
-hipError_t launch_subspace_small(DType xt, const void* X, long long outer, int n, long long inner, const float* U,
-                                 int r, double* part, int nwg, hipStream_t st);
+bool make_subspace_small(DType xt, const void* X, long long outer, int n, long long inner, const float* U, int r,
+                         double* part, int nwg, int32_t* zero, int nzero, Item* out);
 // The last two modes of X seen as (planes, rows, cols), both from one read of X.
 bool subspace_pair_supported(int rows, int cols, int r_rows, int r_cols);
 int subspace_pair_nwg(long long planes, int rows, int cols);
-hipError_t launch_subspace_pair(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows,
-                                int r_rows, double* part_rows, const float* U_cols, int r_cols, double* part_cols,
-                                int nwg, hipStream_t st);
+bool make_subspace_pair(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows, int r_rows,
+                        double* part_rows, const float* U_cols, int r_cols, double* part_cols, int nwg, Item* out);
 
+// Both when rows, cols and both ranks are at most 8: vector-ALU kernel, no MFMA padding.
+bool subspace_tiny_supported(int rows, int cols, int r_rows, int r_cols);
+int subspace_tiny_nwg(long long planes);
+bool make_subspace_tiny(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows, int r_rows,
+                        double* part_rows, const float* U_cols, int r_cols, double* part_cols, int nwg, Item* out);
+
+// ---- Orthogonalize (asi_orth.hip) ---------------------------------------------------------------------------
 struct OrthJob {
     const double* part;  // (nsplit, n, r) partial sums of P
-    int nsplit;
-    int n, r;
     double* P64;         // (n, r) scratch
     float* Uout;         // (n, r)
-    int mode1;           // 1-based mode number for *info
-    // fast path (r <= 64)
-    int nblk;            // row slices = orth_slices(n)
-    double* Gpart;       // (nblk, r, r) slice Gram matrices
+    int32_t* info;       // nullable
+    // fast path (r <= 64) and wide path
+    double* Gpart;       // (nblk, r (r+1) / 2) packed slice Gram matrices; slow path: (r, r) Gram matrix
     double* R;           // (r, r)
     double* Dinv;        // (ceil(r/16), 16, 16) inverses of R's diagonal blocks
-    double* scal;        // 66 doubles of bookkeeping
-    // slow path (r > 64)
-    double* G;           // (r, r)
+    double* scal;        // 66 doubles of bookkeeping (wide path: 2 + 192)
+    int32_t* ctr;        // 2 arrival counters, zero before the first orth launch of a call
+    int nsplit;
+    int n, r;
+    int mode1;           // 1-based mode number for *info
+    int nblk;            // row slices = orth_slices(n) (wide path: orth_wide_gram_blocks(n))
+    int pad_;
 };
-struct OrthArgs {
+struct OrthArgs {        // the modes of one tensor that share a path
     OrthJob job[4];
     int njobs;
-    int32_t* info;       // nullable
 };
 struct PresumJob {
     const double* in;    // (nsplit, cnt)
@@ -80,34 +179,51 @@ struct PresumArgs {
     PresumJob job[4];
     int njobs;
 };
-hipError_t launch_orth_presum(const PresumArgs& a, hipStream_t st);
+bool make_orth_presum(const PresumArgs& a, Item* out);
 bool orth_fast_supported(int r);
 int orth_slices(int n);
-hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st);
-hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t st);
-hipError_t launch_orth_apply(const OrthArgs& a, int final_pass, hipStream_t st);
+// gram0: sums the partial sums of P, slice Grams; the last workgroup of a mode factors (shifted pass)
+//        and clears *info.
+// apply(0): Q0 = P R0^-1, slice Grams of Q0; the last workgroup of a mode factors again.
+// apply(1): U = Q0 R1^-1 in fp32.
+bool make_orth_gram0(const OrthArgs& a, Item* out);
+bool make_orth_apply(const OrthArgs& a, int final_pass, Item* out);
 // wide path, 64 < r <= 192: nblk = orth_wide_gram_blocks(n), scal holds 2 + 192 doubles,
-// P64 must already hold the summed P (launch_orth_presum with a single group does that)
+// P64 must already hold the summed P (make_orth_presum with a single group does that)
 bool orth_wide_supported(int r);
 int orth_wide_gram_blocks(int n);
-hipError_t launch_orthw_gram(const OrthArgs& a, hipStream_t st);
-hipError_t launch_orthw_chol(const OrthArgs& a, int pass, int last, hipStream_t st);
-hipError_t launch_orthw_apply(const OrthArgs& a, int final_pass, hipStream_t st);
-hipError_t launch_orth_big(const OrthArgs& a, hipStream_t st);
-hipError_t launch_init_ctrl(int32_t* info, hipStream_t st);   // *info = 0 if non-null
-hipError_t launch_set_i32(int32_t* p, int32_t v, hipStream_t st);
+bool make_orthw_gram(const OrthArgs& a, Item* out);
+bool make_orthw_chol(const OrthArgs& a, int pass, int last, Item* out);
+bool make_orthw_apply(const OrthArgs& a, int final_pass, Item* out);
+bool make_orth_big(const OrthArgs& a, Item* out);
+bool make_init_ctrl(int32_t* info, Item* out);   // *info = 0
 
-// Step 4 of Eq. 14: T[o,j,kh,kw] = sum_{i,y,x} G1[i,o,y,x] * Zpad[i,j,y*s-p+kh*d, x*s-p+kw*d]
+// ---- step 4 of Eq. 14: T[o,j,kh,kw] = sum_{i,y,x} G1[i,o,y,x] * Zpad[i,j,y*s-p+kh*d, x*s-p+kw*d] -----------
 // G1: (r1, cout, Ho, Wo);  Z: (r1, r2, H, W);  Tpart: (nsplit, cout, r2, kh, kw), split over i.
 struct CorrGeom {
     int r1, r2, cout, H, W, Ho, Wo, kh, kw, sh, sw, ph, pw, dh, dw;
 };
 int corr_splits(const CorrGeom& g);
-hipError_t launch_corr(const float* G1, const float* Z, float* Tpart, const CorrGeom& g, int nsplit,
-                       hipStream_t st);
+bool make_corr(const float* G1, const float* Z, float* Tpart, const CorrGeom& g, int nsplit, Item* out);
 
-// Step 5 of Eq. 14 with groups: dW[o,c,t] (+)= sum_j T[o,j,t] * U2[(o/og)*cg + c, j]
-hipError_t launch_expand_grouped(const float* T, const float* U2, float* dW, int cout, int r2, int taps,
-                                 int cg, int og, int beta, hipStream_t st);
+// ---- step 5 of Eq. 14 with groups: dW[o,c,t] (+)= sum_j T[o,j,t] * U2[(o/og)*cg + c, j] -----------------------
+struct ExpandJob {
+    const float* T;
+    const float* U2;
+    float* dW;
+    int cout, r2, taps, cg, og, beta;
+};
+bool make_expand_grouped(const float* T, const float* U2, float* dW, int cout, int r2, int taps, int cg, int og,
+                         int beta, Item* out);
+
+// per-kind batch launchers (called by launch_items)
+hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, char* label_out);
+hipError_t launch_pair_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_sum_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_expand_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_small_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_corr_items(const Item* const* items, int n, hipStream_t st);
 
 }  // namespace asi

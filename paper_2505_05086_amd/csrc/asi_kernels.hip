@@ -2,23 +2,15 @@
 //
 // Contractions over a tensor seen from a mode, X[o,i,j] (outer, n, inner):
 //   pair: P[i,q]    = sum_{o,j} X[o,i,j] Y[o,q,j]      (A_m V of Alg. 1)
-// plus partial-sum reduction, the step-4 correlation of Eq. 14 and its grouped step 5.
+// plus partial-sum reduction and the grouped step 5 of Eq. 14.  Every kernel serves the
+// argument blocks of several layers side by side.
 #include "asi_device.h"
 #include "asi_kernels.h"
 
-#include <cstdarg>
 #include <cstdio>
+#include <cstring>
 
 namespace asi {
-
-static thread_local char g_last_label[160] = "";
-void set_last_label(const char* fmt, ...) {
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(g_last_label, sizeof(g_last_label), fmt, ap);
-    va_end(ap);
-}
-const char* last_label() { return g_last_label; }
 
 // ---------------------------------------------------------------------------
 // pair: P[i,q] = sum_c X[i,c] Y[q,c] on fp64 MFMA.  A workgroup owns 64 rows i x 32 outputs q
@@ -31,16 +23,23 @@ constexpr int PR_TI = 64, PR_TQ = 32, PR_TK = 32;
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 template <typename T, bool LASTMODE>
-__global__ __launch_bounds__(256) void k_pair(const T* __restrict__ X, long long outer, int n, long long inner,
-                                              const float* __restrict__ Y, int r, double* __restrict__ part,
-                                              long long cols_per_split) {
+__global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
     __shared__ float Xs[PR_TK][PR_TI + 4];
     __shared__ float Ys[PR_TK][PR_TQ + 4];
+    int lb;
+    const PairJob& jb = bt.job[locate(bt, &lb)];
+    const T* __restrict__ X = static_cast<const T*>(jb.X);
+    const float* __restrict__ Y = jb.Y;
+    double* __restrict__ part = jb.part;
+    const long long outer = jb.outer, inner = jb.inner, cols_per_split = jb.cols_per_split;
+    const int n = jb.n, r = jb.r;
+    const int bz = lb / (jb.gx * jb.gy), rem = lb - bz * (jb.gx * jb.gy), by = rem / jb.gx, bx = rem - by * jb.gx;
     const long long ncols = outer * inner;
-    const int i0 = blockIdx.x * PR_TI, q0 = blockIdx.y * PR_TQ, s = blockIdx.z;
+    const int i0 = bx * PR_TI, q0 = by * PR_TQ, s = bz;
     const long long cbeg = (long long)s * cols_per_split;
     const long long cend = (cbeg + cols_per_split < ncols) ? cbeg + cols_per_split : ncols;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
+    if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;   // arrival counters of later launches
 
     float xr[8], yr[4];
     auto fetch = [&](long long c0) {
@@ -137,20 +136,37 @@ int pair_splits(long long outer, int n, long long inner, int r) {
     return ns;
 }
 
-hipError_t launch_pair(DType xt, const void* X, long long outer, int n, long long inner, const float* Y, int r,
-                       double* part, int nsplit, hipStream_t st) {
+bool make_pair(DType xt, const void* X, long long outer, int n, long long inner, const float* Y, int r, double* part,
+               int nsplit, int32_t* zero, int nzero, Item* out) {
     const long long ncols = outer * inner;
-    if (ncols <= 0 || n <= 0 || r <= 0 || nsplit <= 0) return hipErrorInvalidValue;
-    const long long cps = pair_cols_per_split(ncols, nsplit);
-    dim3 grid((unsigned)((n + PR_TI - 1) / PR_TI), (unsigned)((r + PR_TQ - 1) / PR_TQ), (unsigned)nsplit);
+    if (ncols <= 0 || n <= 0 || r <= 0 || nsplit <= 0 || !X || !Y || !part || nzero < 0 || nzero > 256) return false;
+    PairJob jb;
+    std::memset(&jb, 0, sizeof(jb));
+    jb.X = X; jb.outer = outer; jb.inner = inner; jb.cols_per_split = pair_cols_per_split(ncols, nsplit);
+    jb.Y = Y; jb.part = part; jb.n = n; jb.r = r;
+    jb.gx = (n + PR_TI - 1) / PR_TI; jb.gy = (r + PR_TQ - 1) / PR_TQ; jb.gz = nsplit;
+    jb.zero = zero; jb.nzero = zero ? nzero : 0;
     const bool last = (inner == 1);
-    set_last_label("k_pair<%s, %s>", xt == F32 ? "float" : "asi::bf16_t", last ? "true" : "false");
-    if (xt == F32) {
-        if (last) hipLaunchKernelGGL((k_pair<float, true>), grid, 256, 0, st, (const float*)X, outer, n, inner, Y, r, part, cps);
-        else      hipLaunchKernelGGL((k_pair<float, false>), grid, 256, 0, st, (const float*)X, outer, n, inner, Y, r, part, cps);
+    *out = Item();
+    out->kind = IT_PAIR; out->key = (xt == BF16 ? 1u : 0u) | (last ? 2u : 0u);
+    out->nblocks = jb.gx * jb.gy * jb.gz;
+    std::snprintf(out->label, sizeof(out->label), "k_pair<%s, %s>", xt == F32 ? "float" : "asi::bf16_t", last ? "true" : "false");
+    static_assert(sizeof(PairJob) <= kItemArgMax, "argument block");
+    std::memcpy(out->arg, &jb, sizeof(jb));
+    return true;
+}
+
+hipError_t launch_pair_items(const Item* const* items, int n, hipStream_t st) {
+    Batch<PairJob> b;
+    dim3 grid;
+    if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
+    const unsigned key = items[0]->key;
+    if (!(key & 1u)) {
+        if (key & 2u) hipLaunchKernelGGL((k_pair<float, true>), grid, 256, 0, st, b);
+        else          hipLaunchKernelGGL((k_pair<float, false>), grid, 256, 0, st, b);
     } else {
-        if (last) hipLaunchKernelGGL((k_pair<bf16_t, true>), grid, 256, 0, st, (const bf16_t*)X, outer, n, inner, Y, r, part, cps);
-        else      hipLaunchKernelGGL((k_pair<bf16_t, false>), grid, 256, 0, st, (const bf16_t*)X, outer, n, inner, Y, r, part, cps);
+        if (key & 2u) hipLaunchKernelGGL((k_pair<bf16_t, true>), grid, 256, 0, st, b);
+        else          hipLaunchKernelGGL((k_pair<bf16_t, false>), grid, 256, 0, st, b);
     }
     return hipGetLastError();
 }
@@ -159,64 +175,120 @@ hipError_t launch_pair(DType xt, const void* X, long long outer, int n, long lon
 // sum of split partials
 // ---------------------------------------------------------------------------
 template <typename PT>
-__global__ __launch_bounds__(256) void k_sum_partials(const PT* __restrict__ part, int nsplit, long long count,
-                                                      float* __restrict__ out, int beta) {
-    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(256) void k_sum_partials(Batch<SumJob> bt) {
+    int lb;
+    const SumJob& jb = bt.job[locate(bt, &lb)];
+    const PT* __restrict__ part = static_cast<const PT*>(jb.part);
+    const long long count = jb.count;
+    const long long e = (long long)lb * 256 + threadIdx.x;
     if (e >= count) return;
     double s = 0.0;
-    for (int sp = 0; sp < nsplit; ++sp) s += (double)part[(long long)sp * count + e];
-    out[e] = beta ? out[e] + (float)s : (float)s;
+    for (int sp0 = 0; sp0 < jb.nsplit; sp0 += 8) {          // 8 loads in flight
+        PT t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = part[(sp0 + u < jb.nsplit) ? (long long)(sp0 + u) * count + e : e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (sp0 + u < jb.nsplit) ? (double)t[u] : 0.0;
+    }
+    jb.out[e] = jb.beta ? jb.out[e] + (float)s : (float)s;
 }
 
-hipError_t launch_sum_partials(const float* part, int nsplit, long long count, float* out, int beta, hipStream_t st) {
-    if (count <= 0) return hipErrorInvalidValue;
-    const long long gx = (count + 255) / 256;
-    set_last_label("k_sum_partials<float>");
-    hipLaunchKernelGGL(k_sum_partials<float>, dim3((unsigned)gx), 256, 0, st, part, nsplit, count, out, beta);
-    return hipGetLastError();
+static bool fill_sum(const void* part, bool f64, int nsplit, long long count, float* out, int beta, Item* it) {
+    if (count <= 0 || nsplit <= 0 || !part || !out || (count + 255) / 256 > 0x3fffffffLL) return false;
+    SumJob jb;
+    std::memset(&jb, 0, sizeof(jb));
+    jb.part = part; jb.out = out; jb.count = count; jb.nsplit = nsplit; jb.beta = beta;
+    *it = Item();
+    it->kind = f64 ? IT_SUM_F64 : IT_SUM_F32;
+    it->nblocks = (int)((count + 255) / 256);
+    std::snprintf(it->label, sizeof(it->label), "k_sum_partials<%s>", f64 ? "double" : "float");
+    std::memcpy(it->arg, &jb, sizeof(jb));
+    return true;
 }
-hipError_t launch_sum_partials_f64(const double* part, int nsplit, long long count, float* out, int beta,
-                                   hipStream_t st) {
-    if (count <= 0) return hipErrorInvalidValue;
-    const long long gx = (count + 255) / 256;
-    set_last_label("k_sum_partials<double>");
-    hipLaunchKernelGGL(k_sum_partials<double>, dim3((unsigned)gx), 256, 0, st, part, nsplit, count, out, beta);
-    return hipGetLastError();
+bool make_sum_partials(const float* part, int nsplit, long long count, float* out, int beta, Item* it) {
+    return fill_sum(part, false, nsplit, count, out, beta, it);
 }
-
-__global__ void k_set_i32(int32_t* p, int32_t v) { *p = v; }
-hipError_t launch_set_i32(int32_t* p, int32_t v, hipStream_t st) {
-    hipLaunchKernelGGL(k_set_i32, 1, 1, 0, st, p, v);
+bool make_sum_partials_f64(const double* part, int nsplit, long long count, float* out, int beta, Item* it) {
+    return fill_sum(part, true, nsplit, count, out, beta, it);
+}
+hipError_t launch_sum_items(const Item* const* items, int n, hipStream_t st) {
+    Batch<SumJob> b;
+    dim3 grid;
+    if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
+    if (items[0]->kind == IT_SUM_F64) hipLaunchKernelGGL(k_sum_partials<double>, grid, 256, 0, st, b);
+    else hipLaunchKernelGGL(k_sum_partials<float>, grid, 256, 0, st, b);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
 // Step 5 of Eq. 14 for grouped convolutions
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_expand_grouped(const float* __restrict__ T, const float* __restrict__ U2,
-                                                        float* __restrict__ dW, int cout, int r2, int taps, int cg,
-                                                        int og, int beta) {
-    const long long total = (long long)cout * cg * taps;
-    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(256) void k_expand_grouped(Batch<ExpandJob> bt) {
+    int lb;
+    const ExpandJob& jb = bt.job[locate(bt, &lb)];
+    const int r2 = jb.r2, taps = jb.taps, cg = jb.cg, og = jb.og;
+    const long long total = (long long)jb.cout * cg * taps;
+    const long long e = (long long)lb * 256 + threadIdx.x;
     if (e >= total) return;
     const int t = (int)(e % taps);
     const int c = (int)((e / taps) % cg);
     const int o = (int)(e / ((long long)taps * cg));
-    const float* tp = T + (long long)o * r2 * taps + t;
-    const float* up = U2 + ((long long)(o / og) * cg + c) * r2;
+    const float* tp = jb.T + (long long)o * r2 * taps + t;
+    const float* up = jb.U2 + ((long long)(o / og) * cg + c) * r2;
     float acc = 0.f;
     for (int j = 0; j < r2; ++j) acc = fmaf(tp[(long long)j * taps], up[j], acc);
-    dW[e] = beta ? dW[e] + acc : acc;
+    jb.dW[e] = jb.beta ? jb.dW[e] + acc : acc;
 }
 
-hipError_t launch_expand_grouped(const float* T, const float* U2, float* dW, int cout, int r2, int taps, int cg,
-                                 int og, int beta, hipStream_t st) {
+bool make_expand_grouped(const float* T, const float* U2, float* dW, int cout, int r2, int taps, int cg, int og,
+                         int beta, Item* out) {
     const long long total = (long long)cout * cg * taps;
-    if (total <= 0) return hipErrorInvalidValue;
-    set_last_label("k_expand_grouped");
-    hipLaunchKernelGGL(k_expand_grouped, dim3((unsigned)((total + 255) / 256)), 256, 0, st, T, U2, dW, cout, r2,
-                       taps, cg, og, beta);
+    if (total <= 0 || !T || !U2 || !dW || (total + 255) / 256 > 0x3fffffffLL) return false;
+    ExpandJob jb = {T, U2, dW, cout, r2, taps, cg, og, beta};
+    *out = Item();
+    out->kind = IT_EXPAND;
+    out->nblocks = (int)((total + 255) / 256);
+    std::snprintf(out->label, sizeof(out->label), "k_expand_grouped");
+    std::memcpy(out->arg, &jb, sizeof(jb));
+    return true;
+}
+hipError_t launch_expand_items(const Item* const* items, int n, hipStream_t st) {
+    Batch<ExpandJob> b;
+    dim3 grid;
+    if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_expand_grouped, grid, 256, 0, st, b);
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// one launch for the items of several layers
+// ---------------------------------------------------------------------------
+// key bits of the mode-product kernels that only bound sizes (see asi_ttm.hip): NBR, KS
+static unsigned launch_class(const Item& it) {
+    if (it.kind == IT_TTM || it.kind == IT_KSPLIT) return it.key & 0xfu;
+    return it.key;
+}
+bool same_launch(const Item& a, const Item& b) {
+    return a.kind == b.kind && a.aux == b.aux && launch_class(a) == launch_class(b);
+}
+
+hipError_t launch_items(const Item* const* items, int n, hipStream_t st, char* label_out) {
+    if (n <= 0 || n > kMaxBatch) return hipErrorInvalidValue;
+    for (int j = 1; j < n; ++j)
+        if (!same_launch(*items[0], *items[j])) return hipErrorInvalidValue;
+    if (label_out) std::snprintf(label_out, 96, "%s", items[0]->label);
+    switch (items[0]->kind) {
+        case IT_TTM: case IT_KSPLIT: return launch_ttm_items(items, n, st, label_out);
+        case IT_PAIR: return launch_pair_items(items, n, st);
+        case IT_SUM_F32: case IT_SUM_F64: return launch_sum_items(items, n, st);
+        case IT_EXPAND: return launch_expand_items(items, n, st);
+        case IT_SMALL: return launch_small_items(items, n, st);
+        case IT_TINY: return launch_tiny_items(items, n, st);
+        case IT_PRESUM: case IT_GRAM0: case IT_APPLY: case IT_ORTHW_GRAM: case IT_ORTHW_CHOL: case IT_ORTHW_APPLY:
+        case IT_ORTH_BIG: case IT_INIT: return launch_orth_items(items, n, st);
+        case IT_CORR_MFMA: case IT_CORR: return launch_corr_items(items, n, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace asi

@@ -20,6 +20,9 @@
 #include "asi_device.h"
 #include "asi_kernels.h"
 
+#include <cstdio>
+#include <cstring>
+
 namespace asi {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
@@ -43,7 +46,19 @@ __device__ __forceinline__ void flag_info(int32_t* info, int mode1, int col1) {
     if (info) atomicCAS(info, 0, mode1 * 1000 + col1);
 }
 
-__device__ __forceinline__ void find_job(const OrthArgs& a, int* ji, int* blk) {
+// the modes of all layers of one launch
+constexpr int kMaxOrthJobs = 4 * kMaxBatch;
+struct OrthBatch {
+    OrthJob job[kMaxOrthJobs];
+    int njobs;
+};
+struct PresumBatch {
+    PresumJob job[kMaxOrthJobs];
+    int njobs;
+};
+static_assert(sizeof(OrthBatch) <= 4096, "kernel argument limit");
+
+__device__ __forceinline__ void find_job(const OrthBatch& a, int* ji, int* blk) {
     int j = 0, b = blockIdx.x;
     while (j + 1 < a.njobs && b >= a.job[j].nblk) { b -= a.job[j].nblk; ++j; }
     *ji = j; *blk = b;
@@ -77,7 +92,7 @@ __device__ void gram_from_lds(const double (*Ps)[OP_LD], int r, double* __restri
 // ---- first level of the partial-sum tree -----------------------------------------------------
 // When a mode arrives with more than 32 split partial sums, groups of 32 are added first
 // (fixed order inside a group), so that no workgroup of gram0 has to walk hundreds of them.
-__global__ __launch_bounds__(256) void k_orth_presum(PresumArgs a) {
+__global__ __launch_bounds__(256) void k_orth_presum(PresumBatch a) {
     int j = 0, b = blockIdx.x;
     while (j + 1 < a.njobs && b >= a.job[j].nchunks * a.job[j].ngroups) { b -= a.job[j].nchunks * a.job[j].ngroups; ++j; }
     const PresumJob jb = a.job[j];
@@ -92,88 +107,6 @@ __global__ __launch_bounds__(256) void k_orth_presum(PresumArgs a) {
 #pragma unroll
     for (int u = 0; u < 32; ++u) s += t[u];
     jb.out[(long long)g * jb.cnt + e] = s;
-}
-
-hipError_t launch_orth_presum(const PresumArgs& a, hipStream_t st) {
-    if (a.njobs <= 0 || a.njobs > 4) return hipErrorInvalidValue;
-    long long blocks = 0;
-    for (int j = 0; j < a.njobs; ++j) {
-        const PresumJob& jb = a.job[j];
-        if (!jb.in || !jb.out || jb.cnt <= 0 || jb.nsplit <= 0) return hipErrorInvalidValue;
-        if (jb.nchunks != (int)((jb.cnt + 255) / 256) || jb.ngroups != (jb.nsplit + 31) / 32) return hipErrorInvalidValue;
-        blocks += (long long)jb.nchunks * jb.ngroups;
-    }
-    set_last_label("k_orth_presum");
-    hipLaunchKernelGGL(k_orth_presum, dim3((unsigned)blocks), 256, 0, st, a);
-    return hipGetLastError();
-}
-
-// ---- gram0 ----------------------------------------------------------------------------------
-// RM bounds the ranks of the launch's modes: a slice has at most 32 * RM elements, ITS per thread.
-template <int RM>
-__global__ __launch_bounds__(256) void k_orth_gram0(OrthArgs a) {
-    __shared__ double Ps[OP_RS][OP_LD];
-    __shared__ double red[256];
-    int ji, blk;
-    find_job(a, &ji, &blk);
-    const OrthJob jb = a.job[ji];
-    const int n = jb.n, r = jb.r, tid = threadIdx.x;
-    if (blockIdx.x == 0 && tid == 0 && a.info) *a.info = 0;      // nothing has reported yet
-    const int i0 = blk * OP_RS;
-    const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
-    const long long cnt = (long long)n * r;
-    const int E = nrows * r;
-    for (int e = tid; e < OP_RS * OP_LD; e += 256) (&Ps[0][0])[e] = 0.0;
-    // Sum of the split partial sums.  A slice of 256 or more elements gives every thread ITS
-    // elements and SB splits per round; a smaller one shares its splits among `nsg` thread
-    // groups whose results are added in group order.  All loads of a round are in flight together.
-    constexpr int ITS = RM / 8, SB = 32 / ITS;
-    const bool small = E < 256;
-    const int nsg = small ? 256 / E : 1;
-    const int sg = small ? tid / E : 0;
-    const int idx0 = small ? tid - sg * E : tid;
-    const bool act0 = sg < nsg;
-    double sum[ITS];
-#pragma unroll
-    for (int it = 0; it < ITS; ++it) sum[it] = 0.0;
-    for (int sp0 = sg; sp0 < jb.nsplit; sp0 += SB * nsg) {
-        double t[SB][ITS];
-#pragma unroll
-        for (int u = 0; u < SB; ++u)
-#pragma unroll
-            for (int it = 0; it < ITS; ++it) {
-                const int sp = sp0 + u * nsg, idx = idx0 + 256 * it;
-                const bool ok = act0 && idx < E && (it == 0 || !small) && sp < jb.nsplit;
-                t[u][it] = ldg_f64(jb.part, (long long)sp * cnt + (long long)i0 * r + idx, ok);
-            }
-#pragma unroll
-        for (int u = 0; u < SB; ++u)
-#pragma unroll
-            for (int it = 0; it < ITS; ++it) sum[it] += t[u][it];
-    }
-    if (small && nsg > 1) {
-        if (act0) red[sg * E + idx0] = sum[0];
-        __syncthreads();
-        if (act0 && sg == 0) {
-            double s2 = 0.0;
-            for (int g2 = 0; g2 < nsg; ++g2) s2 += red[g2 * E + idx0];
-            sum[0] = s2;
-        }
-    } else {
-        __syncthreads();      // the zero fill above is complete
-    }
-    if (act0 && sg == 0) {
-#pragma unroll
-        for (int it = 0; it < ITS; ++it) {
-            const int idx = idx0 + 256 * it;
-            if (idx < E && (it == 0 || !small)) {
-                jb.P64[(long long)i0 * r + idx] = sum[it];
-                Ps[idx / r][idx % r] = sum[it];
-            }
-        }
-    }
-    __syncthreads();
-    gram_from_lds(Ps, r, jb.Gpart + (long long)blk * ((r * (r + 1)) / 2));
 }
 
 // ---- chol -----------------------------------------------------------------------------------
@@ -273,21 +206,33 @@ __device__ void chol_block16(double (*Gs)[OP_LD], double (*rowbuf)[64][4], doubl
     BSTAMP(27);
 }
 
-// Blocked right-looking Cholesky of the matrix in Gs (identity padded to a multiple of 16):
+// One workgroup (256 threads): sums the slice Grams of a mode, adds the shift (first pass) and
+// factors the matrix, identity padded to a multiple of 16, by blocked right-looking Cholesky:
 // wave 0 factors a diagonal block, then the four waves solve that block row and update the
-// trailing blocks with fp64 MFMA.  scal[0] = trace(P^T P), scal[1 + k] = running product of the
+// trailing blocks with fp64 MFMA.  Writes R, the inverses of R's diagonal blocks and the
+// bookkeeping in scal; with `last` it reports a rank-deficient P through *info.  scal[0] = trace(P^T P), scal[1 + k] = running product of the
 // R diagonals, scal[65] = first bad pivot.
+struct CholSmem {
+    double Gs[OP_RMAX][OP_LD];
+    double dinv[OP_RMAX];
+    double rdiag[OP_RMAX];
+    double pinvs[OP_RMAX];
+    double rowbuf[2][64][4];
+    double Xs[OP_RMAX / 16][16][17];
+    double s_trace;
+    int s_bad;
+};
+
 template <int RM>
-__global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int last) {
-    __shared__ double Gs[OP_RMAX][OP_LD];
-    __shared__ double dinv[OP_RMAX];
-    __shared__ double rdiag[OP_RMAX];
-    __shared__ double pinvs[OP_RMAX];
-    __shared__ double rowbuf[2][64][4];
-    __shared__ double Xs[OP_RMAX / 16][16][17];
-    __shared__ double s_trace;
-    __shared__ int s_bad;
-    const OrthJob jb = a.job[blockIdx.x];
+__device__ void chol_job(const OrthJob& jb, int pass, int last, int32_t* info, CholSmem& sm) {
+    double (*Gs)[OP_LD] = sm.Gs;
+    double* dinv = sm.dinv;
+    double* rdiag = sm.rdiag;
+    double* pinvs = sm.pinvs;
+    double (*rowbuf)[64][4] = sm.rowbuf;
+    double (*Xs)[16][17] = sm.Xs;
+    double& s_trace = sm.s_trace;
+    int& s_bad = sm.s_bad;
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     const int nb = (r + 15) / 16;
@@ -431,22 +376,127 @@ __global__ __launch_bounds__(256) void k_orth_chol(OrthArgs a, int pass, int las
             double badv = (pass == 0) ? 0.0 : jb.scal[65];
             if (badv == 0.0 && s_bad) badv = (double)s_bad;
             jb.scal[65] = badv;
-            if (last && a.info) {
-                if (badv != 0.0) flag_info(a.info, jb.mode1, (int)badv);
-                if (mask) flag_info(a.info, jb.mode1, __ffsll((long long)mask));
+            if (last && info) {
+                if (badv != 0.0) flag_info(info, jb.mode1, (int)badv);
+                if (mask) flag_info(info, jb.mode1, __ffsll((long long)mask));
             }
         }
     }
 }
 
+// ---- hand-over from the slices of a mode to its factorisation ------------------------------
+// Every workgroup of a mode calls this after its global writes.  Returns true in exactly one of
+// them, the one that arrives last; by then the writes of all the others are visible to it.  The
+// counter must be zero before the launch and is zero again afterwards.
+__device__ bool last_arrival(int32_t* ctr, int nblk, int* s_flag) {
+    __threadfence();                       // this thread's writes are visible device-wide ...
+    __syncthreads();                       // ... for every thread of the workgroup
+    if (threadIdx.x == 0) {
+        const int ticket = atomicAdd(ctr, 1);
+        *s_flag = (ticket == nblk - 1);
+        if (ticket == nblk - 1) *ctr = 0;
+    }
+    __syncthreads();
+    const bool last = *s_flag != 0;
+    if (last) __threadfence();             // order the reads below after the other workgroups' arrivals
+    return last;
+}
+
+// ---- gram0 ----------------------------------------------------------------------------------
+// RM bounds the ranks of the launch's modes: a slice has at most 32 * RM elements, ITS per thread.
+template <int RM>
+__global__ __launch_bounds__(256) void k_orth_gram0(OrthBatch a) {
+    __shared__ __align__(16) unsigned char raw[sizeof(CholSmem)];
+    __shared__ int s_last;
+    double (*Ps)[OP_LD] = reinterpret_cast<double (*)[OP_LD]>(raw);                 // [OP_RS][OP_LD]
+    double* red = reinterpret_cast<double*>(raw) + OP_RS * OP_LD;                     // [256]
+    static_assert(sizeof(CholSmem) >= (OP_RS * OP_LD + 256) * sizeof(double), "slice buffers fit");
+    int ji, blk;
+    find_job(a, &ji, &blk);
+    const OrthJob jb = a.job[ji];
+    const int n = jb.n, r = jb.r, tid = threadIdx.x;
+    if (blk == 0 && tid == 0 && jb.info) *jb.info = 0;            // nothing has reported yet
+    const int i0 = blk * OP_RS;
+    const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
+    const long long cnt = (long long)n * r;
+    const int E = nrows * r;
+    for (int e = tid; e < OP_RS * OP_LD; e += 256) (&Ps[0][0])[e] = 0.0;
+    // Sum of the split partial sums.  A slice of 256 or more elements gives every thread ITS
+    // elements and SB splits per round; a smaller one shares its splits among `nsg` thread
+    // groups whose results are added in group order.  All loads of a round are in flight together.
+    constexpr int ITS = RM / 8, SB = 32 / ITS;
+    const bool small = E < 256;
+    const int nsg = small ? 256 / E : 1;
+    const int sg = small ? tid / E : 0;
+    const int idx0 = small ? tid - sg * E : tid;
+    const bool act0 = sg < nsg;
+    double sum[ITS];
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) sum[it] = 0.0;
+    for (int sp0 = sg; sp0 < jb.nsplit; sp0 += SB * nsg) {
+        double t[SB][ITS];
+#pragma unroll
+        for (int u = 0; u < SB; ++u)
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) {
+                const int sp = sp0 + u * nsg, idx = idx0 + 256 * it;
+                const bool ok = act0 && idx < E && (it == 0 || !small) && sp < jb.nsplit;
+                t[u][it] = ldg_f64(jb.part, (long long)sp * cnt + (long long)i0 * r + idx, ok);
+            }
+#pragma unroll
+        for (int u = 0; u < SB; ++u)
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) sum[it] += t[u][it];
+    }
+    if (small && nsg > 1) {
+        if (act0) red[sg * E + idx0] = sum[0];
+        __syncthreads();
+        if (act0 && sg == 0) {
+            double s2 = 0.0;
+            for (int g2 = 0; g2 < nsg; ++g2) s2 += red[g2 * E + idx0];
+            sum[0] = s2;
+        }
+    } else {
+        __syncthreads();      // the zero fill above is complete
+    }
+    if (act0 && sg == 0) {
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const int idx = idx0 + 256 * it;
+            if (idx < E && (it == 0 || !small)) {
+                jb.P64[(long long)i0 * r + idx] = sum[it];
+                Ps[idx / r][idx % r] = sum[it];
+            }
+        }
+    }
+    __syncthreads();
+    gram_from_lds(Ps, r, jb.Gpart + (long long)blk * ((r * (r + 1)) / 2));
+    // the workgroup that finishes a mode's last slice goes on to factor its Gram matrix
+    if (!last_arrival(jb.ctr + 0, jb.nblk, &s_last)) return;
+    chol_job<RM>(jb, 0, 0, jb.info, *reinterpret_cast<CholSmem*>(raw));
+}
+
 // ---- apply ----------------------------------------------------------------------------------
 // 256 threads load the slice, R and the diagonal-block inverses in one round of loads; waves 0 and 1
 // then solve 16 rows each.
+struct ApplySmem {
+    double Ps[OP_RS][OP_LD];
+    double Rs[OP_RMAX][OP_LD];
+    double Ds[OP_RMAX / 16][16][17];
+};
+union ApplyOrChol {                      // the factorisation reuses the memory of the finished solve
+    ApplySmem ap;
+    CholSmem ch;
+};
+
 template <int RM>
-__global__ __launch_bounds__(256) void k_orth_apply(OrthArgs a, int final_pass) {
-    __shared__ double Ps[OP_RS][OP_LD];
-    __shared__ double Rs[OP_RMAX][OP_LD];
-    __shared__ double Ds[OP_RMAX / 16][16][17];
+__global__ __launch_bounds__(256) void k_orth_apply(OrthBatch a, int final_pass) {
+    __shared__ __align__(16) unsigned char raw[sizeof(ApplyOrChol)];
+    __shared__ int s_last;
+    ApplySmem& ap = *reinterpret_cast<ApplySmem*>(raw);
+    double (*Ps)[OP_LD] = ap.Ps;
+    double (*Rs)[OP_LD] = ap.Rs;
+    double (*Ds)[16][17] = ap.Ds;
     int ji, blk;
     find_job(a, &ji, &blk);
     const OrthJob jb = a.job[ji];
@@ -525,6 +575,9 @@ __global__ __launch_bounds__(256) void k_orth_apply(OrthArgs a, int final_pass) 
     } else {
         for (int idx = tid; idx < nrows * r; idx += 256) jb.P64[(long long)i0 * r + idx] = Ps[idx / r][idx % r];
         gram_from_lds(Ps, r, jb.Gpart + (long long)blk * ((r * (r + 1)) / 2));
+        // the workgroup that finishes a mode's last slice factors the Gram matrix of Q0
+        if (!last_arrival(jb.ctr + 1, jb.nblk, &s_last)) return;
+        chol_job<RM>(jb, 1, 1, jb.info, *reinterpret_cast<CholSmem*>(raw));
     }
 }
 
@@ -539,7 +592,7 @@ constexpr int OW_LD = OW_RMAX + 1;
 constexpr int OW_ROWS = 128;            // rows per gramw block
 constexpr int OW_MAXPAIR = 20;          // block pairs per wave: ceil(78 / 4)
 
-__global__ __launch_bounds__(256) void k_orthw_gram(OrthArgs a) {
+__global__ __launch_bounds__(256) void k_orthw_gram(OrthBatch a) {
     __shared__ double Ps[OP_RS][OW_LD];
     int ji, blk;
     find_job(a, &ji, &blk);
@@ -603,7 +656,7 @@ __global__ __launch_bounds__(256) void k_orthw_gram(OrthArgs a) {
 
 extern __shared__ double ow_dyn[];
 
-__global__ __launch_bounds__(1024) void k_orthw_chol(OrthArgs a, int pass, int last) {
+__global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int last) {
     const OrthJob jb = a.job[blockIdx.x];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     double* Gp = ow_dyn;                              // packed upper triangle, r (r + 1) / 2
@@ -714,16 +767,16 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthArgs a, int pass, int l
         double bad = (pass == 0) ? 0.0 : jb.scal[1 + OW_RMAX];
         if (bad == 0.0 && s_bad) bad = (double)s_bad;
         jb.scal[1 + OW_RMAX] = bad;
-        if (last && a.info) {
-            if (bad != 0.0) flag_info(a.info, jb.mode1, (int)bad);
+        if (last && jb.info) {
+            if (bad != 0.0) flag_info(jb.info, jb.mode1, (int)bad);
             const double floor_ = 1e-12 * sqrt(s_trace);
             for (int k = 0; k < r; ++k)
-                if (!(rdiag[k] > floor_)) { flag_info(a.info, jb.mode1, k + 1); break; }
+                if (!(rdiag[k] > floor_)) { flag_info(jb.info, jb.mode1, k + 1); break; }
         }
     }
 }
 
-__global__ __launch_bounds__(128) void k_orthw_apply(OrthArgs a, int final_pass) {
+__global__ __launch_bounds__(128) void k_orthw_apply(OrthBatch a, int final_pass) {
     __shared__ double Ps[OP_RS][OW_LD];
     int ji, blk;
     find_job(a, &ji, &blk);
@@ -799,15 +852,15 @@ __global__ __launch_bounds__(128) void k_orthw_apply(OrthArgs a, int final_pass)
 constexpr int ORTH_NT = 512;
 constexpr int ORTH_MAXR = 1024;
 
-__global__ __launch_bounds__(ORTH_NT) void k_orth_big(OrthArgs a) {
+__global__ __launch_bounds__(ORTH_NT) void k_orth_big(OrthBatch a) {
     __shared__ double rdiag[ORTH_MAXR];
     __shared__ double s_inv;
     __shared__ double s_trace2;
     const OrthJob jb = a.job[blockIdx.x];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     double* __restrict__ P = jb.P64;
-    double* __restrict__ G = jb.G;
-    int32_t* info = a.info;
+    double* __restrict__ G = jb.Gpart;
+    int32_t* info = jb.info;
     const long long cnt = (long long)n * r;
     for (long long e = tid; e < cnt; e += ORTH_NT) {
         double s = 0.0;
@@ -886,7 +939,18 @@ __global__ __launch_bounds__(ORTH_NT) void k_orth_big(OrthArgs a) {
 // ---- host side -------------------------------------------------------------------------------
 bool orth_fast_supported(int r) { return r <= OP_RMAX; }
 int orth_slices(int n) { return (n + OP_RS - 1) / OP_RS; }
+bool orth_wide_supported(int r) { return r > OP_RMAX && r <= OW_RMAX; }
+int orth_wide_gram_blocks(int n) { return (n + OW_ROWS - 1) / OW_ROWS; }
 
+static bool put_orth(int kind, int aux, const char* label, const OrthArgs& a, int nblocks, Item* out) {
+    if (nblocks <= 0) return false;
+    *out = Item();
+    out->kind = kind; out->aux = aux; out->nblocks = nblocks;
+    std::snprintf(out->label, sizeof(out->label), "%s", label);
+    static_assert(sizeof(OrthArgs) <= kItemArgMax && sizeof(PresumArgs) <= kItemArgMax, "argument block");
+    std::memcpy(out->arg, &a, sizeof(a));
+    return true;
+}
 static int total_blocks(const OrthArgs& a) {
     int t = 0;
     for (int j = 0; j < a.njobs; ++j) t += a.job[j].nblk;
@@ -897,50 +961,10 @@ static bool fast_args_ok(const OrthArgs& a) {
     for (int j = 0; j < a.njobs; ++j) {
         const OrthJob& jb = a.job[j];
         if (jb.n <= 0 || jb.r <= 0 || jb.r > OP_RMAX || jb.nblk != orth_slices(jb.n)) return false;
-        if (!jb.Gpart || !jb.R || !jb.Dinv || !jb.scal || !jb.P64 || !jb.Uout || !jb.part) return false;
+        if (!jb.Gpart || !jb.R || !jb.Dinv || !jb.scal || !jb.P64 || !jb.Uout || !jb.part || !jb.ctr) return false;
     }
     return true;
 }
-// register shape of a launch: the largest rank among its modes, rounded up to 16
-static int rank_class(const OrthArgs& a) {
-    int rmax = 0;
-    for (int j = 0; j < a.njobs; ++j) rmax = a.job[j].r > rmax ? a.job[j].r : rmax;
-    return rmax <= 16 ? 16 : (rmax <= 32 ? 32 : (rmax <= 48 ? 48 : 64));
-}
-hipError_t launch_orth_gram0(const OrthArgs& a, hipStream_t st) {
-    if (!fast_args_ok(a)) return hipErrorInvalidValue;
-    const int rm = rank_class(a);
-    set_last_label("k_orth_gram0<%d>", rm);
-    const dim3 grid(total_blocks(a));
-    if (rm == 16) hipLaunchKernelGGL(k_orth_gram0<16>, grid, 256, 0, st, a);
-    else if (rm == 32) hipLaunchKernelGGL(k_orth_gram0<32>, grid, 256, 0, st, a);
-    else if (rm == 48) hipLaunchKernelGGL(k_orth_gram0<48>, grid, 256, 0, st, a);
-    else hipLaunchKernelGGL(k_orth_gram0<64>, grid, 256, 0, st, a);
-    return hipGetLastError();
-}
-hipError_t launch_orth_chol(const OrthArgs& a, int pass, int last, hipStream_t st) {
-    if (!fast_args_ok(a)) return hipErrorInvalidValue;
-    const int rm = rank_class(a);
-    set_last_label("k_orth_chol<%d>", rm);
-    if (rm == 16) hipLaunchKernelGGL(k_orth_chol<16>, dim3(a.njobs), 256, 0, st, a, pass, last);
-    else if (rm == 32) hipLaunchKernelGGL(k_orth_chol<32>, dim3(a.njobs), 256, 0, st, a, pass, last);
-    else if (rm == 48) hipLaunchKernelGGL(k_orth_chol<48>, dim3(a.njobs), 256, 0, st, a, pass, last);
-    else hipLaunchKernelGGL(k_orth_chol<64>, dim3(a.njobs), 256, 0, st, a, pass, last);
-    return hipGetLastError();
-}
-hipError_t launch_orth_apply(const OrthArgs& a, int final_pass, hipStream_t st) {
-    if (!fast_args_ok(a)) return hipErrorInvalidValue;
-    const int rm = rank_class(a);
-    set_last_label("k_orth_apply<%d>", rm);
-    const dim3 grid(total_blocks(a));
-    if (rm == 16) hipLaunchKernelGGL(k_orth_apply<16>, grid, 256, 0, st, a, final_pass);
-    else if (rm == 32) hipLaunchKernelGGL(k_orth_apply<32>, grid, 256, 0, st, a, final_pass);
-    else if (rm == 48) hipLaunchKernelGGL(k_orth_apply<48>, grid, 256, 0, st, a, final_pass);
-    else hipLaunchKernelGGL(k_orth_apply<64>, grid, 256, 0, st, a, final_pass);
-    return hipGetLastError();
-}
-bool orth_wide_supported(int r) { return r > OP_RMAX && r <= OW_RMAX; }
-int orth_wide_gram_blocks(int n) { return (n + OW_ROWS - 1) / OW_ROWS; }
 static bool wide_args_ok(const OrthArgs& a) {
     if (a.njobs <= 0 || a.njobs > 4) return false;
     for (int j = 0; j < a.njobs; ++j) {
@@ -950,52 +974,139 @@ static bool wide_args_ok(const OrthArgs& a) {
     }
     return true;
 }
-hipError_t launch_orthw_gram(const OrthArgs& a, hipStream_t st) {
-    if (!wide_args_ok(a)) return hipErrorInvalidValue;
-    set_last_label("k_orthw_gram");
-    hipLaunchKernelGGL(k_orthw_gram, dim3(total_blocks(a)), 256, 0, st, a);
-    return hipGetLastError();
-}
-hipError_t launch_orthw_chol(const OrthArgs& a, int pass, int last, hipStream_t st) {
-    if (!wide_args_ok(a)) return hipErrorInvalidValue;
-    int rmax = 0;
-    for (int j = 0; j < a.njobs; ++j) rmax = a.job[j].r > rmax ? a.job[j].r : rmax;
-    const size_t lds = sizeof(double) * ((size_t)rmax * (rmax + 1) / 2 + 2 * (size_t)rmax);
-    static size_t lds_allowed = 0;                 // the attribute only ever needs to grow
-    if (lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_orthw_chol),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        lds_allowed = lds;
+
+bool make_orth_presum(const PresumArgs& a, Item* out) {
+    if (a.njobs <= 0 || a.njobs > 4) return false;
+    long long blocks = 0;
+    for (int j = 0; j < a.njobs; ++j) {
+        const PresumJob& jb = a.job[j];
+        if (!jb.in || !jb.out || jb.cnt <= 0 || jb.nsplit <= 0) return false;
+        if (jb.nchunks != (int)((jb.cnt + 255) / 256) || jb.ngroups != (jb.nsplit + 31) / 32) return false;
+        blocks += (long long)jb.nchunks * jb.ngroups;
     }
-    set_last_label("k_orthw_chol");
-    hipLaunchKernelGGL(k_orthw_chol, dim3(a.njobs), 1024, lds, st, a, pass, last);
-    return hipGetLastError();
+    if (blocks > 0x3fffffffLL) return false;
+    *out = Item();
+    out->kind = IT_PRESUM; out->nblocks = (int)blocks;
+    std::snprintf(out->label, sizeof(out->label), "k_orth_presum");
+    std::memcpy(out->arg, &a, sizeof(a));
+    return true;
 }
-hipError_t launch_orthw_apply(const OrthArgs& a, int final_pass, hipStream_t st) {
-    if (!wide_args_ok(a)) return hipErrorInvalidValue;
-    int blocks = 0;
-    for (int j = 0; j < a.njobs; ++j) blocks += orth_slices(a.job[j].n);
+bool make_orth_gram0(const OrthArgs& a, Item* out) {
+    return fast_args_ok(a) && put_orth(IT_GRAM0, 0, "k_orth_gram0", a, total_blocks(a), out);
+}
+bool make_orth_apply(const OrthArgs& a, int final_pass, Item* out) {
+    return fast_args_ok(a) && put_orth(IT_APPLY, final_pass ? 1 : 0, "k_orth_apply", a, total_blocks(a), out);
+}
+bool make_orthw_gram(const OrthArgs& a, Item* out) {
+    return wide_args_ok(a) && put_orth(IT_ORTHW_GRAM, 0, "k_orthw_gram", a, total_blocks(a), out);
+}
+bool make_orthw_chol(const OrthArgs& a, int pass, int last, Item* out) {
+    return wide_args_ok(a) && put_orth(IT_ORTHW_CHOL, (pass ? 1 : 0) | (last ? 2 : 0), "k_orthw_chol", a, a.njobs, out);
+}
+bool make_orthw_apply(const OrthArgs& a, int final_pass, Item* out) {
+    if (!wide_args_ok(a)) return false;
     OrthArgs b = a;                                // apply walks 32-row slices
     for (int j = 0; j < b.njobs; ++j) b.job[j].nblk = orth_slices(b.job[j].n);
-    set_last_label("k_orthw_apply");
-    hipLaunchKernelGGL(k_orthw_apply, dim3(blocks), 128, 0, st, b, final_pass);
-    return hipGetLastError();
+    return put_orth(IT_ORTHW_APPLY, final_pass ? 1 : 0, "k_orthw_apply", b, total_blocks(b), out);
 }
-hipError_t launch_orth_big(const OrthArgs& a, hipStream_t st) {
-    if (a.njobs <= 0 || a.njobs > 4) return hipErrorInvalidValue;
+bool make_orth_big(const OrthArgs& a, Item* out) {
+    if (a.njobs <= 0 || a.njobs > 4) return false;
     for (int j = 0; j < a.njobs; ++j)
-        if (a.job[j].r > ORTH_MAXR || !a.job[j].G || !a.job[j].P64) return hipErrorInvalidValue;
-    set_last_label("k_orth_big");
-    hipLaunchKernelGGL(k_orth_big, dim3(a.njobs), ORTH_NT, 0, st, a);
-    return hipGetLastError();
+        if (a.job[j].r > ORTH_MAXR || !a.job[j].Gpart || !a.job[j].P64 || !a.job[j].part || !a.job[j].Uout) return false;
+    return put_orth(IT_ORTH_BIG, 0, "k_orth_big", a, a.njobs, out);
 }
 
-__global__ void k_init_ctrl(int32_t* info) {
-    if (threadIdx.x == 0 && info) *info = 0;
+struct InitBatch {
+    int32_t* p[kMaxBatch];
+    int n;
+};
+__global__ void k_init_ctrl(InitBatch b) {
+    if (threadIdx.x < b.n && b.p[threadIdx.x]) *b.p[threadIdx.x] = 0;
 }
-hipError_t launch_init_ctrl(int32_t* info, hipStream_t st) {
-    hipLaunchKernelGGL(k_init_ctrl, 1, 64, 0, st, info);
+bool make_init_ctrl(int32_t* info, Item* out) {
+    if (!info) return false;
+    *out = Item();
+    out->kind = IT_INIT; out->nblocks = 1;
+    std::snprintf(out->label, sizeof(out->label), "k_init_ctrl");
+    std::memcpy(out->arg, &info, sizeof(info));
+    return true;
+}
+
+hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st) {
+    if (n <= 0 || n > kMaxBatch) return hipErrorInvalidValue;
+    const int kind = items[0]->kind, aux = items[0]->aux;
+    if (kind == IT_INIT) {
+        InitBatch b;
+        b.n = n;
+        for (int j = 0; j < kMaxBatch; ++j) b.p[j] = nullptr;
+        for (int j = 0; j < n; ++j) std::memcpy(&b.p[j], items[j]->arg, sizeof(int32_t*));
+        hipLaunchKernelGGL(k_init_ctrl, 1, 64, 0, st, b);
+        return hipGetLastError();
+    }
+    long long blocks = 0;
+    for (int j = 0; j < n; ++j) blocks += items[j]->nblocks;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks);
+    if (kind == IT_PRESUM) {
+        PresumBatch b;
+        b.njobs = 0;
+        for (int j = 0; j < n; ++j) {
+            PresumArgs a;
+            std::memcpy(&a, items[j]->arg, sizeof(a));
+            for (int k = 0; k < a.njobs; ++k) b.job[b.njobs++] = a.job[k];
+        }
+        hipLaunchKernelGGL(k_orth_presum, grid, 256, 0, st, b);
+        return hipGetLastError();
+    }
+    OrthBatch b;
+    b.njobs = 0;
+    int rmax = 0;
+    for (int j = 0; j < n; ++j) {
+        OrthArgs a;
+        std::memcpy(&a, items[j]->arg, sizeof(a));
+        for (int k = 0; k < a.njobs; ++k) {
+            b.job[b.njobs++] = a.job[k];
+            rmax = a.job[k].r > rmax ? a.job[k].r : rmax;
+        }
+    }
+    const int rm = rmax <= 16 ? 16 : (rmax <= 32 ? 32 : (rmax <= 48 ? 48 : 64));   // register shape of the fast kernels
+    switch (kind) {
+        case IT_GRAM0:
+            if (rm == 16) hipLaunchKernelGGL(k_orth_gram0<16>, grid, 256, 0, st, b);
+            else if (rm == 32) hipLaunchKernelGGL(k_orth_gram0<32>, grid, 256, 0, st, b);
+            else if (rm == 48) hipLaunchKernelGGL(k_orth_gram0<48>, grid, 256, 0, st, b);
+            else hipLaunchKernelGGL(k_orth_gram0<64>, grid, 256, 0, st, b);
+            break;
+        case IT_APPLY:
+            if (rm == 16) hipLaunchKernelGGL(k_orth_apply<16>, grid, 256, 0, st, b, aux);
+            else if (rm == 32) hipLaunchKernelGGL(k_orth_apply<32>, grid, 256, 0, st, b, aux);
+            else if (rm == 48) hipLaunchKernelGGL(k_orth_apply<48>, grid, 256, 0, st, b, aux);
+            else hipLaunchKernelGGL(k_orth_apply<64>, grid, 256, 0, st, b, aux);
+            break;
+        case IT_ORTHW_GRAM:
+            hipLaunchKernelGGL(k_orthw_gram, grid, 256, 0, st, b);
+            break;
+        case IT_ORTHW_CHOL: {
+            const size_t lds = sizeof(double) * ((size_t)rmax * (rmax + 1) / 2 + 2 * (size_t)rmax);
+            static size_t lds_allowed = 0;                 // the attribute only ever needs to grow
+            if (lds > lds_allowed) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_orthw_chol),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (e != hipSuccess) return e;
+                lds_allowed = lds;
+            }
+            hipLaunchKernelGGL(k_orthw_chol, grid, 1024, lds, st, b, aux & 1, (aux >> 1) & 1);
+            break;
+        }
+        case IT_ORTHW_APPLY:
+            hipLaunchKernelGGL(k_orthw_apply, grid, 128, 0, st, b, aux);
+            break;
+        case IT_ORTH_BIG:
+            hipLaunchKernelGGL(k_orth_big, grid, ORTH_NT, 0, st, b);
+            break;
+        default:
+            return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -20,6 +20,8 @@
 #include "asi_device.h"
 #include "asi_kernels.h"
 #include <algorithm>
+#include <cstdio>
+#include <cstring>
 
 namespace asi {
 
@@ -30,6 +32,7 @@ constexpr int SS_TC = 128;                 // fibres (unfolding columns) per til
 constexpr int SS_PAD = 4;
 constexpr int SS_LDS_FLOATS = 64 * (SS_TC + SS_PAD);   // 33 KB
 constexpr int SS_PRE = (SS_LDS_FLOATS + 255) / 256;    // prefetch registers per thread
+static const int SS_MAX_WG = 1024;
 
 struct SmallView {
     const float* U;      // (n, r) previous factor
@@ -37,6 +40,7 @@ struct SmallView {
     int n, r;
     int sI;              // LDS stride between consecutive mode indices
     int div, mulA, mulB; // LDS offset of fibre c at mode index 0: (c / div) * mulA + (c % div) * mulB
+    float inv_div;       // 1 / div: c stays below 2^14, so the rounded float quotient is exact
     int cols_per_o;      // fibres one outer slice contributes (whole_o tiles)
 };
 struct SmallJob {
@@ -48,28 +52,39 @@ struct SmallJob {
     long long tiles_per_o;
     long long ntiles;
     int nviews;
+    int nwg;             // workgroups of this job; each walks tiles nwg apart
+    int32_t* zero;       // nullable: `nzero` int32 to clear (arrival counters of the orth launches that follow)
+    int nzero;
     SmallView v[2];
 };
 
+#ifdef ASI_DEBUG_TIMING
+__device__ long long g_ss_stamps[64];
+#define SSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) g_ss_stamps[i] = wall_clock64(); } while (0)
+extern "C" int asi_debug_ss_stamps(long long* out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_ss_stamps), sizeof(long long) * 64);
+}
+#else
+#define SSTAMP(i) do {} while (0)
+#endif
+
 template <typename T, int NBM, int NBR, int NV, bool WHOLE_O>
-__global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
+__global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
+    int lb;
+    const SmallJob& jb = bt.job[locate(bt, &lb)];
     __shared__ float smem[SS_LDS_FLOATS];
-    __shared__ int colofs[NV][SS_TC];
     __shared__ float Us[NV][NBM * 16][NBR * 16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lg = lane >> 4, ll = lane & 15;
     const T* __restrict__ X = static_cast<const T*>(jb.X);
+    if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
+    SSTAMP(0);
 
     for (int e = tid; e < NV * NBM * 16 * NBR * 16; e += 256) {
         const int vi = e / (NBM * 16 * NBR * 16), rem = e - vi * (NBM * 16 * NBR * 16);
         const int i = rem / (NBR * 16), q = rem - i * (NBR * 16);
         const SmallView& sv = jb.v[vi];
         Us[vi][i][q] = ldg_f32(sv.U, (long long)i * sv.r + q, i < sv.n && q < sv.r);
-    }
-    for (int e = tid; e < NV * SS_TC; e += 256) {
-        const int vi = e / SS_TC, c = e - vi * SS_TC;
-        const SmallView& sv = jb.v[vi];
-        colofs[vi][c] = (c / sv.div) * sv.mulA + (c % sv.div) * sv.mulB;
     }
 
     v4d pacc[NV][NBM][NBR];
@@ -82,8 +97,10 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
 
     const int n0 = jb.v[0].n;
     const int rowI = SS_TC + SS_PAD;
-    for (long long tile = blockIdx.x; tile < jb.ntiles; tile += gridDim.x) {
-        __syncthreads();   // everyone is done with the previous tile (and Us / colofs are written)
+    SSTAMP(1);
+    for (long long tile = lb; tile < jb.ntiles; tile += jb.nwg) {
+        __syncthreads();   // everyone is done with the previous tile (and Us is written)
+        SSTAMP(2);
         int no_or_vc;
         // the whole tile is requested before any of it is stored: one memory latency per tile
         if (WHOLE_O) {
@@ -123,6 +140,7 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
             no_or_vc = vc;
         }
         __syncthreads();
+        SSTAMP(3);
 #pragma unroll
         for (int vi = 0; vi < NV; ++vi) {
             const SmallView& sv = jb.v[vi];
@@ -135,7 +153,8 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
                 for (int nb = 0; nb < NBR; ++nb) vacc[nb] = (v4f){0.f, 0.f, 0.f, 0.f};
                 const int cA = cb * 16 + ll;
                 const bool okA = cA < valid_cols;
-                const int ofsA = colofs[vi][cA];
+                const int qA = (int)(((float)cA + 0.5f) * sv.inv_div);
+                const int ofsA = qA * sv.mulA + (cA - qA * sv.div) * sv.mulB;
 #pragma unroll
                 for (int ks = 0; ks < NBM * 4; ++ks) {
                     if (4 * ks < n) {
@@ -151,7 +170,8 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
                 for (int v = 0; v < 4; ++v) {
                     const int cB = cb * 16 + 4 * lg + v;
                     const bool okB = cB < valid_cols;
-                    const int ofsB = colofs[vi][cB];
+                    const int qB = (int)(((float)cB + 0.5f) * sv.inv_div);
+                    const int ofsB = qB * sv.mulA + (cB - qB * sv.div) * sv.mulB;
                     double bv[NBR];
 #pragma unroll
                     for (int nb = 0; nb < NBR; ++nb) bv[nb] = (double)vacc[nb][v];
@@ -169,6 +189,7 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
             }
         }
     }
+    SSTAMP(4);
     // sum the four waves' accumulators through LDS, wave after wave (fixed order)
     double* red = reinterpret_cast<double*>(smem);   // (NBM*16) x (NBR*16) doubles <= 32 KB
 #pragma unroll
@@ -190,26 +211,33 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(SmallJob jb) {
             __syncthreads();
         }
         const int n = jb.v[vi].n, r = jb.v[vi].r;
-        double* out = jb.v[vi].part + (long long)blockIdx.x * n * r;
+        double* out = jb.v[vi].part + (long long)lb * n * r;
         for (int e = tid; e < n * r; e += 256) {
             const int i = e / r, q = e - i * r;
             out[e] = red[i * (NBR * 16) + q];
         }
     }
+    SSTAMP(5);
 }
 
 // ---- host side ---------------------------------------------------------------------
 bool subspace_small_supported(int n, int r) { return n <= 64 && r <= 64 && r <= n; }
 
-static const int SS_MAX_WG = 512;
+// Outer slices per tile when a tile is a run of whole slices: as many as the LDS buffer holds, but
+// no fewer than ~SS_MAX_WG tiles in all: the MFMA chains of a tile are latency bound, and only
+// several resident workgroups per CU hide that.
+static long long whole_To(long long outer, long long o_elems) {
+    long long To = SS_LDS_FLOATS / o_elems;
+    const long long spread = (outer + SS_MAX_WG - 1) / SS_MAX_WG;
+    if (To > spread) To = spread;
+    return To < 1 ? 1 : To;
+}
 
 // tile geometry of one mode seen as (outer, n, inner)
 static void single_geometry(long long outer, int n, long long inner, SmallJob* jb) {
     jb->outer = outer; jb->inner = inner; jb->o_elems = (long long)n * inner;
     if (inner < SS_TC && (long long)n * inner <= SS_LDS_FLOATS) {
-        long long To = SS_TC / inner;
-        const long long cap = SS_LDS_FLOATS / ((long long)n * inner);
-        if (To > cap) To = cap;
+        long long To = whole_To(outer, (long long)n * inner);
         jb->whole_o = 1; jb->To = (int)To; jb->tiles_per_o = 0;
         jb->ntiles = (outer + To - 1) / To;
     } else {
@@ -231,44 +259,42 @@ bool subspace_pair_supported(int rows, int cols, int r_rows, int r_cols) {
     if ((rows + 15) / 16 != (cols + 15) / 16) return false;           // one register shape for both views
     const int nbr = std::max((r_rows + 15) / 16, (r_cols + 15) / 16);
     if (nbr > 2) return false;
-    return (long long)rows * cols <= SS_LDS_FLOATS && rows <= SS_TC && cols <= SS_TC;
+    return (long long)rows * cols <= SS_LDS_FLOATS;
 }
-static int pair_To(int rows, int cols) {
-    long long To = std::min(SS_TC / rows, SS_TC / cols);
-    const long long cap = SS_LDS_FLOATS / ((long long)rows * cols);
-    if (To > cap) To = cap;
-    return (int)To;
-}
+static int pair_To(long long planes, int rows, int cols) { return (int)whole_To(planes, (long long)rows * cols); }
 int subspace_pair_nwg(long long planes, int rows, int cols) {
-    const int To = pair_To(rows, cols);
+    const int To = pair_To(planes, rows, cols);
     const long long ntiles = (planes + To - 1) / To;
     return (int)(ntiles < SS_MAX_WG ? ntiles : SS_MAX_WG);
 }
 
-template <typename T, int NV>
-static hipError_t launch_small_t(const SmallJob& jb, int nbm, int nbr, int nwg, hipStream_t st) {
-#define ASI_SS_CASE(M, R)                                                                       \
-    if (nbm == M && nbr == R) {                                                                 \
-        set_last_label("k_subspace_small<%s, %d, %d, %d, %s>", sizeof(T) == 4 ? "float" : "asi::bf16_t", M, R, NV,   \
-                       jb.whole_o ? "true" : "false");                                                          \
-        if (jb.whole_o) hipLaunchKernelGGL((k_subspace_small<T, M, R, NV, true>), dim3(nwg), 256, 0, st, jb);   \
-        else if constexpr (NV == 1) hipLaunchKernelGGL((k_subspace_small<T, M, R, NV, false>), dim3(nwg), 256, 0, st, jb); \
-        return hipGetLastError();                                                               \
-    }
-    ASI_SS_CASE(1, 1) ASI_SS_CASE(2, 1) ASI_SS_CASE(2, 2) ASI_SS_CASE(3, 1) ASI_SS_CASE(3, 2)
-    ASI_SS_CASE(4, 1) ASI_SS_CASE(4, 2)
-    if constexpr (NV == 1) {
-        ASI_SS_CASE(3, 3) ASI_SS_CASE(4, 3) ASI_SS_CASE(4, 4)
-    }
-#undef ASI_SS_CASE
-    return hipErrorInvalidValue;
+// key: [0] bf16, [1] two views, [2] whole_o, [4..6] NBM, [8..10] NBR
+static bool small_key_ok(int nbm, int nbr, int nv) {
+    if (nbm < 1 || nbm > 4 || nbr < 1 || nbr > nbm) return false;
+    return nv == 1 || nbr <= 2;
+}
+static bool finish_small(DType xt, SmallJob& jb, int nbm, int nbr, int nwg, Item* out) {
+    if (!small_key_ok(nbm, nbr, jb.nviews) || nwg <= 0 || nwg > jb.ntiles) return false;
+    if (jb.nviews == 2 && !jb.whole_o) return false;
+    jb.nwg = nwg;
+    *out = Item();
+    out->kind = IT_SMALL;
+    out->key = (xt == BF16 ? 1u : 0u) | (jb.nviews == 2 ? 2u : 0u) | (jb.whole_o ? 4u : 0u) | ((unsigned)nbm << 4) |
+               ((unsigned)nbr << 8);
+    out->nblocks = nwg;
+    std::snprintf(out->label, sizeof(out->label), "k_subspace_small<%s, %d, %d, %d, %s>", xt == F32 ? "float" : "asi::bf16_t",
+                  nbm, nbr, jb.nviews, jb.whole_o ? "true" : "false");
+    static_assert(sizeof(SmallJob) <= kItemArgMax, "argument block");
+    std::memcpy(out->arg, &jb, sizeof(jb));
+    return true;
 }
 
-hipError_t launch_subspace_small(DType xt, const void* X, long long outer, int n, long long inner, const float* U,
-                                 int r, double* part, int nwg, hipStream_t st) {
-    if (!subspace_small_supported(n, r) || nwg <= 0) return hipErrorInvalidValue;
+bool make_subspace_small(DType xt, const void* X, long long outer, int n, long long inner, const float* U, int r,
+                         double* part, int nwg, int32_t* zero, int nzero, Item* out) {
+    if (!subspace_small_supported(n, r) || !X || !U || !part || nzero < 0 || nzero > 256) return false;
     SmallJob jb;
-    jb.X = X;
+    std::memset(&jb, 0, sizeof(jb));
+    jb.X = X; jb.zero = zero; jb.nzero = zero ? nzero : 0;
     single_geometry(outer, n, inner, &jb);
     jb.nviews = 1;
     SmallView& v = jb.v[0];
@@ -278,31 +304,242 @@ hipError_t launch_subspace_small(DType xt, const void* X, long long outer, int n
     } else {
         v.sI = SS_TC + SS_PAD; v.div = SS_TC; v.mulA = 0; v.mulB = 1; v.cols_per_o = 0;
     }
+    v.inv_div = 1.0f / (float)v.div;
     jb.v[1] = jb.v[0];
-    if (nwg > jb.ntiles) return hipErrorInvalidValue;
-    const int nbm = (n + 15) / 16, nbr = (r + 15) / 16;
-    return xt == F32 ? launch_small_t<float, 1>(jb, nbm, nbr, nwg, st) : launch_small_t<bf16_t, 1>(jb, nbm, nbr, nwg, st);
+    return finish_small(xt, jb, (n + 15) / 16, (r + 15) / 16, nwg, out);
 }
 
 // Modes "rows" and "cols" of X seen as (planes, rows, cols), both from one read of X.
-hipError_t launch_subspace_pair(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows,
-                                int r_rows, double* part_rows, const float* U_cols, int r_cols, double* part_cols,
-                                int nwg, hipStream_t st) {
-    if (!subspace_pair_supported(rows, cols, r_rows, r_cols) || nwg <= 0) return hipErrorInvalidValue;
+bool make_subspace_pair(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows, int r_rows,
+                        double* part_rows, const float* U_cols, int r_cols, double* part_cols, int nwg, Item* out) {
+    if (!subspace_pair_supported(rows, cols, r_rows, r_cols) || !X || !U_rows || !U_cols || !part_rows || !part_cols)
+        return false;
     SmallJob jb;
+    std::memset(&jb, 0, sizeof(jb));
     jb.X = X; jb.outer = planes; jb.inner = cols; jb.o_elems = (long long)rows * cols;
-    jb.whole_o = 1; jb.To = pair_To(rows, cols); jb.tiles_per_o = 0;
+    jb.whole_o = 1; jb.To = pair_To(planes, rows, cols); jb.tiles_per_o = 0;
     jb.ntiles = (planes + jb.To - 1) / jb.To;
     jb.nviews = 2;
     SmallView& a = jb.v[0];      // fibres run along rows: element (i, c = (plane, col)) at plane*rows*cols + i*cols + col
     a.U = U_rows; a.part = part_rows; a.n = rows; a.r = r_rows;
     a.sI = cols; a.div = cols; a.mulA = rows * cols; a.mulB = 1; a.cols_per_o = cols;
+    a.inv_div = 1.0f / (float)cols;
     SmallView& b = jb.v[1];      // fibres run along cols: element (i, c = (plane, row)) at plane*rows*cols + row*cols + i
     b.U = U_cols; b.part = part_cols; b.n = cols; b.r = r_cols;
     b.sI = 1; b.div = rows; b.mulA = rows * cols; b.mulB = cols; b.cols_per_o = rows;
-    if (nwg > jb.ntiles) return hipErrorInvalidValue;
-    const int nbm = (rows + 15) / 16, nbr = std::max((r_rows + 15) / 16, (r_cols + 15) / 16);
-    return xt == F32 ? launch_small_t<float, 2>(jb, nbm, nbr, nwg, st) : launch_small_t<bf16_t, 2>(jb, nbm, nbr, nwg, st);
+    b.inv_div = 1.0f / (float)rows;
+    return finish_small(xt, jb, (rows + 15) / 16, std::max((r_rows + 15) / 16, (r_cols + 15) / 16), nwg, out);
+}
+
+// ---- the last two modes when both are tiny (rows, cols <= 8, ranks <= 8) ------------------------------
+// For a 7x7 plane and rank 5 the 16x16 MFMA blocks above are 14 % full, so here the vector ALU does
+// the work with no padding beyond 8: thread (plane, view) keeps the plane's contribution
+//   P += X (X^T U)   (view 0, fibres along rows)     or     P += X^T (X U)   (view 1, fibres along cols)
+// for its planes in fp64 registers (V = fibre^T U in fp32, the products of P exact in fp64).  Sums over
+// the planes of a workgroup are taken in a fixed order: lanes of a wave by xor shuffles, then waves.
+constexpr int TY_PL = 128;           // planes per tile: 256 threads = 128 planes x 2 views
+
+// value of the lane a data-parallel move selects (every lane of a row active)
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+struct TinyJob {
+    const void* X;
+    long long planes, ntiles;
+    const float* U[2];    // (rows, r[0]) and (cols, r[1])
+    double* part[2];      // (nwg, rows, r[0]) and (nwg, cols, r[1])
+    int rows, cols, r[2];
+    int nwg;
+};
+
+template <typename T, int RP>
+__global__ __launch_bounds__(256) void k_subspace_tiny(Batch<TinyJob> bt) {
+    __shared__ float tile[TY_PL * 64];
+    __shared__ float Us[2][8][RP];
+    __shared__ double red[4][2][8 * RP];
+    int lb;
+    const TinyJob& jb = bt.job[locate(bt, &lb)];
+    const T* __restrict__ X = static_cast<const T*>(jb.X);
+    const int tid = threadIdx.x, view = tid & 1, pl = tid >> 1, wave = tid >> 6, lane = tid & 63;
+    const int rows = jb.rows, cols = jb.cols, pe = rows * cols;
+    const int n_v = view ? cols : rows;          // length of this view's fibres (the mode size)
+    const int m_v = view ? rows : cols;          // fibres per plane
+    const int sI = view ? 1 : cols, sC = view ? cols : 1;    // element (i, c) of the plane at i*sI + c*sC
+    for (int e = tid; e < 2 * 8 * RP; e += 256) {
+        const int vi = e / (8 * RP), rem = e - vi * (8 * RP), i = rem / RP, q = rem - i * RP;
+        const int nn = vi ? cols : rows;
+        Us[vi][i][q] = ldg_f32(jb.U[vi], (long long)i * jb.r[vi] + q, i < nn && q < jb.r[vi]);
+    }
+    __syncthreads();
+    SSTAMP(10);
+    float u[8][RP];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int q = 0; q < RP; ++q) u[i][q] = Us[view][i][q];
+    double P[8][RP];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int q = 0; q < RP; ++q) P[i][q] = 0.0;
+
+    for (long long t = lb; t < jb.ntiles; t += jb.nwg) {
+        const long long p0 = t * TY_PL;
+        const int np = (int)((jb.planes - p0 < TY_PL) ? jb.planes - p0 : TY_PL);
+        const int count = np * pe;
+        const T* src = X + p0 * pe;
+        __syncthreads();                          // previous tile consumed
+        T pre[TY_PL * 64 / 256];
+#pragma unroll
+        for (int k = 0; k < TY_PL * 64 / 256; ++k) {
+            const int e = k * 256 + tid;
+            pre[k] = src[e < count ? e : 0];      // clamped, not branched: all loads stay in flight
+        }
+#pragma unroll
+        for (int k = 0; k < TY_PL * 64 / 256; ++k) {
+            const int e = k * 256 + tid;
+            if (e < count) tile[e] = to_f32(pre[k]);
+        }
+        __syncthreads();
+        SSTAMP(11);
+        if (pl < np) {
+            const float* xp = tile + pl * pe;
+#pragma unroll 1
+            for (int c = 0; c < m_v; ++c) {                  // one fibre at a time keeps the register count down
+                float x[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[i] = ldg_f32(xp, i * sI + c * sC, i < n_v);
+                float v[RP];
+#pragma unroll
+                for (int q = 0; q < RP; ++q) v[q] = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int q = 0; q < RP; ++q) v[q] = fmaf(x[i], u[i][q], v[q]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int q = 0; q < RP; ++q) P[i][q] = fma((double)x[i], (double)v[q], P[i][q]);
+            }
+        }
+    }
+    SSTAMP(12);
+    // Sum over the lanes of the same view (same lane parity).  Inside a row of 16 lanes by data-parallel
+    // moves: partner lane^2, then rotations by 4 and 8; across the four rows by two xor shuffles.  One
+    // step for all accumulators at a time, so that their moves are in flight together.
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int q = 0; q < RP; ++q) P[i][q] += dpp_move<0x4E>(P[i][q]);        // quad_perm [2,3,0,1]
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int q = 0; q < RP; ++q) P[i][q] += dpp_move<0x124>(P[i][q]);       // row_ror:4
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int q = 0; q < RP; ++q) P[i][q] += dpp_move<0x128>(P[i][q]);       // row_ror:8
+#pragma unroll
+    for (int m = 16; m <= 32; m <<= 1)
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int q = 0; q < RP; ++q) P[i][q] += __shfl_xor(P[i][q], m);
+    if (lane < 2) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int q = 0; q < RP; ++q) red[wave][lane][i * RP + q] = P[i][q];
+    }
+    __syncthreads();
+    for (int e = tid; e < 2 * 8 * RP; e += 256) {
+        const int vi = e / (8 * RP), rem = e - vi * (8 * RP), i = rem / RP, q = rem - i * RP;
+        const int nn = vi ? cols : rows, rr = jb.r[vi];
+        if (i < nn && q < rr) {
+            const double s = (red[0][vi][rem] + red[1][vi][rem]) + (red[2][vi][rem] + red[3][vi][rem]);
+            jb.part[vi][((long long)lb * nn + i) * rr + q] = s;
+        }
+    }
+    SSTAMP(13);
+}
+
+bool subspace_tiny_supported(int rows, int cols, int r_rows, int r_cols) {
+    return rows <= 8 && cols <= 8 && r_rows <= 8 && r_cols <= 8 && r_rows <= rows && r_cols <= cols;
+}
+int subspace_tiny_nwg(long long planes) {
+    const long long ntiles = (planes + TY_PL - 1) / TY_PL;
+    return (int)(ntiles < SS_MAX_WG ? ntiles : SS_MAX_WG);
+}
+bool make_subspace_tiny(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows, int r_rows,
+                        double* part_rows, const float* U_cols, int r_cols, double* part_cols, int nwg, Item* out) {
+    if (!subspace_tiny_supported(rows, cols, r_rows, r_cols) || !X || !U_rows || !U_cols || !part_rows || !part_cols)
+        return false;
+    TinyJob jb;
+    std::memset(&jb, 0, sizeof(jb));
+    jb.X = X; jb.planes = planes; jb.ntiles = (planes + TY_PL - 1) / TY_PL;
+    jb.U[0] = U_rows; jb.U[1] = U_cols; jb.part[0] = part_rows; jb.part[1] = part_cols;
+    jb.rows = rows; jb.cols = cols; jb.r[0] = r_rows; jb.r[1] = r_cols; jb.nwg = nwg;
+    if (nwg <= 0 || nwg > jb.ntiles) return false;
+    const int rmax = std::max(r_rows, r_cols);
+    const int rp = rmax <= 4 ? 4 : (rmax <= 6 ? 6 : 8);
+    *out = Item();
+    out->kind = IT_TINY;
+    out->key = (xt == BF16 ? 1u : 0u) | ((unsigned)rp << 4);
+    out->nblocks = nwg;
+    std::snprintf(out->label, sizeof(out->label), "k_subspace_tiny<%s, %d>", xt == F32 ? "float" : "asi::bf16_t", rp);
+    static_assert(sizeof(TinyJob) <= kItemArgMax, "argument block");
+    std::memcpy(out->arg, &jb, sizeof(jb));
+    return true;
+}
+hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st) {
+    Batch<TinyJob> b;
+    dim3 grid;
+    if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
+    const unsigned key = items[0]->key;
+    const int rp = (int)(key >> 4);
+    if (!(key & 1u)) {
+        if (rp == 4) hipLaunchKernelGGL((k_subspace_tiny<float, 4>), grid, 256, 0, st, b);
+        else if (rp == 6) hipLaunchKernelGGL((k_subspace_tiny<float, 6>), grid, 256, 0, st, b);
+        else hipLaunchKernelGGL((k_subspace_tiny<float, 8>), grid, 256, 0, st, b);
+    } else {
+        if (rp == 4) hipLaunchKernelGGL((k_subspace_tiny<bf16_t, 4>), grid, 256, 0, st, b);
+        else if (rp == 6) hipLaunchKernelGGL((k_subspace_tiny<bf16_t, 6>), grid, 256, 0, st, b);
+        else hipLaunchKernelGGL((k_subspace_tiny<bf16_t, 8>), grid, 256, 0, st, b);
+    }
+    return hipGetLastError();
+}
+
+template <typename T, int NV>
+static bool launch_small_t(const Batch<SmallJob>& b, dim3 grid, int nbm, int nbr, bool whole_o, hipStream_t st) {
+#define ASI_SS_CASE(M, R)                                                                                \
+    if (nbm == M && nbr == R) {                                                                          \
+        if (whole_o) hipLaunchKernelGGL((k_subspace_small<T, M, R, NV, true>), grid, 256, 0, st, b);     \
+        else if constexpr (NV == 1) hipLaunchKernelGGL((k_subspace_small<T, M, R, NV, false>), grid, 256, 0, st, b); \
+        return true;                                                                                     \
+    }
+    ASI_SS_CASE(1, 1) ASI_SS_CASE(2, 1) ASI_SS_CASE(2, 2) ASI_SS_CASE(3, 1) ASI_SS_CASE(3, 2)
+    ASI_SS_CASE(4, 1) ASI_SS_CASE(4, 2)
+    if constexpr (NV == 1) {
+        ASI_SS_CASE(3, 3) ASI_SS_CASE(4, 3) ASI_SS_CASE(4, 4)
+    }
+#undef ASI_SS_CASE
+    return false;
+}
+
+hipError_t launch_small_items(const Item* const* items, int n, hipStream_t st) {
+    Batch<SmallJob> b;
+    dim3 grid;
+    if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
+    const unsigned key = items[0]->key;
+    const bool bf16 = key & 1u, two = key & 2u, whole_o = key & 4u;
+    const int nbm = (int)((key >> 4) & 7u), nbr = (int)((key >> 8) & 7u);
+    bool ok;
+    if (!bf16) ok = two ? launch_small_t<float, 2>(b, grid, nbm, nbr, whole_o, st) : launch_small_t<float, 1>(b, grid, nbm, nbr, whole_o, st);
+    else ok = two ? launch_small_t<bf16_t, 2>(b, grid, nbm, nbr, whole_o, st) : launch_small_t<bf16_t, 1>(b, grid, nbm, nbr, whole_o, st);
+    return ok ? hipGetLastError() : hipErrorInvalidValue;
 }
 
 }  // namespace asi

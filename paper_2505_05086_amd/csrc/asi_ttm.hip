@@ -14,33 +14,46 @@
 // layer): a workgroup owns only 16 columns, its four waves split the mode index between them,
 // every operand goes from global memory straight into the MFMA registers (all loads of a round
 // are in flight together) and the four partial tiles are added through LDS.
+//
+// Both kernels take the argument blocks of several layers side by side (Batch<TtmJob>).
 #include "asi_device.h"
 #include "asi_kernels.h"
+
+#include <cstdio>
+#include <cstring>
 
 namespace asi {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int TM_TC = 64, TM_KC = 32, TM_TQ = 64, TM_LD = TM_TC + 4;
-
-struct KronSpec {
-    const float* M2;       // second factor; element (i2, q2) at M2[i2 * ms_i + q2 * ms_q]
-    long long ms_i, ms_q;
-    int n2, r2;            // i = i1 * n2 + i2,  q = q1 * r2 + q2
-};
+constexpr int TM_TC = 64, TM_TQ = 64, TM_LD = TM_TC + 4;
+constexpr int TM_KCMAX = 64;
 
 template <typename T, bool LASTMODE, int NBR, bool KRON>
-__global__ __launch_bounds__(256) void k_ttm_mfma(const T* __restrict__ X, long long outer, int n, long long inner,
-                                                  const float* __restrict__ Mp, long long ms_i, long long ms_q, int r,
-                                                  float* __restrict__ Y, int beta, KronSpec kr) {
-    __shared__ float smem[2 * TM_KC * TM_LD];       // Xs | Ms during the K loop, Ys (64 x TM_LD) afterwards
+__global__ __launch_bounds__(256) void k_ttm_mfma(Batch<TtmJob> bt) {
+    // K chunk: 32 when there are many columns (chunks overlap across workgroups), 64 for the merged
+    // modes, whose K is long and whose columns are few
+    constexpr int TM_KC = KRON ? 64 : 32;
+    constexpr int TM_LR = TM_KC / 4;      // loads per thread and operand for one chunk
+    __shared__ float smem[2 * TM_KCMAX * TM_LD];    // Xs | Ms during the K loop, Ys (64 x TM_LD) afterwards
     float (*Xs)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem);
-    float (*Ms)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem + TM_KC * TM_LD);
+    float (*Ms)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem + TM_KCMAX * TM_LD);
     float (*Ys)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem);
+    int lb;
+    const TtmJob& jb = bt.job[locate(bt, &lb)];
+    const T* __restrict__ X = static_cast<const T*>(jb.X);
+    const float* __restrict__ Mp = jb.Mp;
+    float* __restrict__ Y = jb.Y;
+    const long long outer = jb.outer, inner = jb.inner, ms_i = jb.ms_i, ms_q = jb.ms_q;
+    const int n = jb.n, r = jb.r, beta = jb.beta;
+    const KronSpec kr = jb.kr;
+    const int by = lb / jb.gx, bx = lb - by * jb.gx;
     const long long ncols = outer * inner;
-    const long long c0 = (long long)blockIdx.x * TM_TC;
-    const int q0 = blockIdx.y * TM_TQ;
+    const int tcols = jb.tile_cols;                  // columns of a tile in use (<= TM_TC)
+    const long long c0 = (long long)bx * tcols;
+    const int q0 = by * TM_TQ;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
+    if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
 
     // loader coordinates
     long long ld_base = -1;
@@ -48,32 +61,38 @@ __global__ __launch_bounds__(256) void k_ttm_mfma(const T* __restrict__ X, long 
     if (!LASTMODE) {
         l_c = tid & 63; l_i = tid >> 6;              // rows l_i + 4t
         const long long c = c0 + l_c;
-        if (c < ncols) {
+        if (c < ncols && l_c < tcols) {
             const long long o = c / inner, j = c - o * inner;
             ld_base = o * (long long)n * inner + j;
         }
     } else {
-        l_i = tid & 31; l_c = tid >> 5;              // columns l_c + 8t
+        l_i = tid & (TM_KC - 1); l_c = tid / TM_KC;   // columns l_c + (256 / TM_KC) t
     }
     const int m_q = tid & 63, m_i = tid >> 6;        // Ms loader: rows m_i + 4t
 
-    float xr[8], mr[8];
+    // Kronecker indices by a rounded float quotient: exact for arguments below 2^14 (checked on the host)
+    const float inv_n2 = 1.0f / (float)kr.n2, inv_r2 = 1.0f / (float)kr.r2;
+    float xr[TM_LR], mr[TM_LR];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
+        for (int t = 0; t < TM_LR; ++t) {
             if (!LASTMODE) {
                 const int i = k0 + l_i + 4 * t;
-                xr[t] = ldg_f32(X, ld_base + (long long)i * inner, ld_base >= 0 && i < n);
+                xr[t] = (k0 + 4 * t < n) ? ldg_f32(X, ld_base + (long long)i * inner, ld_base >= 0 && i < n) : 0.f;
             } else {
-                const long long c = c0 + l_c + 8 * t;
+                const int cl = l_c + (256 / TM_KC) * t;
+                const long long c = c0 + cl;
                 const int i = k0 + l_i;
-                xr[t] = ldg_f32(X, c * (long long)n + i, c < ncols && i < n);
+                xr[t] = ldg_f32(X, c * (long long)n + i, c < ncols && cl < tcols && i < n);
             }
             const int i = k0 + m_i + 4 * t, q = q0 + m_q;
-            if (!KRON) {
+            if (k0 + 4 * t >= n) {
+                mr[t] = 0.f;                          // uniform: the chunk ends before this row group
+            } else if (!KRON) {
                 mr[t] = ldg_f32(Mp, (long long)i * ms_i + (long long)q * ms_q, i < n && q < r);
             } else {
-                const int i1 = i / kr.n2, i2 = i - i1 * kr.n2, q1 = q / kr.r2, q2 = q - q1 * kr.r2;
+                const int i1 = (int)(((float)i + 0.5f) * inv_n2), i2 = i - i1 * kr.n2;
+                const int q1 = (int)(((float)q + 0.5f) * inv_r2), q2 = q - q1 * kr.r2;
                 const bool ok = i < n && q < r;
                 mr[t] = ldg_f32(Mp, (long long)i1 * ms_i + (long long)q1 * ms_q, ok) *
                         ldg_f32(kr.M2, (long long)i2 * kr.ms_i + (long long)q2 * kr.ms_q, ok);
@@ -82,9 +101,9 @@ __global__ __launch_bounds__(256) void k_ttm_mfma(const T* __restrict__ X, long 
     };
     auto stash = [&]() {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
+        for (int t = 0; t < TM_LR; ++t) {
             if (!LASTMODE) Xs[l_i + 4 * t][l_c] = xr[t];
-            else Xs[l_i][l_c + 8 * t] = xr[t];
+            else Xs[l_i][l_c + (256 / TM_KC) * t] = xr[t];
             Ms[m_i + 4 * t][m_q] = mr[t];
         }
     };
@@ -117,10 +136,25 @@ __global__ __launch_bounds__(256) void k_ttm_mfma(const T* __restrict__ X, long 
         for (int v = 0; v < 4; ++v) Ys[16 * nb + ll][16 * wave + 4 * lg + v] = acc[nb][v];
     __syncthreads();
     const int rq = (r - q0 < TM_TQ) ? r - q0 : TM_TQ;
-    if (!LASTMODE) {
+    if (!LASTMODE && inner < TM_TC) {
+        // short inner extent: a tile holds whole outer indices, and for one outer index the (q, j)
+        // pairs of this workgroup are one contiguous run of Y
+        const int k_o = tcols / (int)inner;
+        const long long o0 = (long long)bx * k_o;
+        const int nvo = (int)((outer - o0 < k_o) ? outer - o0 : k_o);
+        const int run = rq * (int)inner, total = nvo * run;          // total <= 4096: float quotients are exact
+        const float inv_run = 1.0f / (float)run, inv_in = 1.0f / (float)inner;
+        for (int e = tid; e < total; e += 256) {
+            const int ol = (int)(((float)e + 0.5f) * inv_run), rem = e - ol * run;
+            const int ql = (int)(((float)rem + 0.5f) * inv_in), j = rem - ql * (int)inner;
+            const long long idx = ((o0 + ol) * r + q0) * inner + rem;
+            const float v = Ys[ql][ol * (int)inner + j];
+            Y[idx] = beta ? Y[idx] + v : v;
+        }
+    } else if (!LASTMODE) {
         const int cl = tid & 63;
         const long long c = c0 + cl;
-        if (c < ncols) {
+        if (c < ncols && cl < tcols) {
             const long long o = c / inner, j = c - o * inner;
             for (int ql = tid >> 6; ql < rq; ql += 4) {
                 const long long idx = (o * r + q0 + ql) * inner + j;
@@ -131,7 +165,7 @@ __global__ __launch_bounds__(256) void k_ttm_mfma(const T* __restrict__ X, long 
         for (int e = tid; e < TM_TC * rq; e += 256) {
             const int cl = e / rq, ql = e - cl * rq;
             const long long c = c0 + cl;
-            if (c < ncols) {
+            if (c < ncols && cl < tcols) {
                 const long long idx = c * r + q0 + ql;
                 Y[idx] = beta ? Y[idx] + Ys[ql][cl] : Ys[ql][cl];
             }
@@ -140,33 +174,47 @@ __global__ __launch_bounds__(256) void k_ttm_mfma(const T* __restrict__ X, long 
 }
 
 // ---- long fibres, few columns ------------------------------------------------------------------
-// Round = 16*KS mode indices: wave w, step s multiplies rows k0 + 16s + 4w .. +3.
-//   A operand (16 columns x 4 i) and B operand (4 i x 16 q) are loaded by the lanes that use them.
-template <typename T, int NBR, int KS>
-__global__ __launch_bounds__(256) void k_ttm_ksplit(const T* __restrict__ X, long long outer, int n, long long inner,
-                                                    const float* __restrict__ Mp, long long ms_i, long long ms_q, int r,
-                                                    float* __restrict__ Y, int beta) {
-    __shared__ float red[4][NBR * 16][17];
+// A workgroup owns 16*CB columns.  Round = 16*KS mode indices: wave w, step s multiplies rows
+// k0 + 16s + 4w .. +3.  A operands (16 columns x 4 i, one per column block) and B operands
+// (4 i x 16 q) are loaded by the lanes that use them; CB column blocks share each B operand.
+template <typename T, int NBR, int KS, int CB>
+__global__ __launch_bounds__(256) void k_ttm_ksplit(Batch<TtmJob> bt) {
+    __shared__ float red[4][NBR * 16][16 * CB + 1];
+    int lb;
+    const TtmJob& jb = bt.job[locate(bt, &lb)];
+    const T* __restrict__ X = static_cast<const T*>(jb.X);
+    const float* __restrict__ Mp = jb.Mp;
+    float* __restrict__ Y = jb.Y;
+    const long long outer = jb.outer, inner = jb.inner, ms_i = jb.ms_i, ms_q = jb.ms_q;
+    const int n = jb.n, r = jb.r, beta = jb.beta;
+    const int by = lb / jb.gx, bx = lb - by * jb.gx;
     const long long ncols = outer * inner;
-    const long long c0 = (long long)blockIdx.x * 16;
-    const int q0 = blockIdx.y * (NBR * 16);
+    const long long c0 = (long long)bx * (16 * CB);
+    const int q0 = by * (NBR * 16);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
-    const long long c = c0 + ll;
-    const bool cok = c < ncols;
-    long long xbase = 0;
-    if (cok) {
-        const long long o = c / inner, j = c - o * inner;
-        xbase = o * (long long)n * inner + j;
-    }
-    v4f acc[NBR];
+    if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
+    long long xbase[CB];
+    bool cok[CB];
 #pragma unroll
-    for (int nb = 0; nb < NBR; ++nb) acc[nb] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int cb = 0; cb < CB; ++cb) {
+        const long long c = c0 + 16 * cb + ll;
+        cok[cb] = c < ncols;
+        const long long cc = cok[cb] ? c : 0;
+        const long long o = cc / inner, j = cc - o * inner;
+        xbase[cb] = o * (long long)n * inner + j;
+    }
+    v4f acc[CB][NBR];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int nb = 0; nb < NBR; ++nb) acc[cb][nb] = (v4f){0.f, 0.f, 0.f, 0.f};
     for (int k0 = 0; k0 < n; k0 += 16 * KS) {
-        float xr[KS], mr[NBR][KS];
+        float xr[CB][KS], mr[NBR][KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const int i = k0 + 16 * s + 4 * wave + lg;
-            xr[s] = ldg_f32(X, xbase + (long long)i * inner, cok && i < n);
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) xr[cb][s] = ldg_f32(X, xbase[cb] + (long long)i * inner, cok[cb] && i < n);
 #pragma unroll
             for (int nb = 0; nb < NBR; ++nb) {
                 const int q = q0 + 16 * nb + ll;
@@ -176,20 +224,25 @@ __global__ __launch_bounds__(256) void k_ttm_ksplit(const T* __restrict__ X, lon
 #pragma unroll
         for (int s = 0; s < KS; ++s)
 #pragma unroll
-            for (int nb = 0; nb < NBR; ++nb)
-                acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[s], mr[nb][s], acc[nb], 0, 0, 0);
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int nb = 0; nb < NBR; ++nb)
+                    acc[cb][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xr[cb][s], mr[nb][s], acc[cb][nb], 0, 0, 0);
     }
-    // lane holds column 4*lg + v, output 16nb + ll
+    // lane holds column 16cb + 4*lg + v, output 16nb + ll
 #pragma unroll
-    for (int nb = 0; nb < NBR; ++nb)
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) red[wave][16 * nb + ll][4 * lg + v] = acc[nb][v];
+        for (int nb = 0; nb < NBR; ++nb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[wave][16 * nb + ll][16 * cb + 4 * lg + v] = acc[cb][nb][v];
     __syncthreads();
-    const int cl = tid & 15;
+    constexpr int W = 16 * CB;
+    const int cl = tid % W;
     const long long cc = c0 + cl;
     if (cc < ncols) {
         const long long o = cc / inner, j = cc - o * inner;
-        for (int ql = tid >> 4; ql < NBR * 16; ql += 16) {
+        for (int ql = tid / W; ql < NBR * 16; ql += 256 / W) {
             const int q = q0 + ql;
             if (q < r) {
                 const float v = (red[0][ql][cl] + red[1][ql][cl]) + (red[2][ql][cl] + red[3][ql][cl]);
@@ -200,32 +253,14 @@ __global__ __launch_bounds__(256) void k_ttm_ksplit(const T* __restrict__ X, lon
     }
 }
 
-template <typename T, int NBR>
-static hipError_t launch_ksplit_n(const T* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
-                                  long long ms_q, int r, float* Y, int beta, dim3 grid, hipStream_t st) {
-    const int ks = n <= 64 ? 4 : (n <= 128 ? 8 : 16);
-    set_last_label("k_ttm_ksplit<%s, %d, %d>", sizeof(T) == 4 ? "float" : "asi::bf16_t", NBR, ks);
-    if (ks == 4) hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 4>), grid, 256, 0, st, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta);
-    else if (ks == 8) hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 8>), grid, 256, 0, st, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta);
-    else hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 16>), grid, 256, 0, st, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta);
-    return hipGetLastError();
+// ---- host side -----------------------------------------------------------------------------------
+// key bits: [0] bf16 input, [1] LASTMODE, [2] KRON, [3] split kernel, [4..6] NBR-1, [8..12] KS
+// (the split kernel's column blocks per workgroup follow from NBR: 4 up to NBR = 3, else 2)
+static unsigned ttm_key(bool bf16, bool last, bool kron, bool ksplit, int nbr, int ks) {
+    return (bf16 ? 1u : 0u) | (last ? 2u : 0u) | (kron ? 4u : 0u) | (ksplit ? 8u : 0u) | ((unsigned)(nbr - 1) << 4) |
+           ((unsigned)ks << 8);
 }
-
-template <typename T>
-static hipError_t launch_ksplit_t(const T* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
-                                  long long ms_q, int r, float* Y, int beta, hipStream_t st) {
-    const long long ncols = outer * inner;
-    const long long gx = (ncols + 15) / 16;
-    if (gx > 0x7fffffffLL) return hipErrorInvalidValue;
-    const int nbr = r >= 64 ? 4 : (r + 15) / 16;
-    dim3 grid((unsigned)gx, (unsigned)((r + nbr * 16 - 1) / (nbr * 16)));
-    switch (nbr) {
-        case 1: return launch_ksplit_n<T, 1>(X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, grid, st);
-        case 2: return launch_ksplit_n<T, 2>(X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, grid, st);
-        case 3: return launch_ksplit_n<T, 3>(X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, grid, st);
-        default: return launch_ksplit_n<T, 4>(X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, grid, st);
-    }
-}
+static int ksplit_cb(int nbr) { return nbr <= 3 ? 4 : 2; }
 
 // The tiled kernel walks the mode index in n/32 dependent steps with ncols/64 workgroups; when that
 // leaves most of the chip idle the split kernel is the faster one.
@@ -233,54 +268,120 @@ static bool prefer_ksplit(long long ncols, int n, long long inner) {
     return inner > 1 && n > 64 && (ncols + TM_TC - 1) / TM_TC < 512;
 }
 
-template <typename T, bool LAST, bool KRON>
-static hipError_t launch_ttm_t(const T* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
-                               long long ms_q, int r, float* Y, int beta, const KronSpec& kr, hipStream_t st) {
+static bool fill_ttm(DType xt, const void* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
+                     long long ms_q, int r, float* Y, int beta, const KronSpec& kr, Item* out) {
     const long long ncols = outer * inner;
-    const long long gx = (ncols + TM_TC - 1) / TM_TC;
-    if (gx > 0x7fffffffLL) return hipErrorInvalidValue;
-    dim3 grid((unsigned)gx, (unsigned)((r + TM_TQ - 1) / TM_TQ));
-    const int rr = r < TM_TQ ? r : TM_TQ;
-    const int nbr = (rr + 15) / 16;
-    set_last_label("k_ttm_mfma<%s, %s, %d, %s>", sizeof(T) == 4 ? "float" : "asi::bf16_t", LAST ? "true" : "false",
-                   nbr > 4 ? 4 : nbr, KRON ? "true" : "false");
+    if (ncols <= 0 || n <= 0 || r <= 0 || !X || !Mp || !Y) return false;
+    const bool last = (inner == 1), kron = kr.M2 != nullptr;
+    TtmJob jb;
+    std::memset(&jb, 0, sizeof(jb));
+    jb.X = X; jb.outer = outer; jb.inner = inner; jb.Mp = Mp; jb.ms_i = ms_i; jb.ms_q = ms_q; jb.Y = Y;
+    jb.kr = kr; jb.n = n; jb.r = r; jb.beta = beta;
+    const char* tn = xt == F32 ? "float" : "asi::bf16_t";
+    *out = Item();
+    if (!kron && prefer_ksplit(ncols, n, inner)) {
+        const int nbr = r >= 64 ? 4 : (r + 15) / 16;
+        const int ks = n <= 64 ? 4 : 8;
+        const int wcols = 16 * ksplit_cb(nbr);
+        const long long gx = (ncols + wcols - 1) / wcols;
+        jb.gx = (int)gx; jb.gy = (r + nbr * 16 - 1) / (nbr * 16);
+        if (gx * jb.gy > 0x3fffffffLL) return false;
+        out->kind = IT_KSPLIT; out->key = ttm_key(xt == BF16, false, false, true, nbr, ks);
+        std::snprintf(out->label, sizeof(out->label), "k_ttm_ksplit<%s, %d, %d, %d>", tn, nbr, ks, ksplit_cb(nbr));
+    } else {
+        // short inner extents: tiles of whole outer indices (stores then run contiguously)
+        jb.tile_cols = (!last && inner < TM_TC) ? (int)(TM_TC / inner * inner) : TM_TC;
+        const long long gx = (!last && inner < TM_TC) ? (outer + TM_TC / inner - 1) / (TM_TC / inner)
+                                                      : (ncols + TM_TC - 1) / TM_TC;
+        const int rr = r < TM_TQ ? r : TM_TQ;
+        const int nbr = (rr + 15) / 16;
+        jb.gx = (int)gx; jb.gy = (r + TM_TQ - 1) / TM_TQ;
+        if (gx * jb.gy > 0x3fffffffLL) return false;
+        out->kind = IT_TTM; out->key = ttm_key(xt == BF16, last, kron, false, nbr, 0);
+        std::snprintf(out->label, sizeof(out->label), "k_ttm_mfma<%s, %s, %d, %s>", tn, last ? "true" : "false", nbr,
+                      kron ? "true" : "false");
+    }
+    out->nblocks = jb.gx * jb.gy;
+    static_assert(sizeof(TtmJob) <= kItemArgMax, "argument block");
+    std::memcpy(out->arg, &jb, sizeof(jb));
+    return true;
+}
+
+bool make_ttm(DType xt, const void* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
+              long long ms_q, int r, float* Y, int beta, Item* out) {
+    const KronSpec none = {nullptr, 0, 0, 1, 1};
+    return fill_ttm(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, none, out);
+}
+
+bool make_ttm_kron(DType xt, const void* X, long long cols, int n1, int n2, const float* M1, long long ms1_i,
+                   long long ms1_q, int r1, const float* M2, long long ms2_i, long long ms2_q, int r2, float* Y,
+                   int beta, Item* out) {
+    if (cols <= 0 || n1 <= 0 || n2 <= 0 || r1 <= 0 || r2 <= 0 || !M1 || !M2) return false;
+    const KronSpec kr = {M2, ms2_i, ms2_q, n2, r2};
+    return fill_ttm(xt, X, cols, n1 * n2, 1, M1, ms1_i, ms1_q, r1 * r2, Y, beta, kr, out);
+}
+
+template <typename T, bool LAST, bool KRON>
+static void launch_tiled(int nbr, const Batch<TtmJob>& b, dim3 grid, hipStream_t st) {
     switch (nbr) {
-        case 1: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 1, KRON>), grid, 256, 0, st, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, kr); break;
-        case 2: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 2, KRON>), grid, 256, 0, st, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, kr); break;
-        case 3: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 3, KRON>), grid, 256, 0, st, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, kr); break;
-        default: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 4, KRON>), grid, 256, 0, st, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, kr); break;
+        case 1: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 1, KRON>), grid, 256, 0, st, b); break;
+        case 2: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 2, KRON>), grid, 256, 0, st, b); break;
+        case 3: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 3, KRON>), grid, 256, 0, st, b); break;
+        default: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 4, KRON>), grid, 256, 0, st, b); break;
+    }
+}
+template <typename T, int NBR>
+static void launch_split(int ks, const Batch<TtmJob>& b, dim3 grid, hipStream_t st) {
+    constexpr int CB = NBR <= 3 ? 4 : 2;
+    if (ks == 4) hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 4, CB>), grid, 256, 0, st, b);
+    else hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 8, CB>), grid, 256, 0, st, b);
+}
+
+hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, char* label_out) {
+    Batch<TtmJob> b;
+    dim3 grid;
+    if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
+    const unsigned key = items[0]->key;
+    const bool bf16 = key & 1u, last = key & 2u, kron = key & 4u, ksplit = key & 8u;
+    // the instantiation with the most column blocks / steps serves every item
+    int nbr = 1, ks = 0;
+    for (int j = 0; j < n; ++j) {
+        const int nj = (int)((items[j]->key >> 4) & 7u) + 1, kj = (int)(items[j]->key >> 8);
+        nbr = nj > nbr ? nj : nbr;
+        ks = kj > ks ? kj : ks;
+    }
+    if (label_out) {
+        const char* tn = bf16 ? "asi::bf16_t" : "float";
+        if (ksplit) std::snprintf(label_out, 96, "k_ttm_ksplit<%s, %d, %d, %d>", tn, nbr, ks, ksplit_cb(nbr));
+        else std::snprintf(label_out, 96, "k_ttm_mfma<%s, %s, %d, %s>", tn, last ? "true" : "false", nbr, kron ? "true" : "false");
+    }
+    if (ksplit) {
+        if (!bf16) {
+            switch (nbr) {
+                case 1: launch_split<float, 1>(ks, b, grid, st); break;
+                case 2: launch_split<float, 2>(ks, b, grid, st); break;
+                case 3: launch_split<float, 3>(ks, b, grid, st); break;
+                default: launch_split<float, 4>(ks, b, grid, st); break;
+            }
+        } else {
+            switch (nbr) {
+                case 1: launch_split<bf16_t, 1>(ks, b, grid, st); break;
+                case 2: launch_split<bf16_t, 2>(ks, b, grid, st); break;
+                case 3: launch_split<bf16_t, 3>(ks, b, grid, st); break;
+                default: launch_split<bf16_t, 4>(ks, b, grid, st); break;
+            }
+        }
+    } else if (kron) {           // always LASTMODE
+        if (!bf16) launch_tiled<float, true, true>(nbr, b, grid, st);
+        else launch_tiled<bf16_t, true, true>(nbr, b, grid, st);
+    } else if (!bf16) {
+        if (last) launch_tiled<float, true, false>(nbr, b, grid, st);
+        else launch_tiled<float, false, false>(nbr, b, grid, st);
+    } else {
+        if (last) launch_tiled<bf16_t, true, false>(nbr, b, grid, st);
+        else launch_tiled<bf16_t, false, false>(nbr, b, grid, st);
     }
     return hipGetLastError();
-}
-
-hipError_t launch_ttm(DType xt, const void* X, long long outer, int n, long long inner, const float* Mp,
-                      long long ms_i, long long ms_q, int r, float* Y, int beta, hipStream_t st) {
-    const long long ncols = outer * inner;
-    if (ncols <= 0 || n <= 0 || r <= 0) return hipErrorInvalidValue;
-    const bool last = (inner == 1);
-    const KronSpec none = {nullptr, 0, 0, 1, 1};
-    if (prefer_ksplit(ncols, n, inner)) {
-        return xt == F32 ? launch_ksplit_t<float>((const float*)X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, st)
-                         : launch_ksplit_t<bf16_t>((const bf16_t*)X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, st);
-    }
-    if (xt == F32) {
-        return last ? launch_ttm_t<float, true, false>((const float*)X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, none, st)
-                    : launch_ttm_t<float, false, false>((const float*)X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, none, st);
-    }
-    return last ? launch_ttm_t<bf16_t, true, false>((const bf16_t*)X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, none, st)
-                : launch_ttm_t<bf16_t, false, false>((const bf16_t*)X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, none, st);
-}
-
-// Two adjacent trailing modes at once: X is (cols, n1*n2) row-major, Y is (cols, r1*r2),
-//   Y[c, q1*r2 + q2] = sum_{i1,i2} X[c, i1*n2 + i2] * M1(i1,q1) * M2(i2,q2),  Mk(i,q) = Mk[i*msk_i + q*msk_q].
-hipError_t launch_ttm_kron(DType xt, const void* X, long long cols, int n1, int n2, const float* M1, long long ms1_i,
-                           long long ms1_q, int r1, const float* M2, long long ms2_i, long long ms2_q, int r2, float* Y,
-                           int beta, hipStream_t st) {
-    if (cols <= 0 || n1 <= 0 || n2 <= 0 || r1 <= 0 || r2 <= 0 || !M1 || !M2) return hipErrorInvalidValue;
-    const KronSpec kr = {M2, ms2_i, ms2_q, n2, r2};
-    const int n = n1 * n2, r = r1 * r2;
-    if (xt == F32) return launch_ttm_t<float, true, true>((const float*)X, cols, n, 1, M1, ms1_i, ms1_q, r, Y, beta, kr, st);
-    return launch_ttm_t<bf16_t, true, true>((const bf16_t*)X, cols, n, 1, M1, ms1_i, ms1_q, r, Y, beta, kr, st);
 }
 
 }  // namespace asi

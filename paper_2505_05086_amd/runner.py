@@ -84,3 +84,45 @@ class LayerRunner:
         self.compress(A)
         self.core(A)
         return self.weight_grad(grad_out)
+
+
+class BatchRunner:
+    """Several layers stepped together through the batched entry points: every kernel launch
+    serves all of them.  Owns one LayerRunner per layer for the device buffers."""
+
+    def __init__(self, layers, device="cuda"):
+        if not 1 <= len(layers) <= B.MAX_BATCH:
+            raise ValueError(f"1..{B.MAX_BATCH} layers per batch")
+        self.runs = [LayerRunner(lay, device) for lay in layers]
+        kinds = {r.layer.kind for r in self.runs}
+        if len(kinds) != 1:
+            raise ValueError("a batch holds conv2d layers or linear layers, not both")
+        self.kind = kinds.pop()
+
+    def compress(self, A: Sequence[torch.Tensor]) -> None:
+        rs = self.runs
+        B.asi_compress_batch([r.desc for r in rs], A, [r.U[r.cur] for r in rs], [r.U[1 - r.cur] for r in rs],
+                             [r.ws for r in rs], [r.info for r in rs])
+        for r in rs:
+            r.cur = 1 - r.cur
+
+    def core(self, A: Sequence[torch.Tensor]) -> None:
+        rs = self.runs
+        B.asi_core_project_batch([r.desc for r in rs], A, [r.U[r.cur] for r in rs], [r.S for r in rs],
+                                 [r.ws for r in rs])
+
+    def weight_grad(self, grad_out: Sequence[torch.Tensor], accumulate: bool = False) -> List[torch.Tensor]:
+        rs = self.runs
+        acc = [accumulate] * len(rs)
+        if self.kind == "conv2d":
+            B.asi_weight_grad_conv2d_batch([r.desc for r in rs], [r.S for r in rs], [r.U[r.cur] for r in rs], grad_out,
+                                           [r.conv for r in rs], [r.dW for r in rs], acc, [r.ws for r in rs])
+        else:
+            B.asi_weight_grad_linear_batch([r.desc for r in rs], [r.S for r in rs], [r.U[r.cur] for r in rs], grad_out,
+                                           [r.dout for r in rs], [r.dW for r in rs], acc, [r.ws for r in rs])
+        return [r.dW for r in rs]
+
+    def step(self, A: Sequence[torch.Tensor], grad_out: Sequence[torch.Tensor]) -> List[torch.Tensor]:
+        self.compress(A)
+        self.core(A)
+        return self.weight_grad(grad_out)

@@ -99,3 +99,55 @@ def test_binding_refuses_host_tensors():
     x = torch.zeros(8, 6, 5, 4)
     with pytest.raises(ValueError):
         asi.asi_core_project(d, x, [x] * 4, x, x)
+
+
+def test_batched_entry_points_reject_bad_arguments():
+    L = asi.lib()
+    good = asi.make_desc((8, 6, 5, 4), (2, 3, 2, 2))
+    bad = asi.make_desc((8, 6, 5, 4), (2, 3, 2, 5))
+    need = asi.asi_workspace_bytes(good)
+
+    def descs(*ds):
+        arr = (B.TensorDesc * len(ds))()
+        for i, d in enumerate(ds):
+            arr[i] = d
+        return arr
+
+    def ptrs(n, v=0x1000):
+        arr = (C.c_void_p * n)()
+        for i in range(n):
+            arr[i] = v
+        return arr
+
+    def modes(n):
+        inner = [_arr() for _ in range(n)]
+        outer = (C.c_void_p * n)()
+        for i, a in enumerate(inner):
+            outer[i] = C.addressof(a)
+        return outer, inner
+
+    def sizes(*vals):
+        arr = (C.c_size_t * len(vals))()
+        for i, v in enumerate(vals):
+            arr[i] = v
+        return arr
+
+    up, k1 = modes(2)
+    uo, k2 = modes(2)
+    call = lambda n, ds, sz: L.asi_compress_batch(n, ds, ptrs(2), up, uo, ptrs(2), sz, None, None)
+    assert call(0, descs(good, good), sizes(need, need)) == 2                 # count out of range
+    assert call(9, descs(good, good), sizes(need, need)) == 2
+    assert call(2, descs(good, bad), sizes(need, need)) == 1                  # second layer rejected: nothing runs
+    assert call(2, descs(good, good), sizes(need, need - 1)) == 3
+    assert L.asi_compress_batch(2, None, ptrs(2), up, uo, ptrs(2), sizes(need, need), None, None) == 1
+    assert L.asi_core_project_batch(2, descs(good, good), ptrs(2), up, ptrs(2, 0), ptrs(2), sizes(need, need), None) == 1
+    cv = (B.Conv2dDesc * 2)()
+    cv[0] = asi.make_conv(6, 3, 3, pad=(1, 1))
+    cv[1] = asi.make_conv(6, 9, 9)
+    big = 1 << 24
+    assert L.asi_weight_grad_conv2d_batch(2, descs(good, good), ptrs(2), up, ptrs(2), cv, ptrs(2), None, ptrs(2),
+                                          sizes(big, big), None) == 1
+    d3 = asi.make_desc((8, 6, 5), (2, 3, 2))
+    dout = (C.c_int64 * 2)(7, 0)
+    assert L.asi_weight_grad_linear_batch(2, descs(d3, d3), ptrs(2), up, ptrs(2), dout, ptrs(2), None, ptrs(2),
+                                          sizes(big, big), None) == 1
