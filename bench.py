@@ -57,9 +57,10 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, help="workload (1-5), default the ResNet-18 tail")
     ap.add_argument("--distinct", type=int, default=8, help="distinct input steps kept in HBM and cycled")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams the layers are spread over (0 = one per layer)")
-    ap.add_argument("--batch", type=int, default=1,
-                    help="1: all layers of a step go through the batched entry points (every launch serves all layers); "
-                         "0: one call chain per layer, spread over --streams")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="layers per batched call (every launch serves that many layers), 1 = all layers in one batch "
+                         "up to the library's limit; batches run on their own streams; 0: one call chain per layer, "
+                         "spread over --streams")
     ap.add_argument("--graph", type=int, default=1, help="replay each step from a captured HIP graph (1) or launch eagerly (0)")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB ten times (calibrates rocprofv3 byte counters)")
@@ -123,7 +124,7 @@ def main():
     streams = [LayerStream(cfg.index, li, lay, cfg.theta) for li, lay in enumerate(cfg.layers)]
     batches = None
     if args.batch:
-        mb = asi.binding.MAX_BATCH
+        mb = asi.binding.MAX_BATCH if args.batch == 1 else min(args.batch, asi.binding.MAX_BATCH)
         batches = [BatchRunner(cfg.layers[i:i + mb]) for i in range(0, len(cfg.layers), mb)]
         runners = [r for b in batches for r in b.runs]
     else:
@@ -146,16 +147,25 @@ def main():
     # spread over side streams (default priority) that fork from / join the main stream.
     nstreams = len(runners) if args.streams <= 0 else min(args.streams, len(runners))
     if batches is not None:
-        nstreams = 1
+        nstreams = len(batches)
     main_stream = torch.cuda.current_stream()
     side = [torch.cuda.Stream() for _ in range(nstreams)] if nstreams > 1 else [None]
 
-    def batched_step(a, g):
+    def batched_step(a, g, concurrent=True):
+        cur = torch.cuda.current_stream()
+        multi = concurrent and len(batches) > 1
+        if multi:
+            for s in side:
+                s.wait_stream(cur)
         i = 0
-        for b in batches:
+        for bi, b in enumerate(batches):
             n = len(b.runs)
-            b.step(a[i:i + n], g[i:i + n])
+            with torch.cuda.stream(side[bi] if multi else cur):
+                b.step(a[i:i + n], g[i:i + n])
             i += n
+        if multi:
+            for s in side:
+                cur.wait_stream(s)
 
     def one_step(k):
         a, g = A_dev[k % ndist], dY_dev[k % ndist]
@@ -227,7 +237,7 @@ def main():
     for k in range(nprof):
         a_, g_ = A_dev[k % ndist], dY_dev[k % ndist]
         if batches is not None:
-            batched_step(a_, g_)
+            batched_step(a_, g_, concurrent=False)
         else:
             for r, at, gt in zip(runners, a_, g_):
                 r.step(at, gt)

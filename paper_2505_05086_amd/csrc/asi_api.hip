@@ -140,7 +140,9 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
 // The products are ordered to minimise multiply-adds.  For small spatial extents the H and W
 // modes are contracted together by one pass with the Kronecker product of their factors, so
 // the tensor is treated as (B, C, H*W) with three "super modes".
-constexpr int kKronMaxN = 256, kKronMaxR = 64;
+// merged products pay off while the contraction fits one or two K chunks of the kernel; a longer
+// one is a chain of dependent chunks on few workgroups and two separate products are faster
+constexpr int kKronMaxN = 64, kKronMaxR = 64, kKronMaxOut = 256;
 
 struct CorePlan {
     int d = 0;                       // super modes
@@ -245,7 +247,7 @@ ConvPlan plan_conv(const Shape& s, const ConvGeom& cg, void* ws) {
     const CorrGeom& g = cg.g;
     Carver c(ws);
     p.G1 = c.take<float>((size_t)g.r1 * g.cout * g.Ho * g.Wo);
-    if ((long long)s.r[2] * s.r[3] > kKronMaxN || (long long)g.H * g.W > kKronMaxN)
+    if ((long long)s.r[2] * s.r[3] > kKronMaxN || (long long)g.H * g.W > kKronMaxOut)
         p.Z1 = c.take<float>((size_t)g.r1 * g.r2 * g.H * s.r[3]);      // else Z comes from one merged pass
     p.Z = c.take<float>((size_t)g.r1 * g.r2 * g.H * g.W);
     p.nsplit = corr_splits(g);

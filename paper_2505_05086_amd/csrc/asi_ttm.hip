@@ -29,11 +29,12 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr int TM_TC = 64, TM_TQ = 64, TM_LD = TM_TC + 4;
 constexpr int TM_KCMAX = 64;
 
-template <typename T, bool LASTMODE, int NBR, bool KRON>
+// KM: 0 = plain matrix, 1 = Kronecker product, 2 = Kronecker product with K chunks of 64 (long merged
+// modes with few columns; otherwise chunks of 32, which overlap across workgroups)
+template <typename T, bool LASTMODE, int NBR, int KM>
 __global__ __launch_bounds__(256) void k_ttm_mfma(Batch<TtmJob> bt) {
-    // K chunk: 32 when there are many columns (chunks overlap across workgroups), 64 for the merged
-    // modes, whose K is long and whose columns are few
-    constexpr int TM_KC = KRON ? 64 : 32;
+    constexpr bool KRON = KM != 0;
+    constexpr int TM_KC = KM == 2 ? 64 : 32;
     constexpr int TM_LR = TM_KC / 4;      // loads per thread and operand for one chunk
     __shared__ float smem[2 * TM_KCMAX * TM_LD];    // Xs | Ms during the K loop, Ys (64 x TM_LD) afterwards
     float (*Xs)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem);
@@ -254,13 +255,14 @@ __global__ __launch_bounds__(256) void k_ttm_ksplit(Batch<TtmJob> bt) {
 }
 
 // ---- host side -----------------------------------------------------------------------------------
-// key bits: [0] bf16 input, [1] LASTMODE, [2] KRON, [3] split kernel, [4..6] NBR-1, [8..12] KS
-// (the split kernel's column blocks per workgroup follow from NBR: 4 up to NBR = 3, else 2)
-static unsigned ttm_key(bool bf16, bool last, bool kron, bool ksplit, int nbr, int ks) {
+// key bits: [0] bf16 input, [1] LASTMODE, [2] KRON, [3] split kernel, [4..6] NBR-1, [8..12] KS,
+// [13] split kernel with several column blocks per workgroup (4 up to NBR = 3, else 2),
+// [14] Kronecker product with K chunks of 64.  Bits 4..12 only bound sizes.
+static unsigned ttm_key(bool bf16, bool last, bool kron, bool ksplit, int nbr, int ks, bool wide, bool kc64) {
     return (bf16 ? 1u : 0u) | (last ? 2u : 0u) | (kron ? 4u : 0u) | (ksplit ? 8u : 0u) | ((unsigned)(nbr - 1) << 4) |
-           ((unsigned)ks << 8);
+           ((unsigned)ks << 8) | (wide ? 0x2000u : 0u) | (kc64 ? 0x4000u : 0u);
 }
-static int ksplit_cb(int nbr) { return nbr <= 3 ? 4 : 2; }
+static int ksplit_cb(int nbr, bool wide) { return !wide ? 1 : (nbr <= 3 ? 4 : 2); }
 
 // The tiled kernel walks the mode index in n/32 dependent steps with ncols/64 workgroups; when that
 // leaves most of the chip idle the split kernel is the faster one.
@@ -281,13 +283,16 @@ static bool fill_ttm(DType xt, const void* X, long long outer, int n, long long 
     *out = Item();
     if (!kron && prefer_ksplit(ncols, n, inner)) {
         const int nbr = r >= 64 ? 4 : (r + 15) / 16;
-        const int ks = n <= 64 ? 4 : 8;
-        const int wcols = 16 * ksplit_cb(nbr);
+        // several column blocks per workgroup share the matrix operand; worth it once that still
+        // leaves a workgroup for every other CU
+        const bool wide = ncols / (16 * ksplit_cb(nbr, true)) >= 128;
+        const int ks = n <= 64 ? 4 : (wide ? 8 : (n <= 128 ? 8 : 16));
+        const int wcols = 16 * ksplit_cb(nbr, wide);
         const long long gx = (ncols + wcols - 1) / wcols;
         jb.gx = (int)gx; jb.gy = (r + nbr * 16 - 1) / (nbr * 16);
         if (gx * jb.gy > 0x3fffffffLL) return false;
-        out->kind = IT_KSPLIT; out->key = ttm_key(xt == BF16, false, false, true, nbr, ks);
-        std::snprintf(out->label, sizeof(out->label), "k_ttm_ksplit<%s, %d, %d, %d>", tn, nbr, ks, ksplit_cb(nbr));
+        out->kind = IT_KSPLIT; out->key = ttm_key(xt == BF16, false, false, true, nbr, ks, wide, false);
+        std::snprintf(out->label, sizeof(out->label), "k_ttm_ksplit<%s, %d, %d, %d>", tn, nbr, ks, ksplit_cb(nbr, wide));
     } else {
         // short inner extents: tiles of whole outer indices (stores then run contiguously)
         jb.tile_cols = (!last && inner < TM_TC) ? (int)(TM_TC / inner * inner) : TM_TC;
@@ -297,9 +302,9 @@ static bool fill_ttm(DType xt, const void* X, long long outer, int n, long long 
         const int nbr = (rr + 15) / 16;
         jb.gx = (int)gx; jb.gy = (r + TM_TQ - 1) / TM_TQ;
         if (gx * jb.gy > 0x3fffffffLL) return false;
-        out->kind = IT_TTM; out->key = ttm_key(xt == BF16, last, kron, false, nbr, 0);
-        std::snprintf(out->label, sizeof(out->label), "k_ttm_mfma<%s, %s, %d, %s>", tn, last ? "true" : "false", nbr,
-                      kron ? "true" : "false");
+        out->kind = IT_TTM; out->key = ttm_key(xt == BF16, last, kron, false, nbr, 0, false, kron && n > 64);
+        std::snprintf(out->label, sizeof(out->label), "k_ttm_mfma<%s, %s, %d, %d>", tn, last ? "true" : "false", nbr,
+                      kron ? (n > 64 ? 2 : 1) : 0);
     }
     out->nblocks = jb.gx * jb.gy;
     static_assert(sizeof(TtmJob) <= kItemArgMax, "argument block");
@@ -321,20 +326,26 @@ bool make_ttm_kron(DType xt, const void* X, long long cols, int n1, int n2, cons
     return fill_ttm(xt, X, cols, n1 * n2, 1, M1, ms1_i, ms1_q, r1 * r2, Y, beta, kr, out);
 }
 
-template <typename T, bool LAST, bool KRON>
+template <typename T, bool LAST, int KM>
 static void launch_tiled(int nbr, const Batch<TtmJob>& b, dim3 grid, hipStream_t st) {
     switch (nbr) {
-        case 1: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 1, KRON>), grid, 256, 0, st, b); break;
-        case 2: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 2, KRON>), grid, 256, 0, st, b); break;
-        case 3: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 3, KRON>), grid, 256, 0, st, b); break;
-        default: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 4, KRON>), grid, 256, 0, st, b); break;
+        case 1: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 1, KM>), grid, 256, 0, st, b); break;
+        case 2: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 2, KM>), grid, 256, 0, st, b); break;
+        case 3: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 3, KM>), grid, 256, 0, st, b); break;
+        default: hipLaunchKernelGGL((k_ttm_mfma<T, LAST, 4, KM>), grid, 256, 0, st, b); break;
     }
 }
 template <typename T, int NBR>
-static void launch_split(int ks, const Batch<TtmJob>& b, dim3 grid, hipStream_t st) {
+static void launch_split(int ks, bool wide, const Batch<TtmJob>& b, dim3 grid, hipStream_t st) {
     constexpr int CB = NBR <= 3 ? 4 : 2;
-    if (ks == 4) hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 4, CB>), grid, 256, 0, st, b);
-    else hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 8, CB>), grid, 256, 0, st, b);
+    if (wide) {
+        if (ks == 4) hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 4, CB>), grid, 256, 0, st, b);
+        else hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 8, CB>), grid, 256, 0, st, b);
+    } else {
+        if (ks == 4) hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 4, 1>), grid, 256, 0, st, b);
+        else if (ks == 8) hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 8, 1>), grid, 256, 0, st, b);
+        else hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 16, 1>), grid, 256, 0, st, b);
+    }
 }
 
 hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, char* label_out) {
@@ -343,43 +354,44 @@ hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, cha
     if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
     const unsigned key = items[0]->key;
     const bool bf16 = key & 1u, last = key & 2u, kron = key & 4u, ksplit = key & 8u;
+    const bool wide = key & 0x2000u, kc64 = key & 0x4000u;
     // the instantiation with the most column blocks / steps serves every item
     int nbr = 1, ks = 0;
     for (int j = 0; j < n; ++j) {
-        const int nj = (int)((items[j]->key >> 4) & 7u) + 1, kj = (int)(items[j]->key >> 8);
+        const int nj = (int)((items[j]->key >> 4) & 7u) + 1, kj = (int)((items[j]->key >> 8) & 31u);
         nbr = nj > nbr ? nj : nbr;
         ks = kj > ks ? kj : ks;
     }
     if (label_out) {
         const char* tn = bf16 ? "asi::bf16_t" : "float";
-        if (ksplit) std::snprintf(label_out, 96, "k_ttm_ksplit<%s, %d, %d, %d>", tn, nbr, ks, ksplit_cb(nbr));
-        else std::snprintf(label_out, 96, "k_ttm_mfma<%s, %s, %d, %s>", tn, last ? "true" : "false", nbr, kron ? "true" : "false");
+        if (ksplit) std::snprintf(label_out, 96, "k_ttm_ksplit<%s, %d, %d, %d>", tn, nbr, ks, ksplit_cb(nbr, wide));
+        else std::snprintf(label_out, 96, "k_ttm_mfma<%s, %s, %d, %d>", tn, last ? "true" : "false", nbr, kron ? (kc64 ? 2 : 1) : 0);
     }
     if (ksplit) {
         if (!bf16) {
             switch (nbr) {
-                case 1: launch_split<float, 1>(ks, b, grid, st); break;
-                case 2: launch_split<float, 2>(ks, b, grid, st); break;
-                case 3: launch_split<float, 3>(ks, b, grid, st); break;
-                default: launch_split<float, 4>(ks, b, grid, st); break;
+                case 1: launch_split<float, 1>(ks, wide, b, grid, st); break;
+                case 2: launch_split<float, 2>(ks, wide, b, grid, st); break;
+                case 3: launch_split<float, 3>(ks, wide, b, grid, st); break;
+                default: launch_split<float, 4>(ks, wide, b, grid, st); break;
             }
         } else {
             switch (nbr) {
-                case 1: launch_split<bf16_t, 1>(ks, b, grid, st); break;
-                case 2: launch_split<bf16_t, 2>(ks, b, grid, st); break;
-                case 3: launch_split<bf16_t, 3>(ks, b, grid, st); break;
-                default: launch_split<bf16_t, 4>(ks, b, grid, st); break;
+                case 1: launch_split<bf16_t, 1>(ks, wide, b, grid, st); break;
+                case 2: launch_split<bf16_t, 2>(ks, wide, b, grid, st); break;
+                case 3: launch_split<bf16_t, 3>(ks, wide, b, grid, st); break;
+                default: launch_split<bf16_t, 4>(ks, wide, b, grid, st); break;
             }
         }
     } else if (kron) {           // always LASTMODE
-        if (!bf16) launch_tiled<float, true, true>(nbr, b, grid, st);
-        else launch_tiled<bf16_t, true, true>(nbr, b, grid, st);
+        if (!bf16) { if (kc64) launch_tiled<float, true, 2>(nbr, b, grid, st); else launch_tiled<float, true, 1>(nbr, b, grid, st); }
+        else { if (kc64) launch_tiled<bf16_t, true, 2>(nbr, b, grid, st); else launch_tiled<bf16_t, true, 1>(nbr, b, grid, st); }
     } else if (!bf16) {
-        if (last) launch_tiled<float, true, false>(nbr, b, grid, st);
-        else launch_tiled<float, false, false>(nbr, b, grid, st);
+        if (last) launch_tiled<float, true, 0>(nbr, b, grid, st);
+        else launch_tiled<float, false, 0>(nbr, b, grid, st);
     } else {
-        if (last) launch_tiled<bf16_t, true, false>(nbr, b, grid, st);
-        else launch_tiled<bf16_t, false, false>(nbr, b, grid, st);
+        if (last) launch_tiled<bf16_t, true, 0>(nbr, b, grid, st);
+        else launch_tiled<bf16_t, false, 0>(nbr, b, grid, st);
     }
     return hipGetLastError();
 }
