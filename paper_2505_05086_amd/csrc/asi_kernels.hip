@@ -14,12 +14,12 @@ namespace asi {
 
 // ---------------------------------------------------------------------------
 // pair: P[i,q] = sum_c X[i,c] Y[q,c] on fp64 MFMA.  A workgroup owns 64 rows i x 32 outputs q
-// over one split of the unfolding columns; chunks of 32 columns are prefetched into registers
+// over one split of the unfolding columns; chunks of 64 columns are prefetched into registers
 // while the previous chunk is multiplied.  Wave w multiplies rows 16w..16w+15:
 //   A operand (16 i x 4 c) = Xs[4ks + lane/16][16w + lane%16],  B operand (4 c x 16 q) = Ys[4ks + lane/16][16nb + lane%16]
 // fp32 values are widened to fp64, so every product is exact and the sums are carried in fp64.
 // ---------------------------------------------------------------------------
-constexpr int PR_TI = 64, PR_TQ = 32, PR_TK = 32;
+constexpr int PR_TI = 64, PR_TQ = 32, PR_TK = 64;
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 template <typename T, bool LASTMODE>
@@ -41,10 +41,11 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;   // arrival counters of later launches
 
-    float xr[8], yr[4];
+    constexpr int NX = PR_TI * PR_TK / 256, NY = PR_TQ * PR_TK / 256, RS = 256 / PR_TK;   // loads per thread, row step
+    float xr[NX], yr[NY];
     auto fetch = [&](long long c0) {
         if (!LASTMODE) {
-            const int cl = tid & 31;
+            const int cl = tid & (PR_TK - 1);
             const long long c = c0 + cl;
             const bool valid = c < cend;
             long long xbase = 0, ybase = 0;
@@ -54,25 +55,25 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
                 ybase = o * (long long)r * inner + j;
             }
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const int i = i0 + (tid >> 5) + 8 * t;
+            for (int t = 0; t < NX; ++t) {
+                const int i = i0 + tid / PR_TK + RS * t;
                 xr[t] = ldg_f32(X, xbase + (long long)i * inner, valid && i < n);
             }
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int q = q0 + (tid >> 5) + 8 * t;
+            for (int t = 0; t < NY; ++t) {
+                const int q = q0 + tid / PR_TK + RS * t;
                 yr[t] = ldg_f32(Y, ybase + (long long)q * inner, valid && q < r);
             }
         } else {  // inner == 1
             const int i = i0 + (tid & 63);
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
+            for (int t = 0; t < NX; ++t) {
                 const long long c = c0 + (tid >> 6) + 4 * t;
                 xr[t] = ldg_f32(X, c * (long long)n + i, c < cend && i < n);
             }
             const int q = q0 + (tid & 31);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < NY; ++t) {
                 const long long c = c0 + (tid >> 5) + 8 * t;
                 yr[t] = ldg_f32(Y, c * (long long)r + q, c < cend && q < r);
             }
@@ -80,16 +81,16 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
     };
     auto stash = [&]() {
         if (!LASTMODE) {
-            const int cl = tid & 31;
+            const int cl = tid & (PR_TK - 1);
 #pragma unroll
-            for (int t = 0; t < 8; ++t) Xs[cl][(tid >> 5) + 8 * t] = xr[t];
+            for (int t = 0; t < NX; ++t) Xs[cl][tid / PR_TK + RS * t] = xr[t];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) Ys[cl][(tid >> 5) + 8 * t] = yr[t];
+            for (int t = 0; t < NY; ++t) Ys[cl][tid / PR_TK + RS * t] = yr[t];
         } else {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) Xs[(tid >> 6) + 4 * t][tid & 63] = xr[t];
+            for (int t = 0; t < NX; ++t) Xs[(tid >> 6) + 4 * t][tid & 63] = xr[t];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) Ys[(tid >> 5) + 8 * t][tid & 31] = yr[t];
+            for (int t = 0; t < NY; ++t) Ys[(tid >> 5) + 8 * t][tid & 31] = yr[t];
         }
     };
 
@@ -126,7 +127,7 @@ int pair_splits(long long outer, int n, long long inner, int r) {
     const long long ncols = outer * inner;
     const long long tiles = (long long)((n + PR_TI - 1) / PR_TI) * ((r + PR_TQ - 1) / PR_TQ);
     long long want = 512 / (tiles > 0 ? tiles : 1);           // aim at ~512 workgroups
-    const long long maxs = (ncols + 511) / 512;               // at least 512 columns per split
+    const long long maxs = (ncols + 255) / 256;               // at least 256 columns per split
     if (want > maxs) want = maxs;
     if (want > 64) want = 64;
     if (want < 1) want = 1;

@@ -169,6 +169,8 @@ EDGE_CONV = [
     ((1, 1, 3, 300), (1, 1, 2, 3), 2, 1, 1, 0, 1, 1),          # singleton modes, long last mode
     ((130, 3, 2, 2), (12, 3, 2, 2), 3, 2, 1, 0, 1, 1),         # long first mode, even kernel
     ((2, 70, 33, 17), (2, 20, 9, 6), 5, 5, 2, 2, 1, 1),        # 5x5 kernel, several tiles per mode
+    ((3, 4, 8, 8), (2, 3, 8, 7), 5, 3, 1, 1, 1, 1),            # 8x8 planes at (almost) full rank: widest tiny-plane kernel
+    ((4100, 32, 7, 7), (6, 8, 5, 5), 8, 3, 1, 1, 1, 1),        # more 7x7 planes than workgroups: each walks several tiles
 ]
 
 
