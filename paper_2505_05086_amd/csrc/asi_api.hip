@@ -336,10 +336,11 @@ asi_status add_ttm_kron(Program& pg, const char* role, DType xt, const void* X, 
     return ASI_OK;
 }
 asi_status add_pair(Program& pg, const char* role, DType xt, const void* X, long long outer, int n, long long inner,
-                    const float* Y, int r, double* part, int nsplit, int32_t* zero, int nzero) {
+                    const float* Y, int r, double* part, int nsplit, int32_t* zero, int nzero,
+                    const PresumArgs* ride = nullptr, double ride_bytes = 0.0) {
     const double cols = (double)outer * (double)inner;
-    ASI_ADD(pg, role, cols * n * esize(xt) + 4.0 * cols * r + 8.0 * n * r * nsplit, 2.0 * cols * n * r,
-            make_pair(xt, X, outer, n, inner, Y, r, part, nsplit, zero, nzero, it__));
+    ASI_ADD(pg, role, cols * n * esize(xt) + 4.0 * cols * r + 8.0 * n * r * nsplit + ride_bytes, 2.0 * cols * n * r,
+            make_pair(xt, X, outer, n, inner, Y, r, part, nsplit, zero, nzero, ride, it__));
     return ASI_OK;
 }
 #define ASI_TRYS(expr)                                 \
@@ -409,10 +410,28 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
     std::memset(&pre2, 0, sizeof(pre2));
     double wide_b = 0, wide_f = 0, pre2_b = 0, chol_b = 0, chol_f = 0, wchol_b = 0, wchol_f = 0;
     double fast_b = 0, fast_f = 0, slow_b = 0, slow_f = 0, pre_b = 0;
+    // Launch order of the subspace steps: the modes served by one kernel first, then the modes that
+    // take two (V, then P).  The last P launch also carries the first level of the partial-sum tree of
+    // the modes before it (independent work in extra workgroups), which saves a launch of its own.
+    int order[4], nord = 0, last_two = -1;
+    for (int m = 0; m < s.d; ++m)
+        if (p.fused[m] || (p.paired && m >= 2)) order[nord++] = m;
+    for (int m = 0; m < s.d; ++m)
+        if (!(p.fused[m] || (p.paired && m >= 2))) { order[nord++] = m; last_two = m; }
+    PresumJob prejob[4];
+    bool preneed[4] = {false, false, false, false};
     for (int m = 0; m < s.d; ++m) {
+        if (!p.part2[m]) continue;
+        PresumJob& pj = prejob[m];
+        pj.in = p.part[m]; pj.out = p.part2[m]; pj.cnt = (long long)s.n[m] * s.r[m]; pj.nsplit = p.nsplit[m];
+        pj.nchunks = (int)((pj.cnt + 255) / 256); pj.ngroups = p.nsplit2[m];
+        preneed[m] = true;
+    }
+    bool zero_given = false;
+    for (int k = 0; k < nord; ++k) {
+        const int m = order[k];
         const long long outer = s.outer(m), inner = s.inner(m);
         const int n = (int)s.n[m], r = s.r[m];
-        int32_t* zero = (m == 0) ? p.ctr8 : nullptr;     // the first mode's kernel clears the arrival counters
         if (p.paired && m == 2) {
             // H and W modes: both subspace steps from one read of the activation's planes
             const double tot = (double)s.numel;
@@ -428,25 +447,43 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
             // done together with mode 3
         } else if (p.fused[m]) {
             // short fibres: V and P from one LDS tile of complete fibres, V never stored
+            int32_t* zero = zero_given ? nullptr : p.ctr8;       // one early kernel clears the arrival counters
+            zero_given = true;
             const double cols = (double)outer * (double)inner;
             ASI_ADD(pg, "", cols * n * esize(s.dt) + 4.0 * n * r + 8.0 * n * r * p.nsplit[m], 4.0 * cols * n * r,
                     make_subspace_small(s.dt, A, outer, n, inner, U_prev[m], r, p.part[m], p.nsplit[m], zero, 8, it__));
         } else {
+            int32_t* zero = zero_given ? nullptr : p.ctr8;
+            zero_given = true;
             // V = A_m^T U_prev, kept as a tensor with mode m of size r
             ASI_TRYS(add_ttm(pg, "V", s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0));
             // P = A_m V, split over the unfolding's columns
-            ASI_TRYS(add_pair(pg, "P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], zero, 8));
+            PresumArgs ride;
+            std::memset(&ride, 0, sizeof(ride));
+            double ride_b = 0;
+            if (m == last_two)
+                for (int k2 = 0; k2 < k; ++k2) {
+                    const int m2 = order[k2];
+                    if (!preneed[m2]) continue;
+                    ride.job[ride.njobs++] = prejob[m2];
+                    ride_b += 8.0 * s.n[m2] * s.r[m2] * (p.nsplit[m2] + p.nsplit2[m2]);
+                    preneed[m2] = false;
+                }
+            ASI_TRYS(add_pair(pg, "P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], zero, 8,
+                              ride.njobs ? &ride : nullptr, ride_b));
         }
+    }
+    for (int m = 0; m < s.d; ++m)
+        if (preneed[m]) {
+            pre.job[pre.njobs++] = prejob[m];
+            pre_b += 8.0 * s.n[m] * s.r[m] * (p.nsplit[m] + p.nsplit2[m]);
+        }
+    for (int m = 0; m < s.d; ++m) {
+        const int n = (int)s.n[m], r = s.r[m];
         OrthArgs& oa = p.fast_orth[m] ? fast : (p.wide_orth[m] ? wide : slow);
         OrthJob& j = oa.job[oa.njobs++];
         j.part = p.part[m]; j.nsplit = p.nsplit[m]; j.n = n; j.r = r;
-        if (p.part2[m]) {
-            PresumJob& pj = pre.job[pre.njobs++];
-            pj.in = p.part[m]; pj.out = p.part2[m]; pj.cnt = (long long)n * r; pj.nsplit = p.nsplit[m];
-            pj.nchunks = (int)((pj.cnt + 255) / 256); pj.ngroups = p.nsplit2[m];
-            pre_b += 8.0 * n * r * (p.nsplit[m] + p.nsplit2[m]);
-            j.part = p.part2[m]; j.nsplit = p.nsplit2[m];
-        }
+        if (p.part2[m]) { j.part = p.part2[m]; j.nsplit = p.nsplit2[m]; }     // the tree's first level has run
         j.P64 = p.P64[m]; j.Uout = U_out[m]; j.mode1 = m + 1; j.info = info;
         j.nblk = p.nblk[m]; j.Gpart = p.Gpart[m]; j.R = p.R[m]; j.Dinv = p.Dinv[m]; j.scal = p.scal[m];
         j.ctr = p.ctr8 + 2 * m;

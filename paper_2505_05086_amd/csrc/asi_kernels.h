@@ -103,6 +103,38 @@ bool make_ttm_kron(DType xt, const void* X, long long cols, int n1, int n2, cons
                    long long ms1_q, int r1, const float* M2, long long ms2_i, long long ms2_q, int r2, float* Y,
                    int beta, Item* out);
 
+struct PresumJob {
+    const double* in;    // (nsplit, cnt)
+    double* out;         // (ngroups, cnt), ngroups = ceil(nsplit / 32)
+    long long cnt;
+    int nsplit, nchunks, ngroups;   // nchunks = ceil(cnt / 256)
+};
+struct PresumArgs {
+    PresumJob job[4];
+    int njobs;
+};
+// device side: workgroup b of the partial-sum tree's first level (groups of 32 splits, fixed order)
+__device__ __forceinline__ void presum_block(const PresumJob* jobs, int njobs, int b) {
+    int j = 0;
+    while (j + 1 < njobs && b >= jobs[j].nchunks * jobs[j].ngroups) { b -= jobs[j].nchunks * jobs[j].ngroups; ++j; }
+    const PresumJob& jb = jobs[j];
+    const int g = b / jb.nchunks, chunk = b - g * jb.nchunks;
+    const long long e = (long long)chunk * 256 + threadIdx.x;
+    if (e >= jb.cnt) return;
+    const int s0 = g * 32;
+    double t[32];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+        const bool ok = s0 + u < jb.nsplit;
+        const double v = jb.in[ok ? (long long)(s0 + u) * jb.cnt + e : 0];
+        t[u] = ok ? v : 0.0;
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int u = 0; u < 32; ++u) s += t[u];
+    jb.out[(long long)g * jb.cnt + e] = s;
+}
+
 // ---- pair: part[s][i][q] = sum_{c in split s} X[i,c] * Y[q,c]  over unfolding columns c = (o,j) -----
 // X: (outer, n, inner) dtype xt;  Y: (outer, r, inner) fp32;  part: (nsplit, n, r) fp64
 // (products of fp32 values are exact in fp64 and the sums are carried in fp64).
@@ -115,10 +147,15 @@ struct PairJob {
     int gx, gy, gz;        // row tiles x output tiles x splits
     int32_t* zero;         // nullable: `nzero` int32 the kernel clears
     int nzero;
+    // independent work that rides along in extra workgroups: the first level of the partial-sum
+    // tree of OTHER modes, whose partial sums are complete before this launch
+    int pre_blocks;
+    PresumArgs pre;
 };
 int pair_splits(long long outer, int n, long long inner, int r);
 bool make_pair(DType xt, const void* X, long long outer, int n, long long inner, const float* Y, int r, double* part,
-               int nsplit, int32_t* zero, int nzero, Item* out);
+               int nsplit, int32_t* zero, int nzero, const PresumArgs* pre, Item* out);
+int presum_blocks(const PresumArgs& a);      // workgroups of the tree's first level, -1 if a is malformed
 
 // ---- out[e] = (beta ? out[e] : 0) + sum_s part[s*count + e] ---------------------------------------------
 struct SumJob {
@@ -167,16 +204,6 @@ struct OrthJob {
 };
 struct OrthArgs {        // the modes of one tensor that share a path
     OrthJob job[4];
-    int njobs;
-};
-struct PresumJob {
-    const double* in;    // (nsplit, cnt)
-    double* out;         // (ngroups, cnt), ngroups = ceil(nsplit / 32)
-    long long cnt;
-    int nsplit, nchunks, ngroups;   // nchunks = ceil(cnt / 256)
-};
-struct PresumArgs {
-    PresumJob job[4];
     int njobs;
 };
 bool make_orth_presum(const PresumArgs& a, Item* out);

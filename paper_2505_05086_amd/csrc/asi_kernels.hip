@@ -33,6 +33,10 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
     double* __restrict__ part = jb.part;
     const long long outer = jb.outer, inner = jb.inner, cols_per_split = jb.cols_per_split;
     const int n = jb.n, r = jb.r;
+    if (lb >= jb.gx * jb.gy * jb.gz) {             // extra workgroups: another mode's partial-sum tree
+        presum_block(jb.pre.job, jb.pre.njobs, lb - jb.gx * jb.gy * jb.gz);
+        return;
+    }
     const int bz = lb / (jb.gx * jb.gy), rem = lb - bz * (jb.gx * jb.gy), by = rem / jb.gx, bx = rem - by * jb.gx;
     const long long ncols = outer * inner;
     const int i0 = bx * PR_TI, q0 = by * PR_TQ, s = bz;
@@ -137,8 +141,20 @@ int pair_splits(long long outer, int n, long long inner, int r) {
     return ns;
 }
 
+int presum_blocks(const PresumArgs& a) {
+    if (a.njobs <= 0 || a.njobs > 4) return -1;
+    long long blocks = 0;
+    for (int j = 0; j < a.njobs; ++j) {
+        const PresumJob& jb = a.job[j];
+        if (!jb.in || !jb.out || jb.cnt <= 0 || jb.nsplit <= 0) return -1;
+        if (jb.nchunks != (int)((jb.cnt + 255) / 256) || jb.ngroups != (jb.nsplit + 31) / 32) return -1;
+        blocks += (long long)jb.nchunks * jb.ngroups;
+    }
+    return blocks > 0x3fffffffLL ? -1 : (int)blocks;
+}
+
 bool make_pair(DType xt, const void* X, long long outer, int n, long long inner, const float* Y, int r, double* part,
-               int nsplit, int32_t* zero, int nzero, Item* out) {
+               int nsplit, int32_t* zero, int nzero, const PresumArgs* pre, Item* out) {
     const long long ncols = outer * inner;
     if (ncols <= 0 || n <= 0 || r <= 0 || nsplit <= 0 || !X || !Y || !part || nzero < 0 || nzero > 256) return false;
     PairJob jb;
@@ -147,10 +163,15 @@ bool make_pair(DType xt, const void* X, long long outer, int n, long long inner,
     jb.Y = Y; jb.part = part; jb.n = n; jb.r = r;
     jb.gx = (n + PR_TI - 1) / PR_TI; jb.gy = (r + PR_TQ - 1) / PR_TQ; jb.gz = nsplit;
     jb.zero = zero; jb.nzero = zero ? nzero : 0;
+    if (pre) {
+        jb.pre_blocks = presum_blocks(*pre);
+        if (jb.pre_blocks < 0) return false;
+        jb.pre = *pre;
+    }
     const bool last = (inner == 1);
     *out = Item();
     out->kind = IT_PAIR; out->key = (xt == BF16 ? 1u : 0u) | (last ? 2u : 0u);
-    out->nblocks = jb.gx * jb.gy * jb.gz;
+    out->nblocks = jb.gx * jb.gy * jb.gz + jb.pre_blocks;
     std::snprintf(out->label, sizeof(out->label), "k_pair<%s, %s>", xt == F32 ? "float" : "asi::bf16_t", last ? "true" : "false");
     static_assert(sizeof(PairJob) <= kItemArgMax, "argument block");
     std::memcpy(out->arg, &jb, sizeof(jb));

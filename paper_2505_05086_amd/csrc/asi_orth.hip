@@ -92,22 +92,7 @@ __device__ void gram_from_lds(const double (*Ps)[OP_LD], int r, double* __restri
 // ---- first level of the partial-sum tree -----------------------------------------------------
 // When a mode arrives with more than 32 split partial sums, groups of 32 are added first
 // (fixed order inside a group), so that no workgroup of gram0 has to walk hundreds of them.
-__global__ __launch_bounds__(256) void k_orth_presum(PresumBatch a) {
-    int j = 0, b = blockIdx.x;
-    while (j + 1 < a.njobs && b >= a.job[j].nchunks * a.job[j].ngroups) { b -= a.job[j].nchunks * a.job[j].ngroups; ++j; }
-    const PresumJob jb = a.job[j];
-    const int g = b / jb.nchunks, chunk = b - g * jb.nchunks;
-    const long long e = (long long)chunk * 256 + threadIdx.x;
-    if (e >= jb.cnt) return;
-    const int s0 = g * 32;
-    double t[32];
-#pragma unroll
-    for (int u = 0; u < 32; ++u) t[u] = ldg_f64(jb.in, (long long)(s0 + u) * jb.cnt + e, s0 + u < jb.nsplit);
-    double s = 0.0;
-#pragma unroll
-    for (int u = 0; u < 32; ++u) s += t[u];
-    jb.out[(long long)g * jb.cnt + e] = s;
-}
+__global__ __launch_bounds__(256) void k_orth_presum(PresumBatch a) { presum_block(a.job, a.njobs, blockIdx.x); }
 
 // ---- chol -----------------------------------------------------------------------------------
 __device__ __forceinline__ double bcast_lane(double x, int src) {      // src uniform
@@ -976,17 +961,10 @@ static bool wide_args_ok(const OrthArgs& a) {
 }
 
 bool make_orth_presum(const PresumArgs& a, Item* out) {
-    if (a.njobs <= 0 || a.njobs > 4) return false;
-    long long blocks = 0;
-    for (int j = 0; j < a.njobs; ++j) {
-        const PresumJob& jb = a.job[j];
-        if (!jb.in || !jb.out || jb.cnt <= 0 || jb.nsplit <= 0) return false;
-        if (jb.nchunks != (int)((jb.cnt + 255) / 256) || jb.ngroups != (jb.nsplit + 31) / 32) return false;
-        blocks += (long long)jb.nchunks * jb.ngroups;
-    }
-    if (blocks > 0x3fffffffLL) return false;
+    const int blocks = presum_blocks(a);
+    if (blocks <= 0) return false;
     *out = Item();
-    out->kind = IT_PRESUM; out->nblocks = (int)blocks;
+    out->kind = IT_PRESUM; out->nblocks = blocks;
     std::snprintf(out->label, sizeof(out->label), "k_orth_presum");
     std::memcpy(out->arg, &a, sizeof(a));
     return true;
