@@ -580,6 +580,13 @@ asi_status build_conv(const asi_tensor_desc* desc, const float* S, const float* 
     if (!p.Z1) {
         // 2+3. Z = S x_3 U3 x_4 U4 in one pass:  M(a*r4 + b, h*W + w) = U3[h,a] * U4[w,b]   (r1, r2, H, W)
         ASI_TRYS(add_ttm_kron(pg, "Z", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, U[3], 1, r4, g.W, p.Z));
+        // G1 and Z do not depend on each other: one launch for both when their kernels allow it
+        Item duo;
+        const size_t ni = pg.items.size();
+        if (make_ttm_duo(pg.items[ni - 2], pg.items[ni - 1], &duo)) {
+            pg.items.pop_back();
+            pg.items.back() = duo;
+        }
     } else {
         // 2. Z1 = S x_3 U3                                        (r1, r2, H, r4)
         ASI_TRYS(add_ttm(pg, "Z1", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0));

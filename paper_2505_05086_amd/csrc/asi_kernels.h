@@ -19,7 +19,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
-    IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY
+    IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO
 };
 
 struct Item {
@@ -135,6 +135,11 @@ __device__ __forceinline__ void presum_block(const PresumJob* jobs, int njobs, i
     jb.out[(long long)g * jb.cnt + e] = s;
 }
 
+// One launch for two independent products made by make_ttm / make_ttm_kron (tagged with role, bytes, flops):
+// a plain tiled product not along the last mode, and a small merged (Kronecker) product.  Returns false
+// if the items do not have these forms.
+bool make_ttm_duo(const Item& a, const Item& z, Item* out);
+
 // ---- pair: part[s][i][q] = sum_{c in split s} X[i,c] * Y[q,c]  over unfolding columns c = (o,j) -----
 // X: (outer, n, inner) dtype xt;  Y: (outer, r, inner) fp32;  part: (nsplit, n, r) fp64
 // (products of fp32 values are exact in fp64 and the sums are carried in fp64).
@@ -245,6 +250,7 @@ bool make_expand_grouped(const float* T, const float* U2, float* dW, int cout, i
 
 // per-kind batch launchers (called by launch_items)
 hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, char* label_out);
+hipError_t launch_ttm_duo_items(const Item* const* items, int n, hipStream_t st, char* label_out);
 hipError_t launch_pair_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_sum_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_expand_items(const Item* const* items, int n, hipStream_t st);

@@ -288,6 +288,7 @@ hipError_t launch_expand_items(const Item* const* items, int n, hipStream_t st) 
 // key bits of the mode-product kernels that only bound sizes (see asi_ttm.hip): NBR, KS
 static unsigned launch_class(const Item& it) {
     if (it.kind == IT_TTM || it.kind == IT_KSPLIT) return it.key & 0x600fu;
+    if (it.kind == IT_TTM_DUO) return it.key & 0xfu;
     return it.key;
 }
 bool same_launch(const Item& a, const Item& b) {
@@ -301,6 +302,7 @@ hipError_t launch_items(const Item* const* items, int n, hipStream_t st, char* l
     if (label_out) std::snprintf(label_out, 96, "%s", items[0]->label);
     switch (items[0]->kind) {
         case IT_TTM: case IT_KSPLIT: return launch_ttm_items(items, n, st, label_out);
+        case IT_TTM_DUO: return launch_ttm_duo_items(items, n, st, label_out);
         case IT_PAIR: return launch_pair_items(items, n, st);
         case IT_SUM_F32: case IT_SUM_F64: return launch_sum_items(items, n, st);
         case IT_EXPAND: return launch_expand_items(items, n, st);

@@ -31,17 +31,17 @@ constexpr int TM_KCMAX = 64;
 
 // KM: 0 = plain matrix, 1 = Kronecker product, 2 = Kronecker product with K chunks of 64 (long merged
 // modes with few columns; otherwise chunks of 32, which overlap across workgroups)
+constexpr int TM_SMEM = 2 * TM_KCMAX * TM_LD;   // floats: Xs | Ms during the K loop, Ys (64 x TM_LD) afterwards
+
+// one tile (workgroup lb of job jb); smem holds TM_SMEM floats
 template <typename T, bool LASTMODE, int NBR, int KM>
-__global__ __launch_bounds__(256) void k_ttm_mfma(Batch<TtmJob> bt) {
+__device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) {
     constexpr bool KRON = KM != 0;
     constexpr int TM_KC = KM == 2 ? 64 : 32;
     constexpr int TM_LR = TM_KC / 4;      // loads per thread and operand for one chunk
-    __shared__ float smem[2 * TM_KCMAX * TM_LD];    // Xs | Ms during the K loop, Ys (64 x TM_LD) afterwards
     float (*Xs)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem);
     float (*Ms)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem + TM_KCMAX * TM_LD);
     float (*Ys)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem);
-    int lb;
-    const TtmJob& jb = bt.job[locate(bt, &lb)];
     const T* __restrict__ X = static_cast<const T*>(jb.X);
     const float* __restrict__ Mp = jb.Mp;
     float* __restrict__ Y = jb.Y;
@@ -172,6 +172,30 @@ __global__ __launch_bounds__(256) void k_ttm_mfma(Batch<TtmJob> bt) {
             }
         }
     }
+}
+
+template <typename T, bool LASTMODE, int NBR, int KM>
+__global__ __launch_bounds__(256) void k_ttm_mfma(Batch<TtmJob> bt) {
+    __shared__ float smem[TM_SMEM];
+    int lb;
+    const TtmJob& jb = bt.job[locate(bt, &lb)];
+    ttm_tile<T, LASTMODE, NBR, KM>(jb, lb, smem);
+}
+
+// Two independent products in one launch: a plain product along a leading mode (G1 = grad_out x_1 U1^T
+// of Eq. 14) and, in extra workgroups, a small merged product of fp32 data (Z = S x_3 U3 x_4 U4).
+struct TtmDuoJob {
+    TtmJob a;        // dtype T, not the last mode, plain matrix, NBR column blocks
+    TtmJob z;        // fp32, trailing modes merged by a Kronecker product, K chunks of 32
+    int a_blocks;
+};
+template <typename T, int NBR>
+__global__ __launch_bounds__(256) void k_ttm_duo(Batch<TtmDuoJob> bt) {
+    __shared__ float smem[TM_SMEM];
+    int lb;
+    const TtmDuoJob& jb = bt.job[locate(bt, &lb)];
+    if (lb < jb.a_blocks) ttm_tile<T, false, NBR, 0>(jb.a, lb, smem);
+    else ttm_tile<float, true, 4, 1>(jb.z, lb - jb.a_blocks, smem);
 }
 
 // ---- long fibres, few columns ------------------------------------------------------------------
@@ -346,6 +370,54 @@ static void launch_split(int ks, bool wide, const Batch<TtmJob>& b, dim3 grid, h
         else if (ks == 8) hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 8, 1>), grid, 256, 0, st, b);
         else hipLaunchKernelGGL((k_ttm_ksplit<T, NBR, 16, 1>), grid, 256, 0, st, b);
     }
+}
+
+// a: a tiled plain product that is not along the last mode; z: a Kronecker product with short K.
+// Fails (and leaves *out alone) if the two do not have these forms; the caller then launches them apart.
+bool make_ttm_duo(const Item& a, const Item& z, Item* out) {
+    if (a.kind != IT_TTM || z.kind != IT_TTM) return false;
+    if ((a.key & 0x600eu) != 0u) return false;                 // not last mode, plain, tiled, chunks of 32
+    if ((z.key & 0x600fu) != (2u | 4u)) return false;          // fp32, last mode, Kronecker, tiled, chunks of 32
+    TtmDuoJob jb;
+    std::memcpy(&jb.a, a.arg, sizeof(TtmJob));
+    std::memcpy(&jb.z, z.arg, sizeof(TtmJob));
+    jb.a_blocks = a.nblocks;
+    if ((long long)a.nblocks + z.nblocks > 0x3fffffffLL) return false;
+    const int nbr = (int)((a.key >> 4) & 7u) + 1;
+    Item it;
+    it.kind = IT_TTM_DUO;
+    it.key = (a.key & 1u) | ((unsigned)(nbr - 1) << 4);
+    it.nblocks = a.nblocks + z.nblocks;
+    std::snprintf(it.label, sizeof(it.label), "k_ttm_duo<%s, %d>", (a.key & 1u) ? "asi::bf16_t" : "float", nbr);
+    std::snprintf(it.role, sizeof(it.role), "%s+%s", a.role, z.role);
+    it.bytes = a.bytes + z.bytes; it.flops = a.flops + z.flops;
+    static_assert(sizeof(TtmDuoJob) <= kItemArgMax, "argument block");
+    std::memcpy(it.arg, &jb, sizeof(jb));
+    *out = it;
+    return true;
+}
+
+hipError_t launch_ttm_duo_items(const Item* const* items, int n, hipStream_t st, char* label_out) {
+    Batch<TtmDuoJob> b;
+    dim3 grid;
+    if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
+    const bool bf16 = items[0]->key & 1u;
+    int nbr = 1;
+    for (int j = 0; j < n; ++j) {
+        const int nj = (int)((items[j]->key >> 4) & 7u) + 1;
+        nbr = nj > nbr ? nj : nbr;
+    }
+    if (label_out) std::snprintf(label_out, 96, "k_ttm_duo<%s, %d>", bf16 ? "asi::bf16_t" : "float", nbr);
+#define ASI_DUO(TT)                                                                              \
+    switch (nbr) {                                                                               \
+        case 1: hipLaunchKernelGGL((k_ttm_duo<TT, 1>), grid, 256, 0, st, b); break;              \
+        case 2: hipLaunchKernelGGL((k_ttm_duo<TT, 2>), grid, 256, 0, st, b); break;              \
+        case 3: hipLaunchKernelGGL((k_ttm_duo<TT, 3>), grid, 256, 0, st, b); break;              \
+        default: hipLaunchKernelGGL((k_ttm_duo<TT, 4>), grid, 256, 0, st, b); break;             \
+    }
+    if (!bf16) { ASI_DUO(float) } else { ASI_DUO(bf16_t) }
+#undef ASI_DUO
+    return hipGetLastError();
 }
 
 hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, char* label_out) {
