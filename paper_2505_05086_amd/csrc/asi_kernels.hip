@@ -133,7 +133,7 @@ int pair_splits(long long outer, int n, long long inner, int r) {
     long long want = 512 / (tiles > 0 ? tiles : 1);           // aim at ~512 workgroups
     const long long maxs = (ncols + 255) / 256;               // at least 256 columns per split
     if (want > maxs) want = maxs;
-    if (want > 64) want = 64;
+    if (want > 32) want = 32;                                 // what the Gram kernel sums without a tree level
     if (want < 1) want = 1;
     // no empty split: shrink until the last split starts inside the column range
     int ns = (int)want;

@@ -70,6 +70,10 @@ __device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) 
         l_i = tid & (TM_KC - 1); l_c = tid / TM_KC;   // columns l_c + (256 / TM_KC) t
     }
     const int m_q = tid & 63, m_i = tid >> 6;        // Ms loader: rows m_i + 4t
+    // a matrix stored with the mode index contiguous (the transposed factor of step 5 of Eq. 14) is
+    // loaded with the lanes along that index instead: row tid % KC, outputs tid / KC + (256 / KC) t
+    const bool m_tr = !KRON && ms_i == 1 && ms_q != 1;
+    const int t_i = tid & (TM_KC - 1), t_q = tid / TM_KC;
 
     // Kronecker indices by a rounded float quotient: exact for arguments below 2^14 (checked on the host)
     const float inv_n2 = 1.0f / (float)kr.n2, inv_r2 = 1.0f / (float)kr.r2;
@@ -87,10 +91,15 @@ __device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) 
                 xr[t] = ldg_f32(X, c * (long long)n + i, c < ncols && cl < tcols && i < n);
             }
             const int i = k0 + m_i + 4 * t, q = q0 + m_q;
-            if (k0 + 4 * t >= n) {
+            if (k0 + 4 * t >= n && !m_tr) {
                 mr[t] = 0.f;                          // uniform: the chunk ends before this row group
             } else if (!KRON) {
-                mr[t] = ldg_f32(Mp, (long long)i * ms_i + (long long)q * ms_q, i < n && q < r);
+                if (m_tr) {
+                    const int it = k0 + t_i, qt = q0 + t_q + (256 / TM_KC) * t;
+                    mr[t] = ldg_f32(Mp, (long long)it + (long long)qt * ms_q, it < n && qt < r);
+                } else {
+                    mr[t] = ldg_f32(Mp, (long long)i * ms_i + (long long)q * ms_q, i < n && q < r);
+                }
             } else {
                 const int i1 = (int)(((float)i + 0.5f) * inv_n2), i2 = i - i1 * kr.n2;
                 const int q1 = (int)(((float)q + 0.5f) * inv_r2), q2 = q - q1 * kr.r2;
@@ -105,7 +114,8 @@ __device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) 
         for (int t = 0; t < TM_LR; ++t) {
             if (!LASTMODE) Xs[l_i + 4 * t][l_c] = xr[t];
             else Xs[l_i][l_c + (256 / TM_KC) * t] = xr[t];
-            Ms[m_i + 4 * t][m_q] = mr[t];
+            if (m_tr) Ms[t_i][t_q + (256 / TM_KC) * t] = mr[t];
+            else Ms[m_i + 4 * t][m_q] = mr[t];
         }
     };
 
