@@ -133,21 +133,35 @@ __device__ void chol_block16(double (*Gs)[OP_LD], double (*rowbuf)[64][4], doubl
     int bad = *bad_io;
     double f[4];
     BSTAMP(21);
+    // Panel K0..K0+3.  Its 4x4 diagonal block (10 values, fetched from their lanes in one go) is
+    // factored redundantly by every lane, which keeps the cross-lane traffic off the chain of
+    // reciprocals; each lane then applies the multipliers to its own four row entries.
+    // F[kk] = (row K0+kk of this lane's column) / pivot.
 #define ASI_CHOL_PANEL(K0, F)                                                                       \
     {                                                                                               \
+        double a_[4][4], pi_[4], m_[4][4];                                                          \
+        _Pragma("unroll") for (int kk = 0; kk < 4; ++kk)                                            \
+            _Pragma("unroll") for (int k2 = kk; k2 < 4; ++k2) a_[kk][k2] = bcast_lane(col[(K0) + kk], (K0) + k2); \
         _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                          \
-            const int k = (K0) + kk;                                                                \
-            double p = bcast_lane(col[k], k);                                                       \
+            double p = a_[kk][kk];                                                                  \
             const bool okp = p > 0.0;                /* false for zero, negative, NaN */            \
-            bad = (!okp && bad == 0) ? base + k + 1 : bad;                                          \
+            bad = (!okp && bad == 0) ? base + (K0) + kk + 1 : bad;                                  \
             p = okp ? p : 1.0;                                                                      \
             double pinv = __builtin_amdgcn_rcp(p);                                                  \
             pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);   /* two Newton steps: full accuracy */     \
             pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);                                             \
-            F[kk] = col[k] * pinv;                                                                  \
-            _Pragma("unroll") for (int a2 = k + 1; a2 < (K0) + 4; ++a2)                             \
-                col[a2] = fma(-bcast_lane(col[a2], k), F[kk], col[a2]);                             \
-            if (j == k) { col[k] = p; pinvs[base + k] = pinv; }   /* the pivot actually used */     \
+            pi_[kk] = pinv;                                                                         \
+            a_[kk][kk] = p;                          /* the pivot actually used */                  \
+            _Pragma("unroll") for (int k2 = kk + 1; k2 < 4; ++k2) m_[kk][k2] = a_[kk][k2] * pinv;   \
+            _Pragma("unroll") for (int k2 = kk + 1; k2 < 4; ++k2)                                   \
+                _Pragma("unroll") for (int k3 = k2; k3 < 4; ++k3) a_[k2][k3] = fma(-m_[kk][k2], a_[kk][k3], a_[k2][k3]); \
+        }                                                                                           \
+        _Pragma("unroll") for (int k2 = 1; k2 < 4; ++k2)                                            \
+            _Pragma("unroll") for (int kk = 0; kk < k2; ++kk)                                       \
+                col[(K0) + k2] = fma(-m_[kk][k2], col[(K0) + kk], col[(K0) + k2]);                  \
+        _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                          \
+            F[kk] = col[(K0) + kk] * pi_[kk];                                                       \
+            if (j == (K0) + kk) { col[(K0) + kk] = a_[kk][kk]; pinvs[base + (K0) + kk] = pi_[kk]; } \
         }                                                                                           \
     }
 #define ASI_CHOL_UPDATE(A_LO, A_HI, RB)                                                             \
@@ -179,14 +193,13 @@ __device__ void chol_block16(double (*Gs)[OP_LD], double (*rowbuf)[64][4], doubl
 #undef ASI_CHOL_UPDATE
     BSTAMP(26);
     *bad_io = bad;
-    if (xl) {
+    // lanes 0..15 write their column of the block (entries below the diagonal are never read again),
+    // lanes 48..63 their row of the inverse factor: one run of stores for both
+    if (j < 16 || xl) {
+        double* dst = xl ? &Xb[j - 48][0] : &Gs[base][base + j];
+        const int step = xl ? 1 : OP_LD;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) Xb[j - 48][q] = col[q];
-    }
-    if (j < 16) {
-#pragma unroll
-        for (int k = 0; k < 16; ++k)
-            if (k <= j) Gs[base + k][base + j] = col[k];
+        for (int k = 0; k < 16; ++k) dst[k * step] = col[k];
     }
     BSTAMP(27);
 }
