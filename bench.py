@@ -22,10 +22,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # published dense peaks of the units each kernel uses (TFLOP/s); "mfma_f32+f64" is the harmonic
 # mean for a kernel whose flops are half fp32 MFMA (V = A_m^T U) and half fp64 MFMA (P = A_m V)
-PEAK_TFLOPS = {"mfma_f32": 157.3, "mfma_f64": 78.6, "mfma_bf16": 2500.0, "valu_f32": 78.6, "valu_f64": 78.6,
-               "mfma_f32+f64": 2.0 / (1.0 / 157.3 + 1.0 / 78.6)}
+PEAK_TFLOPS = {"mfma_f32": 157.3, "mfma_f64": 78.6, "mfma_bf16": 2500.0, "valu_f32": 157.3, "valu_f64": 78.6,
+               "mfma_f32+f64": 2.0 / (1.0 / 157.3 + 1.0 / 78.6), "valu_f32+f64": 2.0 / (1.0 / 157.3 + 1.0 / 78.6)}
 # which arithmetic unit each kernel symbol runs its contraction on
-KERNEL_UNIT = {"k_subspace_small": "mfma_f32+f64", "k_ttm_mfma": "mfma_f32", "k_pair": "mfma_f64",
+KERNEL_UNIT = {"k_subspace_small": "mfma_f32+f64", "k_subspace_tiny": "valu_f32+f64", "k_ttm_mfma": "mfma_f32",
+               "k_ttm_ksplit": "mfma_f32", "k_ttm_duo": "mfma_f32", "k_pair": "mfma_f64",
                "k_corr_mfma": "mfma_f32", "k_corr": "valu_f32",
                "k_orth_gram0": "mfma_f64", "k_orth_apply": "mfma_f64", "k_orth_chol": "valu_f64",
                "k_orthw_gram": "mfma_f64", "k_orthw_apply": "mfma_f64", "k_orthw_chol": "valu_f64",

@@ -256,7 +256,7 @@ hipError_t launch_sum_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_expand_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_small_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st);
-hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st, char* label_out);
 hipError_t launch_corr_items(const Item* const* items, int n, hipStream_t st);
 
 }  // namespace asi

@@ -1023,7 +1023,7 @@ bool make_init_ctrl(int32_t* info, Item* out) {
     return true;
 }
 
-hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st) {
+hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st, char* label_out) {
     if (n <= 0 || n > kMaxBatch) return hipErrorInvalidValue;
     const int kind = items[0]->kind, aux = items[0]->aux;
     if (kind == IT_INIT) {
@@ -1061,6 +1061,8 @@ hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st) {
         }
     }
     const int rm = rmax <= 16 ? 16 : (rmax <= 32 ? 32 : (rmax <= 48 ? 48 : 64));   // register shape of the fast kernels
+    if (label_out && (kind == IT_GRAM0 || kind == IT_APPLY))
+        std::snprintf(label_out, 96, "%s<%d>", kind == IT_GRAM0 ? "k_orth_gram0" : "k_orth_apply", rm);
     switch (kind) {
         case IT_GRAM0:
             if (rm == 16) hipLaunchKernelGGL(k_orth_gram0<16>, grid, 256, 0, st, b);
