@@ -247,7 +247,8 @@ def main():
     asi.asi_profile_enable(False)
     per_kernel = {}
     for site, v in rep.items():
-        sym = site.split(":")[0]
+        cut = site.rfind(":")             # "instantiation:role"; the instantiation itself may hold "::"
+        sym = site[:cut] if cut > 0 and site[cut - 1] != ":" and ">" not in site[cut:] else site
         a = per_kernel.setdefault(sym, {"launches": 0, "ms": 0.0, "bytes": 0.0, "flops": 0.0})
         for key in a:
             a[key] += v[key]
