@@ -120,7 +120,7 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
             p.Gpart[m] = c.take<double>((size_t)p.nblk[m] * r * r);
             p.R[m] = c.take<double>(r * r);
             p.Dinv[m] = c.take<double>(((r + 15) / 16) * 256);
-            p.scal[m] = c.take<double>(66);
+            p.scal[m] = c.take<double>(68);
         } else if (orth_wide_supported((int)r)) {
             p.wide_orth[m] = true;
             p.nblk[m] = orth_wide_gram_blocks((int)n);

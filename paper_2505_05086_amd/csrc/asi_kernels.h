@@ -199,7 +199,7 @@ struct OrthJob {
     double* Gpart;       // (nblk, r (r+1) / 2) packed slice Gram matrices; slow path: (r, r) Gram matrix
     double* R;           // (r, r)
     double* Dinv;        // (ceil(r/16), 16, 16) inverses of R's diagonal blocks
-    double* scal;        // 66 doubles of bookkeeping (wide path: 2 + 192)
+    double* scal;        // 68 doubles of bookkeeping (wide path: 2 + 192)
     int32_t* ctr;        // 2 arrival counters, zero before the first orth launch of a call
     int nsplit;
     int n, r;

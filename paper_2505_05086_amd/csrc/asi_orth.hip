@@ -31,6 +31,7 @@ constexpr int OP_RS = 32;              // rows per slice
 constexpr int OP_RMAX = 64;
 constexpr int OP_LD = OP_RMAX + 1;
 constexpr double OP_EPS = 1.1102230246251565e-16;
+constexpr double OP_DONE_TOL = 1e-7;   // |Q0^T Q0 - I| below which the first pass is the result
 
 #ifdef ASI_DEBUG_TIMING
 __device__ long long g_orth_stamps[64];
@@ -209,7 +210,7 @@ __device__ void chol_block16(double (*Gs)[OP_LD], double (*rowbuf)[64][4], doubl
 // wave 0 factors a diagonal block, then the four waves solve that block row and update the
 // trailing blocks with fp64 MFMA.  Writes R, the inverses of R's diagonal blocks and the
 // bookkeeping in scal; with `last` it reports a rank-deficient P through *info.  scal[0] = trace(P^T P), scal[1 + k] = running product of the
-// R diagonals, scal[65] = first bad pivot.
+// R diagonals, scal[65] = first bad pivot, scal[66] = 1 when the first pass needed no second.
 struct CholSmem {
     double Gs[OP_RMAX][OP_LD];
     double dinv[OP_RMAX];
@@ -235,8 +236,6 @@ __device__ void chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     const int nb = (r + 15) / 16;
     STAMP(0);
-    // identity everywhere first, so that the padding up to a multiple of 16 needs no special case
-    for (int e = tid; e < OP_RMAX * 64; e += 256) Gs[e >> 6][e & 63] = ((e >> 6) == (e & 63)) ? 1.0 : 0.0;
     // sum of the slice Grams (packed upper triangles): ITS elements per thread, SB slices per
     // round, all ITS * SB loads of a round in flight together
     constexpr int ITS = (RM * (RM + 1) / 2 + 255) / 256;
@@ -259,82 +258,140 @@ __device__ void chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
 #pragma unroll
             for (int it = 0; it < ITS; ++it) sum[it] += t[u][it];
     }
-    __syncthreads();
+    // Gs = the summed Gram matrix, padded with the identity up to a multiple of 16
+    auto scatter = [&]() {
+        __syncthreads();
+        for (int e = tid; e < OP_RMAX * 64; e += 256) Gs[e >> 6][e & 63] = ((e >> 6) == (e & 63)) ? 1.0 : 0.0;
+        __syncthreads();
 #pragma unroll
-    for (int it = 0; it < ITS; ++it) {
-        const int e = tid + 256 * it;
-        if (e < T) {
-            // row ga of the packed triangle: largest ga with tri_idx(r, ga, ga) <= e
-            int ga = (int)(((2 * r + 1) - sqrtf((float)((2 * r + 1) * (2 * r + 1) - 8 * e))) * 0.5f);
-            ga = ga < 0 ? 0 : (ga > r - 1 ? r - 1 : ga);
-            while (ga > 0 && tri_idx(r, ga, ga) > e) --ga;
-            while (ga + 1 < r && tri_idx(r, ga + 1, ga + 1) <= e) ++ga;
-            const int gb = ga + (e - tri_idx(r, ga, ga));
-            Gs[ga][gb] = sum[it];
-            Gs[gb][ga] = sum[it];
+        for (int it = 0; it < ITS; ++it) {
+            const int e = tid + 256 * it;
+            if (e < T) {
+                // row ga of the packed triangle: largest ga with tri_idx(r, ga, ga) <= e
+                int ga = (int)(((2 * r + 1) - sqrtf((float)((2 * r + 1) * (2 * r + 1) - 8 * e))) * 0.5f);
+                ga = ga < 0 ? 0 : (ga > r - 1 ? r - 1 : ga);
+                while (ga > 0 && tri_idx(r, ga, ga) > e) --ga;
+                while (ga + 1 < r && tri_idx(r, ga + 1, ga + 1) <= e) ++ga;
+                const int gb = ga + (e - tri_idx(r, ga, ga));
+                Gs[ga][gb] = sum[it];
+                Gs[gb][ga] = sum[it];
+            }
         }
-    }
-    __syncthreads();
+        __syncthreads();
+    };
+    scatter();
     STAMP(1);
     int bad = 0;
-    if (wave == 0) {
-        // trace and diagonal shift (first pass)
-        if (pass == 0) {
+    // blocked right-looking factorisation of Gs in place
+    auto factor = [&]() {
+        for (int P = 0; P < nb; ++P) {
+    #ifdef ASI_DEBUG_TIMING
+            if (wave == 0) chol_block16(Gs, rowbuf, Xs[P], pinvs, 16 * P, &bad, P == 0 && jb.mode1 == 2 && pass == 0);
+    #else
+            if (wave == 0) chol_block16(Gs, rowbuf, Xs[P], pinvs, 16 * P, &bad);
+    #endif
+            if (P == 0) STAMP(6);
+            __syncthreads();
+            if (P == 0) STAMP(7);
+            if (P + 1 < nb) {
+                // block row P right of the diagonal:  U_PJ = L_PP^-1 G_PJ   (unscaled rows, like the diagonal block)
+                for (int J = P + 1 + wave; J < nb; J += 4) {
+                    double bv[4];
+    #pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) bv[ks] = Gs[16 * P + 4 * ks + lg][16 * J + ll];
+                    v4d acc = {0.0, 0.0, 0.0, 0.0};
+    #pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)      // A[i][k] = (L^-1)[i][k] = Xs[P][k][i]
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Xs[P][4 * ks + lg][ll], bv[ks], acc, 0, 0, 0);
+    #pragma unroll
+                    for (int v = 0; v < 4; ++v) Gs[16 * P + lg + 4 * v][16 * J + ll] = acc[v];
+                }
+                __syncthreads();
+                if (P == 0) STAMP(8);
+                // trailing blocks:  G_IJ -= U_PI^T diag(1/pivot) U_PJ,  P < I <= J
+                int cnt = 0;
+                for (int I = P + 1; I < nb; ++I)
+                    for (int J = I; J < nb; ++J, ++cnt) {
+                        if ((cnt & 3) != wave) continue;
+                        v4d acc;
+    #pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[v] = Gs[16 * I + lg + 4 * v][16 * J + ll];
+    #pragma unroll
+                        for (int ks = 0; ks < 4; ++ks) {
+                            const int k = 16 * P + 4 * ks + lg;
+                            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-Gs[k][16 * I + ll], Gs[k][16 * J + ll] * pinvs[k], acc, 0, 0, 0);
+                        }
+    #pragma unroll
+                        for (int v = 0; v < 4; ++v) Gs[16 * I + lg + 4 * v][16 * J + ll] = acc[v];
+                    }
+                __syncthreads();
+                if (P == 0) STAMP(9);
+            }
+        }
+    };
+    if (pass == 1) {
+        // Q0 may already be orthonormal to working accuracy (a warm-started, well-conditioned P): then
+        // the second pass would only reproduce the identity, and the fp32 copy of Q0 that the solve
+        // has written is the result.
+        double dev = 0.0;
+        for (int e = tid; e < r * r; e += 256) {
+            const int ga = e / r, gb = e - ga * r;
+            dev = fmax(dev, fabs(Gs[ga][gb] - (ga == gb ? 1.0 : 0.0)));
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) dev = fmax(dev, __shfl_xor(dev, m));
+        if (lane == 0) rdiag[wave] = dev;
+        __syncthreads();
+        dev = fmax(fmax(rdiag[0], rdiag[1]), fmax(rdiag[2], rdiag[3]));
+        __syncthreads();
+        const bool done = dev <= OP_DONE_TOL;
+        if (tid == 0) jb.scal[66] = done ? 1.0 : 0.0;
+        if (done) {
+            if (tid < 64) {
+                const double floor_ = 1e-12 * sqrt(jb.scal[0]);
+                const bool low = tid < r && !(jb.scal[1 + tid] > floor_);
+                const unsigned long long mask = __ballot(low);
+                if (tid == 0 && last && info) {
+                    const double badv = jb.scal[65];
+                    if (badv != 0.0) flag_info(info, jb.mode1, (int)badv);
+                    if (mask) flag_info(info, jb.mode1, __ffsll((long long)mask));
+                }
+            }
+            return;
+        }
+        if (tid == 0) s_trace = jb.scal[0];
+        factor();
+    } else {
+        // First pass.  Plain Cholesky first; if a pivot is lost (non-positive, or below 1e-12 of its
+        // diagonal entry: cond(P) beyond ~1e6) the factorisation is redone with the diagonal shift
+        // that makes it safe up to cond(P) ~ 1e9.
+        double tr = 0.0;
+        if (wave == 0) {
             const double g = (lane < r) ? Gs[lane][lane] : 0.0;
-            double tr = g;
+            tr = g;
 #pragma unroll
             for (int m = 32; m >= 1; m >>= 1) tr += __shfl_xor(tr, m);
             if (lane == 0) { s_trace = tr; jb.scal[0] = tr; }
-            const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * tr;
-            if (lane < r) Gs[lane][lane] = g + shift;
-        } else if (lane == 0) {
-            s_trace = jb.scal[0];
+            if (lane < r) rdiag[lane] = g;                  // the diagonal before elimination
         }
-    }
-    STAMP(2);
-    for (int P = 0; P < nb; ++P) {
-#ifdef ASI_DEBUG_TIMING
-        if (wave == 0) chol_block16(Gs, rowbuf, Xs[P], pinvs, 16 * P, &bad, P == 0 && jb.mode1 == 2 && pass == 0);
-#else
-        if (wave == 0) chol_block16(Gs, rowbuf, Xs[P], pinvs, 16 * P, &bad);
-#endif
-        if (P == 0) STAMP(6);
+        STAMP(2);
+        factor();
+        if (wave == 0) {
+            const bool lost = lane < r && !(Gs[lane][lane] > 1e-12 * rdiag[lane]);
+            const unsigned long long mask = __ballot(lost);
+            if (lane == 0) s_bad = (bad != 0 || mask != 0) ? 1 : 0;
+        }
         __syncthreads();
-        if (P == 0) STAMP(7);
-        if (P + 1 < nb) {
-            // block row P right of the diagonal:  U_PJ = L_PP^-1 G_PJ   (unscaled rows, like the diagonal block)
-            for (int J = P + 1 + wave; J < nb; J += 4) {
-                double bv[4];
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) bv[ks] = Gs[16 * P + 4 * ks + lg][16 * J + ll];
-                v4d acc = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)      // A[i][k] = (L^-1)[i][k] = Xs[P][k][i]
-                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Xs[P][4 * ks + lg][ll], bv[ks], acc, 0, 0, 0);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) Gs[16 * P + lg + 4 * v][16 * J + ll] = acc[v];
+        if (s_bad) {
+            scatter();
+            bad = 0;
+            if (wave == 0) {
+                const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * tr;
+                if (lane < r) Gs[lane][lane] += shift;
             }
-            __syncthreads();
-            if (P == 0) STAMP(8);
-            // trailing blocks:  G_IJ -= U_PI^T diag(1/pivot) U_PJ,  P < I <= J
-            int cnt = 0;
-            for (int I = P + 1; I < nb; ++I)
-                for (int J = I; J < nb; ++J, ++cnt) {
-                    if ((cnt & 3) != wave) continue;
-                    v4d acc;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[v] = Gs[16 * I + lg + 4 * v][16 * J + ll];
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) {
-                        const int k = 16 * P + 4 * ks + lg;
-                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-Gs[k][16 * I + ll], Gs[k][16 * J + ll] * pinvs[k], acc, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) Gs[16 * I + lg + 4 * v][16 * J + ll] = acc[v];
-                }
-            __syncthreads();
-            if (P == 0) STAMP(9);
+            factor();
         }
+        __syncthreads();
     }
     if (tid == 0) s_bad = bad;
     STAMP(3);
@@ -498,6 +555,8 @@ __global__ __launch_bounds__(256) void k_orth_apply(OrthBatch a, int final_pass)
     int ji, blk;
     find_job(a, &ji, &blk);
     const OrthJob jb = a.job[ji];
+    // the first pass was found to be orthonormal already: its fp32 copy is the result
+    if (final_pass && jb.scal[66] != 0.0) return;
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     const int nb = (r + 15) / 16;
@@ -571,7 +630,11 @@ __global__ __launch_bounds__(256) void k_orth_apply(OrthBatch a, int final_pass)
     if (final_pass) {
         for (int idx = tid; idx < nrows * r; idx += 256) jb.Uout[(long long)i0 * r + idx] = (float)Ps[idx / r][idx % r];
     } else {
-        for (int idx = tid; idx < nrows * r; idx += 256) jb.P64[(long long)i0 * r + idx] = Ps[idx / r][idx % r];
+        for (int idx = tid; idx < nrows * r; idx += 256) {
+            const double q0 = Ps[idx / r][idx % r];
+            jb.P64[(long long)i0 * r + idx] = q0;
+            jb.Uout[(long long)i0 * r + idx] = (float)q0;
+        }
         gram_from_lds(Ps, r, jb.Gpart + (long long)blk * ((r * (r + 1)) / 2));
         // the workgroup that finishes a mode's last slice factors the Gram matrix of Q0
         if (!last_arrival(jb.ctr + 1, jb.nblk, &s_last)) return;
