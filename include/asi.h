@@ -169,7 +169,7 @@ int32_t asi_version(void);
  * bytes and flops that step must move / compute by its definition.  Returns the previous
  * setting.
  * asi_profile_report(buf, buflen): waits for the recorded events and writes one text
- * line per launch site, "site,launches,total_ms,total_bytes,total_flops\n" (site may itself contain commas), NUL-terminated
+ * line per launch site, "site,launches,total_ms,total_bytes,total_flops,total_workgroups\n" (site may itself contain commas), NUL-terminated
  * and truncated to buflen (host memory).  Returns the bytes a full report needs, or -1
  * if an event could not be read. */
 int32_t asi_profile_enable(int32_t on);

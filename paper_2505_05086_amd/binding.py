@@ -276,7 +276,7 @@ def asi_profile_enable(on: bool) -> bool:
 
 
 def asi_profile_report() -> dict:
-    """{site: {"launches", "ms", "bytes", "flops"}} for the launches recorded since enable."""
+    """{site: {"launches", "ms", "bytes", "flops", "workgroups"}} for the launches recorded since enable."""
     need = int(lib().asi_profile_report(None, 0))
     if need < 0:
         raise AsiError(4, "asi_profile_report")
@@ -285,6 +285,7 @@ def asi_profile_report() -> dict:
         raise AsiError(4, "asi_profile_report")
     out = {}
     for line in buf.value.decode().splitlines():
-        site, cnt, ms, by, fl = line.rsplit(",", 4)      # the site itself may contain commas
-        out[site] = {"launches": int(cnt), "ms": float(ms), "bytes": float(by), "flops": float(fl)}
+        site, cnt, ms, by, fl, wg = line.rsplit(",", 5)      # the site itself may contain commas
+        out[site] = {"launches": int(cnt), "ms": float(ms), "bytes": float(by), "flops": float(fl),
+                     "workgroups": float(wg)}
     return out

@@ -287,7 +287,7 @@ bool ws_ok(const void* ws, size_t have, size_t need) {
 // tagged with the bytes and flops the step must move / compute by its definition.
 struct ProfRec {
     std::string site;
-    double bytes, flops;
+    double bytes, flops, wgs;
     hipEvent_t e0, e1;
 };
 std::mutex g_prof_mu;
@@ -378,8 +378,8 @@ asi_status flush(std::vector<Program>& progs, hipStream_t st) {
                 (void)hipEventRecord(rec.e1, st);
                 // "kernel instantiation:role", e.g. "k_ttm_mfma<float, false, 3, false>:core"
                 rec.site = std::string(label) + (group[0]->role[0] ? std::string(":") + group[0]->role : std::string());
-                rec.bytes = rec.flops = 0;
-                for (int j = 0; j < n; ++j) { rec.bytes += group[j]->bytes; rec.flops += group[j]->flops; }
+                rec.bytes = rec.flops = rec.wgs = 0;
+                for (int j = 0; j < n; ++j) { rec.bytes += group[j]->bytes; rec.flops += group[j]->flops; rec.wgs += group[j]->nblocks; }
                 std::lock_guard<std::mutex> lk(g_prof_mu);
                 g_prof.push_back(rec);
             }
@@ -659,20 +659,20 @@ int32_t asi_profile_enable(int32_t on) {
 
 int64_t asi_profile_report(char* buf, int64_t buflen) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
-    struct Agg { long long count = 0; double ms = 0, bytes = 0, flops = 0; };
+    struct Agg { long long count = 0; double ms = 0, bytes = 0, flops = 0, wgs = 0; };
     std::map<std::string, Agg> agg;
     for (auto& r : g_prof) {
         if (hipEventSynchronize(r.e1) != hipSuccess) return -1;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) return -1;
         Agg& a = agg[r.site];
-        a.count += 1; a.ms += ms; a.bytes += r.bytes; a.flops += r.flops;
+        a.count += 1; a.ms += ms; a.bytes += r.bytes; a.flops += r.flops; a.wgs += r.wgs;
     }
     std::string out;
-    char line[256];
+    char line[320];
     for (auto& kv : agg) {
-        std::snprintf(line, sizeof(line), "%s,%lld,%.6f,%.1f,%.1f\n", kv.first.c_str(), kv.second.count, kv.second.ms,
-                      kv.second.bytes, kv.second.flops);
+        std::snprintf(line, sizeof(line), "%s,%lld,%.6f,%.1f,%.1f,%.0f\n", kv.first.c_str(), kv.second.count,
+                      kv.second.ms, kv.second.bytes, kv.second.flops, kv.second.wgs);
         out += line;
     }
     if (buf && buflen > 0) {
