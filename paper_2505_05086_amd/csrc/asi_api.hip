@@ -504,11 +504,12 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
     if (info && !fast.njobs) ASI_ADD(pg, "", 4.0, 0.0, make_init_ctrl(info, it__));     // otherwise gram0 clears it
     if (pre.njobs) ASI_ADD(pg, "", pre_b, pre_b / 8.0, make_orth_presum(pre, it__));
     if (fast.njobs) {
-        // Orthogonalize: shifted Cholesky-QR, then one plain Cholesky-QR pass
-        // (each of the first two launches ends with the Cholesky factorisation of its Gram matrices)
+        // Orthogonalize: Cholesky-QR (with a diagonal shift if the plain factorisation loses a pivot),
+        // then a second Cholesky-QR pass unless the first result is orthonormal to 1e-7 already.
+        // Each launch ends with the factorisation of its Gram matrices in the last workgroup of a
+        // mode; the second pass, when needed, is carried out by that workgroup too.
         ASI_ADD(pg, "", fast_b + chol_b, fast_f + chol_f, make_orth_gram0(fast, it__));
-        ASI_ADD(pg, "", 2 * fast_b + chol_b, 2 * fast_f + chol_f, make_orth_apply(fast, 0, it__));
-        ASI_ADD(pg, "", 1.5 * fast_b, fast_f, make_orth_apply(fast, 1, it__));
+        ASI_ADD(pg, "", 2.5 * fast_b + chol_b, 2 * fast_f + chol_f, make_orth_apply(fast, it__));
     }
     if (wide.njobs) {
         ASI_ADD(pg, "", pre2_b, pre2_b / 8.0, make_orth_presum(pre2, it__));

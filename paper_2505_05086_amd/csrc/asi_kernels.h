@@ -219,7 +219,7 @@ int orth_slices(int n);
 // apply(0): Q0 = P R0^-1, slice Grams of Q0; the last workgroup of a mode factors again.
 // apply(1): U = Q0 R1^-1 in fp32.
 bool make_orth_gram0(const OrthArgs& a, Item* out);
-bool make_orth_apply(const OrthArgs& a, int final_pass, Item* out);
+bool make_orth_apply(const OrthArgs& a, Item* out);
 // wide path, 64 < r <= 192: nblk = orth_wide_gram_blocks(n), scal holds 2 + 192 doubles,
 // P64 must already hold the summed P (make_orth_presum with a single group does that)
 bool orth_wide_supported(int r);

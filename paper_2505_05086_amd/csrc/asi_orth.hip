@@ -223,7 +223,7 @@ struct CholSmem {
 };
 
 template <int RM>
-__device__ void chol_job(const OrthJob& jb, int pass, int last, int32_t* info, CholSmem& sm) {
+__device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, CholSmem& sm) {
     double (*Gs)[OP_LD] = sm.Gs;
     double* dinv = sm.dinv;
     double* rdiag = sm.rdiag;
@@ -357,7 +357,7 @@ __device__ void chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
                     if (mask) flag_info(info, jb.mode1, __ffsll((long long)mask));
                 }
             }
-            return;
+            return false;
         }
         if (tid == 0) s_trace = jb.scal[0];
         factor();
@@ -437,6 +437,7 @@ __device__ void chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
             }
         }
     }
+    return true;
 }
 
 // ---- hand-over from the slices of a mode to its factorisation ------------------------------
@@ -544,19 +545,14 @@ union ApplyOrChol {                      // the factorisation reuses the memory 
     CholSmem ch;
 };
 
+// One 32-row slice: P64[slice] <- P64[slice] R^-1.  The first pass stores the result in fp64 for
+// the second pass, its fp32 copy in Uout (the result if the first pass turns out to be enough) and
+// the slice's Gram matrix; the final pass stores fp32 only.
 template <int RM>
-__global__ __launch_bounds__(256) void k_orth_apply(OrthBatch a, int final_pass) {
-    __shared__ __align__(16) unsigned char raw[sizeof(ApplyOrChol)];
-    __shared__ int s_last;
-    ApplySmem& ap = *reinterpret_cast<ApplySmem*>(raw);
+__device__ void apply_slice(const OrthJob& jb, int blk, int final_pass, ApplySmem& ap) {
     double (*Ps)[OP_LD] = ap.Ps;
     double (*Rs)[OP_LD] = ap.Rs;
     double (*Ds)[16][17] = ap.Ds;
-    int ji, blk;
-    find_job(a, &ji, &blk);
-    const OrthJob jb = a.job[ji];
-    // the first pass was found to be orthonormal already: its fp32 copy is the result
-    if (final_pass && jb.scal[66] != 0.0) return;
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     const int nb = (r + 15) / 16;
@@ -636,9 +632,28 @@ __global__ __launch_bounds__(256) void k_orth_apply(OrthBatch a, int final_pass)
             jb.Uout[(long long)i0 * r + idx] = (float)q0;
         }
         gram_from_lds(Ps, r, jb.Gpart + (long long)blk * ((r * (r + 1)) / 2));
-        // the workgroup that finishes a mode's last slice factors the Gram matrix of Q0
-        if (!last_arrival(jb.ctr + 1, jb.nblk, &s_last)) return;
-        chol_job<RM>(jb, 1, 1, jb.info, *reinterpret_cast<CholSmem*>(raw));
+    }
+}
+
+// Second half of the orthonormalisation in one launch: every workgroup solves its slice with the
+// first-pass factor; the one that finishes a mode's last slice checks Q0^T Q0 against the identity
+// and, only if that fails, factors it and solves all slices of the mode once more by itself (a
+// rare, slow path: it trades a launch per call for serial work on ill-conditioned inputs).
+template <int RM>
+__global__ __launch_bounds__(256) void k_orth_apply(OrthBatch a) {
+    __shared__ __align__(16) unsigned char raw[sizeof(ApplyOrChol)];
+    __shared__ int s_last;
+    ApplySmem& ap = *reinterpret_cast<ApplySmem*>(raw);
+    int ji, blk;
+    find_job(a, &ji, &blk);
+    const OrthJob jb = a.job[ji];
+    apply_slice<RM>(jb, blk, 0, ap);
+    if (!last_arrival(jb.ctr + 1, jb.nblk, &s_last)) return;
+    if (!chol_job<RM>(jb, 1, 1, jb.info, *reinterpret_cast<CholSmem*>(raw))) return;
+    for (int b2 = 0; b2 < jb.nblk; ++b2) {
+        __threadfence();                   // R, Dinv (and every slice of Q0) are read back from memory
+        __syncthreads();
+        apply_slice<RM>(jb, b2, 1, ap);
     }
 }
 
@@ -1048,8 +1063,8 @@ bool make_orth_presum(const PresumArgs& a, Item* out) {
 bool make_orth_gram0(const OrthArgs& a, Item* out) {
     return fast_args_ok(a) && put_orth(IT_GRAM0, 0, "k_orth_gram0", a, total_blocks(a), out);
 }
-bool make_orth_apply(const OrthArgs& a, int final_pass, Item* out) {
-    return fast_args_ok(a) && put_orth(IT_APPLY, final_pass ? 1 : 0, "k_orth_apply", a, total_blocks(a), out);
+bool make_orth_apply(const OrthArgs& a, Item* out) {
+    return fast_args_ok(a) && put_orth(IT_APPLY, 0, "k_orth_apply", a, total_blocks(a), out);
 }
 bool make_orthw_gram(const OrthArgs& a, Item* out) {
     return wide_args_ok(a) && put_orth(IT_ORTHW_GRAM, 0, "k_orthw_gram", a, total_blocks(a), out);
@@ -1134,10 +1149,10 @@ hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st, ch
             else hipLaunchKernelGGL(k_orth_gram0<64>, grid, 256, 0, st, b);
             break;
         case IT_APPLY:
-            if (rm == 16) hipLaunchKernelGGL(k_orth_apply<16>, grid, 256, 0, st, b, aux);
-            else if (rm == 32) hipLaunchKernelGGL(k_orth_apply<32>, grid, 256, 0, st, b, aux);
-            else if (rm == 48) hipLaunchKernelGGL(k_orth_apply<48>, grid, 256, 0, st, b, aux);
-            else hipLaunchKernelGGL(k_orth_apply<64>, grid, 256, 0, st, b, aux);
+            if (rm == 16) hipLaunchKernelGGL(k_orth_apply<16>, grid, 256, 0, st, b);
+            else if (rm == 32) hipLaunchKernelGGL(k_orth_apply<32>, grid, 256, 0, st, b);
+            else if (rm == 48) hipLaunchKernelGGL(k_orth_apply<48>, grid, 256, 0, st, b);
+            else hipLaunchKernelGGL(k_orth_apply<64>, grid, 256, 0, st, b);
             break;
         case IT_ORTHW_GRAM:
             hipLaunchKernelGGL(k_orthw_gram, grid, 256, 0, st, b);
