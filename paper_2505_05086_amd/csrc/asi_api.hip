@@ -137,7 +137,7 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
 }
 
 // ---- core projection ----------------------------------------------------------
-// The products are ordered to minimise multiply-adds.  For small spatial extents the H and W
+// The products are ordered by a cost that follows their measured time (see core_cost).  For small spatial extents the H and W
 // modes are contracted together by one pass with the Kronecker product of their factors, so
 // the tensor is treated as (B, C, H*W) with three "super modes".
 // merged products pay off while the contraction fits one or two K chunks of the kernel; a longer
@@ -155,19 +155,27 @@ struct CorePlan {
 };
 
 bool kron_ok(long long n_a, long long n_b, int r_a, int r_b) {
+#ifdef ASI_DEBUG_TIMING
+    if (const char* e = std::getenv("ASI_DBG_KRON_MAXN")) return n_a * n_b <= std::atoi(e) && (long long)r_a * r_b <= kKronMaxR;
+#endif
     return n_a * n_b <= kKronMaxN && (long long)r_a * r_b <= kKronMaxR;
 }
 
-// multiply-adds of the products taken in the order perm
+// Cost of the products taken in the order perm.  Every product is one pass over its input, so the
+// elements read and written count first and the multiply-adds count at the rate the product
+// kernels sustain relative to their data movement (about 64 per element moved).  Counting
+// multiply-adds alone would start with the cheap halvings along H and W, i.e. with the largest
+// number of full passes; this measure starts with the mode that shrinks the tensor most.
 double core_cost(const CorePlan& p, const int* perm) {
     long long cur[4];
     for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
     double cost = 0.0;
     for (int k = 0; k < p.d; ++k) {
         const int m = perm[k];
-        double sz = 1.0;
-        for (int q = 0; q < p.d; ++q) sz *= (double)cur[q];
-        cost += sz * p.r[m];
+        double in = 1.0;
+        for (int q = 0; q < p.d; ++q) in *= (double)cur[q];
+        const double out = in / (double)cur[m] * p.r[m];
+        cost += in + out + in * p.r[m] / 64.0;
         cur[m] = p.r[m];
     }
     return cost;
@@ -201,6 +209,10 @@ CorePlan plan_core(const Shape& s, void* ws, const int* order = nullptr) {
         }
     } while (std::next_permutation(perm, perm + p.d));
     if (order) std::memcpy(p.order, order, sizeof(int) * 4);
+#ifdef ASI_DEBUG_TIMING
+    if (const char* e = std::getenv("ASI_DBG_CORE_ORDER"))
+        for (int k = 0; k < p.d && e[2 * k]; ++k) p.order[k] = e[2 * k] - '0';
+#endif
     Carver c(ws);
     p.buf[0] = c.take<float>(need[0]);
     p.buf[1] = c.take<float>(need[1]);
