@@ -12,6 +12,7 @@
 #include "asi_kernels.h"
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 namespace asi {
@@ -28,6 +29,7 @@ struct CorrPlan {
     int rows_in;     // Z rows a chunk touches
     int wp;          // slab row length
     int slab;        // rows_in * wp
+    int zld;         // floats between the slabs of consecutive core channels in LDS
     int nchunks;     // r1 * nyc
     int cps;         // chunks per split
     int nsplit;
@@ -55,6 +57,16 @@ static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
     p->wp = (g.Wo - 1) * g.sw + (g.kw - 1) * g.dw + 1;
     p->slab = p->rows_in * p->wp;
     if ((long long)p->slab * 16 > CR_ZMAX) return false;
+    // In the multiply loop lane (j = l%16, k = l/16) reads slab j at the window origin of position k,
+    // and the positions of a lane group are sw floats apart.  With unit stride a slab pitch of
+    // 2 mod 32 puts the 32 lanes of a half wave on 32 different banks (a pitch that is a multiple
+    // of 32, e.g. 6 rows x 16 columns, puts the 16 slabs on one bank); otherwise an odd pitch.
+    p->zld = p->slab;
+    while (g.sw == 1 ? (p->zld % 32 != 2) : (p->zld % 2 == 0)) ++p->zld;
+#ifdef ASI_DEBUG_TIMING
+    if (const char* e = std::getenv("ASI_DBG_ZLD_MOD")) { p->zld = p->slab; while (p->zld % 32 != std::atoi(e)) ++p->zld; }
+#endif
+    if ((long long)p->zld * 16 > CR_ZMAX) p->zld = p->slab;
     p->nchunks = g.r1 * p->nyc;
     const long long base = (long long)((g.cout + CR_TO - 1) / CR_TO) * ((g.r2 + 15) / 16);
     long long want = (256 + base - 1) / base;
@@ -135,6 +147,9 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
         }
     };
     CSTAMP(0);
+#ifdef ASI_DEBUG_TIMING
+    if (threadIdx.x == 0 && blockIdx.x == 0) g_corr_stamps[60] = clock64();
+#endif
     if (ch_beg < ch_end) fetch(ch_beg);
     for (int ch = ch_beg; ch < ch_end; ++ch) {
         CSTAMP(1 + 4 * (ch - ch_beg));
@@ -148,29 +163,56 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
 #pragma unroll
         for (int u = 0; u < CR_ZMAX / 256; ++u) {
             const int e = u * 256 + tid;
-            if (e < ztotal) Zs[e] = z_t[u];
+            const int jl = (int)(((float)e + 0.5f) * inv_slab);
+            if (e < ztotal) Zs[e + jl * (pl.zld - pl.slab)] = z_t[u];
         }
         __syncthreads();
         CSTAMP(2 + 4 * (ch - ch_beg));
         if (ch + 1 < ch_end) fetch(ch + 1);                // in flight while this chunk is multiplied
         CSTAMP(3 + 4 * (ch - ch_beg));
-        const float* zrow = Zs + ll * pl.slab;
-#pragma unroll 4
-        for (int ks = 0; ks < CR_KC / 4; ++ks) {
-            if (4 * ks < kcv) {
-                const int k = 4 * ks + lg;
-                // window origin of position k inside the slab: (k / Wo) * sh * wp + (k % Wo) * sw
-                const int yl = (int)(((float)k + 0.5f) * inv_wo), x = k - yl * g.Wo;
-                const float a = As[k][16 * wave + ll];
-                const float* zp = zrow + ((yl < pl.ry) ? yl * row_step + x * g.sw : 0);
+#ifdef ASI_DEBUG_TIMING
+        if (threadIdx.x == 0 && blockIdx.x == 0 && ch == ch_beg) g_corr_stamps[40] = clock64();
+#endif
+        // operands of step ks: the A value and one B value per tap.  The loads of step ks + 1 are
+        // issued before the products of step ks, so that LDS latency is paid once per chunk and not
+        // once per product.  The step count is rounded up to even: positions past the chunk's end
+        // have zero A values (the loader's predicate) and read the slab origin, so they add nothing,
+        // and the loop body stays free of branches.
+        const int nks2 = ((kcv + 7) >> 3) << 1;
+        const int zbase = ll * pl.zld;
+        auto operands = [&](int ks, float& a, float (&bq)[MAXT]) {
+            const int k = 4 * ks + lg;
+            // window origin of position k inside the slab: (k / Wo) * sh * wp + (k % Wo) * sw
+            // (24-bit multiplies: one instruction each, and every factor here is far below 2^23)
+            const int yl = (int)(((float)k + 0.5f) * inv_wo), x = k - __mul24(yl, g.Wo);
+            a = As[k][16 * wave + ll];
+            const int org = __mul24(yl, row_step) + __mul24(x, g.sw);
+            const int zo = zbase + ((yl < pl.ry) ? org : 0);
 #pragma unroll
-                for (int t = 0; t < MAXT; ++t)
-                    if (EXACT || t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, zp[tapofs[t]], acc[t], 0, 0, 0);
-            }
+            for (int t = 0; t < MAXT; ++t) bq[t] = (EXACT || t < taps) ? Zs[zo + tapofs[t]] : 0.f;
+        };
+        float a0, a1, b0[MAXT], b1[MAXT];
+        operands(0, a0, b0);
+#pragma unroll 1
+        for (int ks = 0; ks < nks2; ks += 2) {
+            operands(ks + 1, a1, b1);
+#pragma unroll
+            for (int t = 0; t < MAXT; ++t)
+                if (EXACT || t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[t], acc[t], 0, 0, 0);
+            operands(ks + 2 < CR_KC / 4 ? ks + 2 : CR_KC / 4 - 1, a0, b0);
+#pragma unroll
+            for (int t = 0; t < MAXT; ++t)
+                if (EXACT || t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[t], acc[t], 0, 0, 0);
         }
         CSTAMP(4 + 4 * (ch - ch_beg));
+#ifdef ASI_DEBUG_TIMING
+        if (threadIdx.x == 0 && blockIdx.x == 0 && ch == ch_beg) g_corr_stamps[41] = clock64();
+#endif
     }
     CSTAMP(62);
+#ifdef ASI_DEBUG_TIMING
+    if (threadIdx.x == 0 && blockIdx.x == 0) g_corr_stamps[61] = clock64();
+#endif
     // lane holds o = o0 + 16w + 4*lg + v, j = j0 + ll
     const long long total = (long long)g.cout * g.r2 * taps;
 #pragma unroll
