@@ -36,11 +36,13 @@ constexpr double OP_DONE_TOL = 1e-7;   // |Q0^T Q0 - I| below which the first pa
 #ifdef ASI_DEBUG_TIMING
 __device__ long long g_orth_stamps[64];
 #define STAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 2 && pass == 0) g_orth_stamps[i] = wall_clock64(); } while (0)
+#define KSTAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 2) g_orth_stamps[i] = wall_clock64(); } while (0)
 extern "C" int asi_debug_orth_stamps(long long* out) {
     return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_orth_stamps), sizeof(long long) * 64);
 }
 #else
 #define STAMP(i) do {} while (0)
+#define KSTAMP(i) do {} while (0)
 #endif
 
 __device__ __forceinline__ void flag_info(int32_t* info, int mode1, int col1) {
@@ -471,6 +473,7 @@ __global__ __launch_bounds__(256) void k_orth_gram0(OrthBatch a) {
     find_job(a, &ji, &blk);
     const OrthJob jb = a.job[ji];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
+    if (blk == 0) KSTAMP(40);
     if (blk == 0 && tid == 0 && jb.info) *jb.info = 0;            // nothing has reported yet
     const int i0 = blk * OP_RS;
     const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
@@ -526,10 +529,14 @@ __global__ __launch_bounds__(256) void k_orth_gram0(OrthBatch a) {
         }
     }
     __syncthreads();
+    if (blk == 0) KSTAMP(41);
     gram_from_lds(Ps, r, jb.Gpart + (long long)blk * ((r * (r + 1)) / 2));
+    if (blk == 0) KSTAMP(42);
     // the workgroup that finishes a mode's last slice goes on to factor its Gram matrix
     if (!last_arrival(jb.ctr + 0, jb.nblk, &s_last)) return;
+    KSTAMP(43);
     chol_job<RM>(jb, 0, 0, jb.info, *reinterpret_cast<CholSmem*>(raw));
+    KSTAMP(44);
 }
 
 // ---- apply ----------------------------------------------------------------------------------
@@ -647,9 +654,14 @@ __global__ __launch_bounds__(256) void k_orth_apply(OrthBatch a) {
     int ji, blk;
     find_job(a, &ji, &blk);
     const OrthJob jb = a.job[ji];
+    if (blk == 0) KSTAMP(50);
     apply_slice<RM>(jb, blk, 0, ap);
+    if (blk == 0) KSTAMP(51);
     if (!last_arrival(jb.ctr + 1, jb.nblk, &s_last)) return;
-    if (!chol_job<RM>(jb, 1, 1, jb.info, *reinterpret_cast<CholSmem*>(raw))) return;
+    KSTAMP(52);
+    const bool again = chol_job<RM>(jb, 1, 1, jb.info, *reinterpret_cast<CholSmem*>(raw));
+    KSTAMP(53);
+    if (!again) return;
     for (int b2 = 0; b2 < jb.nblk; ++b2) {
         __threadfence();                   // R, Dinv (and every slice of Q0) are read back from memory
         __syncthreads();

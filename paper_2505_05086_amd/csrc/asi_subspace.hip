@@ -146,46 +146,60 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
             const SmallView& sv = jb.v[vi];
             const int n = sv.n, sI = sv.sI;
             const int valid_cols = WHOLE_O ? no_or_vc * sv.cols_per_o : no_or_vc;
+            // The loop body is free of branches and every group of LDS reads is issued before the
+            // products that consume it, so that a fibre block pays LDS latency twice, not once per product.
+            // B operands of step A do not depend on the fibre block (rows i >= n of Us are zero)
+            float ub[NBM * 4][NBR];
+#pragma unroll
+            for (int ks = 0; ks < NBM * 4; ++ks)
+#pragma unroll
+                for (int nb = 0; nb < NBR; ++nb) ub[ks][nb] = Us[vi][4 * ks + lg][16 * nb + ll];
             for (int cb = wave; cb * 16 < valid_cols; cb += 4) {
                 // step A: V for 16 fibres
-                v4f vacc[NBR];
-#pragma unroll
-                for (int nb = 0; nb < NBR; ++nb) vacc[nb] = (v4f){0.f, 0.f, 0.f, 0.f};
                 const int cA = cb * 16 + ll;
                 const bool okA = cA < valid_cols;
                 const int qA = (int)(((float)cA + 0.5f) * sv.inv_div);
                 const int ofsA = qA * sv.mulA + (cA - qA * sv.div) * sv.mulB;
+                float av[NBM * 4];
 #pragma unroll
                 for (int ks = 0; ks < NBM * 4; ++ks) {
-                    if (4 * ks < n) {
-                        const int i = 4 * ks + lg;
-                        const float a = ldg_f32(smem, ofsA + i * sI, okA && i < n);
-#pragma unroll
-                        for (int nb = 0; nb < NBR; ++nb)
-                            vacc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Us[vi][i][16 * nb + ll], vacc[nb], 0, 0, 0);
-                    }
+                    const int i = 4 * ks + lg;
+                    const bool ok = okA && i < n;
+                    const float x = smem[ok ? ofsA + i * sI : 0];
+                    av[ks] = ok ? x : 0.f;
                 }
+                v4f vacc[NBR];
+#pragma unroll
+                for (int nb = 0; nb < NBR; ++nb) vacc[nb] = (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < NBM * 4; ++ks)
+#pragma unroll
+                    for (int nb = 0; nb < NBR; ++nb)
+                        vacc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ks], ub[ks][nb], vacc[nb], 0, 0, 0);
                 // step B: P += X V over the same 16 fibres
+                double a2[4][NBM];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int cB = cb * 16 + 4 * lg + v;
                     const bool okB = cB < valid_cols;
                     const int qB = (int)(((float)cB + 0.5f) * sv.inv_div);
                     const int ofsB = qB * sv.mulA + (cB - qB * sv.div) * sv.mulB;
-                    double bv[NBR];
-#pragma unroll
-                    for (int nb = 0; nb < NBR; ++nb) bv[nb] = (double)vacc[nb][v];
 #pragma unroll
                     for (int mb = 0; mb < NBM; ++mb) {
-                        if (16 * mb < n) {
-                            const int i = 16 * mb + ll;
-                            const double a = (okB && i < n) ? (double)smem[ofsB + i * sI] : 0.0;
-#pragma unroll
-                            for (int nb = 0; nb < NBR; ++nb)
-                                pacc[vi][mb][nb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bv[nb], pacc[vi][mb][nb], 0, 0, 0);
-                        }
+                        const int i = 16 * mb + ll;
+                        const bool ok = okB && i < n;
+                        const float x = smem[ok ? ofsB + i * sI : 0];
+                        a2[v][mb] = ok ? (double)x : 0.0;
                     }
                 }
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int mb = 0; mb < NBM; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NBR; ++nb)
+                            pacc[vi][mb][nb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a2[v][mb], (double)vacc[nb][v],
+                                                                                    pacc[vi][mb][nb], 0, 0, 0);
             }
         }
     }
