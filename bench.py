@@ -230,29 +230,30 @@ def main():
         # queue run one after the other.  Which streams share is not visible from the API, so it
         # is measured: two different layers' graphs replayed on a pair of streams take about the
         # time of the longer one if the queues differ and the sum if they are the same.
-        def pair_us(sa, sb, reps=6):
-            ga, gb = layer_graphs[0][0], layer_graphs[1][0]
+        def probe_us(jobs, reps=6):
+            """Time per round of replaying the given (graph, stream) jobs side by side."""
             t0_, t1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            used = {s_ for _, s_ in jobs if s_ is not main_stream}
             torch.cuda.synchronize()
             t0_.record(main_stream)
-            for s_ in {sa, sb}:
-                if s_ is not main_stream:
-                    s_.wait_stream(main_stream)
+            for s_ in used:
+                s_.wait_stream(main_stream)
             for _ in range(reps):
-                with torch.cuda.stream(sa):
-                    ga.replay()
-                with torch.cuda.stream(sb):
-                    gb.replay()
-            for s_ in {sa, sb}:
-                if s_ is not main_stream:
-                    main_stream.wait_stream(s_)
+                for g_, s_ in jobs:
+                    with torch.cuda.stream(s_):
+                        g_.replay()
+            for s_ in used:
+                main_stream.wait_stream(s_)
             t1_.record(main_stream)
             torch.cuda.synchronize()
             return t0_.elapsed_time(t1_) * 1e3 / reps
 
+        ga, gb = layer_graphs[0][0], layer_graphs[1][0]
+        probe_us([(ga, main_stream), (gb, main_stream)], 2)
+        ta, tb = probe_us([(ga, main_stream)]), probe_us([(gb, main_stream)])
+        # side by side two chains take about the longer one, on one queue their sum
+        shared_above = max(ta, tb) + 0.5 * min(ta, tb)
         candidates = [main_stream] + [torch.cuda.Stream() for _ in range(11)]
-        pair_us(main_stream, main_stream, 2)
-        serial = pair_us(main_stream, main_stream)
         chosen, tested = [main_stream], 0
         for cand in candidates[1:]:
             if len(chosen) >= nstreams:
@@ -260,12 +261,13 @@ def main():
             apart = True
             for c in chosen:
                 tested += 1
-                if pair_us(c, cand) > 0.8 * serial:
+                if probe_us([(ga, c), (gb, cand)]) > shared_above:
                     apart = False
                     break
             if apart:
                 chosen.append(cand)
-        queue_probe = {"streams_on_distinct_queues": len(chosen), "pairs_timed": tested, "same_queue_pair_us": serial}
+        queue_probe = {"streams_on_distinct_queues": len(chosen), "pairs_timed": tested,
+                       "chain_us": [ta, tb], "same_queue_above_us": shared_above}
         side = [chosen[i % len(chosen)] for i in range(nstreams)]
 
     def fork():
