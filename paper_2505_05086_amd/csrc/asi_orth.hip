@@ -128,10 +128,17 @@ __device__ void chol_block16(double (*Gs)[OP_LD], double (*rowbuf)[64][4], doubl
     BSTAMP(20);
     const bool xl = j >= 48;            // identity lane
     double col[16];
+    {
+        // All 16 reads are issued before any is used.  Left to itself the compiler sinks each read
+        // into the branch that selects it (only lanes 0..15 keep the value) and waits for one LDS
+        // round trip per row; the empty asm pins the reads in front of the selects.
+        double g[16];
 #pragma unroll
-    for (int a2 = 0; a2 < 16; ++a2) {
-        const double g = Gs[base + a2][base + (j & 15)];
-        col[a2] = xl ? ((a2 == j - 48) ? 1.0 : 0.0) : (j < 16 ? g : 0.0);
+        for (int a2 = 0; a2 < 16; ++a2) g[a2] = Gs[base + a2][base + (j & 15)];
+#pragma unroll
+        for (int a2 = 0; a2 < 16; ++a2) asm volatile("" : "+v"(g[a2]));
+#pragma unroll
+        for (int a2 = 0; a2 < 16; ++a2) col[a2] = xl ? ((a2 == j - 48) ? 1.0 : 0.0) : (j < 16 ? g[a2] : 0.0);
     }
     int bad = *bad_io;
     double f[4];

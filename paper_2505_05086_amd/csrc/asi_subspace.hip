@@ -32,7 +32,13 @@ constexpr int SS_TC = 128;                 // fibres (unfolding columns) per til
 constexpr int SS_PAD = 4;
 constexpr int SS_LDS_FLOATS = 64 * (SS_TC + SS_PAD);   // 33 KB
 constexpr int SS_PRE = (SS_LDS_FLOATS + 255) / 256;    // prefetch registers per thread
+#ifdef ASI_DEBUG_TIMING
+#include <cstdlib>
+static int ss_max_wg_dbg() { const char* e = std::getenv("ASI_DBG_SS_MAX_WG"); return e ? std::atoi(e) : 1024; }
+#define SS_MAX_WG (ss_max_wg_dbg())
+#else
 static const int SS_MAX_WG = 1024;
+#endif
 
 struct SmallView {
     const float* U;      // (n, r) previous factor
