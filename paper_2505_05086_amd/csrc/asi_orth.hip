@@ -117,6 +117,10 @@ __device__ __forceinline__ double bcast_lane(double x, int src) {      // src un
 // diagonal the pivots R[k][k]^2, and pinvs[base+k] their reciprocals.
 // Lanes 48..63 carry the columns of an identity block through the same row operations, which
 // leaves the inverse of the block's unit lower triangular factor in Xb[i][j] = (L^-1)[j][i].
+// e / r for 0 <= e < 2^16 and 1 <= r <= 64 without an integer division: the rounded float quotient
+// of (e + 0.5) is exact in that range (the same device as in the product kernels).
+__device__ __forceinline__ int small_div(int e, float inv_r) { return (int)(((float)e + 0.5f) * inv_r); }
+
 #ifdef ASI_DEBUG_TIMING
 #define BSTAMP(i) do { if (dbg && threadIdx.x == 0) g_orth_stamps[i] = wall_clock64(); } while (0)
 #else
@@ -343,8 +347,9 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
         // the second pass would only reproduce the identity, and the fp32 copy of Q0 that the solve
         // has written is the result.
         double dev = 0.0;
+        const float inv_r1 = 1.0f / (float)r;
         for (int e = tid; e < r * r; e += 256) {
-            const int ga = e / r, gb = e - ga * r;
+            const int ga = small_div(e, inv_r1), gb = e - ga * r;
             dev = fmax(dev, fabs(Gs[ga][gb] - (ga == gb ? 1.0 : 0.0)));
         }
 #pragma unroll
@@ -409,18 +414,26 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
         if (!(p > 0.0)) p = 1.0;
         const double d = sqrt(p);
         dinv[tid] = 1.0 / d;
+        pinvs[tid] = d;                     // the pivots' reciprocals are not needed any more
         const double rd = (pass == 0 ? 1.0 : jb.scal[1 + tid]) * d;
         rdiag[tid] = rd;
         jb.scal[1 + tid] = rd;
     }
     __syncthreads();
-    {   // R = rows scaled by 1 / R[k][k], zeros below the diagonal
+    {   // R = rows scaled by 1 / R[k][k], zeros below the diagonal (reads first, selects after)
         const int gb = tid & 63;
+        double gv[RM / 4], dv[RM / 4], iv[RM / 4];
 #pragma unroll
         for (int it = 0; it < RM / 4; ++it) {
             const int ga = (tid >> 6) + 4 * it;
-            if (ga < r && gb < r)
-                jb.R[ga * r + gb] = (ga < gb) ? Gs[ga][gb] * dinv[ga] : (ga == gb ? 1.0 / dinv[ga] : 0.0);
+            gv[it] = Gs[ga][gb]; dv[it] = pinvs[ga]; iv[it] = dinv[ga];
+        }
+#pragma unroll
+        for (int it = 0; it < RM / 4; ++it) asm volatile("" : "+v"(gv[it]), "+v"(dv[it]), "+v"(iv[it]));
+#pragma unroll
+        for (int it = 0; it < RM / 4; ++it) {
+            const int ga = (tid >> 6) + 4 * it;
+            if (ga < r && gb < r) jb.R[ga * r + gb] = (ga < gb) ? gv[it] * iv[it] : (ga == gb ? dv[it] : 0.0);
         }
     }
     STAMP(4);
@@ -531,7 +544,8 @@ __global__ __launch_bounds__(256) void k_orth_gram0(OrthBatch a) {
             const int idx = idx0 + 256 * it;
             if (idx < E && (it == 0 || !small)) {
                 jb.P64[(long long)i0 * r + idx] = sum[it];
-                Ps[idx / r][idx % r] = sum[it];
+                const int pi = small_div(idx, 1.0f / (float)r);
+                Ps[pi][idx - pi * r] = sum[it];
             }
         }
     }
@@ -573,6 +587,7 @@ __device__ void apply_slice(const OrthJob& jb, int blk, int final_pass, ApplySme
     const int i0 = blk * OP_RS;
     const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
     constexpr int PI = RM / 8, RI = RM * RM / 256, DI = RM / 16;
+    const float inv_r = 1.0f / (float)r;
     double tp[PI], tr[RI], td[DI];
 #pragma unroll
     for (int u = 0; u < PI; ++u) {
@@ -595,12 +610,14 @@ __device__ void apply_slice(const OrthJob& jb, int blk, int final_pass, ApplySme
 #pragma unroll
     for (int u = 0; u < PI; ++u) {
         const int idx = u * 256 + tid;
-        if (idx < nrows * r) Ps[idx / r][idx % r] = tp[u];
+        const int pi = small_div(idx, inv_r);
+        if (idx < nrows * r) Ps[pi][idx - pi * r] = tp[u];
     }
 #pragma unroll
     for (int u = 0; u < RI; ++u) {
         const int e = u * 256 + tid;
-        if (e < r * r) Rs[e / r][e % r] = tr[u];
+        const int ri = small_div(e, inv_r);
+        if (e < r * r) Rs[ri][e - ri * r] = tr[u];
     }
 #pragma unroll
     for (int u = 0; u < DI; ++u) {
@@ -638,10 +655,14 @@ __device__ void apply_slice(const OrthJob& jb, int blk, int final_pass, ApplySme
         __syncthreads();
     }
     if (final_pass) {
-        for (int idx = tid; idx < nrows * r; idx += 256) jb.Uout[(long long)i0 * r + idx] = (float)Ps[idx / r][idx % r];
+        for (int idx = tid; idx < nrows * r; idx += 256) {
+            const int pi = small_div(idx, inv_r);
+            jb.Uout[(long long)i0 * r + idx] = (float)Ps[pi][idx - pi * r];
+        }
     } else {
         for (int idx = tid; idx < nrows * r; idx += 256) {
-            const double q0 = Ps[idx / r][idx % r];
+            const int pi = small_div(idx, inv_r);
+            const double q0 = Ps[pi][idx - pi * r];
             jb.P64[(long long)i0 * r + idx] = q0;
             jb.Uout[(long long)i0 * r + idx] = (float)q0;
         }
