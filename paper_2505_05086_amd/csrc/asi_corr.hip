@@ -69,7 +69,11 @@ static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
     if ((long long)p->zld * 16 > CR_ZMAX) p->zld = p->slab;
     p->nchunks = g.r1 * p->nyc;
     const long long base = (long long)((g.cout + CR_TO - 1) / CR_TO) * ((g.r2 + 15) / 16);
-    long long want = (256 + base - 1) / base;
+    long long target = 256;
+#ifdef ASI_DEBUG_TIMING
+    if (const char* e = std::getenv("ASI_DBG_CORR_WG")) target = std::atoi(e);
+#endif
+    long long want = (target + base - 1) / base;
     if (want > p->nchunks) want = p->nchunks;
     if (want < 1) want = 1;
     p->cps = (int)((p->nchunks + want - 1) / want);
@@ -89,8 +93,13 @@ extern "C" int asi_debug_corr_stamps(long long* out) {
 
 template <int MAXT, bool EXACT>
 __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
-    __shared__ float As[CR_KC][CR_TO + 1];
-    __shared__ float Zs[CR_ZMAX];
+    // As | Zs during the K loop; afterwards (kernels of up to 9 taps) the 64 x (16 taps) result tile
+    constexpr int CR_TS_LD = 16 * MAXT + 1;
+    constexpr int CR_LDS = (MAXT <= 9 && CR_TO * CR_TS_LD > CR_KC * (CR_TO + 1) + CR_ZMAX) ? CR_TO * CR_TS_LD
+                                                                                           : CR_KC * (CR_TO + 1) + CR_ZMAX;
+    __shared__ float lds_raw[CR_LDS];
+    float (*As)[CR_TO + 1] = reinterpret_cast<float (*)[CR_TO + 1]>(lds_raw);
+    float* Zs = lds_raw + CR_KC * (CR_TO + 1);
     int lb;
     const CorrJob& jb = bt.job[locate(bt, &lb)];
     const float* __restrict__ G1 = jb.G1;
@@ -215,16 +224,43 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
 #endif
     // lane holds o = o0 + 16w + 4*lg + v, j = j0 + ll
     const long long total = (long long)g.cout * g.r2 * taps;
+    if constexpr (MAXT <= 9) {
+        // For one output channel the (j, tap) values of this workgroup are one contiguous run of T.
+        // Stored straight from the accumulators every lane of a store would hit its own cache line
+        // (the taps are innermost, lanes differ in j and o); through LDS the stores are contiguous.
+        __syncthreads();                                   // the last chunk's tiles are no longer read
+        float* Ts = lds_raw;
 #pragma unroll
-    for (int t = 0; t < MAXT; ++t) {
-        if (t < taps) {
+        for (int t = 0; t < MAXT; ++t)
+            if (t < taps) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int o = o0 + 16 * wave + 4 * lg + v, j = j0 + ll;
-                if (o < g.cout && j < g.r2) Tpart[(long long)z * total + ((long long)o * g.r2 + j) * taps + t] = acc[t][v];
+                for (int v = 0; v < 4; ++v) Ts[(16 * wave + 4 * lg + v) * CR_TS_LD + ll * taps + t] = acc[t][v];
+            }
+        __syncthreads();
+        const int nj = (g.r2 - j0 < 16) ? g.r2 - j0 : 16;
+        const int rowlen = nj * taps;                      // <= 144
+        const float inv_rowlen = 1.0f / (float)rowlen;
+        for (int e = tid; e < CR_TO * rowlen; e += 256) {   // e < 9216: the rounded float quotient is exact
+            const int ol = (int)(((float)e + 0.5f) * inv_rowlen), c = e - ol * rowlen;
+            const int o = o0 + ol;
+            if (o < g.cout) Tpart[(long long)z * total + ((long long)o * g.r2 + j0) * taps + c] = Ts[ol * CR_TS_LD + c];
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < MAXT; ++t) {
+            if (t < taps) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int o = o0 + 16 * wave + 4 * lg + v, j = j0 + ll;
+                    if (o < g.cout && j < g.r2) Tpart[(long long)z * total + ((long long)o * g.r2 + j) * taps + t] = acc[t][v];
+                }
             }
         }
     }
+#ifdef ASI_DEBUG_TIMING
+    __threadfence();
+    CSTAMP(63);
+#endif
 }
 
 // one thread per T[o,j,kh,kw] and split of the r1 axis: any geometry
