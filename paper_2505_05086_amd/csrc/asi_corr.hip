@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
     float (*As)[CR_TO + 1] = reinterpret_cast<float (*)[CR_TO + 1]>(lds_raw);
     float* Zs = lds_raw + CR_KC * (CR_TO + 1);
     int lb;
-    const CorrJob& jb = bt.job[locate(bt, &lb)];
+    const CorrJob& jb = bt.job[locate_xcd(bt, &lb)];     // the tiles of one split share its G1 rows and Z slabs
     const float* __restrict__ G1 = jb.G1;
     const float* __restrict__ Z = jb.Z;
     float* __restrict__ Tpart = jb.Tpart;

@@ -57,6 +57,21 @@ __device__ __forceinline__ int locate(const Batch<J>& b, int* local) {
     *local = bid - b.first[j];
     return j;
 }
+// Workgroups are handed to the 8 XCDs (each with its own L2) in round-robin order of their index, so
+// neighbouring indices never share an L2.  This renumbering gives every XCD one contiguous eighth
+// of a job's nb blocks instead: tiles that touch the same cache lines (adjacent column groups of an
+// unfolding, the tiles of one operand) then meet in one L2 rather than each fetching the line from
+// memory.  A bijection on [0, nb); only performance depends on the dispatch order.
+__device__ __forceinline__ int xcd_order(int lb, int nb) {
+    const int chunk = nb >> 3, rem = nb & 7, x = lb & 7, k = lb >> 3;
+    return x * chunk + (x < rem ? x : rem) + k;
+}
+template <typename J>
+__device__ __forceinline__ int locate_xcd(const Batch<J>& b, int* local) {
+    const int j = locate(b, local);
+    *local = xcd_order(*local, b.first[j + 1] - b.first[j]);
+    return j;
+}
 // host side: argument blocks of items[0..n) side by side, grid = all their workgroups
 template <typename J>
 inline bool gather(const Item* const* items, int n, Batch<J>* b, dim3* grid) {

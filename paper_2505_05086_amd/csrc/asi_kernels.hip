@@ -37,6 +37,7 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
         presum_block(jb.pre.job, jb.pre.njobs, lb - jb.gx * jb.gy * jb.gz);
         return;
     }
+    lb = xcd_order(lb, jb.gx * jb.gy * jb.gz);      // the tiles of one split share its columns of X and V
     const int bz = lb / (jb.gx * jb.gy), rem = lb - bz * (jb.gx * jb.gy), by = rem / jb.gx, bx = rem - by * jb.gx;
     const long long ncols = outer * inner;
     const int i0 = bx * PR_TI, q0 = by * PR_TQ, s = bz;

@@ -188,7 +188,7 @@ template <typename T, bool LASTMODE, int NBR, int KM>
 __global__ __launch_bounds__(256) void k_ttm_mfma(Batch<TtmJob> bt) {
     __shared__ float smem[TM_SMEM];
     int lb;
-    const TtmJob& jb = bt.job[locate(bt, &lb)];
+    const TtmJob& jb = bt.job[locate_xcd(bt, &lb)];
     ttm_tile<T, LASTMODE, NBR, KM>(jb, lb, smem);
 }
 
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(256) void k_ttm_duo(Batch<TtmDuoJob> bt) {
     __shared__ float smem[TM_SMEM];
     int lb;
     const TtmDuoJob& jb = bt.job[locate(bt, &lb)];
-    if (lb < jb.a_blocks) ttm_tile<T, false, NBR, 0>(jb.a, lb, smem);
+    if (lb < jb.a_blocks) ttm_tile<T, false, NBR, 0>(jb.a, xcd_order(lb, jb.a_blocks), smem);
     else ttm_tile<float, true, 4, 1>(jb.z, lb - jb.a_blocks, smem);
 }
 
@@ -216,7 +216,7 @@ template <typename T, int NBR, int KS, int CB>
 __global__ __launch_bounds__(256) void k_ttm_ksplit(Batch<TtmJob> bt) {
     __shared__ float red[4][NBR * 16][16 * CB + 1];
     int lb;
-    const TtmJob& jb = bt.job[locate(bt, &lb)];
+    const TtmJob& jb = bt.job[locate_xcd(bt, &lb)];
     const T* __restrict__ X = static_cast<const T*>(jb.X);
     const float* __restrict__ Mp = jb.Mp;
     float* __restrict__ Y = jb.Y;
