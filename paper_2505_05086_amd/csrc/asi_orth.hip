@@ -781,66 +781,114 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
     __shared__ double s_trace;
     __shared__ int s_bad;
     auto pidx = [r](int ga, int gb) { return ga * r - (ga * (ga - 1)) / 2 + (gb - ga); };
-    if (tid == 0) s_bad = 0;
-    for (int e = tid; e < r * r; e += 1024) {
-        const int ga = e / r, gb = e - ga * r;
-        if (ga <= gb) {
-            double s = 0.0;
-            for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
-                double t[8];
+    __shared__ int s_lost;
+    __shared__ double s_red[16];
+    if (tid == 0) { s_bad = 0; s_lost = 0; }
+    // Gp = sum of the slice Grams; returns this thread's share of max |G - I|
+    auto sum_gram = [&]() {
+        double dev = 0.0;
+        for (int e = tid; e < r * r; e += 1024) {
+            const int ga = e / r, gb = e - ga * r;
+            if (ga <= gb) {
+                double s = 0.0;
+                for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
+                    double t[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) t[u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, b0 + u < jb.nblk);
+                    for (int u = 0; u < 8; ++u) t[u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, b0 + u < jb.nblk);
 #pragma unroll
-                for (int u = 0; u < 8; ++u) s += t[u];
+                    for (int u = 0; u < 8; ++u) s += t[u];
+                }
+                Gp[pidx(ga, gb)] = s;
+                dev = fmax(dev, fabs(s - (ga == gb ? 1.0 : 0.0)));
             }
-            Gp[pidx(ga, gb)] = s;
         }
-    }
+        return dev;
+    };
+    // unblocked right-looking factorisation in place; a pivot that is not above 1e-12 of its diagonal
+    // entry (rdiag holds the diagonal before elimination) is recorded in s_lost
+    const int tx = tid & 255, ty = tid >> 8;
+    auto factor = [&]() {
+        for (int k = 0; k < r; ++k) {
+            double p = Gp[pidx(k, k)];
+            if (tid == 0 && !(p > 1e-12 * rdiag[k])) s_lost = 1;
+            if (!(p > 0.0)) {
+                if (tid == 0 && s_bad == 0) s_bad = k + 1;
+                p = 1.0;
+            }
+            if (tx > k && tx < r) {
+                double pinv = __builtin_amdgcn_rcp(p);
+                pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
+                pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
+                const double f = Gp[pidx(k, tx)] * pinv;
+                const int rowk = pidx(k, k) - k;          // Gp[rowk + ga] = G[k][ga]
+                for (int ga0 = k + 1 + ty; ga0 <= tx; ga0 += 32) {
+                    double gk[8], gg[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int ga = ga0 + 4 * u;
+                        const bool ok = ga <= tx;
+                        gk[u] = ok ? Gp[rowk + ga] : 0.0;
+                        gg[u] = ok ? Gp[pidx(ga, tx)] : 0.0;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int ga = ga0 + 4 * u;
+                        if (ga <= tx) Gp[pidx(ga, tx)] = fma(-gk[u], f, gg[u]);
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    };
+    double dev = sum_gram();
     __syncthreads();
     if (pass == 0) {
+        // Plain Cholesky first; only if a pivot is lost is the Gram matrix summed again, shifted and
+        // factored once more (the same policy as the r <= 64 path).
         if (tid == 0) {
             double tr = 0.0;
             for (int k = 0; k < r; ++k) tr += Gp[pidx(k, k)];
             s_trace = tr;
             jb.scal[0] = tr;
         }
+        if (tid < r) rdiag[tid] = Gp[pidx(tid, tid)];
         __syncthreads();
-        const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * s_trace;
-        if (tid < r) Gp[pidx(tid, tid)] += shift;
-        __syncthreads();
-    } else if (tid == 0) {
-        s_trace = jb.scal[0];
-    }
-    const int tx = tid & 255, ty = tid >> 8;
-    for (int k = 0; k < r; ++k) {
-        double p = Gp[pidx(k, k)];
-        if (!(p > 0.0)) {
-            if (tid == 0 && s_bad == 0) s_bad = k + 1;
-            p = 1.0;
+        factor();
+        if (s_lost) {
+            __syncthreads();
+            if (tid == 0) { s_bad = 0; s_lost = 0; }
+            sum_gram();
+            __syncthreads();
+            const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * s_trace;
+            if (tid < r) Gp[pidx(tid, tid)] += shift;
+            __syncthreads();
+            factor();
         }
-        if (tx > k && tx < r) {
-            double pinv = __builtin_amdgcn_rcp(p);
-            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
-            pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
-            const double f = Gp[pidx(k, tx)] * pinv;
-            const int rowk = pidx(k, k) - k;          // Gp[rowk + ga] = G[k][ga]
-            for (int ga0 = k + 1 + ty; ga0 <= tx; ga0 += 32) {
-                double gk[8], gg[8];
+    } else {
+        // Second pass: if Q0 is orthonormal to 1e-7 already, its fp32 copy (written by the first solve)
+        // is the result and the final solve returns at once.
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int ga = ga0 + 4 * u;
-                    const bool ok = ga <= tx;
-                    gk[u] = ok ? Gp[rowk + ga] : 0.0;
-                    gg[u] = ok ? Gp[pidx(ga, tx)] : 0.0;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int ga = ga0 + 4 * u;
-                    if (ga <= tx) Gp[pidx(ga, tx)] = fma(-gk[u], f, gg[u]);
-                }
+        for (int m = 32; m >= 1; m >>= 1) dev = fmax(dev, __shfl_xor(dev, m));
+        if ((tid & 63) == 0) s_red[tid >> 6] = dev;
+        __syncthreads();
+        dev = 0.0;
+        for (int w = 0; w < 16; ++w) dev = fmax(dev, s_red[w]);
+        const bool done = dev <= OP_DONE_TOL;
+        if (tid == 0) {
+            jb.scal[2 + OW_RMAX] = done ? 1.0 : 0.0;
+            s_trace = jb.scal[0];
+            if (done && last && jb.info) {
+                const double bad = jb.scal[1 + OW_RMAX];
+                if (bad != 0.0) flag_info(jb.info, jb.mode1, (int)bad);
+                const double floor_ = 1e-12 * sqrt(s_trace);
+                for (int k = 0; k < r; ++k)
+                    if (!(jb.scal[1 + k] > floor_)) { flag_info(jb.info, jb.mode1, k + 1); break; }
             }
         }
+        if (done) return;
+        if (tid < r) rdiag[tid] = Gp[pidx(tid, tid)];
         __syncthreads();
+        factor();
     }
     if (tid < r) {
         double p = Gp[pidx(tid, tid)];
@@ -897,6 +945,8 @@ __global__ __launch_bounds__(128) void k_orthw_apply(OrthBatch a, int final_pass
     int ji, blk;
     find_job(a, &ji, &blk);
     const OrthJob jb = a.job[ji];
+    // the first pass was found to be orthonormal already: its fp32 copy is the result
+    if (final_pass && jb.scal[2 + OW_RMAX] != 0.0) return;
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     const int nb = (r + 15) / 16;
@@ -960,7 +1010,11 @@ __global__ __launch_bounds__(128) void k_orthw_apply(OrthBatch a, int final_pass
     if (final_pass) {
         for (int idx = tid; idx < nrows * r; idx += 128) jb.Uout[(long long)i0 * r + idx] = (float)Ps[idx / r][idx % r];
     } else {
-        for (int idx = tid; idx < nrows * r; idx += 128) jb.P64[(long long)i0 * r + idx] = Ps[idx / r][idx % r];
+        for (int idx = tid; idx < nrows * r; idx += 128) {
+            const double q0 = Ps[idx / r][idx % r];
+            jb.P64[(long long)i0 * r + idx] = q0;
+            jb.Uout[(long long)i0 * r + idx] = (float)q0;
+        }
     }
 }
 

@@ -193,7 +193,7 @@ def test_edge_conv_shapes(case, dtype):
 
 
 EDGE_LINEAR = [((3, 5, 7), (2, 3, 4), 6), ((4, 9, 30), (4, 9, 30), 3), ((2, 33, 130), (1, 7, 20), 70),
-               ((64, 1, 5), (3, 1, 2), 1)]
+               ((64, 1, 5), (3, 1, 2), 1), ((6, 50, 300), (3, 34, 100), 40)]      # the last: a rank above 64
 
 
 @pytest.mark.parametrize("case", EDGE_LINEAR)
@@ -264,34 +264,52 @@ def test_rank_deficient_input_sets_info():
     assert int(run.info.item()) == 0
 
 
-@pytest.mark.parametrize("ratio", [1e-1, 1e-2, 3e-3])
-def test_ill_conditioned_subspace_product_stays_orthonormal(ratio):
-    """cond(P), P = A_m (A_m^T U), grows like ratio^-3 here: ~1e3 at 0.1 (settled by the first
-    Cholesky-QR pass), up to 1e6 at 0.01 (needs the second pass), 5e7 at 0.003 (mode 2 loses a
-    pivot to the 1e-12 threshold in the plain factorisation and takes the shifted one).  The basis must come out orthonormal to fp32 rounding on every route, and must
-    contain the dominant directions the oracle finds (the weakest ones are below the fp32 rounding
-    of V and are not comparable)."""
-    lay = Layer("illcond", (16, 40, 9, 9), (6, 12, 4, 4), "f32", "conv2d", 8, k=3, pad=1)
-    rng = np.random.default_rng(20250505)
-    core = rng.standard_normal(lay.ranks)
-    A = core
+def _graded_tensor(lay, ratio, seed=20250505):
+    """Tucker tensor whose factor columns decay geometrically to `ratio`: an ill-conditioned P."""
+    rng = np.random.default_rng(seed)
+    A = rng.standard_normal(lay.ranks)
     for m, (n, r) in enumerate(zip(lay.dims, lay.ranks)):
         q, _ = np.linalg.qr(rng.standard_normal((n, r)))
         q = q * (ratio ** (np.arange(r) / (r - 1)))[None, :]       # column j scaled by ratio^(j/(r-1))
         A = np.moveaxis(np.tensordot(q, A, axes=(1, m)), 0, m)
-    A = (A / np.max(np.abs(A))).astype(np.float32)
-    st = LayerStream(9, 7, lay)
+    return (A / np.max(np.abs(A))).astype(np.float32)
+
+
+def _check_orthonormal_basis(lay, A, stream_id, tag):
+    st = LayerStream(9, stream_id, lay)
     run = _runner(lay)
     run.set_factors(st.u_prev0())
     U_gpu = run.compress(run.upload(A))
     torch.cuda.synchronize()
-    assert int(run.info.item()) == 0
+    assert int(run.info.item()) == 0, tag
     U_or = O.compress(A.astype(F64), [u.astype(F64) for u in st.u_prev0()])
     for m, (ug, uo) in enumerate(zip(U_gpu, U_or)):
         ug = _np(ug)
         assert np.all(np.isfinite(ug))
         eo = np.max(np.abs(ug.T @ ug - np.eye(ug.shape[1])))
-        assert eo < 1e-5, f"ratio {ratio} mode {m}: U^T U - I = {eo:.2e}"
+        assert eo < 1e-5, f"{tag} mode {m}: U^T U - I = {eo:.2e}"
         lead = uo[:, :2]                                           # QR keeps the column order of P
         out = np.linalg.norm(lead - ug @ (ug.T @ lead))
-        assert out < 1e-3, f"ratio {ratio} mode {m}: dominant directions outside the basis by {out:.2e}"
+        assert out < 1e-3, f"{tag} mode {m}: dominant directions outside the basis by {out:.2e}"
+
+
+@pytest.mark.parametrize("ratio", [1e-1, 1e-2, 3e-3])
+def test_ill_conditioned_subspace_product_stays_orthonormal(ratio):
+    """cond(P), P = A_m (A_m^T U), grows like ratio^-3 here: ~1e3 at 0.1 (settled by the first
+    Cholesky-QR pass), up to 1e6 at 0.01 (needs the second pass), 5e7 at 0.003 (mode 2 loses a
+    pivot to the 1e-12 threshold in the plain factorisation and takes the shifted one).
+    The basis must come out orthonormal to fp32 rounding on every route, and must
+    contain the dominant directions the oracle finds (the weakest ones are below the fp32 rounding
+    of V and are not comparable)."""
+    lay = Layer("illcond", (16, 40, 9, 9), (6, 12, 4, 4), "f32", "conv2d", 8, k=3, pad=1)
+    _check_orthonormal_basis(lay, _graded_tensor(lay, ratio), 7, f"ratio {ratio}")
+
+
+@pytest.mark.parametrize("ratio", [0.3, 0.05])
+def test_ill_conditioned_wide_rank_stays_orthonormal(ratio):
+    """The same for a rank above 64 (the wide orthogonalisation kernels): for the 90-column mode
+    cond(P) is 4e5 at 0.3 (second pass needed) and 5e8 at 0.05 (a pivot falls below 1e-12 of its
+    diagonal entry: shifted retry).  The well-conditioned route of these kernels (second pass
+    skipped) is covered by the rank-100 case of the linear edge shapes."""
+    lay = Layer("illcond", (8, 40, 260), (6, 16, 90), "f32", "linear", 12)
+    _check_orthonormal_basis(lay, _graded_tensor(lay, ratio), 8, f"wide ratio {ratio}")
