@@ -126,7 +126,28 @@ __device__ __forceinline__ int small_div(int e, float inv_r) { return (int)(((fl
 #else
 #define BSTAMP(i) do {} while (0)
 #endif
-__device__ void chol_block16(double (*Gs)[OP_LD], double (*rowbuf)[64][4], double (*Xb)[17], double* pinvs, int base,
+// The matrix is reached through an accessor (ld(row, col), st(row, col, value)): a square LDS array
+// for r <= 64, the packed upper triangle for wider matrices.  Only entries with row <= col are used.
+struct GramSquare {
+    double (*Gs)[OP_LD];
+    __device__ __forceinline__ double ld(int row, int col) const { return Gs[row][col]; }
+    __device__ __forceinline__ void st(int row, int col, double v) const { Gs[row][col] = v; }
+};
+struct GramPacked {                      // row-wise packed upper triangle of an r x r matrix, identity beyond r
+    double* Gp;
+    int r;
+    __device__ __forceinline__ int idx(int row, int col) const { return row * r - (row * (row - 1)) / 2 + (col - row); }
+    __device__ __forceinline__ double ld(int row, int col) const {
+        const bool in = row <= col && col < r;
+        const double v = Gp[in ? idx(row, col) : 0];
+        return in ? v : (row == col ? 1.0 : 0.0);
+    }
+    __device__ __forceinline__ void st(int row, int col, double v) const {
+        if (row <= col && col < r) Gp[idx(row, col)] = v;
+    }
+};
+template <class GA>
+__device__ void chol_block16(const GA G, double (*rowbuf)[64][4], double (*Xb)[17], double* pinvs, int base,
                              int* bad_io, bool dbg = false) {
     const int j = threadIdx.x;          // 0..63
     BSTAMP(20);
@@ -138,7 +159,7 @@ __device__ void chol_block16(double (*Gs)[OP_LD], double (*rowbuf)[64][4], doubl
         // round trip per row; the empty asm pins the reads in front of the selects.
         double g[16];
 #pragma unroll
-        for (int a2 = 0; a2 < 16; ++a2) g[a2] = Gs[base + a2][base + (j & 15)];
+        for (int a2 = 0; a2 < 16; ++a2) g[a2] = G.ld(base + a2, base + (j & 15));
 #pragma unroll
         for (int a2 = 0; a2 < 16; ++a2) asm volatile("" : "+v"(g[a2]));
 #pragma unroll
@@ -209,11 +230,12 @@ __device__ void chol_block16(double (*Gs)[OP_LD], double (*rowbuf)[64][4], doubl
     *bad_io = bad;
     // lanes 0..15 write their column of the block (entries below the diagonal are never read again),
     // lanes 48..63 their row of the inverse factor: one run of stores for both
-    if (j < 16 || xl) {
-        double* dst = xl ? &Xb[j - 48][0] : &Gs[base][base + j];
-        const int step = xl ? 1 : OP_LD;
+    if (xl) {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) dst[k * step] = col[k];
+        for (int k = 0; k < 16; ++k) Xb[j - 48][k] = col[k];
+    } else if (j < 16) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) G.st(base + k, base + j, col[k]);
     }
     BSTAMP(27);
 }
@@ -299,9 +321,9 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
     auto factor = [&]() {
         for (int P = 0; P < nb; ++P) {
     #ifdef ASI_DEBUG_TIMING
-            if (wave == 0) chol_block16(Gs, rowbuf, Xs[P], pinvs, 16 * P, &bad, P == 0 && jb.mode1 == 2 && pass == 0);
+            if (wave == 0) chol_block16(GramSquare{Gs}, rowbuf, Xs[P], pinvs, 16 * P, &bad, P == 0 && jb.mode1 == 2 && pass == 0);
     #else
-            if (wave == 0) chol_block16(Gs, rowbuf, Xs[P], pinvs, 16 * P, &bad);
+            if (wave == 0) chol_block16(GramSquare{Gs}, rowbuf, Xs[P], pinvs, 16 * P, &bad);
     #endif
             if (P == 0) STAMP(6);
             __syncthreads();
@@ -787,58 +809,91 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
     // Gp = sum of the slice Grams; returns this thread's share of max |G - I|
     auto sum_gram = [&]() {
         double dev = 0.0;
-        for (int e = tid; e < r * r; e += 1024) {
-            const int ga = e / r, gb = e - ga * r;
-            if (ga <= gb) {
-                double s = 0.0;
-                for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
-                    double t[8];
+        // four elements per thread and round, eight slices each: 32 loads in flight
+        for (int e0 = tid; e0 < r * r; e0 += 4 * 1024) {
+            double s[4] = {0.0, 0.0, 0.0, 0.0};
+            for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
+                double t[4][8];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) t[u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, b0 + u < jb.nblk);
+                for (int c = 0; c < 4; ++c)
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) s += t[u];
+                    for (int u = 0; u < 8; ++u) {
+                        const int e = e0 + 1024 * c;
+                        t[c][u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, e < r * r && b0 + u < jb.nblk);
+                    }
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) s[c] += t[c][u];
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int e = e0 + 1024 * c;
+                const int ga = e / r, gb = e - ga * r;
+                if (e < r * r && ga <= gb) {
+                    Gp[pidx(ga, gb)] = s[c];
+                    dev = fmax(dev, fabs(s[c] - (ga == gb ? 1.0 : 0.0)));
                 }
-                Gp[pidx(ga, gb)] = s;
-                dev = fmax(dev, fabs(s - (ga == gb ? 1.0 : 0.0)));
             }
         }
         return dev;
     };
-    // unblocked right-looking factorisation in place; a pivot that is not above 1e-12 of its diagonal
-    // entry (rdiag holds the diagonal before elimination) is recorded in s_lost
-    const int tx = tid & 255, ty = tid >> 8;
+    // Blocked right-looking factorisation in place, the scheme of the r <= 64 path on the packed
+    // triangle: wave 0 factors a 16x16 diagonal block in registers (chol_block16, which also leaves
+    // the inverse of the block's unit triangular factor in Xs and the pivots' reciprocals in pinvs),
+    // then the 16 waves solve the block row and update the trailing blocks on fp64 MFMA.  Rows are
+    // left unscaled (row k holds R[k][j] R[k][k], the diagonal the pivots R[k][k]^2).  A pivot that is
+    // not above 1e-12 of its diagonal entry (rdiag holds the diagonal before elimination) sets s_lost.
+    const int nb = (r + 15) / 16;
+    double* pinvs = rdiag + r;                               // nb * 16
+    double (*Xs)[17] = reinterpret_cast<double (*)[17]>(pinvs + nb * 16);
+    double (*rowbuf)[64][4] = reinterpret_cast<double (*)[64][4]>(pinvs + nb * 16 + 16 * 17);
+    const GramPacked G{Gp, r};
+    const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     auto factor = [&]() {
-        for (int k = 0; k < r; ++k) {
-            double p = Gp[pidx(k, k)];
-            if (tid == 0 && !(p > 1e-12 * rdiag[k])) s_lost = 1;
-            if (!(p > 0.0)) {
-                if (tid == 0 && s_bad == 0) s_bad = k + 1;
-                p = 1.0;
-            }
-            if (tx > k && tx < r) {
-                double pinv = __builtin_amdgcn_rcp(p);
-                pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
-                pinv = fma(fma(-p, pinv, 1.0), pinv, pinv);
-                const double f = Gp[pidx(k, tx)] * pinv;
-                const int rowk = pidx(k, k) - k;          // Gp[rowk + ga] = G[k][ga]
-                for (int ga0 = k + 1 + ty; ga0 <= tx; ga0 += 32) {
-                    double gk[8], gg[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int ga = ga0 + 4 * u;
-                        const bool ok = ga <= tx;
-                        gk[u] = ok ? Gp[rowk + ga] : 0.0;
-                        gg[u] = ok ? Gp[pidx(ga, tx)] : 0.0;
-                    }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int ga = ga0 + 4 * u;
-                        if (ga <= tx) Gp[pidx(ga, tx)] = fma(-gk[u], f, gg[u]);
-                    }
-                }
-            }
+        int bad = 0;
+        for (int P = 0; P < nb; ++P) {
+            if (wave == 0) chol_block16(G, rowbuf, Xs, pinvs, 16 * P, &bad);
             __syncthreads();
+            if (tid < 16 && 16 * P + tid < r) {
+                const double p = G.ld(16 * P + tid, 16 * P + tid);          // the pivot actually used
+                if (!(p > 1e-12 * rdiag[16 * P + tid])) s_lost = 1;
+            }
+            if (P + 1 < nb) {
+                // block row P right of the diagonal:  U_PJ = L_PP^-1 G_PJ
+                for (int J = P + 1 + wave; J < nb; J += 16) {
+                    double bv[4];
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) bv[ks] = G.ld(16 * P + 4 * ks + lg, 16 * J + ll);
+                    v4d acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)      // A[i][k] = (L^-1)[i][k] = Xs[k][i]
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Xs[4 * ks + lg][ll], bv[ks], acc, 0, 0, 0);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) G.st(16 * P + lg + 4 * v, 16 * J + ll, acc[v]);
+                }
+                __syncthreads();
+                // trailing blocks:  G_IJ -= U_PI^T diag(1/pivot) U_PJ,  P < I <= J
+                int cnt = 0;
+                for (int I = P + 1; I < nb; ++I)
+                    for (int J = I; J < nb; ++J, ++cnt) {
+                        if ((cnt & 15) != wave) continue;
+                        v4d acc;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[v] = G.ld(16 * I + lg + 4 * v, 16 * J + ll);
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks) {
+                            const int k = 16 * P + 4 * ks + lg;
+                            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-G.ld(k, 16 * I + ll), G.ld(k, 16 * J + ll) * pinvs[k], acc, 0, 0, 0);
+                        }
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) G.st(16 * I + lg + 4 * v, 16 * J + ll, acc[v]);
+                    }
+                __syncthreads();
+            }
         }
+        if (tid == 0) s_bad = bad;
+        __syncthreads();
     };
     double dev = sum_gram();
     __syncthreads();
@@ -854,7 +909,7 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
         if (tid < r) rdiag[tid] = Gp[pidx(tid, tid)];
         __syncthreads();
         factor();
-        if (s_lost) {
+        if (s_lost || s_bad) {
             __syncthreads();
             if (tid == 0) { s_bad = 0; s_lost = 0; }
             sum_gram();
@@ -913,7 +968,6 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
         if (ga < gb) Gp[pidx(ga, gb)] *= dinv[ga];
     }
     __syncthreads();
-    const int nb = (r + 15) / 16;
     if (tid < nb * 16) {
         const int b = tid >> 4, i = tid & 15, base = 16 * b;
         double x[16];
@@ -1252,7 +1306,9 @@ hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st, ch
             hipLaunchKernelGGL(k_orthw_gram, grid, 256, 0, st, b);
             break;
         case IT_ORTHW_CHOL: {
-            const size_t lds = sizeof(double) * ((size_t)rmax * (rmax + 1) / 2 + 2 * (size_t)rmax);
+            // packed triangle, dinv, rdiag, pivot reciprocals, inverse block factor, row exchange buffer
+            const size_t nb16 = (size_t)((rmax + 15) / 16) * 16;
+            const size_t lds = sizeof(double) * ((size_t)rmax * (rmax + 1) / 2 + 2 * (size_t)rmax + nb16 + 16 * 17 + 2 * 64 * 4);
             static size_t lds_allowed = 0;                 // the attribute only ever needs to grow
             if (lds > lds_allowed) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_orthw_chol),
