@@ -22,6 +22,13 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr int CR_TO = 64;            // output channels per workgroup
 constexpr int CR_KC = 64;            // output positions per chunk
 constexpr int CR_ZMAX = 4096;        // floats of LDS for the Z slab
+// Waves per workgroup: 4 own 16 output channels each; with 8 the second four take every other
+// K step of a chunk on accumulators of their own (summed through LDS at the end).  One wave per
+// SIMD cannot overlap its operand reads and address arithmetic with its products (a step costs
+// their sum, ~55-63 cycles per MFMA against 32); two waves per SIMD fill each other's gaps.
+constexpr int CR_NW = 8;
+constexpr int CR_NT = 64 * CR_NW;
+constexpr int CR_KG = CR_NW / 4;     // K-step groups
 
 struct CorrPlan {
     int ry;          // output rows per chunk
@@ -92,11 +99,11 @@ extern "C" int asi_debug_corr_stamps(long long* out) {
 #endif
 
 template <int MAXT, bool EXACT>
-__global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
-    // As | Zs during the K loop; afterwards (kernels of up to 9 taps) the 64 x (16 taps) result tile
-    constexpr int CR_TS_LD = 16 * MAXT + 1;
-    constexpr int CR_LDS = (MAXT <= 9 && CR_TO * CR_TS_LD > CR_KC * (CR_TO + 1) + CR_ZMAX) ? CR_TO * CR_TS_LD
-                                                                                           : CR_KC * (CR_TO + 1) + CR_ZMAX;
+__global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
+    // As | Zs during the K loop; afterwards the 64 x (16 x up to 9 taps) result tile
+    constexpr int CR_TG = MAXT < 9 ? MAXT : 9;           // taps per pass of the result through LDS
+    constexpr int CR_TS_LD = 16 * CR_TG + 1;
+    constexpr int CR_LDS = (CR_TO * CR_TS_LD > CR_KC * (CR_TO + 1) + CR_ZMAX) ? CR_TO * CR_TS_LD : CR_KC * (CR_TO + 1) + CR_ZMAX;
     __shared__ float lds_raw[CR_LDS];
     float (*As)[CR_TO + 1] = reinterpret_cast<float (*)[CR_TO + 1]>(lds_raw);
     float* Zs = lds_raw + CR_KC * (CR_TO + 1);
@@ -108,7 +115,7 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
     const CorrGeom g = jb.g;
     const CorrPlan pl = jb.pl;
     const int bz = lb / (jb.gx * jb.gy), brem = lb - bz * (jb.gx * jb.gy), by = brem / jb.gx, bx = brem - by * jb.gx;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kgrp = tid >> 8, lg = lane >> 4, ll = lane & 15;
     const int taps = g.kh * g.kw;
     const int o0 = bx * CR_TO, j0 = by * 16, z = bz;
     const int HoWo = g.Ho * g.Wo;
@@ -128,7 +135,8 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
     const int ztotal = 16 * pl.slab;
     const float inv_slab = 1.0f / (float)pl.slab, inv_wp = 1.0f / (float)pl.wp, inv_wo = 1.0f / (float)g.Wo;
     const int row_step = g.sh * pl.wp;
-    float a_t[16], z_t[CR_ZMAX / 256];
+    constexpr int NA = CR_KC * CR_TO / CR_NT, NZ = CR_ZMAX / CR_NT;     // loads per thread and chunk
+    float a_t[NA], z_t[NZ];
     // loads of one chunk into registers: the G1 tile (64 channels x kcv positions, contiguous
     // along k) and the Z slab with its zero halo (rows ylo.., columns -pw..)
     auto fetch = [&](int ch) {
@@ -138,14 +146,14 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
         const int kcv = rows * g.Wo;
         const int k = tid & 63;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int o = o0 + (tid >> 6) + 4 * u;
+        for (int u = 0; u < NA; ++u) {
+            const int o = o0 + (tid >> 6) + CR_NW * u;
             a_t[u] = ldg_f32(G1, (i * g.cout + o) * HoWo + y0 * g.Wo + k, k < kcv && o < g.cout);
         }
         const int ylo = y0 * g.sh - g.ph;
 #pragma unroll
-        for (int u = 0; u < CR_ZMAX / 256; ++u) {
-            const int e = u * 256 + tid;
+        for (int u = 0; u < NZ; ++u) {
+            const int e = u * CR_NT + tid;
             // e < 4096: the rounded float quotient is exact, no integer division needed
             const int jl = (int)(((float)e + 0.5f) * inv_slab), rem = e - jl * pl.slab;
             const int rr = (int)(((float)rem + 0.5f) * inv_wp), cc = rem - rr * pl.wp;
@@ -168,10 +176,10 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
         const int kcv = rows * g.Wo;                       // valid positions in this chunk
         __syncthreads();                                   // previous chunk consumed
 #pragma unroll
-        for (int u = 0; u < 16; ++u) As[tid & 63][(tid >> 6) + 4 * u] = a_t[u];
+        for (int u = 0; u < NA; ++u) As[tid & 63][(tid >> 6) + CR_NW * u] = a_t[u];
 #pragma unroll
-        for (int u = 0; u < CR_ZMAX / 256; ++u) {
-            const int e = u * 256 + tid;
+        for (int u = 0; u < NZ; ++u) {
+            const int e = u * CR_NT + tid;
             const int jl = (int)(((float)e + 0.5f) * inv_slab);
             if (e < ztotal) Zs[e + jl * (pl.zld - pl.slab)] = z_t[u];
         }
@@ -187,14 +195,20 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
         // once per product.  The step count is rounded up to even: positions past the chunk's end
         // have zero A values (the loader's predicate) and read the slab origin, so they add nothing,
         // and the loop body stays free of branches.
-        const int nks2 = ((kcv + 7) >> 3) << 1;
+        // steps of this wave's K group: ks = kgrp, kgrp + CR_KG, ...; their number is rounded up to even
+        const int nsteps = (((kcv + 3) >> 2) + CR_KG - 1) / CR_KG;
+        const int nst2 = (nsteps + 1) & ~1;
         const int zbase = ll * pl.zld;
-        auto operands = [&](int ks, float& a, float (&bq)[MAXT]) {
+        auto operands = [&](int st, float& a, float (&bq)[MAXT]) {
+            int ks = st * CR_KG + kgrp;
+            ks = ks < CR_KC / 4 ? ks : CR_KC / 4 - 1;          // only the read-ahead past the last step is clamped
             const int k = 4 * ks + lg;
             // window origin of position k inside the slab: (k / Wo) * sh * wp + (k % Wo) * sw
             // (24-bit multiplies: one instruction each, and every factor here is far below 2^23)
             const int yl = (int)(((float)k + 0.5f) * inv_wo), x = k - __mul24(yl, g.Wo);
-            a = As[k][16 * wave + ll];
+            // (a 24-bit multiply here too: the 64-bit multiply-add the compiler would pick takes a
+            // register of the next chunk's loads as its unused upper addend and waits for them)
+            a = lds_raw[__mul24(k, CR_TO + 1) + 16 * wave + ll];   // As[k][..]; rows past the chunk's end are zero
             const int org = __mul24(yl, row_step) + __mul24(x, g.sw);
             const int zo = zbase + ((yl < pl.ry) ? org : 0);
 #pragma unroll
@@ -203,12 +217,12 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
         float a0, a1, b0[MAXT], b1[MAXT];
         operands(0, a0, b0);
 #pragma unroll 1
-        for (int ks = 0; ks < nks2; ks += 2) {
-            operands(ks + 1, a1, b1);
+        for (int st = 0; st < nst2; st += 2) {
+            operands(st + 1, a1, b1);
 #pragma unroll
             for (int t = 0; t < MAXT; ++t)
                 if (EXACT || t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[t], acc[t], 0, 0, 0);
-            operands(ks + 2 < CR_KC / 4 ? ks + 2 : CR_KC / 4 - 1, a0, b0);
+            operands(st + 2, a0, b0);
 #pragma unroll
             for (int t = 0; t < MAXT; ++t)
                 if (EXACT || t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[t], acc[t], 0, 0, 0);
@@ -223,44 +237,46 @@ __global__ __launch_bounds__(256, 2) void k_corr_mfma(Batch<CorrJob> bt) {
     if (threadIdx.x == 0 && blockIdx.x == 0) g_corr_stamps[61] = clock64();
 #endif
     // lane holds o = o0 + 16w + 4*lg + v, j = j0 + ll
+    // The result goes through LDS, up to 9 taps at a time: the K groups add their tiles there, and
+    // for one output channel the (j, tap) values of this workgroup are then one contiguous run of T
+    // (stored straight from the accumulators every lane of a store would hit its own cache line:
+    // the taps are innermost, lanes differ in j and o).
     const long long total = (long long)g.cout * g.r2 * taps;
-    if constexpr (MAXT <= 9) {
-        // For one output channel the (j, tap) values of this workgroup are one contiguous run of T.
-        // Stored straight from the accumulators every lane of a store would hit its own cache line
-        // (the taps are innermost, lanes differ in j and o); through LDS the stores are contiguous.
-        __syncthreads();                                   // the last chunk's tiles are no longer read
-        float* Ts = lds_raw;
+    const int nj = (g.r2 - j0 < 16) ? g.r2 - j0 : 16;
+    float* Ts = lds_raw;
 #pragma unroll
-        for (int t = 0; t < MAXT; ++t)
-            if (t < taps) {
+    for (int t0 = 0; t0 < MAXT; t0 += CR_TG) {
+        if (t0 < taps) {
+            const int tg = (taps - t0 < CR_TG) ? taps - t0 : CR_TG;
+            __syncthreads();                               // the tiles (or the previous pass) are no longer read
 #pragma unroll
-                for (int v = 0; v < 4; ++v) Ts[(16 * wave + 4 * lg + v) * CR_TS_LD + ll * taps + t] = acc[t][v];
-            }
-        __syncthreads();
-        const int nj = (g.r2 - j0 < 16) ? g.r2 - j0 : 16;
-        const int rowlen = nj * taps;                      // <= 144
-        const float inv_rowlen = 1.0f / (float)rowlen;
-        for (int e = tid; e < CR_TO * rowlen; e += 256) {   // e < 9216: the rounded float quotient is exact
-            const int ol = (int)(((float)e + 0.5f) * inv_rowlen), c = e - ol * rowlen;
-            const int o = o0 + ol;
-            if (o < g.cout) Tpart[(long long)z * total + ((long long)o * g.r2 + j0) * taps + c] = Ts[ol * CR_TS_LD + c];
-        }
-    } else {
+            for (int kg = CR_KG - 1; kg >= 0; --kg) {      // the K groups add their tiles one after the other
+                if (kgrp == kg) {
 #pragma unroll
-        for (int t = 0; t < MAXT; ++t) {
-            if (t < taps) {
+                    for (int tt = 0; tt < CR_TG; ++tt)
+                        if (t0 + tt < MAXT && tt < tg) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int o = o0 + 16 * wave + 4 * lg + v, j = j0 + ll;
-                    if (o < g.cout && j < g.r2) Tpart[(long long)z * total + ((long long)o * g.r2 + j) * taps + t] = acc[t][v];
+                            for (int v = 0; v < 4; ++v) {
+                                float* p = &Ts[(16 * wave + 4 * lg + v) * CR_TS_LD + ll * tg + tt];
+                                *p = (kg == CR_KG - 1) ? acc[(t0 + tt < MAXT) ? t0 + tt : 0][v]
+                                                       : *p + acc[(t0 + tt < MAXT) ? t0 + tt : 0][v];
+                            }
+                        }
                 }
+                __syncthreads();
+            }
+            const int rowlen = nj * tg;                    // <= 144
+            const float inv_rowlen = 1.0f / (float)rowlen, inv_tg = 1.0f / (float)tg;
+            for (int e = tid; e < CR_TO * rowlen; e += CR_NT) {   // e < 9216: the rounded float quotients are exact
+                const int ol = (int)(((float)e + 0.5f) * inv_rowlen), c = e - ol * rowlen;
+                const int jl = (int)(((float)c + 0.5f) * inv_tg), tt = c - jl * tg;
+                const int o = o0 + ol;
+                if (o < g.cout)
+                    Tpart[(long long)z * total + ((long long)o * g.r2 + j0 + jl) * taps + t0 + tt] = Ts[ol * CR_TS_LD + c];
             }
         }
     }
-#ifdef ASI_DEBUG_TIMING
-    __threadfence();
     CSTAMP(63);
-#endif
 }
 
 // one thread per T[o,j,kh,kw] and split of the r1 axis: any geometry
@@ -351,10 +367,10 @@ hipError_t launch_corr_items(const Item* const* items, int n, hipStream_t st) {
         return hipGetLastError();
     }
     switch (items[0]->key) {
-        case 0: hipLaunchKernelGGL((k_corr_mfma<1, true>), grid, 256, 0, st, b); break;
-        case 1: hipLaunchKernelGGL((k_corr_mfma<9, true>), grid, 256, 0, st, b); break;
-        case 2: hipLaunchKernelGGL((k_corr_mfma<9, false>), grid, 256, 0, st, b); break;
-        default: hipLaunchKernelGGL((k_corr_mfma<25, false>), grid, 256, 0, st, b); break;
+        case 0: hipLaunchKernelGGL((k_corr_mfma<1, true>), grid, CR_NT, 0, st, b); break;
+        case 1: hipLaunchKernelGGL((k_corr_mfma<9, true>), grid, CR_NT, 0, st, b); break;
+        case 2: hipLaunchKernelGGL((k_corr_mfma<9, false>), grid, CR_NT, 0, st, b); break;
+        default: hipLaunchKernelGGL((k_corr_mfma<25, false>), grid, CR_NT, 0, st, b); break;
     }
     return hipGetLastError();
 }
