@@ -20,10 +20,14 @@ namespace asi {
 // fp32 values are widened to fp64, so every product is exact and the sums are carried in fp64.
 // ---------------------------------------------------------------------------
 constexpr int PR_TI = 64, PR_TQ = 32, PR_TK = 64;
+// Waves per workgroup: 4 own 16 rows of the tile each; the second four take every other K step of
+// a chunk on accumulators of their own, added through LDS at the end.  One wave per SIMD pays its
+// operand reads and conversions on top of its products; two waves per SIMD overlap them.
+constexpr int PR_NW = 8, PR_NT = 64 * PR_NW, PR_KG = PR_NW / 4;
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 template <typename T, bool LASTMODE>
-__global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
+__global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
     __shared__ float Xs[PR_TK][PR_TI + 4];
     __shared__ float Ys[PR_TK][PR_TQ + 4];
     int lb;
@@ -34,7 +38,7 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
     const long long outer = jb.outer, inner = jb.inner, cols_per_split = jb.cols_per_split;
     const int n = jb.n, r = jb.r;
     if (lb >= jb.gx * jb.gy * jb.gz) {             // extra workgroups: another mode's partial-sum tree
-        presum_block(jb.pre.job, jb.pre.njobs, lb - jb.gx * jb.gy * jb.gz);
+        if (threadIdx.x < 256) presum_block(jb.pre.job, jb.pre.njobs, lb - jb.gx * jb.gy * jb.gz);
         return;
     }
     lb = xcd_order(lb, jb.gx * jb.gy * jb.gz);      // the tiles of one split share its columns of X and V
@@ -43,10 +47,10 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
     const int i0 = bx * PR_TI, q0 = by * PR_TQ, s = bz;
     const long long cbeg = (long long)s * cols_per_split;
     const long long cend = (cbeg + cols_per_split < ncols) ? cbeg + cols_per_split : ncols;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kgrp = tid >> 8, lg = lane >> 4, ll = lane & 15;
     if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;   // arrival counters of later launches
 
-    constexpr int NX = PR_TI * PR_TK / 256, NY = PR_TQ * PR_TK / 256, RS = 256 / PR_TK;   // loads per thread, row step
+    constexpr int NX = PR_TI * PR_TK / PR_NT, NY = PR_TQ * PR_TK / PR_NT, RS = PR_NT / PR_TK;   // loads per thread, row step
     float xr[NX], yr[NY];
     auto fetch = [&](long long c0) {
         if (!LASTMODE) {
@@ -73,13 +77,13 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
             const int i = i0 + (tid & 63);
 #pragma unroll
             for (int t = 0; t < NX; ++t) {
-                const long long c = c0 + (tid >> 6) + 4 * t;
+                const long long c = c0 + (tid >> 6) + PR_NW * t;
                 xr[t] = ldg_f32(X, c * (long long)n + i, c < cend && i < n);
             }
             const int q = q0 + (tid & 31);
 #pragma unroll
             for (int t = 0; t < NY; ++t) {
-                const long long c = c0 + (tid >> 5) + 8 * t;
+                const long long c = c0 + (tid >> 5) + 2 * PR_NW * t;
                 yr[t] = ldg_f32(Y, c * (long long)r + q, c < cend && q < r);
             }
         }
@@ -93,9 +97,9 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
             for (int t = 0; t < NY; ++t) Ys[cl][tid / PR_TK + RS * t] = yr[t];
         } else {
 #pragma unroll
-            for (int t = 0; t < NX; ++t) Xs[(tid >> 6) + 4 * t][tid & 63] = xr[t];
+            for (int t = 0; t < NX; ++t) Xs[(tid >> 6) + PR_NW * t][tid & 63] = xr[t];
 #pragma unroll
-            for (int t = 0; t < NY; ++t) Ys[(tid >> 5) + 8 * t][tid & 31] = yr[t];
+            for (int t = 0; t < NY; ++t) Ys[(tid >> 5) + 2 * PR_NW * t][tid & 31] = yr[t];
         }
     };
 
@@ -107,19 +111,39 @@ __global__ __launch_bounds__(256) void k_pair(Batch<PairJob> bt) {
         __syncthreads();
         if (c0 + PR_TK < cend) fetch(c0 + PR_TK);
 #pragma unroll
-        for (int ks = 0; ks < PR_TK / 4; ++ks) {
+        for (int ks = kgrp; ks < PR_TK / 4; ks += PR_KG) {
             const double a = (double)Xs[4 * ks + lg][16 * wave + ll];
             acc[0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)Ys[4 * ks + lg][ll], acc[0], 0, 0, 0);
             acc[1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)Ys[4 * ks + lg][16 + ll], acc[1], 0, 0, 0);
         }
     }
+    // the K groups add their accumulators through LDS (the tiles are no longer read), then group 0 stores
+    double* red = reinterpret_cast<double*>(&Xs[0][0]);           // 64 x 32 doubles = 16 KB <= sizeof(Xs)
+    static_assert(sizeof(float) * PR_TK * (PR_TI + 4) >= sizeof(double) * PR_TI * PR_TQ, "reduction buffer fits the X tile");
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int kg = PR_KG - 1; kg >= 1; --kg) {
+        __syncthreads();
+        if (kgrp == kg) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int i = i0 + 16 * wave + lg + 4 * v, q = q0 + 16 * nb + ll;    // fp64 MFMA result layout
-            if (i < n && q < r) part[((long long)s * n + i) * r + q] = acc[nb][v];
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    double* p = red + (16 * wave + lg + 4 * v) * PR_TQ + 16 * nb + ll;
+                    *p = (kg == PR_KG - 1) ? acc[nb][v] : *p + acc[nb][v];
+                }
         }
+    }
+    __syncthreads();
+    if (kgrp == 0) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = i0 + 16 * wave + lg + 4 * v, q = q0 + 16 * nb + ll;    // fp64 MFMA result layout
+                const double sum = PR_KG > 1 ? acc[nb][v] + red[(16 * wave + lg + 4 * v) * PR_TQ + 16 * nb + ll] : acc[nb][v];
+                if (i < n && q < r) part[((long long)s * n + i) * r + q] = sum;
+            }
+    }
 }
 
 static long long pair_cols_per_split(long long ncols, int nsplit) {
@@ -185,11 +209,11 @@ hipError_t launch_pair_items(const Item* const* items, int n, hipStream_t st) {
     if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
     const unsigned key = items[0]->key;
     if (!(key & 1u)) {
-        if (key & 2u) hipLaunchKernelGGL((k_pair<float, true>), grid, 256, 0, st, b);
-        else          hipLaunchKernelGGL((k_pair<float, false>), grid, 256, 0, st, b);
+        if (key & 2u) hipLaunchKernelGGL((k_pair<float, true>), grid, PR_NT, 0, st, b);
+        else          hipLaunchKernelGGL((k_pair<float, false>), grid, PR_NT, 0, st, b);
     } else {
-        if (key & 2u) hipLaunchKernelGGL((k_pair<bf16_t, true>), grid, 256, 0, st, b);
-        else          hipLaunchKernelGGL((k_pair<bf16_t, false>), grid, 256, 0, st, b);
+        if (key & 2u) hipLaunchKernelGGL((k_pair<bf16_t, true>), grid, PR_NT, 0, st, b);
+        else          hipLaunchKernelGGL((k_pair<bf16_t, false>), grid, PR_NT, 0, st, b);
     }
     return hipGetLastError();
 }
