@@ -193,7 +193,8 @@ def test_edge_conv_shapes(case, dtype):
 
 
 EDGE_LINEAR = [((3, 5, 7), (2, 3, 4), 6), ((4, 9, 30), (4, 9, 30), 3), ((2, 33, 130), (1, 7, 20), 70),
-               ((64, 1, 5), (3, 1, 2), 1), ((6, 50, 300), (3, 34, 100), 40)]      # the last: a rank above 64
+               ((64, 1, 5), (3, 1, 2), 1), ((6, 50, 300), (3, 34, 100), 40),     # a rank above 64
+               ((3, 20, 600), (2, 8, 24), 50)]                                   # a last mode of 512 or more
 
 
 @pytest.mark.parametrize("case", EDGE_LINEAR)
