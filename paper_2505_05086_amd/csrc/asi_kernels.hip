@@ -41,8 +41,10 @@ __global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
         if (threadIdx.x < 256) presum_block(jb.pre.job, jb.pre.njobs, lb - jb.gx * jb.gy * jb.gz);
         return;
     }
-    lb = xcd_order(lb, jb.gx * jb.gy * jb.gz);      // the tiles of one split share its columns of X and V
-    const int bz = lb / (jb.gx * jb.gy), rem = lb - bz * (jb.gx * jb.gy), by = rem / jb.gx, bx = rem - by * jb.gx;
+    // Neighbouring blocks (one XCD after the renumbering) are the output tiles of the same rows of X,
+    // then the row tiles of the same split: the large operand is fetched from memory once.
+    lb = xcd_order(lb, jb.gx * jb.gy * jb.gz);
+    const int bz = lb / (jb.gx * jb.gy), rem = lb - bz * (jb.gx * jb.gy), bx = rem / jb.gy, by = rem - bx * jb.gy;
     const long long ncols = outer * inner;
     const int i0 = bx * PR_TI, q0 = by * PR_TQ, s = bz;
     const long long cbeg = (long long)s * cols_per_split;

@@ -48,7 +48,7 @@ __device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) 
     const long long outer = jb.outer, inner = jb.inner, ms_i = jb.ms_i, ms_q = jb.ms_q;
     const int n = jb.n, r = jb.r, beta = jb.beta;
     const KronSpec kr = jb.kr;
-    const int by = lb / jb.gx, bx = lb - by * jb.gx;
+    const int bx = lb / jb.gy, by = lb - bx * jb.gy;      // output tiles of the same columns are neighbours (one L2)
     const long long ncols = outer * inner;
     const int tcols = jb.tile_cols;                  // columns of a tile in use (<= TM_TC)
     const long long c0 = (long long)bx * tcols;
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(256) void k_ttm_ksplit(Batch<TtmJob> bt) {
     float* __restrict__ Y = jb.Y;
     const long long outer = jb.outer, inner = jb.inner, ms_i = jb.ms_i, ms_q = jb.ms_q;
     const int n = jb.n, r = jb.r, beta = jb.beta;
-    const int by = lb / jb.gx, bx = lb - by * jb.gx;
+    const int bx = lb / jb.gy, by = lb - bx * jb.gy;      // output tiles of the same columns are neighbours (one L2)
     const long long ncols = outer * inner;
     const long long c0 = (long long)bx * (16 * CB);
     const int q0 = by * (NBR * 16);
