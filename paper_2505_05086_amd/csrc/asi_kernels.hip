@@ -28,8 +28,8 @@ typedef double v4d __attribute__((ext_vector_type(4)));
 
 template <typename T, bool LASTMODE>
 __global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
-    __shared__ float Xs[PR_TK][PR_TI + 4];
-    __shared__ float Ys[PR_TK][PR_TQ + 4];
+    __shared__ float Xs[PR_TK][PR_TI + 1];
+    __shared__ float Ys[PR_TK][PR_TQ + 1];
     int lb;
     const PairJob& jb = bt.job[locate(bt, &lb)];
     const T* __restrict__ X = static_cast<const T*>(jb.X);
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
     }
     // the K groups add their accumulators through LDS (the tiles are no longer read), then group 0 stores
     double* red = reinterpret_cast<double*>(&Xs[0][0]);           // 64 x 32 doubles = 16 KB <= sizeof(Xs)
-    static_assert(sizeof(float) * PR_TK * (PR_TI + 4) >= sizeof(double) * PR_TI * PR_TQ, "reduction buffer fits the X tile");
+    static_assert(sizeof(float) * PR_TK * (PR_TI + 1) >= sizeof(double) * PR_TI * PR_TQ, "reduction buffer fits the X tile");
 #pragma unroll
     for (int kg = PR_KG - 1; kg >= 1; --kg) {
         __syncthreads();
