@@ -21,6 +21,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 namespace asi {
 
@@ -77,68 +78,163 @@ __device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) 
 
     // Kronecker indices by a rounded float quotient: exact for arguments below 2^14 (checked on the host)
     const float inv_n2 = 1.0f / (float)kr.n2, inv_r2 = 1.0f / (float)kr.r2;
-    float xr[TM_LR], mr[TM_LR];
-    auto fetch = [&](int k0) {
-#pragma unroll
-        for (int t = 0; t < TM_LR; ++t) {
-            if (!LASTMODE) {
-                const int i = k0 + l_i + 4 * t;
-                xr[t] = (k0 + 4 * t < n) ? ldg_f32(X, ld_base + (long long)i * inner, ld_base >= 0 && i < n) : 0.f;
-            } else {
-                const int cl = l_c + (256 / TM_KC) * t;
-                const long long c = c0 + cl;
-                const int i = k0 + l_i;
-                xr[t] = ldg_f32(X, c * (long long)n + i, c < ncols && cl < tcols && i < n);
-            }
-            const int i = k0 + m_i + 4 * t, q = q0 + m_q;
-            if (k0 + 4 * t >= n && !m_tr) {
-                mr[t] = 0.f;                          // uniform: the chunk ends before this row group
-            } else if (!KRON) {
-                if (m_tr) {
-                    const int it = k0 + t_i, qt = q0 + t_q + (256 / TM_KC) * t;
-                    mr[t] = ldg_f32(Mp, (long long)it + (long long)qt * ms_q, it < n && qt < r);
-                } else {
-                    mr[t] = ldg_f32(Mp, (long long)i * ms_i + (long long)q * ms_q, i < n && q < r);
-                }
-            } else {
-                const int i1 = (int)(((float)i + 0.5f) * inv_n2), i2 = i - i1 * kr.n2;
-                const int q1 = (int)(((float)q + 0.5f) * inv_r2), q2 = q - q1 * kr.r2;
-                const bool ok = i < n && q < r;
-                mr[t] = ldg_f32(Mp, (long long)i1 * ms_i + (long long)q1 * ms_q, ok) *
-                        ldg_f32(kr.M2, (long long)i2 * kr.ms_i + (long long)q2 * kr.ms_q, ok);
-            }
-        }
-    };
-    auto stash = [&]() {
-#pragma unroll
-        for (int t = 0; t < TM_LR; ++t) {
-            if (!LASTMODE) Xs[l_i + 4 * t][l_c] = xr[t];
-            else Xs[l_i][l_c + (256 / TM_KC) * t] = xr[t];
-            if (m_tr) Ms[t_i][t_q + (256 / TM_KC) * t] = mr[t];
-            else Ms[m_i + 4 * t][m_q] = mr[t];
-        }
-    };
 
     v4f acc[NBR];
 #pragma unroll
     for (int nb = 0; nb < NBR; ++nb) acc[nb] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    fetch(0);
-    for (int k0 = 0; k0 < n; k0 += TM_KC) {
-        __syncthreads();                 // previous chunk fully consumed
-        stash();
-        __syncthreads();
-        if (k0 + TM_KC < n) fetch(k0 + TM_KC);
+    // The K loop, compiled once per matrix layout (MTR) so that the layout is no test inside it.
+    auto kloop = [&](auto mtr_c) {
+        constexpr bool MTR = decltype(mtr_c)::value;
+        // What a chunk's loads return stays untouched in registers until stash() runs, after the
+        // previous chunk's MFMAs: widening or masking a value any earlier would wait for its load.
+        T xr[TM_LR];
+        float mr[TM_LR], m2[KRON ? TM_LR : 1];
+
+        // ---- a chunk that may reach past n: every access tests the mode index
+        auto fetch_part = [&](int k0) {
 #pragma unroll
-        for (int ks = 0; ks < TM_KC / 4; ++ks) {
-            if (k0 + 4 * ks < n) {
-                const float a = Xs[4 * ks + lg][16 * wave + ll];
+            for (int t = 0; t < TM_LR; ++t) {
+                if (!LASTMODE) {
+                    const int i = k0 + l_i + 4 * t;
+                    xr[t] = (k0 + 4 * t < n) ? ldg_raw(X, ld_base + (long long)i * inner, ld_base >= 0 && i < n) : T{};
+                } else {
+                    const int cl = l_c + (256 / TM_KC) * t;
+                    const long long c = c0 + cl;
+                    const int i = k0 + l_i;
+                    xr[t] = ldg_raw(X, c * (long long)n + i, c < ncols && cl < tcols && i < n);
+                }
+                const int i = k0 + m_i + 4 * t, q = q0 + m_q;
+                if (MTR) {
+                    const int it = k0 + t_i, qt = q0 + t_q + (256 / TM_KC) * t;
+                    mr[t] = ldg_raw(Mp, (long long)it + (long long)qt * ms_q, it < n && qt < r);
+                } else if (k0 + 4 * t >= n) {
+                    mr[t] = 0.f;                      // uniform: the chunk ends before this row group
+                    if (KRON) m2[t] = 0.f;
+                } else if (!KRON) {
+                    mr[t] = ldg_raw(Mp, (long long)i * ms_i + (long long)q * ms_q, i < n && q < r);
+                } else {
+                    const int i1 = (int)(((float)i + 0.5f) * inv_n2), i2 = i - i1 * kr.n2;
+                    const int q1 = (int)(((float)q + 0.5f) * inv_r2), q2 = q - q1 * kr.r2;
+                    const bool ok = i < n && q < r;
+                    mr[t] = ldg_raw(Mp, (long long)i1 * ms_i + (long long)q1 * ms_q, ok);
+                    m2[t] = ldg_raw(kr.M2, (long long)i2 * kr.ms_i + (long long)q2 * kr.ms_q, ok);
+                }
+            }
+        };
+
+        // ---- a chunk wholly below n: no test on the mode index.  Lanes outside the tile read the
+        // tile's first column / first output instead (always valid) and stash() drops the value,
+        // so the chunk's loads are one straight run of instructions, all in flight together.
+        const bool x_in = LASTMODE ? true : ld_base >= 0;
+        long long x_org;                              // element index of (this lane's column, row l_i) at k0 = 0
+        if (!LASTMODE) {
+            const long long o = c0 / inner, j = c0 - o * inner;
+            x_org = (x_in ? ld_base : o * (long long)n * inner + j) + (long long)l_i * inner;
+        } else {
+            x_org = c0 * (long long)n + l_i;
+        }
+        const bool qm_in = q0 + m_q < r;                             // plain and Kronecker layouts
+        const int qm = qm_in ? q0 + m_q : q0;
+        const int qm1 = (int)(((float)qm + 0.5f) * inv_r2), qm2 = qm - qm1 * kr.r2;
+        auto fetch_full = [&](int k0) {
+#pragma unroll
+            for (int t = 0; t < TM_LR; ++t) {
+                if (!LASTMODE) {
+                    xr[t] = X[x_org + (long long)(k0 + 4 * t) * inner];
+                } else {
+                    const int cl = l_c + (256 / TM_KC) * t;
+                    const bool in = c0 + cl < ncols && cl < tcols;
+                    xr[t] = X[x_org + k0 + (in ? (long long)cl * n : 0LL)];
+                }
+                if (MTR) {
+                    const int qt = q0 + t_q + (256 / TM_KC) * t;
+                    mr[t] = Mp[(long long)(k0 + t_i) + (long long)(qt < r ? qt : q0) * ms_q];
+                } else if (!KRON) {
+                    mr[t] = Mp[(long long)(k0 + m_i + 4 * t) * ms_i + (long long)qm * ms_q];
+                } else {
+                    const int i = k0 + m_i + 4 * t;
+                    const int i1 = (int)(((float)i + 0.5f) * inv_n2), i2 = i - i1 * kr.n2;
+                    mr[t] = Mp[(long long)i1 * ms_i + (long long)qm1 * ms_q];
+                    m2[t] = kr.M2[(long long)i2 * kr.ms_i + (long long)qm2 * kr.ms_q];
+                }
+            }
+        };
+        // (the masks repeat what fetch_part already applied and add what fetch_full left out)
+        auto stash = [&]() {
+#pragma unroll
+            for (int t = 0; t < TM_LR; ++t) {
+                if (!LASTMODE) {
+                    Xs[l_i + 4 * t][l_c] = x_in ? to_f32(xr[t]) : 0.f;
+                } else {
+                    const int cl = l_c + (256 / TM_KC) * t;
+                    Xs[l_i][cl] = (c0 + cl < ncols && cl < tcols) ? to_f32(xr[t]) : 0.f;
+                }
+                if (MTR) {
+                    const int ql = t_q + (256 / TM_KC) * t;
+                    Ms[t_i][ql] = (q0 + ql < r) ? mr[t] : 0.f;
+                } else {
+                    const float v = KRON ? mr[t] * m2[t] : mr[t];
+                    Ms[m_i + 4 * t][m_q] = qm_in ? v : 0.f;
+                }
+            }
+        };
+        // operands of two K steps at a time, read one group ahead of the MFMAs that use them
+        constexpr int GS = 2, NG = TM_KC / 4 / GS;
+        auto operands = [&](int g, float (&a)[GS], float (&b)[GS][NBR]) {
+#pragma unroll
+            for (int s = 0; s < GS; ++s) {
+                a[s] = Xs[4 * (GS * g + s) + lg][16 * wave + ll];
+#pragma unroll
+                for (int nb = 0; nb < NBR; ++nb) b[s][nb] = Ms[4 * (GS * g + s) + lg][16 * nb + ll];
+            }
+        };
+        auto multiply = [&](const float (&a)[GS], const float (&b)[GS][NBR]) {
+#pragma unroll
+            for (int s = 0; s < GS; ++s)
 #pragma unroll
                 for (int nb = 0; nb < NBR; ++nb)
-                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Ms[4 * ks + lg][16 * nb + ll], acc[nb], 0, 0, 0);
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[s][nb], acc[nb], 0, 0, 0);
+        };
+
+        if (TM_KC <= n) fetch_full(0); else fetch_part(0);
+        for (int k0 = 0; k0 < n; k0 += TM_KC) {
+            __syncthreads();                 // previous chunk fully consumed
+            stash();
+            __syncthreads();
+            const int nx = k0 + TM_KC;
+            if (nx + TM_KC <= n) fetch_full(nx);
+            else if (nx < n) fetch_part(nx);
+            if (nx <= n) {
+                float a0[GS], b0[GS][NBR], a1[GS], b1[GS][NBR];
+                // (scheduling fences: without them the compiler moves every read back next to its MFMA
+                // and waits for it there)
+                operands(0, a0, b0);
+#pragma unroll
+                for (int g = 0; g < NG; g += 2) {
+                    operands(g + 1, a1, b1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    multiply(a0, b0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (g + 2 < NG) operands(g + 2, a0, b0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    multiply(a1, b1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < TM_KC / 4; ++ks) {
+                    if (k0 + 4 * ks < n) {
+                        const float a = Xs[4 * ks + lg][16 * wave + ll];
+#pragma unroll
+                        for (int nb = 0; nb < NBR; ++nb)
+                            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Ms[4 * ks + lg][16 * nb + ll], acc[nb], 0, 0, 0);
+                    }
+                }
             }
         }
-    }
+    };
+    if (m_tr) kloop(std::true_type{}); else kloop(std::false_type{});
     __syncthreads();
     // result layout: lane holds column 16w + 4*lg + v, output 16nb + ll
 #pragma unroll
