@@ -53,55 +53,73 @@ __global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
     if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;   // arrival counters of later launches
 
     constexpr int NX = PR_TI * PR_TK / PR_NT, NY = PR_TQ * PR_TK / PR_NT, RS = PR_NT / PR_TK;   // loads per thread, row step
-    float xr[NX], yr[NY];
+    // A chunk's loads go to addresses that are always valid (a lane outside the tile, the split or the
+    // tensor reads a clamped position instead) and what they return stays untouched in registers until
+    // stash() masks and widens it after the previous chunk's MFMAs: the loads are one straight run of
+    // instructions, all in flight together, and nothing waits for one of them before the multiply.
+    T xr[NX];
+    float yr[NY];
+    const int cl = tid & (PR_TK - 1), rl = tid / PR_TK;
+    // not the last mode: column c = (o, j) of this lane in the chunk to fetch next, carried from chunk
+    // to chunk by additions (PR_TK = so * inner + sj with sj < inner, so at most one carry into o)
+    // (a lane whose column lies beyond the tensor keeps base 0: with a row offset it still reads inside X)
+    long long lc = cbeg + cl, lj = 0, xbase = 0, ybase = 0;
+    const int so = LASTMODE || inner > PR_TK ? 0 : PR_TK / (int)inner;
+    const long long sj = LASTMODE ? 0 : PR_TK - so * inner;
+    const long long xplane = (long long)n * inner, yplane = (long long)r * inner;
+    if (!LASTMODE && lc < ncols) {
+        // quotient by a double division (exact below 2^52) with one correction step
+        long long o = (long long)((double)lc / (double)inner);
+        lj = lc - o * inner;
+        if (lj < 0) { --o; lj += inner; } else if (lj >= inner) { ++o; lj -= inner; }
+        xbase = o * xplane + lj;
+        ybase = o * yplane + lj;
+    }
     auto fetch = [&](long long c0) {
         if (!LASTMODE) {
-            const int cl = tid & (PR_TK - 1);
-            const long long c = c0 + cl;
-            const bool valid = c < cend;
-            long long xbase = 0, ybase = 0;
-            if (valid) {
-                const long long o = c / inner, j = c - o * inner;
-                xbase = o * (long long)n * inner + j;
-                ybase = o * (long long)r * inner + j;
-            }
 #pragma unroll
             for (int t = 0; t < NX; ++t) {
-                const int i = i0 + tid / PR_TK + RS * t;
-                xr[t] = ldg_f32(X, xbase + (long long)i * inner, valid && i < n);
+                const int i = i0 + rl + RS * t;
+                xr[t] = X[xbase + (long long)(i < n ? i : i0) * inner];
             }
 #pragma unroll
             for (int t = 0; t < NY; ++t) {
-                const int q = q0 + tid / PR_TK + RS * t;
-                yr[t] = ldg_f32(Y, ybase + (long long)q * inner, valid && q < r);
+                const int q = q0 + rl + RS * t;
+                yr[t] = Y[ybase + (long long)(q < r ? q : q0) * inner];
             }
+            lc += PR_TK; lj += sj; xbase += so * xplane + sj; ybase += so * yplane + sj;
+            if (lj >= inner) { lj -= inner; xbase += xplane - inner; ybase += yplane - inner; }
+            if (lc >= ncols) { xbase = 0; ybase = 0; }
         } else {  // inner == 1
-            const int i = i0 + (tid & 63);
+            const int i = i0 + (tid & 63), ic = i < n ? i : i0;
 #pragma unroll
             for (int t = 0; t < NX; ++t) {
                 const long long c = c0 + (tid >> 6) + PR_NW * t;
-                xr[t] = ldg_f32(X, c * (long long)n + i, c < cend && i < n);
+                xr[t] = X[(c < cend ? c : c0) * (long long)n + ic];
             }
-            const int q = q0 + (tid & 31);
+            const int q = q0 + (tid & 31), qc = q < r ? q : q0;
 #pragma unroll
             for (int t = 0; t < NY; ++t) {
                 const long long c = c0 + (tid >> 5) + 2 * PR_NW * t;
-                yr[t] = ldg_f32(Y, c * (long long)r + q, c < cend && q < r);
+                yr[t] = Y[(c < cend ? c : c0) * (long long)r + qc];
             }
         }
     };
-    auto stash = [&]() {
+    auto stash = [&](long long c0) {
         if (!LASTMODE) {
-            const int cl = tid & (PR_TK - 1);
+            const bool valid = c0 + cl < cend;
 #pragma unroll
-            for (int t = 0; t < NX; ++t) Xs[cl][tid / PR_TK + RS * t] = xr[t];
+            for (int t = 0; t < NX; ++t) Xs[cl][rl + RS * t] = (valid && i0 + rl + RS * t < n) ? to_f32(xr[t]) : 0.f;
 #pragma unroll
-            for (int t = 0; t < NY; ++t) Ys[cl][tid / PR_TK + RS * t] = yr[t];
+            for (int t = 0; t < NY; ++t) Ys[cl][rl + RS * t] = (valid && q0 + rl + RS * t < r) ? yr[t] : 0.f;
         } else {
+            const bool iv = i0 + (tid & 63) < n, qv = q0 + (tid & 31) < r;
 #pragma unroll
-            for (int t = 0; t < NX; ++t) Xs[(tid >> 6) + PR_NW * t][tid & 63] = xr[t];
+            for (int t = 0; t < NX; ++t)
+                Xs[(tid >> 6) + PR_NW * t][tid & 63] = (iv && c0 + (tid >> 6) + PR_NW * t < cend) ? to_f32(xr[t]) : 0.f;
 #pragma unroll
-            for (int t = 0; t < NY; ++t) Ys[(tid >> 5) + 2 * PR_NW * t][tid & 31] = yr[t];
+            for (int t = 0; t < NY; ++t)
+                Ys[(tid >> 5) + 2 * PR_NW * t][tid & 31] = (qv && c0 + (tid >> 5) + 2 * PR_NW * t < cend) ? yr[t] : 0.f;
         }
     };
 
@@ -109,7 +127,7 @@ __global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
     if (cbeg < cend) fetch(cbeg);
     for (long long c0 = cbeg; c0 < cend; c0 += PR_TK) {
         __syncthreads();
-        stash();
+        stash(c0);
         __syncthreads();
         if (c0 + PR_TK < cend) fetch(c0 + PR_TK);
 #pragma unroll
