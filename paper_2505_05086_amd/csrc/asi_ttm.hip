@@ -86,96 +86,71 @@ __device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) 
     // The K loop, compiled once per matrix layout (MTR) so that the layout is no test inside it.
     auto kloop = [&](auto mtr_c) {
         constexpr bool MTR = decltype(mtr_c)::value;
-        // What a chunk's loads return stays untouched in registers until stash() runs, after the
-        // previous chunk's MFMAs: widening or masking a value any earlier would wait for its load.
+        // Every load goes to an address that is always valid: a lane outside the tile reads the tile's
+        // first column / first output instead, a row past n reads row n - 1.  What the loads return
+        // stays untouched in registers until stash() masks and widens it, after the previous chunk's
+        // MFMAs: the chunk's loads are one straight run of instructions, all in flight together, and
+        // nothing waits for one of them before the multiply.
         T xr[TM_LR];
         float mr[TM_LR], m2[KRON ? TM_LR : 1];
-
-        // ---- a chunk that may reach past n: every access tests the mode index
-        auto fetch_part = [&](int k0) {
-#pragma unroll
-            for (int t = 0; t < TM_LR; ++t) {
-                if (!LASTMODE) {
-                    const int i = k0 + l_i + 4 * t;
-                    xr[t] = (k0 + 4 * t < n) ? ldg_raw(X, ld_base + (long long)i * inner, ld_base >= 0 && i < n) : T{};
-                } else {
-                    const int cl = l_c + (256 / TM_KC) * t;
-                    const long long c = c0 + cl;
-                    const int i = k0 + l_i;
-                    xr[t] = ldg_raw(X, c * (long long)n + i, c < ncols && cl < tcols && i < n);
-                }
-                const int i = k0 + m_i + 4 * t, q = q0 + m_q;
-                if (MTR) {
-                    const int it = k0 + t_i, qt = q0 + t_q + (256 / TM_KC) * t;
-                    mr[t] = ldg_raw(Mp, (long long)it + (long long)qt * ms_q, it < n && qt < r);
-                } else if (k0 + 4 * t >= n) {
-                    mr[t] = 0.f;                      // uniform: the chunk ends before this row group
-                    if (KRON) m2[t] = 0.f;
-                } else if (!KRON) {
-                    mr[t] = ldg_raw(Mp, (long long)i * ms_i + (long long)q * ms_q, i < n && q < r);
-                } else {
-                    const int i1 = (int)(((float)i + 0.5f) * inv_n2), i2 = i - i1 * kr.n2;
-                    const int q1 = (int)(((float)q + 0.5f) * inv_r2), q2 = q - q1 * kr.r2;
-                    const bool ok = i < n && q < r;
-                    mr[t] = ldg_raw(Mp, (long long)i1 * ms_i + (long long)q1 * ms_q, ok);
-                    m2[t] = ldg_raw(kr.M2, (long long)i2 * kr.ms_i + (long long)q2 * kr.ms_q, ok);
-                }
-            }
-        };
-
-        // ---- a chunk wholly below n: no test on the mode index.  Lanes outside the tile read the
-        // tile's first column / first output instead (always valid) and stash() drops the value,
-        // so the chunk's loads are one straight run of instructions, all in flight together.
         const bool x_in = LASTMODE ? true : ld_base >= 0;
-        long long x_org;                              // element index of (this lane's column, row l_i) at k0 = 0
+        long long x_org;                              // element index of (this lane's column, row 0 / l_i)
         if (!LASTMODE) {
             const long long o = c0 / inner, j = c0 - o * inner;
-            x_org = (x_in ? ld_base : o * (long long)n * inner + j) + (long long)l_i * inner;
+            x_org = x_in ? ld_base : o * (long long)n * inner + j;
         } else {
-            x_org = c0 * (long long)n + l_i;
+            x_org = c0 * (long long)n;
         }
         const bool qm_in = q0 + m_q < r;                             // plain and Kronecker layouts
         const int qm = qm_in ? q0 + m_q : q0;
         const int qm1 = (int)(((float)qm + 0.5f) * inv_r2), qm2 = qm - qm1 * kr.r2;
-        auto fetch_full = [&](int k0) {
+        // PART: the chunk may reach past n (rows are clamped, empty row groups skipped: a uniform test);
+        // otherwise it lies wholly below n and no test on the mode index remains
+        auto fetch = [&](int k0, auto part_c) {
+            constexpr bool PART = decltype(part_c)::value;
+            auto row = [&](int i) { return (PART && i >= n) ? n - 1 : i; };
 #pragma unroll
             for (int t = 0; t < TM_LR; ++t) {
+                const bool live = !PART || k0 + 4 * t < n;
                 if (!LASTMODE) {
-                    xr[t] = X[x_org + (long long)(k0 + 4 * t) * inner];
+                    if (live) xr[t] = X[x_org + (long long)row(k0 + l_i + 4 * t) * inner];
+                    else xr[t] = T{};
                 } else {
                     const int cl = l_c + (256 / TM_KC) * t;
                     const bool in = c0 + cl < ncols && cl < tcols;
-                    xr[t] = X[x_org + k0 + (in ? (long long)cl * n : 0LL)];
+                    xr[t] = X[x_org + row(k0 + l_i) + (in ? (long long)cl * n : 0LL)];
                 }
                 if (MTR) {
                     const int qt = q0 + t_q + (256 / TM_KC) * t;
-                    mr[t] = Mp[(long long)(k0 + t_i) + (long long)(qt < r ? qt : q0) * ms_q];
+                    mr[t] = Mp[(long long)row(k0 + t_i) + (long long)(qt < r ? qt : q0) * ms_q];
+                } else if (!live) {
+                    mr[t] = 0.f;
+                    if (KRON) m2[t] = 0.f;
                 } else if (!KRON) {
-                    mr[t] = Mp[(long long)(k0 + m_i + 4 * t) * ms_i + (long long)qm * ms_q];
+                    mr[t] = Mp[(long long)row(k0 + m_i + 4 * t) * ms_i + (long long)qm * ms_q];
                 } else {
-                    const int i = k0 + m_i + 4 * t;
+                    const int i = row(k0 + m_i + 4 * t);
                     const int i1 = (int)(((float)i + 0.5f) * inv_n2), i2 = i - i1 * kr.n2;
                     mr[t] = Mp[(long long)i1 * ms_i + (long long)qm1 * ms_q];
                     m2[t] = kr.M2[(long long)i2 * kr.ms_i + (long long)qm2 * kr.ms_q];
                 }
             }
         };
-        // (the masks repeat what fetch_part already applied and add what fetch_full left out)
-        auto stash = [&]() {
+        auto stash = [&](int k0) {
 #pragma unroll
             for (int t = 0; t < TM_LR; ++t) {
                 if (!LASTMODE) {
-                    Xs[l_i + 4 * t][l_c] = x_in ? to_f32(xr[t]) : 0.f;
+                    Xs[l_i + 4 * t][l_c] = (x_in && k0 + l_i + 4 * t < n) ? to_f32(xr[t]) : 0.f;
                 } else {
                     const int cl = l_c + (256 / TM_KC) * t;
-                    Xs[l_i][cl] = (c0 + cl < ncols && cl < tcols) ? to_f32(xr[t]) : 0.f;
+                    Xs[l_i][cl] = (c0 + cl < ncols && cl < tcols && k0 + l_i < n) ? to_f32(xr[t]) : 0.f;
                 }
                 if (MTR) {
                     const int ql = t_q + (256 / TM_KC) * t;
-                    Ms[t_i][ql] = (q0 + ql < r) ? mr[t] : 0.f;
+                    Ms[t_i][ql] = (q0 + ql < r && k0 + t_i < n) ? mr[t] : 0.f;
                 } else {
                     const float v = KRON ? mr[t] * m2[t] : mr[t];
-                    Ms[m_i + 4 * t][m_q] = qm_in ? v : 0.f;
+                    Ms[m_i + 4 * t][m_q] = (qm_in && k0 + m_i + 4 * t < n) ? v : 0.f;
                 }
             }
         };
@@ -197,14 +172,16 @@ __device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) 
                     acc[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], b[s][nb], acc[nb], 0, 0, 0);
         };
 
-        if (TM_KC <= n) fetch_full(0); else fetch_part(0);
+        const std::true_type partial{};
+        const std::false_type whole{};
+        if (TM_KC <= n) fetch(0, whole); else fetch(0, partial);
         for (int k0 = 0; k0 < n; k0 += TM_KC) {
             __syncthreads();                 // previous chunk fully consumed
-            stash();
+            stash(k0);
             __syncthreads();
             const int nx = k0 + TM_KC;
-            if (nx + TM_KC <= n) fetch_full(nx);
-            else if (nx < n) fetch_part(nx);
+            if (nx + TM_KC <= n) fetch(nx, whole);
+            else if (nx < n) fetch(nx, partial);
             if (nx <= n) {
                 float a0[GS], b0[GS][NBR], a1[GS], b1[GS][NBR];
                 // (scheduling fences: without them the compiler moves every read back next to its MFMA
