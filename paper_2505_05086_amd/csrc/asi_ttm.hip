@@ -31,14 +31,16 @@ constexpr int TM_TC = 64, TM_TQ = 64, TM_LD = TM_TC + 4;
 constexpr int TM_KCMAX = 64;
 
 // KM: 0 = plain matrix, 1 = Kronecker product, 2 = Kronecker product with K chunks of 64 (long merged
-// modes with few columns; otherwise chunks of 32, which overlap across workgroups)
+// modes with few columns; otherwise chunks of 32, which overlap across workgroups), 3 = plain matrix with
+// K chunks of 64 (a long last mode with at most one workgroup per CU: a chunk is a dependent round trip
+// to memory, and nothing else on the CU hides it)
 constexpr int TM_SMEM = 2 * TM_KCMAX * TM_LD;   // floats: Xs | Ms during the K loop, Ys (64 x TM_LD) afterwards
 
 // one tile (workgroup lb of job jb); smem holds TM_SMEM floats
 template <typename T, bool LASTMODE, int NBR, int KM>
 __device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) {
-    constexpr bool KRON = KM != 0;
-    constexpr int TM_KC = KM == 2 ? 64 : 32;
+    constexpr bool KRON = KM == 1 || KM == 2;
+    constexpr int TM_KC = KM >= 2 ? 64 : 32;
     constexpr int TM_LR = TM_KC / 4;      // loads per thread and operand for one chunk
     float (*Xs)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem);
     float (*Ms)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem + TM_KCMAX * TM_LD);
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(256) void k_ttm_ksplit(Batch<TtmJob> bt) {
 // ---- host side -----------------------------------------------------------------------------------
 // key bits: [0] bf16 input, [1] LASTMODE, [2] KRON, [3] split kernel, [4..6] NBR-1, [8..12] KS,
 // [13] split kernel with several column blocks per workgroup (4 up to NBR = 3, else 2),
-// [14] Kronecker product with K chunks of 64.  Bits 4..12 only bound sizes.
+// [14] K chunks of 64 (tiled kernel along the last mode).  Bits 4..12 only bound sizes.
 static unsigned ttm_key(bool bf16, bool last, bool kron, bool ksplit, int nbr, int ks, bool wide, bool kc64) {
     return (bf16 ? 1u : 0u) | (last ? 2u : 0u) | (kron ? 4u : 0u) | (ksplit ? 8u : 0u) | ((unsigned)(nbr - 1) << 4) |
            ((unsigned)ks << 8) | (wide ? 0x2000u : 0u) | (kc64 ? 0x4000u : 0u);
@@ -409,9 +411,10 @@ static bool fill_ttm(DType xt, const void* X, long long outer, int n, long long 
         const int nbr = (rr + 15) / 16;
         jb.gx = (int)gx; jb.gy = (r + TM_TQ - 1) / TM_TQ;
         if (gx * jb.gy > 0x3fffffffLL) return false;
-        out->kind = IT_TTM; out->key = ttm_key(xt == BF16, last, kron, false, nbr, 0, false, kron && n > 64);
+        const bool kc64 = kron ? n > 64 : (last && n >= 256 && gx * jb.gy <= 256);   // (at most one workgroup per CU)
+        out->kind = IT_TTM; out->key = ttm_key(xt == BF16, last, kron, false, nbr, 0, false, kc64);
         std::snprintf(out->label, sizeof(out->label), "k_ttm_mfma<%s, %s, %d, %d>", tn, last ? "true" : "false", nbr,
-                      kron ? (n > 64 ? 2 : 1) : 0);
+                      kron ? (kc64 ? 2 : 1) : (kc64 ? 3 : 0));
     }
     out->nblocks = jb.gx * jb.gy;
     static_assert(sizeof(TtmJob) <= kItemArgMax, "argument block");
@@ -520,7 +523,7 @@ hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, cha
     if (label_out) {
         const char* tn = bf16 ? "asi::bf16_t" : "float";
         if (ksplit) std::snprintf(label_out, 96, "k_ttm_ksplit<%s, %d, %d, %d>", tn, nbr, ks, ksplit_cb(nbr, wide));
-        else std::snprintf(label_out, 96, "k_ttm_mfma<%s, %s, %d, %d>", tn, last ? "true" : "false", nbr, kron ? (kc64 ? 2 : 1) : 0);
+        else std::snprintf(label_out, 96, "k_ttm_mfma<%s, %s, %d, %d>", tn, last ? "true" : "false", nbr, kron ? (kc64 ? 2 : 1) : (kc64 ? 3 : 0));
     }
     if (ksplit) {
         if (!bf16) {
@@ -542,10 +545,12 @@ hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, cha
         if (!bf16) { if (kc64) launch_tiled<float, true, 2>(nbr, b, grid, st); else launch_tiled<float, true, 1>(nbr, b, grid, st); }
         else { if (kc64) launch_tiled<bf16_t, true, 2>(nbr, b, grid, st); else launch_tiled<bf16_t, true, 1>(nbr, b, grid, st); }
     } else if (!bf16) {
-        if (last) launch_tiled<float, true, 0>(nbr, b, grid, st);
+        if (last && kc64) launch_tiled<float, true, 3>(nbr, b, grid, st);
+        else if (last) launch_tiled<float, true, 0>(nbr, b, grid, st);
         else launch_tiled<float, false, 0>(nbr, b, grid, st);
     } else {
-        if (last) launch_tiled<bf16_t, true, 0>(nbr, b, grid, st);
+        if (last && kc64) launch_tiled<bf16_t, true, 3>(nbr, b, grid, st);
+        else if (last) launch_tiled<bf16_t, true, 0>(nbr, b, grid, st);
         else launch_tiled<bf16_t, false, 0>(nbr, b, grid, st);
     }
     return hipGetLastError();
