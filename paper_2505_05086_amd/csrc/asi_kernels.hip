@@ -9,6 +9,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 namespace asi {
 
@@ -28,8 +29,12 @@ typedef double v4d __attribute__((ext_vector_type(4)));
 
 template <typename T, bool LASTMODE>
 __global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
-    __shared__ float Xs[PR_TK][PR_TI + 1];
-    __shared__ float Ys[PR_TK][PR_TQ + 1];
+    // Along the last mode the tiles are held widened (a Y element is an operand of four waves, so widening
+    // once at the store saves most of the conversions); otherwise the stores run down the columns of the
+    // tiles, where 8-byte elements would collide in the LDS banks.
+    using S = std::conditional_t<LASTMODE, double, float>;
+    __shared__ S Xs[PR_TK][PR_TI + 1];
+    __shared__ S Ys[PR_TK][PR_TQ + 1];
     int lb;
     const PairJob& jb = bt.job[locate(bt, &lb)];
     const T* __restrict__ X = static_cast<const T*>(jb.X);
@@ -75,6 +80,16 @@ __global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
         xbase = o * xplane + lj;
         ybase = o * yplane + lj;
     }
+    // last mode: offsets of this lane's elements from the chunk's first element (PR_TK * n < 2^32: host check);
+    // a column past the split's end reads column 0 instead, a row or output past the end the tile's first
+    unsigned xoff[LASTMODE ? NX : 1], yoff[LASTMODE ? NY : 1];
+    const unsigned xoff0 = (i0 + (tid & 63) < n) ? (tid & 63) : 0, yoff0 = (q0 + (tid & 31) < r) ? (tid & 31) : 0;
+    if (LASTMODE) {
+#pragma unroll
+        for (int t = 0; t < NX; ++t) xoff[t] = (unsigned)((tid >> 6) + PR_NW * t) * (unsigned)n + xoff0;
+#pragma unroll
+        for (int t = 0; t < NY; ++t) yoff[t] = (unsigned)((tid >> 5) + 2 * PR_NW * t) * (unsigned)r + yoff0;
+    }
     auto fetch = [&](long long c0) {
         if (!LASTMODE) {
 #pragma unroll
@@ -90,19 +105,14 @@ __global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
             lc += PR_TK; lj += sj; xbase += so * xplane + sj; ybase += so * yplane + sj;
             if (lj >= inner) { lj -= inner; xbase += xplane - inner; ybase += yplane - inner; }
             if (lc >= ncols) { xbase = 0; ybase = 0; }
-        } else {  // inner == 1
-            const int i = i0 + (tid & 63), ic = i < n ? i : i0;
+        } else {  // inner == 1: one 64-bit base per chunk (uniform) and 32-bit lane offsets, fixed for the whole split
+            const T* __restrict__ xb = X + (c0 * (long long)n + i0);
+            const float* __restrict__ yb = Y + (c0 * (long long)r + q0);
+            const int lim = (int)(cend - c0 < PR_TK ? cend - c0 : PR_TK);     // columns of the chunk inside the split
 #pragma unroll
-            for (int t = 0; t < NX; ++t) {
-                const long long c = c0 + (tid >> 6) + PR_NW * t;
-                xr[t] = X[(c < cend ? c : c0) * (long long)n + ic];
-            }
-            const int q = q0 + (tid & 31), qc = q < r ? q : q0;
+            for (int t = 0; t < NX; ++t) xr[t] = xb[(tid >> 6) + PR_NW * t < lim ? xoff[t] : xoff0];
 #pragma unroll
-            for (int t = 0; t < NY; ++t) {
-                const long long c = c0 + (tid >> 5) + 2 * PR_NW * t;
-                yr[t] = Y[(c < cend ? c : c0) * (long long)r + qc];
-            }
+            for (int t = 0; t < NY; ++t) yr[t] = yb[(tid >> 5) + 2 * PR_NW * t < lim ? yoff[t] : yoff0];
         }
     };
     auto stash = [&](long long c0) {
@@ -116,10 +126,10 @@ __global__ __launch_bounds__(PR_NT) void k_pair(Batch<PairJob> bt) {
             const bool iv = i0 + (tid & 63) < n, qv = q0 + (tid & 31) < r;
 #pragma unroll
             for (int t = 0; t < NX; ++t)
-                Xs[(tid >> 6) + PR_NW * t][tid & 63] = (iv && c0 + (tid >> 6) + PR_NW * t < cend) ? to_f32(xr[t]) : 0.f;
+                Xs[(tid >> 6) + PR_NW * t][tid & 63] = (iv && c0 + (tid >> 6) + PR_NW * t < cend) ? (S)to_f32(xr[t]) : (S)0;
 #pragma unroll
             for (int t = 0; t < NY; ++t)
-                Ys[(tid >> 5) + 2 * PR_NW * t][tid & 31] = (qv && c0 + (tid >> 5) + 2 * PR_NW * t < cend) ? yr[t] : 0.f;
+                Ys[(tid >> 5) + 2 * PR_NW * t][tid & 31] = (qv && c0 + (tid >> 5) + 2 * PR_NW * t < cend) ? (S)yr[t] : (S)0;
         }
     };
 
@@ -202,6 +212,7 @@ bool make_pair(DType xt, const void* X, long long outer, int n, long long inner,
                int nsplit, int32_t* zero, int nzero, const PresumArgs* pre, Item* out) {
     const long long ncols = outer * inner;
     if (ncols <= 0 || n <= 0 || r <= 0 || nsplit <= 0 || !X || !Y || !part || nzero < 0 || nzero > 256) return false;
+    if (inner == 1 && (n >= (1 << 24) || r >= (1 << 24))) return false;      // 32-bit offsets inside a chunk of the last mode
     PairJob jb;
     std::memset(&jb, 0, sizeof(jb));
     jb.X = X; jb.outer = outer; jb.inner = inner; jb.cols_per_split = pair_cols_per_split(ncols, nsplit);
