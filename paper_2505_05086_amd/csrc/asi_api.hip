@@ -76,6 +76,8 @@ struct CompressPlan {
     int nsplit2[4] = {};
     double* P64[4] = {};
     double* Gpart[4] = {};
+    double* Gsum[4] = {};           // wide path, many slices: the slice Grams added up by a tree level
+    int ngsum[4] = {};
     double* R[4] = {};
     double* Dinv[4] = {};
     double* scal[4] = {};
@@ -125,6 +127,12 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
             p.wide_orth[m] = true;
             p.nblk[m] = orth_wide_gram_blocks((int)n);
             p.Gpart[m] = c.take<double>((size_t)p.nblk[m] * r * r);
+            // The factorisation is one workgroup; summing megabytes of slice Grams there runs at the
+            // bandwidth of one CU (110 us for 24 slices of 192 x 192), so a tree level does it first.
+            if ((size_t)p.nblk[m] * r * r >= (size_t)1 << 17) {
+                p.ngsum[m] = (p.nblk[m] + 31) / 32;
+                p.Gsum[m] = c.take<double>((size_t)p.ngsum[m] * r * r);
+            }
             p.R[m] = c.take<double>(r * r);
             p.Dinv[m] = c.take<double>(((r + 15) / 16) * 256);
             p.scal[m] = c.take<double>(200);
@@ -414,6 +422,9 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
     if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
 
     OrthArgs fast, wide, slow;
+    PresumArgs gsum;                 // wide modes with many slices: tree level over the slice Grams
+    std::memset(&gsum, 0, sizeof(gsum));
+    double gsum_b = 0;
     std::memset(&fast, 0, sizeof(fast));
     std::memset(&wide, 0, sizeof(wide));
     std::memset(&slow, 0, sizeof(slow));
@@ -499,6 +510,12 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
         j.P64 = p.P64[m]; j.Uout = U_out[m]; j.mode1 = m + 1; j.info = info;
         j.nblk = p.nblk[m]; j.Gpart = p.Gpart[m]; j.R = p.R[m]; j.Dinv = p.Dinv[m]; j.scal = p.scal[m];
         j.ctr = p.ctr8 + 2 * m;
+        if (p.wide_orth[m] && p.Gsum[m]) {
+            PresumJob& gj = gsum.job[gsum.njobs++];
+            gj.in = p.Gpart[m]; gj.out = p.Gsum[m]; gj.cnt = (long long)r * r; gj.nsplit = p.nblk[m];
+            gj.nchunks = (int)((gj.cnt + 255) / 256); gj.ngroups = p.ngsum[m];
+            gsum_b += 8.0 * r * r * (p.nblk[m] + p.ngsum[m]);
+        }
         if (p.wide_orth[m]) {
             PresumJob& pj = pre2.job[pre2.njobs++];
             pj.in = j.part; pj.out = p.P64[m]; pj.cnt = (long long)n * r; pj.nsplit = j.nsplit;
@@ -506,7 +523,7 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
             pre2_b += 8.0 * n * r * (j.nsplit + 1);
         }
         // Cholesky: reads the slice Grams, writes R and the diagonal-block inverses; r^3/3 flops
-        const double cb = 8.0 * ((double)p.nblk[m] * r * r + (double)r * r + 256.0 * ((r + 15) / 16));
+        const double cb = 8.0 * ((double)(p.Gsum[m] ? p.ngsum[m] : p.nblk[m]) * r * r + (double)r * r + 256.0 * ((r + 15) / 16));
         const double cf = (double)r * r * r / 3.0;
         if (p.fast_orth[m]) { chol_b += cb; chol_f += cf; }
         if (p.wide_orth[m]) { wchol_b += cb; wchol_f += cf; }
@@ -525,11 +542,18 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
     }
     if (wide.njobs) {
         ASI_ADD(pg, "", pre2_b, pre2_b / 8.0, make_orth_presum(pre2, it__));
+        OrthArgs wchol = wide;           // the factorisation reads the summed Grams where a tree level made them
+        for (int j = 0; j < wchol.njobs; ++j) {
+            const int m = wchol.job[j].mode1 - 1;
+            if (p.Gsum[m]) { wchol.job[j].Gpart = p.Gsum[m]; wchol.job[j].nblk = p.ngsum[m]; }
+        }
         ASI_ADD(pg, "", wide_b, wide_f, make_orthw_gram(wide, it__));
-        ASI_ADD(pg, "", wchol_b, wchol_f, make_orthw_chol(wide, 0, 0, it__));
+        if (gsum.njobs) ASI_ADD(pg, "", gsum_b, gsum_b / 8.0, make_orth_presum(gsum, it__));
+        ASI_ADD(pg, "", wchol_b, wchol_f, make_orthw_chol(wchol, 0, 0, it__));
         ASI_ADD(pg, "", 2 * wide_b, wide_f, make_orthw_apply(wide, 0, it__));
         ASI_ADD(pg, "", wide_b, wide_f, make_orthw_gram(wide, it__));
-        ASI_ADD(pg, "", wchol_b, wchol_f, make_orthw_chol(wide, 1, 1, it__));
+        if (gsum.njobs) ASI_ADD(pg, "", gsum_b, gsum_b / 8.0, make_orth_presum(gsum, it__));
+        ASI_ADD(pg, "", wchol_b, wchol_f, make_orthw_chol(wchol, 1, 1, it__));
         ASI_ADD(pg, "", 1.5 * wide_b, wide_f, make_orthw_apply(wide, 1, it__));
     }
     if (slow.njobs) ASI_ADD(pg, "", 6 * slow_b, 9 * slow_f, make_orth_big(slow, it__));

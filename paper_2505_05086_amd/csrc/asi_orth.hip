@@ -1189,11 +1189,13 @@ static bool fast_args_ok(const OrthArgs& a) {
     }
     return true;
 }
-static bool wide_args_ok(const OrthArgs& a) {
+// summed: the factorisation may be handed slice Grams that a tree level has already added up (fewer of them)
+static bool wide_args_ok(const OrthArgs& a, bool summed = false) {
     if (a.njobs <= 0 || a.njobs > 4) return false;
     for (int j = 0; j < a.njobs; ++j) {
         const OrthJob& jb = a.job[j];
-        if (jb.n <= 0 || !orth_wide_supported(jb.r) || jb.nblk != orth_wide_gram_blocks(jb.n)) return false;
+        if (jb.n <= 0 || !orth_wide_supported(jb.r)) return false;
+        if (summed ? (jb.nblk < 1 || jb.nblk > orth_wide_gram_blocks(jb.n)) : jb.nblk != orth_wide_gram_blocks(jb.n)) return false;
         if (!jb.Gpart || !jb.R || !jb.Dinv || !jb.scal || !jb.P64 || !jb.Uout) return false;
     }
     return true;
@@ -1218,7 +1220,7 @@ bool make_orthw_gram(const OrthArgs& a, Item* out) {
     return wide_args_ok(a) && put_orth(IT_ORTHW_GRAM, 0, "k_orthw_gram", a, total_blocks(a), out);
 }
 bool make_orthw_chol(const OrthArgs& a, int pass, int last, Item* out) {
-    return wide_args_ok(a) && put_orth(IT_ORTHW_CHOL, (pass ? 1 : 0) | (last ? 2 : 0), "k_orthw_chol", a, a.njobs, out);
+    return wide_args_ok(a, true) && put_orth(IT_ORTHW_CHOL, (pass ? 1 : 0) | (last ? 2 : 0), "k_orthw_chol", a, a.njobs, out);
 }
 bool make_orthw_apply(const OrthArgs& a, int final_pass, Item* out) {
     if (!wide_args_ok(a)) return false;

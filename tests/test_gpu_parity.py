@@ -314,3 +314,11 @@ def test_ill_conditioned_wide_rank_stays_orthonormal(ratio):
     skipped) is covered by the rank-100 case of the linear edge shapes."""
     lay = Layer("illcond", (8, 40, 260), (6, 16, 90), "f32", "linear", 12)
     _check_orthonormal_basis(lay, _graded_tensor(lay, ratio), 8, f"wide ratio {ratio}")
+
+
+@pytest.mark.parametrize("ratio", [0.3, 0.05])
+def test_ill_conditioned_wide_rank_many_slices(ratio):
+    """A wide mode long enough (2100 rows: 17 slices of 128) that its slice Gram matrices are added
+    by a tree level before the factorisation; both passes and the shifted retry read the summed ones."""
+    lay = Layer("illcond", (8, 20, 2100), (6, 16, 90), "f32", "linear", 12)
+    _check_orthonormal_basis(lay, _graded_tensor(lay, ratio), 10, f"wide, many slices, ratio {ratio}")
