@@ -129,7 +129,7 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
             p.Gpart[m] = c.take<double>((size_t)p.nblk[m] * r * r);
             // The factorisation is one workgroup; summing megabytes of slice Grams there runs at the
             // bandwidth of one CU (110 us for 24 slices of 192 x 192), so a tree level does it first.
-            if ((size_t)p.nblk[m] * r * r >= (size_t)1 << 17) {
+            if ((size_t)p.nblk[m] * r * r >= (size_t)1 << 16) {
                 p.ngsum[m] = (p.nblk[m] + 31) / 32;
                 p.Gsum[m] = c.take<double>((size_t)p.ngsum[m] * r * r);
             }

@@ -22,6 +22,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 namespace asi {
 
@@ -37,12 +38,14 @@ constexpr double OP_DONE_TOL = 1e-7;   // |Q0^T Q0 - I| below which the first pa
 __device__ long long g_orth_stamps[64];
 #define STAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 2 && pass == 0) g_orth_stamps[i] = wall_clock64(); } while (0)
 #define KSTAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 2) g_orth_stamps[i] = wall_clock64(); } while (0)
+#define WSTAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 3 && pass == 0) g_orth_stamps[i] = wall_clock64(); } while (0)
 extern "C" int asi_debug_orth_stamps(long long* out) {
     return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_orth_stamps), sizeof(long long) * 64);
 }
 #else
 #define STAMP(i) do {} while (0)
 #define KSTAMP(i) do {} while (0)
+#define WSTAMP(i) do {} while (0)
 #endif
 
 __device__ __forceinline__ void flag_info(int32_t* info, int mode1, int col1) {
@@ -727,7 +730,7 @@ __global__ __launch_bounds__(256) void k_orth_apply(OrthBatch a) {
 //   applyw: 32-row blocks, R's off-diagonal blocks are read straight from global memory
 constexpr int OW_RMAX = 192;
 constexpr int OW_LD = OW_RMAX + 1;
-constexpr int OW_ROWS = 128;            // rows per gramw block
+constexpr int OW_ROWS = 64;             // rows per gramw block
 constexpr int OW_MAXPAIR = 20;          // block pairs per wave: ceil(78 / 4)
 
 __global__ __launch_bounds__(256) void k_orthw_gram(OrthBatch a) {
@@ -794,7 +797,10 @@ __global__ __launch_bounds__(256) void k_orthw_gram(OrthBatch a) {
 
 extern __shared__ double ow_dyn[];
 
-__global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int last) {
+// 512 threads: with 1024 a thread may hold 128 registers, and the diagonal-block factorisation (a column
+// of 16 doubles per lane plus its panels) then spills to scratch memory: 13 us per block instead of 2.
+constexpr int OWC_NT = 512, OWC_NW = OWC_NT / 64;
+__global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, int last) {
     const OrthJob jb = a.job[blockIdx.x];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     double* Gp = ow_dyn;                              // packed upper triangle, r (r + 1) / 2
@@ -802,34 +808,39 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
     double* rdiag = dinv + r;
     __shared__ double s_trace;
     __shared__ int s_bad;
-    auto pidx = [r](int ga, int gb) { return ga * r - (ga * (ga - 1)) / 2 + (gb - ga); };
+    auto pidx = [r](int ga, int gb) __attribute__((always_inline)) { return ga * r - (ga * (ga - 1)) / 2 + (gb - ga); };
     __shared__ int s_lost;
-    __shared__ double s_red[16];
+    __shared__ double s_red[OWC_NW];
     if (tid == 0) { s_bad = 0; s_lost = 0; }
-    // Gp = sum of the slice Grams; returns this thread's share of max |G - I|
-    auto sum_gram = [&]() {
+    // Gp = sum of the slice Grams; returns this thread's share of max |G - I|.  A round keeps 32 loads
+    // per thread in flight: 4 elements x 8 slices, or 16 elements x 2 slices when a tree level has
+    // already added the slices up (quotient e / r by a rounded float product: exact for r * r < 2^21).
+    const float inv_rf = 1.0f / (float)r;
+    auto sum_gram_t = [&](auto c_c, auto u_c) __attribute__((always_inline)) {
+        constexpr int C = decltype(c_c)::value, U = decltype(u_c)::value;
         double dev = 0.0;
-        // four elements per thread and round, eight slices each: 32 loads in flight
-        for (int e0 = tid; e0 < r * r; e0 += 4 * 1024) {
-            double s[4] = {0.0, 0.0, 0.0, 0.0};
-            for (int b0 = 0; b0 < jb.nblk; b0 += 8) {
-                double t[4][8];
+        for (int e0 = tid; e0 < r * r; e0 += C * OWC_NT) {
+            double s[C];
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
+            for (int c = 0; c < C; ++c) s[c] = 0.0;
+            for (int b0 = 0; b0 < jb.nblk; b0 += U) {
+                double t[C][U];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int e = e0 + 1024 * c;
+                for (int c = 0; c < C; ++c)
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int e = e0 + OWC_NT * c;
                         t[c][u] = ldg_f64(jb.Gpart, (long long)(b0 + u) * r * r + e, e < r * r && b0 + u < jb.nblk);
                     }
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
+                for (int c = 0; c < C; ++c)
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) s[c] += t[c][u];
+                    for (int u = 0; u < U; ++u) s[c] += t[c][u];
             }
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int e = e0 + 1024 * c;
-                const int ga = e / r, gb = e - ga * r;
+            for (int c = 0; c < C; ++c) {
+                const int e = e0 + OWC_NT * c;
+                const int ga = small_div(e, inv_rf), gb = e - ga * r;
                 if (e < r * r && ga <= gb) {
                     Gp[pidx(ga, gb)] = s[c];
                     dev = fmax(dev, fabs(s[c] - (ga == gb ? 1.0 : 0.0)));
@@ -838,10 +849,14 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
         }
         return dev;
     };
+    auto sum_gram = [&]() __attribute__((always_inline)) {
+        return jb.nblk <= 2 ? sum_gram_t(std::integral_constant<int, 16>{}, std::integral_constant<int, 2>{})
+                            : sum_gram_t(std::integral_constant<int, 4>{}, std::integral_constant<int, 8>{});
+    };
     // Blocked right-looking factorisation in place, the scheme of the r <= 64 path on the packed
     // triangle: wave 0 factors a 16x16 diagonal block in registers (chol_block16, which also leaves
     // the inverse of the block's unit triangular factor in Xs and the pivots' reciprocals in pinvs),
-    // then the 16 waves solve the block row and update the trailing blocks on fp64 MFMA.  Rows are
+    // then all waves solve the block row and update the trailing blocks on fp64 MFMA.  Rows are
     // left unscaled (row k holds R[k][j] R[k][k], the diagonal the pivots R[k][k]^2).  A pivot that is
     // not above 1e-12 of its diagonal entry (rdiag holds the diagonal before elimination) sets s_lost.
     const int nb = (r + 15) / 16;
@@ -850,75 +865,21 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
     double (*rowbuf)[64][4] = reinterpret_cast<double (*)[64][4]>(pinvs + nb * 16 + 16 * 17);
     const GramPacked G{Gp, r};
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
-    auto factor = [&]() {
-        int bad = 0;
-        for (int P = 0; P < nb; ++P) {
-            if (wave == 0) chol_block16(G, rowbuf, Xs, pinvs, 16 * P, &bad);
-            __syncthreads();
-            if (tid < 16 && 16 * P + tid < r) {
-                const double p = G.ld(16 * P + tid, 16 * P + tid);          // the pivot actually used
-                if (!(p > 1e-12 * rdiag[16 * P + tid])) s_lost = 1;
-            }
-            if (P + 1 < nb) {
-                // block row P right of the diagonal:  U_PJ = L_PP^-1 G_PJ
-                for (int J = P + 1 + wave; J < nb; J += 16) {
-                    double bv[4];
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) bv[ks] = G.ld(16 * P + 4 * ks + lg, 16 * J + ll);
-                    v4d acc = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks)      // A[i][k] = (L^-1)[i][k] = Xs[k][i]
-                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Xs[4 * ks + lg][ll], bv[ks], acc, 0, 0, 0);
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) G.st(16 * P + lg + 4 * v, 16 * J + ll, acc[v]);
-                }
-                __syncthreads();
-                // trailing blocks:  G_IJ -= U_PI^T diag(1/pivot) U_PJ,  P < I <= J
-                int cnt = 0;
-                for (int I = P + 1; I < nb; ++I)
-                    for (int J = I; J < nb; ++J, ++cnt) {
-                        if ((cnt & 15) != wave) continue;
-                        v4d acc;
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) acc[v] = G.ld(16 * I + lg + 4 * v, 16 * J + ll);
-#pragma unroll
-                        for (int ks = 0; ks < 4; ++ks) {
-                            const int k = 16 * P + 4 * ks + lg;
-                            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-G.ld(k, 16 * I + ll), G.ld(k, 16 * J + ll) * pinvs[k], acc, 0, 0, 0);
-                        }
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) G.st(16 * I + lg + 4 * v, 16 * J + ll, acc[v]);
-                    }
-                __syncthreads();
-            }
-        }
-        if (tid == 0) s_bad = bad;
-        __syncthreads();
-    };
+    WSTAMP(0);
     double dev = sum_gram();
     __syncthreads();
+    WSTAMP(1);
     if (pass == 0) {
-        // Plain Cholesky first; only if a pivot is lost is the Gram matrix summed again, shifted and
-        // factored once more (the same policy as the r <= 64 path).
-        if (tid == 0) {
-            double tr = 0.0;
-            for (int k = 0; k < r; ++k) tr += Gp[pidx(k, k)];
-            s_trace = tr;
-            jb.scal[0] = tr;
-        }
         if (tid < r) rdiag[tid] = Gp[pidx(tid, tid)];
         __syncthreads();
-        factor();
-        if (s_lost || s_bad) {
-            __syncthreads();
-            if (tid == 0) { s_bad = 0; s_lost = 0; }
-            sum_gram();
-            __syncthreads();
-            const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * s_trace;
-            if (tid < r) Gp[pidx(tid, tid)] += shift;
-            __syncthreads();
-            factor();
+        if (wave == 0) {                 // trace: lanes sum every 64th diagonal entry, then a fixed-order butterfly
+            double tr = 0.0;
+            for (int k = lane; k < r; k += 64) tr += rdiag[k];
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) tr += __shfl_xor(tr, m);
+            if (lane == 0) { s_trace = tr; jb.scal[0] = tr; }
         }
+        __syncthreads();
     } else {
         // Second pass: if Q0 is orthonormal to 1e-7 already, its fp32 copy (written by the first solve)
         // is the result and the final solve returns at once.
@@ -927,7 +888,7 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
         if ((tid & 63) == 0) s_red[tid >> 6] = dev;
         __syncthreads();
         dev = 0.0;
-        for (int w = 0; w < 16; ++w) dev = fmax(dev, s_red[w]);
+        for (int w = 0; w < OWC_NW; ++w) dev = fmax(dev, s_red[w]);
         const bool done = dev <= OP_DONE_TOL;
         if (tid == 0) {
             jb.scal[2 + OW_RMAX] = done ? 1.0 : 0.0;
@@ -943,8 +904,101 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
         if (done) return;
         if (tid < r) rdiag[tid] = Gp[pidx(tid, tid)];
         __syncthreads();
-        factor();
     }
+    WSTAMP(2);
+    // First pass: plain Cholesky first; only if a pivot is lost is the Gram matrix summed again, shifted
+    // and factored once more (the same policy as the r <= 64 path).  The factorisation is written once,
+    // inside this loop: as a lambda called from three places it was not inlined, its captured pointers
+    // went through scratch memory and every LDS access in it became a flat access.
+    for (int attempt = 0;; ++attempt) {
+        int bad = 0;
+        for (int P = 0; P < nb; ++P) {
+            if (P == 0) WSTAMP(10);
+            if (wave == 0) chol_block16(G, rowbuf, Xs, pinvs, 16 * P, &bad);
+            if (P == 0) WSTAMP(11);
+            __syncthreads();
+            if (P == 0) WSTAMP(12);
+            if (tid < 16 && 16 * P + tid < r) {
+                const double p = G.ld(16 * P + tid, 16 * P + tid);          // the pivot actually used
+                if (!(p > 1e-12 * rdiag[16 * P + tid])) s_lost = 1;
+            }
+            if (P + 1 < nb) {
+                // block row P right of the diagonal:  U_PJ = L_PP^-1 G_PJ
+                for (int J = P + 1 + wave; J < nb; J += OWC_NW) {
+                    double bv[4];
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) bv[ks] = G.ld(16 * P + 4 * ks + lg, 16 * J + ll);
+                    v4d acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)      // A[i][k] = (L^-1)[i][k] = Xs[k][i]
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(Xs[4 * ks + lg][ll], bv[ks], acc, 0, 0, 0);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) G.st(16 * P + lg + 4 * v, 16 * J + ll, acc[v]);
+                }
+                __syncthreads();
+                if (P == 0) WSTAMP(13);
+                // trailing blocks:  G_IJ -= U_PI^T diag(1/pivot) U_PJ,  P < I <= J.  Rows k of the panel lie
+                // above both blocks, so their elements sit at roff[k] + column; a column past r reads the
+                // diagonal entry instead and counts as zero.  The twelve reads of a block pair are issued
+                // together (pinned: left alone, each is moved into a branch of its own and waited for there).
+                int roff[4];
+                double pv[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const int k = 16 * P + 4 * ks + lg;
+                    roff[ks] = k * r - (k * (k + 1)) / 2;
+                    pv[ks] = pinvs[k];
+                }
+                int cnt = 0;
+                for (int I = P + 1; I < nb; ++I)
+                    for (int J = I; J < nb; ++J, ++cnt) {
+                        if ((cnt & (OWC_NW - 1)) != wave) continue;
+                        const int ci = 16 * I + ll, cj = 16 * J + ll;
+                        const bool iin = ci < r, jin = cj < r;
+                        double av[4], bv[4], cv[4];
+                        int cidx[4];
+                        bool cin[4];
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks) {
+                            const int k = 16 * P + 4 * ks + lg;
+                            av[ks] = Gp[roff[ks] + (iin ? ci : k)];
+                            bv[ks] = Gp[roff[ks] + (jin ? cj : k)];
+                        }
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int rw = 16 * I + lg + 4 * v;
+                            cin[v] = rw <= cj && jin;
+                            cidx[v] = cin[v] ? rw * r - (rw * (rw + 1)) / 2 + cj : 0;
+                            cv[v] = Gp[cidx[v]];
+                        }
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(av[ks]), "+v"(bv[ks]), "+v"(cv[ks]));
+                        v4d acc;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[v] = cin[v] ? cv[v] : 0.0;
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks)
+                            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(iin ? -av[ks] : 0.0, jin ? bv[ks] * pv[ks] : 0.0, acc, 0, 0, 0);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (cin[v]) Gp[cidx[v]] = acc[v];
+                    }
+                __syncthreads();
+                if (P == 0) WSTAMP(14);
+            }
+        }
+        if (tid == 0) s_bad = bad;
+        __syncthreads();
+        if (pass != 0 || attempt != 0 || !(s_lost || s_bad)) break;
+        __syncthreads();
+        if (tid == 0) { s_bad = 0; s_lost = 0; }
+        sum_gram();
+        __syncthreads();
+        const double shift = 11.0 * ((double)n * r + (double)r * (r + 1)) * OP_EPS * s_trace;
+        if (tid < r) Gp[pidx(tid, tid)] += shift;
+        __syncthreads();
+    }
+    WSTAMP(3);
     if (tid < r) {
         double p = Gp[pidx(tid, tid)];
         if (!(p > 0.0)) p = 1.0;
@@ -955,19 +1009,20 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
         jb.scal[1 + tid] = rd;
     }
     __syncthreads();
-    for (int e = tid; e < r * r; e += 1024) {
-        const int ga = e / r, gb = e - ga * r;
+    WSTAMP(4);
+    for (int e = tid; e < r * r; e += OWC_NT) {      // R, and the rows scaled in place (each entry has one owner)
+        const int ga = small_div(e, inv_rf), gb = e - ga * r;
         double v = 0.0;
-        if (ga < gb) { v = Gp[pidx(ga, gb)] * dinv[ga]; }
-        else if (ga == gb) v = 1.0 / dinv[ga];
+        if (ga < gb) {
+            v = Gp[pidx(ga, gb)] * dinv[ga];
+            Gp[pidx(ga, gb)] = v;
+        } else if (ga == gb) {
+            v = 1.0 / dinv[ga];
+        }
         jb.R[e] = v;
     }
     __syncthreads();
-    for (int e = tid; e < r * r; e += 1024) {      // scale in place after everyone has read the unscaled rows
-        const int ga = e / r, gb = e - ga * r;
-        if (ga < gb) Gp[pidx(ga, gb)] *= dinv[ga];
-    }
-    __syncthreads();
+    WSTAMP(5);
     if (tid < nb * 16) {
         const int b = tid >> 4, i = tid & 15, base = 16 * b;
         double x[16];
@@ -981,6 +1036,7 @@ __global__ __launch_bounds__(1024) void k_orthw_chol(OrthBatch a, int pass, int 
 #pragma unroll
         for (int j = 0; j < 16; ++j) jb.Dinv[(b * 16 + i) * 16 + j] = x[j];
     }
+    WSTAMP(6);
     if (tid == 0) {
         double bad = (pass == 0) ? 0.0 : jb.scal[1 + OW_RMAX];
         if (bad == 0.0 && s_bad) bad = (double)s_bad;
@@ -1318,7 +1374,7 @@ hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st, ch
                 if (e != hipSuccess) return e;
                 lds_allowed = lds;
             }
-            hipLaunchKernelGGL(k_orthw_chol, grid, 1024, lds, st, b, aux & 1, (aux >> 1) & 1);
+            hipLaunchKernelGGL(k_orthw_chol, grid, OWC_NT, lds, st, b, aux & 1, (aux >> 1) & 1);
             break;
         }
         case IT_ORTHW_APPLY:
