@@ -185,15 +185,24 @@ static long long pair_cols_per_split(long long ncols, int nsplit) {
 int pair_splits(long long outer, int n, long long inner, int r) {
     const long long ncols = outer * inner;
     const long long tiles = (long long)((n + PR_TI - 1) / PR_TI) * ((r + PR_TQ - 1) / PR_TQ);
-    long long want = 512 / (tiles > 0 ? tiles : 1);           // aim at ~512 workgroups
-    const long long maxs = (ncols + 255) / 256;               // at least 256 columns per split
-    if (want > maxs) want = maxs;
-    if (want > 32) want = 32;                                 // what the Gram kernel sums without a tree level
-    if (want < 1) want = 1;
-    // no empty split: shrink until the last split starts inside the column range
-    int ns = (int)want;
-    while (ns > 1 && pair_cols_per_split(ncols, ns) * (ns - 1) >= ncols) --ns;
-    return ns;
+    long long maxs = (ncols + 255) / 256;                     // at least 256 columns per split
+    if (maxs > 32) maxs = 32;                                 // what the Gram kernel sums without a tree level
+    if (maxs < 1) maxs = 1;
+    // The chip holds two workgroups per CU at full rate (512 slots; a single workgroup per CU leaves the
+    // MFMA pipe idle while it loads and stores tiles).  Workgroups beyond that run in further rounds, so
+    // the time goes as rounds x (columns of a split + a fixed cost per workgroup, worth ~128 columns);
+    // the number of splits minimises it.  Few tiles: as many splits as allowed (one round anyway); many
+    // tiles (a 3072 x 192 result is 288): a count that fills whole rounds, not one workgroup per CU.
+    int best = 1;
+    long long best_cost = -1;
+    for (int ns = 1; ns <= (int)maxs; ++ns) {
+        const long long cps = pair_cols_per_split(ncols, ns);
+        if (ns > 1 && cps * (ns - 1) >= ncols) continue;     // the last split would be empty
+        const long long rounds = (tiles * ns + 511) / 512;
+        const long long cost = rounds * (cps + 128);
+        if (best_cost < 0 || cost < best_cost) { best = ns; best_cost = cost; }
+    }
+    return best;
 }
 
 int presum_blocks(const PresumArgs& a) {
