@@ -186,7 +186,7 @@ int pair_splits(long long outer, int n, long long inner, int r) {
     const long long ncols = outer * inner;
     const long long tiles = (long long)((n + PR_TI - 1) / PR_TI) * ((r + PR_TQ - 1) / PR_TQ);
     long long maxs = (ncols + 255) / 256;                     // at least 256 columns per split
-    if (maxs > 32) maxs = 32;                                 // what the Gram kernel sums without a tree level
+    if (maxs > 64) maxs = 64;
     if (maxs < 1) maxs = 1;
     // The chip holds two workgroups per CU at full rate (512 slots; a single workgroup per CU leaves the
     // MFMA pipe idle while it loads and stores tiles).  Workgroups beyond that run in further rounds, so
@@ -199,7 +199,8 @@ int pair_splits(long long outer, int n, long long inner, int r) {
         const long long cps = pair_cols_per_split(ncols, ns);
         if (ns > 1 && cps * (ns - 1) >= ncols) continue;     // the last split would be empty
         const long long rounds = (tiles * ns + 511) / 512;
-        const long long cost = rounds * (cps + 128);
+        // beyond 32 splits the partial sums need a tree level: one more launch on the chain (~600 columns' worth)
+        const long long cost = rounds * (cps + 128) + (ns > 32 ? 600 : 0);
         if (best_cost < 0 || cost < best_cost) { best = ns; best_cost = cost; }
     }
     return best;
