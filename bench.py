@@ -251,8 +251,10 @@ def main():
         ga, gb = layer_graphs[0][0], layer_graphs[1][0]
         probe_us([(ga, main_stream), (gb, main_stream)], 2)
         ta, tb = probe_us([(ga, main_stream)]), probe_us([(gb, main_stream)])
-        # side by side two chains take about the longer one, on one queue their sum
-        shared_above = max(ta, tb) + 0.5 * min(ta, tb)
+        # On one queue two chains take the sum of their times; side by side, between the longer one
+        # (small layers, which only wait on launch and memory latency) and ~80 % of the sum (large
+        # layers that compete for the CUs).
+        shared_above = 0.9 * (ta + tb)
         candidates = [main_stream] + [torch.cuda.Stream() for _ in range(11)]
         chosen, tested = [main_stream], 0
         for cand in candidates[1:]:
