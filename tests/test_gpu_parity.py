@@ -171,6 +171,7 @@ EDGE_CONV = [
     ((2, 70, 33, 17), (2, 20, 9, 6), 5, 5, 2, 2, 1, 1),        # 5x5 kernel, several tiles per mode
     ((3, 4, 8, 8), (2, 3, 8, 7), 5, 3, 1, 1, 1, 1),            # 8x8 planes at (almost) full rank: widest tiny-plane kernel
     ((4100, 32, 7, 7), (6, 8, 5, 5), 8, 3, 1, 1, 1, 1),        # more 7x7 planes than workgroups: each walks several tiles
+    ((40, 70, 33, 31), (4, 20, 6, 5), 6, 3, 1, 1, 1, 1),       # 40920 ragged columns for the 70-channel mode: more than 32 column splits, so a tree level
 ]
 
 
