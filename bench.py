@@ -44,7 +44,8 @@ def measured_traffic(cfg_index: int, symbol: str):
     path = os.path.join(ROOT, "profiles", f"config{cfg_index}_hbm_traffic.json")
     try:
         with open(path) as f:
-            rec = json.load(f).get("kernels", {}).get(symbol)
+            kernels = json.load(f).get("kernels", {})
+            rec = kernels.get(symbol) or kernels.get(symbol.replace("asi::", ""))   # the summary drops the namespace
         return None if rec is None else float(rec["fetch_bytes_per_launch"]) + float(rec["write_bytes_per_launch"])
     except (OSError, ValueError, KeyError):
         return None
