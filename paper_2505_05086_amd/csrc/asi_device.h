@@ -22,12 +22,6 @@ __device__ __forceinline__ float ldg_f32(const T* __restrict__ p, long long idx,
     const T v = p[ok ? idx : 0];
     return ok ? to_f32(v) : 0.f;
 }
-// The same for the stored pattern itself (no widening): zero when the guard fails.
-template <typename T>
-__device__ __forceinline__ T ldg_raw(const T* __restrict__ p, long long idx, bool ok) {
-    const T v = p[ok ? idx : 0];
-    return ok ? v : T{};
-}
 __device__ __forceinline__ double ldg_f64(const double* __restrict__ p, long long idx, bool ok) {
     const double v = p[ok ? idx : 0];
     return ok ? v : 0.0;
