@@ -14,9 +14,11 @@ __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uin
 template <typename T>
 __device__ __forceinline__ float ldf(const T* __restrict__ p, long long idx) { return to_f32(p[idx]); }
 
-// Guarded loads without a branch: the index is clamped to element 0 (always valid) and the
-// value is selected afterwards, so that many loads stay in flight instead of each waiting
-// inside its own conditional block.
+// Guarded loads: the index is clamped to element 0 (always valid) and the value is selected
+// afterwards, so that the load itself needs no branch.  The compiler may still wrap load and
+// widening in a conditional block of its own (it does for bf16 when the guard is a single
+// comparison), and the load is then waited for inside that block; loops whose speed depends on
+// many loads in flight keep what they load as raw bits and mask it later (asi_ttm.hip, k_pair).
 template <typename T>
 __device__ __forceinline__ float ldg_f32(const T* __restrict__ p, long long idx, bool ok) {
     const T v = p[ok ? idx : 0];
