@@ -46,6 +46,11 @@ def test_workspace_query():
     assert asi.asi_workspace_bytes(d, None, 100) == 0                                        # linear needs 3 modes
     d3 = asi.make_desc((4, 5, 6), (2, 3, 4), "bf16")
     assert asi.asi_workspace_bytes(d3, None, 7) > 0
+    # a wide mode (rank above 64) with many Gram slices: the plan includes the tree level's buffer
+    wide = asi.asi_workspace_bytes(asi.make_desc((64, 197, 3072), (32, 64, 192), "bf16"), None, 768)
+    assert wide > 0 and wide % 256 == 0
+    # a rank above the number of columns of its unfolding (90 > 4 * 20) cannot be reached
+    assert asi.asi_workspace_bytes(asi.make_desc((4, 20, 2100), (3, 8, 90)), None, 12) == 0
 
 
 def _arr(n=4):
