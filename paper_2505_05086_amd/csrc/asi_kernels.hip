@@ -353,7 +353,7 @@ hipError_t launch_expand_items(const Item* const* items, int n, hipStream_t st) 
 // ---------------------------------------------------------------------------
 // key bits of the mode-product kernels that only bound sizes (see asi_ttm.hip): NBR, KS
 static unsigned launch_class(const Item& it) {
-    if (it.kind == IT_TTM || it.kind == IT_KSPLIT) return it.key & 0x600fu;
+    if (it.kind == IT_TTM || it.kind == IT_KSPLIT) return it.key & 0xe00fu;
     if (it.kind == IT_TTM_DUO) return it.key & 0xfu;
     return it.key;
 }

@@ -363,10 +363,79 @@ __global__ __launch_bounds__(256) void k_ttm_ksplit(Batch<TtmJob> bt) {
     }
 }
 
+// ---- very short modes on the vector ALU ---------------------------------------------------------
+// A mode of at most 16 entries with at most 16 outputs (the batch mode of a high-resolution layer:
+// 8 x 8 over a million columns) gives the MFMA tiles of k_ttm_mfma nothing to do — a 64-column tile is
+// 2 KB of data, and the launch is bound by the number of workgroups.  Here a thread owns TH_CPT
+// columns: it loads their n values (lanes along the contiguous index), multiplies by the matrix held
+// in LDS (read as whole rows, the same address in every lane) and stores r values per column.
+constexpr int TH_CPT = 2, TH_COLS = 256 * TH_CPT;
+template <typename T, int NMAX>
+__global__ __launch_bounds__(256) void k_ttm_thin(Batch<TtmJob> bt) {
+    __shared__ __align__(16) float Ms[16][16];
+    int lb;
+    const TtmJob& jb = bt.job[locate(bt, &lb)];
+    const T* __restrict__ X = static_cast<const T*>(jb.X);
+    float* __restrict__ Y = jb.Y;
+    const long long outer = jb.outer, inner = jb.inner, ncols = outer * inner;
+    const int n = jb.n, r = jb.r, beta = jb.beta, tid = threadIdx.x;
+    if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
+    {
+        const int i = tid >> 4, q = tid & 15;
+        Ms[i][q] = ldg_f32(jb.Mp, (long long)i * jb.ms_i + (long long)q * jb.ms_q, i < n && q < r);
+    }
+    // (o, j) of the workgroup's first column by one division (uniform), of a thread's columns by additions
+    const long long cw = (long long)lb * TH_COLS;
+    const long long ow = cw / inner, jw = cw - ow * inner;
+    long long xb[TH_CPT], yb[TH_CPT];
+    bool ok[TH_CPT];
+    T xv[TH_CPT][NMAX];
+#pragma unroll
+    for (int t = 0; t < TH_CPT; ++t) {
+        long long o = ow, j = jw + t * 256 + tid;
+        while (j >= inner) { j -= inner; ++o; }
+        ok[t] = cw + t * 256 + tid < ncols;
+        xb[t] = ok[t] ? o * (long long)n * inner + j : 0;          // past the end: column 0, dropped at the store
+        yb[t] = ok[t] ? o * (long long)r * inner + j : 0;
+#pragma unroll
+        for (int i = 0; i < NMAX; ++i) xv[t][i] = X[xb[t] + (long long)(i < n ? i : n - 1) * inner];
+    }
+    __syncthreads();
+    float acc[TH_CPT][16];
+#pragma unroll
+    for (int t = 0; t < TH_CPT; ++t)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[t][q] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i) {
+        float m[16];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const v4f row = *reinterpret_cast<const v4f*>(&Ms[i][4 * q4]);      // rows i >= n are zero
+            m[4 * q4] = row[0]; m[4 * q4 + 1] = row[1]; m[4 * q4 + 2] = row[2]; m[4 * q4 + 3] = row[3];
+        }
+#pragma unroll
+        for (int t = 0; t < TH_CPT; ++t) {
+            const float x = i < n ? to_f32(xv[t][i]) : 0.f;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[t][q] = fmaf(x, m[q], acc[t][q]);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TH_CPT; ++t)
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            if (ok[t] && q < r) {
+                const long long idx = yb[t] + (long long)q * inner;
+                Y[idx] = beta ? Y[idx] + acc[t][q] : acc[t][q];
+            }
+}
+
 // ---- host side -----------------------------------------------------------------------------------
 // key bits: [0] bf16 input, [1] LASTMODE, [2] KRON, [3] split kernel, [4..6] NBR-1, [8..12] KS,
 // [13] split kernel with several column blocks per workgroup (4 up to NBR = 3, else 2),
-// [14] K chunks of 64 (tiled kernel along the last mode).  Bits 4..12 only bound sizes.
+// [14] K chunks of 64 (tiled kernel along the last mode), [15] the vector-ALU kernel for very short modes.
+// Bits 4..12 only bound sizes.
 static unsigned ttm_key(bool bf16, bool last, bool kron, bool ksplit, int nbr, int ks, bool wide, bool kc64) {
     return (bf16 ? 1u : 0u) | (last ? 2u : 0u) | (kron ? 4u : 0u) | (ksplit ? 8u : 0u) | ((unsigned)(nbr - 1) << 4) |
            ((unsigned)ks << 8) | (wide ? 0x2000u : 0u) | (kc64 ? 0x4000u : 0u);
@@ -390,7 +459,13 @@ static bool fill_ttm(DType xt, const void* X, long long outer, int n, long long 
     jb.kr = kr; jb.n = n; jb.r = r; jb.beta = beta;
     const char* tn = xt == F32 ? "float" : "asi::bf16_t";
     *out = Item();
-    if (!kron && prefer_ksplit(ncols, n, inner)) {
+    if (!kron && !last && n <= 16 && r <= 16 && ncols >= (1LL << 18)) {
+        const long long gx = (ncols + TH_COLS - 1) / TH_COLS;
+        if (gx > 0x3fffffffLL) return false;
+        jb.gx = (int)gx; jb.gy = 1;
+        out->kind = IT_TTM; out->key = ttm_key(xt == BF16, false, false, false, 1, 0, false, false) | 0x8000u;
+        std::snprintf(out->label, sizeof(out->label), "k_ttm_thin<%s, %d>", tn, n <= 8 ? 8 : 16);
+    } else if (!kron && prefer_ksplit(ncols, n, inner)) {
         const int nbr = r >= 64 ? 4 : (r + 15) / 16;
         // several column blocks per workgroup share the matrix operand; worth it once that still
         // leaves a workgroup for every other CU
@@ -462,7 +537,7 @@ static void launch_split(int ks, bool wide, const Batch<TtmJob>& b, dim3 grid, h
 // Fails (and leaves *out alone) if the two do not have these forms; the caller then launches them apart.
 bool make_ttm_duo(const Item& a, const Item& z, Item* out) {
     if (a.kind != IT_TTM || z.kind != IT_TTM) return false;
-    if ((a.key & 0x600eu) != 0u) return false;                 // not last mode, plain, tiled, chunks of 32
+    if ((a.key & 0xe00eu) != 0u) return false;                 // not last mode, plain, tiled, chunks of 32
     if ((z.key & 0x600fu) != (2u | 4u)) return false;          // fp32, last mode, Kronecker, tiled, chunks of 32
     TtmDuoJob jb;
     std::memcpy(&jb.a, a.arg, sizeof(TtmJob));
@@ -513,6 +588,18 @@ hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, cha
     const unsigned key = items[0]->key;
     const bool bf16 = key & 1u, last = key & 2u, kron = key & 4u, ksplit = key & 8u;
     const bool wide = key & 0x2000u, kc64 = key & 0x4000u;
+    if (key & 0x8000u) {             // very short mode: one instantiation per bound on n
+        int nmax = 8;
+        for (int j = 0; j < n; ++j) {
+            TtmJob tj;
+            std::memcpy(&tj, items[j]->arg, sizeof(tj));
+            if (tj.n > 8) nmax = 16;
+        }
+        if (label_out) std::snprintf(label_out, 96, "k_ttm_thin<%s, %d>", bf16 ? "asi::bf16_t" : "float", nmax);
+        if (!bf16) { if (nmax == 8) hipLaunchKernelGGL((k_ttm_thin<float, 8>), grid, 256, 0, st, b); else hipLaunchKernelGGL((k_ttm_thin<float, 16>), grid, 256, 0, st, b); }
+        else { if (nmax == 8) hipLaunchKernelGGL((k_ttm_thin<bf16_t, 8>), grid, 256, 0, st, b); else hipLaunchKernelGGL((k_ttm_thin<bf16_t, 16>), grid, 256, 0, st, b); }
+        return hipGetLastError();
+    }
     // the instantiation with the most column blocks / steps serves every item
     int nbr = 1, ks = 0;
     for (int j = 0; j < n; ++j) {

@@ -172,6 +172,8 @@ EDGE_CONV = [
     ((3, 4, 8, 8), (2, 3, 8, 7), 5, 3, 1, 1, 1, 1),            # 8x8 planes at (almost) full rank: widest tiny-plane kernel
     ((4100, 32, 7, 7), (6, 8, 5, 5), 8, 3, 1, 1, 1, 1),        # more 7x7 planes than workgroups: each walks several tiles
     ((40, 70, 33, 31), (4, 20, 6, 5), 6, 3, 1, 1, 1, 1),       # 40920 ragged columns for the 70-channel mode: more than 32 column splits, so a tree level
+    ((8, 6, 128, 128), (4, 5, 12, 12), 16, 3, 1, 1, 1, 1),       # batch of 8 over 262144 columns of grad_out: the vector-ALU product for very short modes
+    ((12, 5, 150, 150), (10, 4, 9, 9), 12, 3, 1, 1, 1, 1),       # the same with 9 to 16 entries, ragged planes
 ]
 
 
