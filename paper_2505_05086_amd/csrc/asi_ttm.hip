@@ -15,7 +15,9 @@
 // every operand goes from global memory straight into the MFMA registers (all loads of a round
 // are in flight together) and the four partial tiles are added through LDS.
 //
-// Both kernels take the argument blocks of several layers side by side (Batch<TtmJob>).
+// k_ttm_thin serves modes of at most 16 entries over very many columns on the vector ALU (further down).
+//
+// All kernels take the argument blocks of several layers side by side (Batch<TtmJob>).
 #include "asi_device.h"
 #include "asi_kernels.h"
 
