@@ -53,8 +53,8 @@ struct SmallJob {
     const void* X;
     long long outer;     // outer slices (whole_o) / rows of tiles
     long long o_elems;   // elements per outer slice
-    long long inner;     // whole_o == 0: row length; tile = n rows x 128 columns
-    int whole_o, To;
+    long long inner;     // whole_o == 0: row length; tile = To groups of (n rows x 128 columns), stacked in LDS
+    int whole_o, To;     // To: outer slices per tile (whole_o), else column groups per tile
     long long tiles_per_o;
     long long ntiles;
     int nviews;
@@ -74,7 +74,7 @@ extern "C" int asi_debug_ss_stamps(long long* out) {
 #define SSTAMP(i) do {} while (0)
 #endif
 
-template <typename T, int NBM, int NBR, int NV, bool WHOLE_O>
+template <typename T, int NBM, int NBR, int NV, bool WHOLE_O, bool STACK = false>   // STACK: several column groups per tile
 __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
     int lb;
     const SmallJob& jb = bt.job[locate(bt, &lb)];
@@ -127,21 +127,40 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
             }
             no_or_vc = no;
         } else {
+            // A short mode leaves most of the 64 LDS rows empty, so a tile takes To groups of 128 columns
+            // and stacks them: LDS row g * n + i holds mode index i of columns 128 g .. 128 g + 127.
+            const int G = jb.To, tcols = SS_TC * G;
             const long long o = tile / jb.tiles_per_o;
-            const long long j0 = (tile - o * jb.tiles_per_o) * SS_TC;
-            const int vc = (int)((jb.inner - j0 < SS_TC) ? jb.inner - j0 : SS_TC);
+            const long long j0 = (tile - o * jb.tiles_per_o) * tcols;
+            const int vc = (int)((jb.inner - j0 < tcols) ? jb.inner - j0 : tcols);
             const int c = tid & (SS_TC - 1);
-            const T* src = X + o * n0 * jb.inner + j0 + c;
+            const T* src = X + o * n0 * jb.inner + j0;
+            const float inv_n0 = 1.0f / (float)n0;
             T pre[32];
+            if constexpr (!STACK) {  // one group: LDS row = mode index
 #pragma unroll
-            for (int u = 0; u < 32; ++u) {
-                const int i = (tid >> 7) + 2 * u;
-                pre[u] = src[(c < vc && i < n0) ? (long long)i * jb.inner : 0];
-            }
+                for (int u = 0; u < 32; ++u) {
+                    const int i = (tid >> 7) + 2 * u;
+                    pre[u] = src[(c < vc && i < n0) ? (long long)i * jb.inner + c : 0];
+                }
 #pragma unroll
-            for (int u = 0; u < 32; ++u) {
-                const int i = (tid >> 7) + 2 * u;
-                if (i < n0) smem[i * rowI + c] = (c < vc) ? to_f32(pre[u]) : 0.f;
+                for (int u = 0; u < 32; ++u) {
+                    const int i = (tid >> 7) + 2 * u;
+                    if (i < n0) smem[i * rowI + c] = (c < vc) ? to_f32(pre[u]) : 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 32; ++u) {
+                    const int row = (tid >> 7) + 2 * u;
+                    const int g = (int)(((float)row + 0.5f) * inv_n0), i = row - g * n0, col = g * SS_TC + c;
+                    pre[u] = src[(g < G && col < vc) ? (long long)i * jb.inner + col : 0];
+                }
+#pragma unroll
+                for (int u = 0; u < 32; ++u) {
+                    const int row = (tid >> 7) + 2 * u;
+                    const int g = (int)(((float)row + 0.5f) * inv_n0), col = g * SS_TC + c;
+                    if (g < G) smem[row * rowI + c] = (col < vc) ? to_f32(pre[u]) : 0.f;
+                }
             }
             no_or_vc = vc;
         }
@@ -261,8 +280,12 @@ static void single_geometry(long long outer, int n, long long inner, SmallJob* j
         jb->whole_o = 1; jb->To = (int)To; jb->tiles_per_o = 0;
         jb->ntiles = (outer + To - 1) / To;
     } else {
-        jb->whole_o = 0; jb->To = 1;
-        jb->tiles_per_o = (inner + SS_TC - 1) / SS_TC;
+        // groups of 128 columns per tile: as many as the 64 LDS rows hold, while ~SS_MAX_WG tiles remain
+        int G = 64 / n;
+        while (G > 1 && outer * ((inner + (long long)SS_TC * G - 1) / ((long long)SS_TC * G)) < SS_MAX_WG) --G;
+        if (G < 1) G = 1;
+        jb->whole_o = 0; jb->To = G;
+        jb->tiles_per_o = (inner + (long long)SS_TC * G - 1) / ((long long)SS_TC * G);
         jb->ntiles = outer * jb->tiles_per_o;
     }
 }
@@ -288,7 +311,7 @@ int subspace_pair_nwg(long long planes, int rows, int cols) {
     return (int)(ntiles < SS_MAX_WG ? ntiles : SS_MAX_WG);
 }
 
-// key: [0] bf16, [1] two views, [2] whole_o, [4..6] NBM, [8..10] NBR
+// key: [0] bf16, [1] two views, [2] whole_o, [3] stacked column groups (n <= 32), [4..6] NBM, [8..10] NBR
 static bool small_key_ok(int nbm, int nbr, int nv) {
     if (nbm < 1 || nbm > 4 || nbr < 1 || nbr > nbm) return false;
     return nv == 1 || nbr <= 2;
@@ -299,11 +322,12 @@ static bool finish_small(DType xt, SmallJob& jb, int nbm, int nbr, int nwg, Item
     jb.nwg = nwg;
     *out = Item();
     out->kind = IT_SMALL;
-    out->key = (xt == BF16 ? 1u : 0u) | (jb.nviews == 2 ? 2u : 0u) | (jb.whole_o ? 4u : 0u) | ((unsigned)nbm << 4) |
-               ((unsigned)nbr << 8);
+    const bool stack = !jb.whole_o && jb.To > 1;
+    out->key = (xt == BF16 ? 1u : 0u) | (jb.nviews == 2 ? 2u : 0u) | (jb.whole_o ? 4u : 0u) | (stack ? 8u : 0u) |
+               ((unsigned)nbm << 4) | ((unsigned)nbr << 8);
     out->nblocks = nwg;
-    std::snprintf(out->label, sizeof(out->label), "k_subspace_small<%s, %d, %d, %d, %s>", xt == F32 ? "float" : "asi::bf16_t",
-                  nbm, nbr, jb.nviews, jb.whole_o ? "true" : "false");
+    std::snprintf(out->label, sizeof(out->label), "k_subspace_small<%s, %d, %d, %d, %s%s>", xt == F32 ? "float" : "asi::bf16_t",
+                  nbm, nbr, jb.nviews, jb.whole_o ? "true" : "false", stack ? ", true" : "");
     static_assert(sizeof(SmallJob) <= kItemArgMax, "argument block");
     std::memcpy(out->arg, &jb, sizeof(jb));
     return true;
@@ -322,7 +346,7 @@ bool make_subspace_small(DType xt, const void* X, long long outer, int n, long l
     if (jb.whole_o) {
         v.sI = (int)inner; v.div = (int)inner; v.mulA = n * (int)inner; v.mulB = 1; v.cols_per_o = (int)inner;
     } else {
-        v.sI = SS_TC + SS_PAD; v.div = SS_TC; v.mulA = 0; v.mulB = 1; v.cols_per_o = 0;
+        v.sI = SS_TC + SS_PAD; v.div = SS_TC; v.mulA = n * (SS_TC + SS_PAD); v.mulB = 1; v.cols_per_o = 0;   // group g starts n rows further down
     }
     v.inv_div = 1.0f / (float)v.div;
     jb.v[1] = jb.v[0];
@@ -533,7 +557,19 @@ hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st) {
 }
 
 template <typename T, int NV>
-static bool launch_small_t(const Batch<SmallJob>& b, dim3 grid, int nbm, int nbr, bool whole_o, hipStream_t st) {
+static bool launch_small_t(const Batch<SmallJob>& b, dim3 grid, int nbm, int nbr, bool whole_o, bool stack, hipStream_t st) {
+    if constexpr (NV == 1) {
+        if (stack) {
+            if (whole_o || nbm > 2) return false;
+            if (nbm == 1 && nbr == 1) hipLaunchKernelGGL((k_subspace_small<T, 1, 1, 1, false, true>), grid, 256, 0, st, b);
+            else if (nbm == 2 && nbr == 1) hipLaunchKernelGGL((k_subspace_small<T, 2, 1, 1, false, true>), grid, 256, 0, st, b);
+            else if (nbm == 2 && nbr == 2) hipLaunchKernelGGL((k_subspace_small<T, 2, 2, 1, false, true>), grid, 256, 0, st, b);
+            else return false;
+            return true;
+        }
+    } else if (stack) {
+        return false;
+    }
 #define ASI_SS_CASE(M, R)                                                                                \
     if (nbm == M && nbr == R) {                                                                          \
         if (whole_o) hipLaunchKernelGGL((k_subspace_small<T, M, R, NV, true>), grid, 256, 0, st, b);     \
@@ -554,11 +590,11 @@ hipError_t launch_small_items(const Item* const* items, int n, hipStream_t st) {
     dim3 grid;
     if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
     const unsigned key = items[0]->key;
-    const bool bf16 = key & 1u, two = key & 2u, whole_o = key & 4u;
+    const bool bf16 = key & 1u, two = key & 2u, whole_o = key & 4u, stack = key & 8u;
     const int nbm = (int)((key >> 4) & 7u), nbr = (int)((key >> 8) & 7u);
     bool ok;
-    if (!bf16) ok = two ? launch_small_t<float, 2>(b, grid, nbm, nbr, whole_o, st) : launch_small_t<float, 1>(b, grid, nbm, nbr, whole_o, st);
-    else ok = two ? launch_small_t<bf16_t, 2>(b, grid, nbm, nbr, whole_o, st) : launch_small_t<bf16_t, 1>(b, grid, nbm, nbr, whole_o, st);
+    if (!bf16) ok = two ? launch_small_t<float, 2>(b, grid, nbm, nbr, whole_o, stack, st) : launch_small_t<float, 1>(b, grid, nbm, nbr, whole_o, stack, st);
+    else ok = two ? launch_small_t<bf16_t, 2>(b, grid, nbm, nbr, whole_o, stack, st) : launch_small_t<bf16_t, 1>(b, grid, nbm, nbr, whole_o, stack, st);
     return ok ? hipGetLastError() : hipErrorInvalidValue;
 }
 
