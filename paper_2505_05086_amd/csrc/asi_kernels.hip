@@ -271,12 +271,13 @@ __global__ __launch_bounds__(256) void k_sum_partials(Batch<SumJob> bt) {
     const long long e = (long long)lb * 256 + threadIdx.x;
     if (e >= count) return;
     double s = 0.0;
-    for (int sp0 = 0; sp0 < jb.nsplit; sp0 += 8) {          // 8 loads in flight
-        PT t[8];
+    constexpr int SU = 16;                                   // loads in flight per round (a round is one memory latency)
+    for (int sp0 = 0; sp0 < jb.nsplit; sp0 += SU) {
+        PT t[SU];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] = part[(sp0 + u < jb.nsplit) ? (long long)(sp0 + u) * count + e : e];
+        for (int u = 0; u < SU; ++u) t[u] = part[(sp0 + u < jb.nsplit) ? (long long)(sp0 + u) * count + e : e];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += (sp0 + u < jb.nsplit) ? (double)t[u] : 0.0;
+        for (int u = 0; u < SU; ++u) s += (sp0 + u < jb.nsplit) ? (double)t[u] : 0.0;
     }
     jb.out[e] = jb.beta ? jb.out[e] + (float)s : (float)s;
 }
