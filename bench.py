@@ -54,8 +54,8 @@ def measured_traffic(cfg_index: int, symbol: str):
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload (1-5), default the ResNet-18 tail")
     ap.add_argument("--distinct", type=int, default=8, help="distinct input steps kept in HBM and cycled")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams the layers are spread over (0 = one per layer)")
