@@ -163,9 +163,6 @@ struct CorePlan {
 };
 
 bool kron_ok(long long n_a, long long n_b, int r_a, int r_b) {
-#ifdef ASI_DEBUG_TIMING
-    if (const char* e = std::getenv("ASI_DBG_KRON_MAXN")) return n_a * n_b <= std::atoi(e) && (long long)r_a * r_b <= kKronMaxR;
-#endif
     return n_a * n_b <= kKronMaxN && (long long)r_a * r_b <= kKronMaxR;
 }
 
@@ -217,10 +214,6 @@ CorePlan plan_core(const Shape& s, void* ws, const int* order = nullptr) {
         }
     } while (std::next_permutation(perm, perm + p.d));
     if (order) std::memcpy(p.order, order, sizeof(int) * 4);
-#ifdef ASI_DEBUG_TIMING
-    if (const char* e = std::getenv("ASI_DBG_CORE_ORDER"))
-        for (int k = 0; k < p.d && e[2 * k]; ++k) p.order[k] = e[2 * k] - '0';
-#endif
     Carver c(ws);
     p.buf[0] = c.take<float>(need[0]);
     p.buf[1] = c.take<float>(need[1]);

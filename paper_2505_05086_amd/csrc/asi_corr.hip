@@ -12,7 +12,6 @@
 #include "asi_kernels.h"
 
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 
 namespace asi {
@@ -70,16 +69,10 @@ static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
     // of 32, e.g. 6 rows x 16 columns, puts the 16 slabs on one bank); otherwise an odd pitch.
     p->zld = p->slab;
     while (g.sw == 1 ? (p->zld % 32 != 2) : (p->zld % 2 == 0)) ++p->zld;
-#ifdef ASI_DEBUG_TIMING
-    if (const char* e = std::getenv("ASI_DBG_ZLD_MOD")) { p->zld = p->slab; while (p->zld % 32 != std::atoi(e)) ++p->zld; }
-#endif
     if ((long long)p->zld * 16 > CR_ZMAX) p->zld = p->slab;
     p->nchunks = g.r1 * p->nyc;
     const long long base = (long long)((g.cout + CR_TO - 1) / CR_TO) * ((g.r2 + 15) / 16);
     long long target = 256;
-#ifdef ASI_DEBUG_TIMING
-    if (const char* e = std::getenv("ASI_DBG_CORR_WG")) target = std::atoi(e);
-#endif
     long long want = (target + base - 1) / base;
     if (want > p->nchunks) want = p->nchunks;
     if (want < 1) want = 1;
@@ -97,15 +90,6 @@ static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
     return true;
 }
 
-#ifdef ASI_DEBUG_TIMING
-__device__ long long g_corr_stamps[64];
-#define CSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && (i) < 64) g_corr_stamps[i] = wall_clock64(); } while (0)
-extern "C" int asi_debug_corr_stamps(long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_corr_stamps), sizeof(long long) * 64);
-}
-#else
-#define CSTAMP(i) do {} while (0)
-#endif
 
 template <int MAXT, bool EXACT>
 __global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
@@ -172,13 +156,8 @@ __global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
             z_t[u] = v;
         }
     };
-    CSTAMP(0);
-#ifdef ASI_DEBUG_TIMING
-    if (threadIdx.x == 0 && blockIdx.x == 0) g_corr_stamps[60] = clock64();
-#endif
     if (ch_beg < ch_end) fetch(ch_beg);
     for (int ch = ch_beg; ch < ch_end; ++ch) {
-        CSTAMP(1 + 4 * (ch - ch_beg));
         const int i = ch / pl.nyc, yc = ch - i * pl.nyc;
         const int y0 = yc * pl.ry;
         const int rows = (g.Ho - y0 < pl.ry) ? g.Ho - y0 : pl.ry;
@@ -193,12 +172,7 @@ __global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
             if (e < ztotal) Zs[e + jl * (pl.zld - pl.slab)] = z_t[u];
         }
         __syncthreads();
-        CSTAMP(2 + 4 * (ch - ch_beg));
         if (ch + 1 < ch_end) fetch(ch + 1);                // in flight while this chunk is multiplied
-        CSTAMP(3 + 4 * (ch - ch_beg));
-#ifdef ASI_DEBUG_TIMING
-        if (threadIdx.x == 0 && blockIdx.x == 0 && ch == ch_beg) g_corr_stamps[40] = clock64();
-#endif
         // operands of step ks: the A value and one B value per tap.  The loads of step ks + 1 are
         // issued before the products of step ks, so that LDS latency is paid once per chunk and not
         // once per product.  The step count is rounded up to even: positions past the chunk's end
@@ -236,15 +210,7 @@ __global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
             for (int t = 0; t < MAXT; ++t)
                 if (EXACT || t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[t], acc[t], 0, 0, 0);
         }
-        CSTAMP(4 + 4 * (ch - ch_beg));
-#ifdef ASI_DEBUG_TIMING
-        if (threadIdx.x == 0 && blockIdx.x == 0 && ch == ch_beg) g_corr_stamps[41] = clock64();
-#endif
     }
-    CSTAMP(62);
-#ifdef ASI_DEBUG_TIMING
-    if (threadIdx.x == 0 && blockIdx.x == 0) g_corr_stamps[61] = clock64();
-#endif
     // lane holds o = o0 + 16w + 4*lg + v, j = j0 + ll
     // The result goes through LDS, up to 9 taps at a time: the K groups add their tiles there, and
     // for one output channel the (j, tap) values of this workgroup are then one contiguous run of T
@@ -285,7 +251,6 @@ __global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
             }
         }
     }
-    CSTAMP(63);
 }
 
 // one thread per T[o,j,kh,kw] and split of the r1 axis: any geometry

@@ -34,19 +34,6 @@ constexpr int OP_LD = OP_RMAX + 1;
 constexpr double OP_EPS = 1.1102230246251565e-16;
 constexpr double OP_DONE_TOL = 1e-7;   // |Q0^T Q0 - I| below which the first pass is the result
 
-#ifdef ASI_DEBUG_TIMING
-__device__ long long g_orth_stamps[64];
-#define STAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 2 && pass == 0) g_orth_stamps[i] = wall_clock64(); } while (0)
-#define KSTAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 2) g_orth_stamps[i] = wall_clock64(); } while (0)
-#define WSTAMP(i) do { if (threadIdx.x == 0 && jb.mode1 == 3 && pass == 0) g_orth_stamps[i] = wall_clock64(); } while (0)
-extern "C" int asi_debug_orth_stamps(long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_orth_stamps), sizeof(long long) * 64);
-}
-#else
-#define STAMP(i) do {} while (0)
-#define KSTAMP(i) do {} while (0)
-#define WSTAMP(i) do {} while (0)
-#endif
 
 __device__ __forceinline__ void flag_info(int32_t* info, int mode1, int col1) {
     if (info) atomicCAS(info, 0, mode1 * 1000 + col1);
@@ -124,11 +111,6 @@ __device__ __forceinline__ double bcast_lane(double x, int src) {      // src un
 // of (e + 0.5) is exact in that range (the same device as in the product kernels).
 __device__ __forceinline__ int small_div(int e, float inv_r) { return (int)(((float)e + 0.5f) * inv_r); }
 
-#ifdef ASI_DEBUG_TIMING
-#define BSTAMP(i) do { if (dbg && threadIdx.x == 0) g_orth_stamps[i] = wall_clock64(); } while (0)
-#else
-#define BSTAMP(i) do {} while (0)
-#endif
 // The matrix is reached through an accessor (ld(row, col), st(row, col, value)): a square LDS array
 // for r <= 64, the packed upper triangle for wider matrices.  Only entries with row <= col are used.
 struct GramSquare {
@@ -151,9 +133,8 @@ struct GramPacked {                      // row-wise packed upper triangle of an
 };
 template <class GA>
 __device__ void chol_block16(const GA G, double (*rowbuf)[64][4], double (*Xb)[17], double* pinvs, int base,
-                             int* bad_io, bool dbg = false) {
+                             int* bad_io) {
     const int j = threadIdx.x;          // 0..63
-    BSTAMP(20);
     const bool xl = j >= 48;            // identity lane
     double col[16];
     {
@@ -170,7 +151,6 @@ __device__ void chol_block16(const GA G, double (*rowbuf)[64][4], double (*Xb)[1
     }
     int bad = *bad_io;
     double f[4];
-    BSTAMP(21);
     // Panel K0..K0+3.  Its 4x4 diagonal block (10 values, fetched from their lanes in one go) is
     // factored redundantly by every lane, which keeps the cross-lane traffic off the chain of
     // reciprocals; each lane then applies the multipliers to its own four row entries.
@@ -214,10 +194,8 @@ __device__ void chol_block16(const GA G, double (*rowbuf)[64][4], double (*Xb)[1
         }                                                                                           \
     }
     ASI_CHOL_PANEL(0, f)
-    BSTAMP(22);
 #pragma unroll
     for (int k0 = 0; k0 + 4 < 16; k0 += 4) {
-        BSTAMP(23 + (k0 >> 2));
         double (*rb)[4] = rowbuf[(k0 >> 2) & 1];
         rb[j][0] = col[k0]; rb[j][1] = col[k0 + 1]; rb[j][2] = col[k0 + 2]; rb[j][3] = col[k0 + 3];
         ASI_CHOL_UPDATE(k0 + 4, k0 + 8, rb)
@@ -229,7 +207,6 @@ __device__ void chol_block16(const GA G, double (*rowbuf)[64][4], double (*Xb)[1
     }
 #undef ASI_CHOL_PANEL
 #undef ASI_CHOL_UPDATE
-    BSTAMP(26);
     *bad_io = bad;
     // lanes 0..15 write their column of the block (entries below the diagonal are never read again),
     // lanes 48..63 their row of the inverse factor: one run of stores for both
@@ -240,7 +217,6 @@ __device__ void chol_block16(const GA G, double (*rowbuf)[64][4], double (*Xb)[1
 #pragma unroll
         for (int k = 0; k < 16; ++k) G.st(base + k, base + j, col[k]);
     }
-    BSTAMP(27);
 }
 
 // One workgroup (256 threads): sums the slice Grams of a mode, adds the shift (first pass) and
@@ -273,7 +249,6 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     const int nb = (r + 15) / 16;
-    STAMP(0);
     // sum of the slice Grams (packed upper triangles): ITS elements per thread, SB slices per
     // round, all ITS * SB loads of a round in flight together
     constexpr int ITS = (RM * (RM + 1) / 2 + 255) / 256;
@@ -318,19 +293,12 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
         __syncthreads();
     };
     scatter();
-    STAMP(1);
     int bad = 0;
     // blocked right-looking factorisation of Gs in place
     auto factor = [&]() {
         for (int P = 0; P < nb; ++P) {
-    #ifdef ASI_DEBUG_TIMING
-            if (wave == 0) chol_block16(GramSquare{Gs}, rowbuf, Xs[P], pinvs, 16 * P, &bad, P == 0 && jb.mode1 == 2 && pass == 0);
-    #else
             if (wave == 0) chol_block16(GramSquare{Gs}, rowbuf, Xs[P], pinvs, 16 * P, &bad);
-    #endif
-            if (P == 0) STAMP(6);
             __syncthreads();
-            if (P == 0) STAMP(7);
             if (P + 1 < nb) {
                 // block row P right of the diagonal:  U_PJ = L_PP^-1 G_PJ   (unscaled rows, like the diagonal block)
                 for (int J = P + 1 + wave; J < nb; J += 4) {
@@ -345,7 +313,6 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
                     for (int v = 0; v < 4; ++v) Gs[16 * P + lg + 4 * v][16 * J + ll] = acc[v];
                 }
                 __syncthreads();
-                if (P == 0) STAMP(8);
                 // trailing blocks:  G_IJ -= U_PI^T diag(1/pivot) U_PJ,  P < I <= J
                 int cnt = 0;
                 for (int I = P + 1; I < nb; ++I)
@@ -363,7 +330,6 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
                         for (int v = 0; v < 4; ++v) Gs[16 * I + lg + 4 * v][16 * J + ll] = acc[v];
                     }
                 __syncthreads();
-                if (P == 0) STAMP(9);
             }
         }
     };
@@ -413,7 +379,6 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
             if (lane == 0) { s_trace = tr; jb.scal[0] = tr; }
             if (lane < r) rdiag[lane] = g;                  // the diagonal before elimination
         }
-        STAMP(2);
         factor();
         if (wave == 0) {
             const bool lost = lane < r && !(Gs[lane][lane] > 1e-12 * rdiag[lane]);
@@ -433,7 +398,6 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
         __syncthreads();
     }
     if (tid == 0) s_bad = bad;
-    STAMP(3);
     if (tid < r) {
         double p = Gs[tid][tid];
         if (!(p > 0.0)) p = 1.0;
@@ -461,14 +425,12 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
             if (ga < r && gb < r) jb.R[ga * r + gb] = (ga < gb) ? gv[it] * iv[it] : (ga == gb ? dv[it] : 0.0);
         }
     }
-    STAMP(4);
     // inverse of each 16x16 diagonal block of R:  (R_bb^-1)[i][j] = (L_bb^-1)[j][i] / R[j][j]
     for (int e = tid; e < nb * 256; e += 256) {
         const int b = e >> 8, i = (e >> 4) & 15, jj = e & 15, base = 16 * b;
         const bool in = base + i < r && base + jj < r && jj >= i;
         jb.Dinv[e] = in ? Xs[b][i][jj] * dinv[base + jj] : 0.0;
     }
-    STAMP(5);
     if (tid < 64) {
         // first column (if any) whose accumulated R diagonal fell to the noise floor
         const double floor_ = 1e-12 * sqrt(s_trace);
@@ -518,7 +480,6 @@ __global__ __launch_bounds__(256) void k_orth_gram0(OrthBatch a) {
     find_job(a, &ji, &blk);
     const OrthJob jb = a.job[ji];
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
-    if (blk == 0) KSTAMP(40);
     if (blk == 0 && tid == 0 && jb.info) *jb.info = 0;            // nothing has reported yet
     const int i0 = blk * OP_RS;
     const int nrows = (n - i0 < OP_RS) ? n - i0 : OP_RS;
@@ -575,14 +536,10 @@ __global__ __launch_bounds__(256) void k_orth_gram0(OrthBatch a) {
         }
     }
     __syncthreads();
-    if (blk == 0) KSTAMP(41);
     gram_from_lds(Ps, r, jb.Gpart + (long long)blk * ((r * (r + 1)) / 2));
-    if (blk == 0) KSTAMP(42);
     // the workgroup that finishes a mode's last slice goes on to factor its Gram matrix
     if (!last_arrival(jb.ctr + 0, jb.nblk, &s_last)) return;
-    KSTAMP(43);
     chol_job<RM>(jb, 0, 0, jb.info, *reinterpret_cast<CholSmem*>(raw));
-    KSTAMP(44);
 }
 
 // ---- apply ----------------------------------------------------------------------------------
@@ -707,13 +664,9 @@ __global__ __launch_bounds__(256) void k_orth_apply(OrthBatch a) {
     int ji, blk;
     find_job(a, &ji, &blk);
     const OrthJob jb = a.job[ji];
-    if (blk == 0) KSTAMP(50);
     apply_slice<RM>(jb, blk, 0, ap);
-    if (blk == 0) KSTAMP(51);
     if (!last_arrival(jb.ctr + 1, jb.nblk, &s_last)) return;
-    KSTAMP(52);
     const bool again = chol_job<RM>(jb, 1, 1, jb.info, *reinterpret_cast<CholSmem*>(raw));
-    KSTAMP(53);
     if (!again) return;
     for (int b2 = 0; b2 < jb.nblk; ++b2) {
         __threadfence();                   // R, Dinv (and every slice of Q0) are read back from memory
@@ -865,10 +818,8 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
     double (*rowbuf)[64][4] = reinterpret_cast<double (*)[64][4]>(pinvs + nb * 16 + 16 * 17);
     const GramPacked G{Gp, r};
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
-    WSTAMP(0);
     double dev = sum_gram();
     __syncthreads();
-    WSTAMP(1);
     if (pass == 0) {
         if (tid < r) rdiag[tid] = Gp[pidx(tid, tid)];
         __syncthreads();
@@ -905,7 +856,6 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
         if (tid < r) rdiag[tid] = Gp[pidx(tid, tid)];
         __syncthreads();
     }
-    WSTAMP(2);
     // First pass: plain Cholesky first; only if a pivot is lost is the Gram matrix summed again, shifted
     // and factored once more (the same policy as the r <= 64 path).  The factorisation is written once,
     // inside this loop: as a lambda called from three places it was not inlined, its captured pointers
@@ -913,11 +863,8 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
     for (int attempt = 0;; ++attempt) {
         int bad = 0;
         for (int P = 0; P < nb; ++P) {
-            if (P == 0) WSTAMP(10);
             if (wave == 0) chol_block16(G, rowbuf, Xs, pinvs, 16 * P, &bad);
-            if (P == 0) WSTAMP(11);
             __syncthreads();
-            if (P == 0) WSTAMP(12);
             if (tid < 16 && 16 * P + tid < r) {
                 const double p = G.ld(16 * P + tid, 16 * P + tid);          // the pivot actually used
                 if (!(p > 1e-12 * rdiag[16 * P + tid])) s_lost = 1;
@@ -936,7 +883,6 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
                     for (int v = 0; v < 4; ++v) G.st(16 * P + lg + 4 * v, 16 * J + ll, acc[v]);
                 }
                 __syncthreads();
-                if (P == 0) WSTAMP(13);
                 // trailing blocks:  G_IJ -= U_PI^T diag(1/pivot) U_PJ,  P < I <= J.  Rows k of the panel lie
                 // above both blocks, so their elements sit at roff[k] + column; a column past r reads the
                 // diagonal entry instead and counts as zero.  The twelve reads of a block pair are issued
@@ -984,7 +930,6 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
                             if (cin[v]) Gp[cidx[v]] = acc[v];
                     }
                 __syncthreads();
-                if (P == 0) WSTAMP(14);
             }
         }
         if (tid == 0) s_bad = bad;
@@ -998,7 +943,6 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
         if (tid < r) Gp[pidx(tid, tid)] += shift;
         __syncthreads();
     }
-    WSTAMP(3);
     if (tid < r) {
         double p = Gp[pidx(tid, tid)];
         if (!(p > 0.0)) p = 1.0;
@@ -1009,7 +953,6 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
         jb.scal[1 + tid] = rd;
     }
     __syncthreads();
-    WSTAMP(4);
     for (int e = tid; e < r * r; e += OWC_NT) {      // R, and the rows scaled in place (each entry has one owner)
         const int ga = small_div(e, inv_rf), gb = e - ga * r;
         double v = 0.0;
@@ -1022,7 +965,6 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
         jb.R[e] = v;
     }
     __syncthreads();
-    WSTAMP(5);
     if (tid < nb * 16) {
         const int b = tid >> 4, i = tid & 15, base = 16 * b;
         double x[16];
@@ -1036,7 +978,6 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
 #pragma unroll
         for (int j = 0; j < 16; ++j) jb.Dinv[(b * 16 + i) * 16 + j] = x[j];
     }
-    WSTAMP(6);
     if (tid == 0) {
         double bad = (pass == 0) ? 0.0 : jb.scal[1 + OW_RMAX];
         if (bad == 0.0 && s_bad) bad = (double)s_bad;

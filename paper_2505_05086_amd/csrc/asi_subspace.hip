@@ -32,13 +32,7 @@ constexpr int SS_TC = 128;                 // fibres (unfolding columns) per til
 constexpr int SS_PAD = 4;
 constexpr int SS_LDS_FLOATS = 64 * (SS_TC + SS_PAD);   // 33 KB
 constexpr int SS_PRE = (SS_LDS_FLOATS + 255) / 256;    // prefetch registers per thread
-#ifdef ASI_DEBUG_TIMING
-#include <cstdlib>
-static int ss_max_wg_dbg() { const char* e = std::getenv("ASI_DBG_SS_MAX_WG"); return e ? std::atoi(e) : 1024; }
-#define SS_MAX_WG (ss_max_wg_dbg())
-#else
 static const int SS_MAX_WG = 1024;
-#endif
 
 struct SmallView {
     const float* U;      // (n, r) previous factor
@@ -64,15 +58,6 @@ struct SmallJob {
     SmallView v[2];
 };
 
-#ifdef ASI_DEBUG_TIMING
-__device__ long long g_ss_stamps[64];
-#define SSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) g_ss_stamps[i] = wall_clock64(); } while (0)
-extern "C" int asi_debug_ss_stamps(long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_ss_stamps), sizeof(long long) * 64);
-}
-#else
-#define SSTAMP(i) do {} while (0)
-#endif
 
 template <typename T, int NBM, int NBR, int NV, bool WHOLE_O, bool STACK = false>   // STACK: several column groups per tile
 __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
@@ -84,7 +69,6 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
     const int lg = lane >> 4, ll = lane & 15;
     const T* __restrict__ X = static_cast<const T*>(jb.X);
     if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
-    SSTAMP(0);
 
     for (int e = tid; e < NV * NBM * 16 * NBR * 16; e += 256) {
         const int vi = e / (NBM * 16 * NBR * 16), rem = e - vi * (NBM * 16 * NBR * 16);
@@ -103,10 +87,8 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
 
     const int n0 = jb.v[0].n;
     const int rowI = SS_TC + SS_PAD;
-    SSTAMP(1);
     for (long long tile = lb; tile < jb.ntiles; tile += jb.nwg) {
         __syncthreads();   // everyone is done with the previous tile (and Us is written)
-        SSTAMP(2);
         int no_or_vc;
         // the whole tile is requested before any of it is stored: one memory latency per tile
         if (WHOLE_O) {
@@ -165,7 +147,6 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
             no_or_vc = vc;
         }
         __syncthreads();
-        SSTAMP(3);
 #pragma unroll
         for (int vi = 0; vi < NV; ++vi) {
             const SmallView& sv = jb.v[vi];
@@ -228,7 +209,6 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
             }
         }
     }
-    SSTAMP(4);
     // sum the four waves' accumulators through LDS, wave after wave (fixed order)
     double* red = reinterpret_cast<double*>(smem);   // (NBM*16) x (NBR*16) doubles <= 32 KB
 #pragma unroll
@@ -256,7 +236,6 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
             out[e] = red[i * (NBR * 16) + q];
         }
     }
-    SSTAMP(5);
 }
 
 // ---- host side ---------------------------------------------------------------------
@@ -418,7 +397,6 @@ __global__ __launch_bounds__(256) void k_subspace_tiny(Batch<TinyJob> bt) {
         Us[vi][i][q] = ldg_f32(jb.U[vi], (long long)i * jb.r[vi] + q, i < nn && q < jb.r[vi]);
     }
     __syncthreads();
-    SSTAMP(10);
     float u[8][RP];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -448,7 +426,6 @@ __global__ __launch_bounds__(256) void k_subspace_tiny(Batch<TinyJob> bt) {
             if (e < count) tile[e] = to_f32(pre[k]);
         }
         __syncthreads();
-        SSTAMP(11);
         if (pl < np) {
             const float* xp = tile + pl * pe;
 #pragma unroll 1
@@ -470,7 +447,6 @@ __global__ __launch_bounds__(256) void k_subspace_tiny(Batch<TinyJob> bt) {
             }
         }
     }
-    SSTAMP(12);
     // Sum over the lanes of the same view (same lane parity).  Inside a row of 16 lanes by data-parallel
     // moves: partner lane^2, then rotations by 4 and 8; across the four rows by two xor shuffles.  One
     // step for all accumulators at a time, so that their moves are in flight together.
@@ -507,7 +483,6 @@ __global__ __launch_bounds__(256) void k_subspace_tiny(Batch<TinyJob> bt) {
             jb.part[vi][((long long)lb * nn + i) * rr + q] = s;
         }
     }
-    SSTAMP(13);
 }
 
 bool subspace_tiny_supported(int rows, int cols, int r_rows, int r_cols) {

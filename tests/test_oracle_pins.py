@@ -348,7 +348,9 @@ def test_lowrank_linear_dw_equals_dense_dw_of_reconstruction():
     for b in range(dims[0]):
         ref += dY[b].T @ Ah[b]
     assert np.max(np.abs(lr - ref)) < 1e-11
-    assert cnt["G1"] == 2 * 4 * 5 * 7 and cnt["dW"] == 4 * 7 * 6
+    # all four terms of the derived cost, as integers worked out by hand for this shape:
+    # r1 B N Do = 2*4*5*7, r1 r2 N Do = 2*3*5*7, r1 r2 r3 Do = 2*3*4*7, r3 Do D = 4*7*6
+    assert cnt == {"G1": 280, "G2": 210, "T": 168, "dW": 168}
 
 
 def test_exact_tucker_compressed_dw_equals_dense_dw():
@@ -416,4 +418,61 @@ def test_cost_closed_forms():
     ov, cv = O.cost_vanilla_forward(dims, 512, 3), O.cost_vanilla_backward(dims, 512, 7, 7, 3)
     assert ov == cv == 9 * 512 * 512 * 64 * 49
     rs = O.speedup_ratio(dims, ranks, 512, 7, 7, 3)
-    assert abs(rs - (ov + cv) / (ov + O.overhead_asi(dims, ranks) + c)) < 1e-12 and 1.0 < rs < 2.0
+    assert 1.0 < rs < 2.0
+
+
+def test_speedup_ratio_against_hand_expanded_integers():
+    """R_S (Eq. 17) on a shape small enough to expand every term of Eq. 13-16 by hand.
+
+    dims (B,C,H,W) = (2,3,4,5), ranks (1,2,2,3), 3x3 convolution to C' = 4 with H' x W' = 4 x 5:
+      O_vanilla = D^2 C C' B H W   = 9*3*4*2*4*5                                  = 4320
+      C_vanilla = D^2 C C' B H' W' = 9*3*4*2*4*5                                  = 4320
+      O_ASI     = sum_m (2*120*r_m + r_m^3) = 240*(1+2+2+3) + (1+8+8+27)          = 1964
+      C_ASI     = 1*2*4*20 + 1*2*2*3*4 + 1*2*3*4*5 + 1*2*4*20*9 + 2*4*3*9
+                = 160 + 48 + 120 + 1440 + 216                                     = 1984
+      R_S = (4320 + 4320) / (4320 + 1964 + 1984) = 8640 / 8268
+    A wrong or missing term in numerator or denominator changes the literal quotient."""
+    dims, ranks = (2, 3, 4, 5), (1, 2, 2, 3)
+    assert O.cost_vanilla_forward(dims, 4, 3) == 4320
+    assert O.cost_vanilla_backward(dims, 4, 4, 5, 3) == 4320
+    assert O.overhead_asi(dims, ranks) == 1964
+    assert O.cost_asi_backward(dims, ranks, 4, 4, 5, 3) == 1984
+    assert abs(O.speedup_ratio(dims, ranks, 4, 4, 5, 3) - 8640.0 / 8268.0) < 1e-15
+    # H' W' differs from H W (stride 2): only C_vanilla and C_ASI's terms 1 and 4 change
+    #   C_vanilla = 9*3*4*2*2*3 = 1296;  C_ASI = 1*2*4*6 + 48 + 120 + 1*2*4*6*9 + 216 = 48+48+120+432+216 = 864
+    assert abs(O.speedup_ratio(dims, ranks, 4, 2, 3, 3) - (4320.0 + 1296.0) / (4320.0 + 1964.0 + 864.0)) < 1e-15
+
+
+def test_max_rel_err_on_hand_made_arrays():
+    """The yardstick of every parity assert: max|x - ref| / max|ref| (not elementwise, not Frobenius)."""
+    ref = np.array([[1.0, -4.0], [0.0, 2.0]])
+    x = np.array([[1.5, -4.0], [0.25, 1.0]])
+    assert O.max_rel_err(x, ref) == 1.0 / 4.0                     # largest difference 1.0 (last entry), largest |ref| 4
+    assert O.max_rel_err(ref, ref) == 0.0
+    assert O.max_rel_err(ref, x) == 1.0 / 4.0                     # max|x| is 4 as well
+    assert O.max_rel_err(2.0 * ref, ref) == 1.0
+    # an error on a zero entry of the reference still counts against the largest entry (no division by zero)
+    assert O.max_rel_err(np.array([0.0, 0.5]), np.array([0.0, 0.0])) == 0.5     # zero reference: absolute error
+    assert O.max_rel_err(np.array([1e-3, 10.0]), np.array([0.0, 10.0])) == 1e-4
+    # non-finite results never pass a bar
+    assert O.max_rel_err(np.array([np.nan, 1.0]), np.array([1.0, 1.0])) == float("inf")
+    assert O.max_rel_err(np.array([np.inf, 1.0]), np.array([1.0, 1.0])) == float("inf")
+    assert O.max_rel_err(np.array([-np.inf]), np.array([1.0])) == float("inf")
+    # float32 inputs are compared in float64
+    assert O.max_rel_err(np.array([1.0], dtype=np.float32), np.array([1.0 + 1e-12])) < 2e-12
+
+
+def test_projector_is_the_orthogonal_projector():
+    rng = _rng(77)
+    U = _orth(rng, 7, 3)
+    Pm = O.projector(U)
+    assert Pm.shape == (7, 7)
+    assert np.max(np.abs(Pm @ Pm - Pm)) < 1e-13 and np.max(np.abs(Pm - Pm.T)) < 1e-15
+    assert abs(np.trace(Pm) - 3.0) < 1e-13
+    # invariant under a rotation and sign change of the basis
+    R, _ = np.linalg.qr(rng.standard_normal((3, 3)))
+    assert np.max(np.abs(O.projector(U @ R) - Pm)) < 1e-13
+    # elementwise against the definition
+    for i in range(7):
+        for j in range(7):
+            assert abs(Pm[i, j] - sum(U[i, k] * U[j, k] for k in range(3))) < 1e-15
