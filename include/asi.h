@@ -91,6 +91,21 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A,
                         const float* const* U_prev, float* const* U_out,
                         void* ws, size_t ws_bytes, int32_t* info, asi_stream_t stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): asi_compress with the library's own scratch memory in
+ * place of `ws`.  The scratch is a static device array of ASI_STATIC_SCRATCH_BYTES that every GPU
+ * the library runs on holds until the process ends; the call allocates and frees nothing.  Same
+ * arguments, results (bit for bit) and error behaviour as asi_compress, plus ASI_ERR_WORKSPACE when
+ * the layer needs more scratch than the array holds (asi_workspace_bytes(desc, NULL, 0) is an upper
+ * bound of that need) — then nothing is enqueued.  The array belongs to the current device; all calls
+ * on one GPU share it, so calls that overlap in time on one GPU (two streams, two threads) race:
+ * order them on one stream.  What a call leaves in the array is of no use to the next; the kernels
+ * clear what they need cleared. */
+#define ASI_STATIC_SCRATCH_BYTES (16u << 20)
+asi_status asi_compress_static(const asi_tensor_desc* desc, const void* A,
+                               const float* const* U_prev, float* const* U_out,
+                               int32_t* info, asi_stream_t stream);
+
 /* Core tensor S = A x_1 U[0]^T x_2 U[1]^T ... x_d U[d-1]^T (Alg. 1's core update with
  * Eq. 4's m-mode product; the order of the products does not change the result).
  *   U[m]  in  device fp32 (dims[m] x ranks[m])
@@ -169,7 +184,8 @@ int32_t asi_version(void);
  * bytes and flops that step must move / compute by its definition.  Returns the previous
  * setting.
  * asi_profile_report(buf, buflen): waits for the recorded events and writes one text
- * line per launch site, "site,launches,total_ms,total_bytes,total_flops,total_workgroups\n" (site may itself contain commas), NUL-terminated
+ * line per launch site, "site,launches,total_ms,total_bytes,total_flops,total_workgroups\n", NUL-terminated
+ * (site = "phase|kernel instantiation[:role]", phase one of compress / core / dW; it may contain commas)
  * and truncated to buflen (host memory).  Returns the bytes a full report needs, or -1
  * if an event could not be read. */
 int32_t asi_profile_enable(int32_t on);

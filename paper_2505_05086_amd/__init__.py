@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     alloc_workspace,
     asi_compress,
     asi_compress_batch,
+    asi_compress_static,
     asi_core_project,
     asi_core_project_batch,
     asi_profile_enable,

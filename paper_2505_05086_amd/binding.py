@@ -20,7 +20,9 @@ STATUS_NAMES = {0: "ASI_OK", 1: "ASI_ERR_INVALID_ARG", 2: "ASI_ERR_UNSUPPORTED",
                 3: "ASI_ERR_WORKSPACE", 4: "ASI_ERR_HIP", 5: "ASI_ERR_NUMERIC"}
 ASI_F32, ASI_BF16 = 0, 1
 
-EXPORTS = ["asi_workspace_bytes", "asi_compress", "asi_core_project", "asi_weight_grad_conv2d",
+STATIC_SCRATCH_BYTES = 16 << 20      # ASI_STATIC_SCRATCH_BYTES of include/asi.h
+
+EXPORTS = ["asi_workspace_bytes", "asi_compress", "asi_compress_static", "asi_core_project", "asi_weight_grad_conv2d",
            "asi_weight_grad_linear", "asi_compress_batch", "asi_core_project_batch",
            "asi_weight_grad_conv2d_batch", "asi_weight_grad_linear_batch", "asi_status_string", "asi_version",
            "asi_profile_enable", "asi_profile_report"]
@@ -60,6 +62,8 @@ def lib() -> C.CDLL:
         L.asi_compress.restype = C.c_int
         L.asi_compress.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, pp, C.c_void_p, C.c_size_t,
                                    C.c_void_p, C.c_void_p]
+        L.asi_compress_static.restype = C.c_int
+        L.asi_compress_static.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, pp, C.c_void_p, C.c_void_p]
         L.asi_core_project.restype = C.c_int
         L.asi_core_project.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, C.c_void_p, C.c_void_p,
                                        C.c_size_t, C.c_void_p]
@@ -156,6 +160,14 @@ def asi_compress(desc: TensorDesc, A: torch.Tensor, U_prev: Sequence[torch.Tenso
     _check_dev(A, ws, info, *U_prev, *U_out)
     _check(lib().asi_compress(C.byref(desc), _ptr(A), _ptr_array(U_prev), _ptr_array(U_out), _ptr(ws),
                               ws.numel(), _ptr(info), _stream()), "asi_compress")
+
+
+def asi_compress_static(desc: TensorDesc, A: torch.Tensor, U_prev: Sequence[torch.Tensor],
+                        U_out: Sequence[torch.Tensor], info: Optional[torch.Tensor] = None) -> None:
+    """asi_compress on the library's static scratch array: no workspace argument, nothing allocated."""
+    _check_dev(A, info, *U_prev, *U_out)
+    _check(lib().asi_compress_static(C.byref(desc), _ptr(A), _ptr_array(U_prev), _ptr_array(U_out), _ptr(info),
+                                     _stream()), "asi_compress_static")
 
 
 def asi_core_project(desc: TensorDesc, A: torch.Tensor, U: Sequence[torch.Tensor], S: torch.Tensor,

@@ -389,7 +389,7 @@ asi_status flush(std::vector<Program>& progs, hipStream_t st) {
             if (launch_items(group, n, st, label) != hipSuccess) return ASI_ERR_HIP;
             if (prof) {
                 (void)hipEventRecord(rec.e1, st);
-                // "kernel instantiation:role", e.g. "k_ttm_mfma<float, false, 3, false>:core"
+                // "phase|kernel instantiation:role", e.g. "core|k_ttm_mfma<float, false, 3, 0>:core"
                 rec.site = std::string(label) + (group[0]->role[0] ? std::string(":") + group[0]->role : std::string());
                 rec.bytes = rec.flops = rec.wgs = 0;
                 for (int j = 0; j < n; ++j) { rec.bytes += group[j]->bytes; rec.flops += group[j]->flops; rec.wgs += group[j]->nblocks; }
@@ -672,6 +672,29 @@ asi_status build_linear(const asi_tensor_desc* desc, const float* S, const float
 
 bool batch_count_ok(int32_t count) { return count >= 1 && count <= kMaxBatch; }
 
+// ---- scratch memory of the entry point that allocates nothing -----------------------------------
+// A file-scope device array: every GPU the library runs on holds its own copy until the process ends.
+// In host code the array's name is only a stand-in for the symbol; the device address of the current
+// GPU's copy is asked for once per device (hipGetSymbolAddress) and used from then on.
+static __device__ __align__(256) unsigned char scratch[ASI_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+asi_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ASI_ERR_HIP;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ASI_ERR_HIP;
+        if (reinterpret_cast<uintptr_t>(p) % kAlign != 0) return ASI_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ASI_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -816,6 +839,20 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float*
                         float* const* U_out, void* ws, size_t ws_bytes, int32_t* info, asi_stream_t stream) {
     if (!desc) return ASI_ERR_INVALID_ARG;
     return asi_compress_batch(1, desc, &A, &U_prev, &U_out, &ws, &ws_bytes, &info, stream);
+}
+
+asi_status asi_compress_static(const asi_tensor_desc* desc, const void* A, const float* const* U_prev,
+                               float* const* U_out, int32_t* info, asi_stream_t stream) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    // the limit is checked before anything touches the device
+    if (plan_compress(s, nullptr).bytes > (size_t)ASI_STATIC_SCRATCH_BYTES) return ASI_ERR_WORKSPACE;
+    void* ws = nullptr;
+    ASI_TRYS(static_scratch(&ws));
+    // Everything the kernels expect to start from zero (the arrival counters) is cleared by the first
+    // kernel of the call itself, so what the previous call left in the array does not matter.
+    return asi_compress(desc, A, U_prev, U_out, ws, (size_t)ASI_STATIC_SCRATCH_BYTES, info, stream);
 }
 
 asi_status asi_core_project(const asi_tensor_desc* desc, const void* A, const float* const* U, float* S,

@@ -78,6 +78,20 @@ def test_compress_rejects_bad_arguments_without_launching():
     assert call(asi.make_desc((8, 1, 1, 1), (2, 1, 1, 1)), FAKE, _arr(), _arr(), FAKE, 1 << 20) == 1
 
 
+def test_compress_static_rejects_before_touching_the_device():
+    """The entry point that allocates nothing checks descriptor and size limit on the host first."""
+    L = asi.lib()
+    call = lambda d: L.asi_compress_static(C.byref(d), FAKE, _arr(), _arr(), None, None)
+    assert call(asi.make_desc((8, 6, 5, 4), (2, 3, 2, 5))) == 1                      # rank > dim
+    assert call(asi.make_desc((8, 6, 5, 4), (2, 3, 2, 2), 7)) == 2                   # dtype
+    big = asi.make_desc((64, 197, 3072), (32, 64, 192), "bf16")
+    assert asi.asi_workspace_bytes(big) > B.STATIC_SCRATCH_BYTES
+    assert call(big) == 3                                                            # beyond the static array
+    src = open(os.path.join(ROOT, "include", "asi.h")).read()
+    assert re.search(r"#define\s+ASI_STATIC_SCRATCH_BYTES\s+\(16u\s*<<\s*20\)", src)
+    assert B.STATIC_SCRATCH_BYTES == 16 << 20
+
+
 def test_other_entry_points_reject_bad_arguments():
     L = asi.lib()
     d4 = asi.make_desc((8, 6, 5, 4), (2, 3, 2, 2))
