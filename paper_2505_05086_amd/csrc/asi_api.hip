@@ -364,7 +364,7 @@ asi_status add_pair(Program& pg, const char* role, DType xt, const void* X, long
 
 // Runs the programs of `count` layers: position by position, the items that can share a
 // launch (same kernel instantiation up to size bounds) go out together.
-asi_status flush(std::vector<Program>& progs, hipStream_t st) {
+asi_status flush(std::vector<Program>& progs, hipStream_t st, const char* phase) {
     size_t maxlen = 0;
     for (auto& pg : progs) maxlen = std::max(maxlen, pg.items.size());
     for (size_t pos = 0; pos < maxlen; ++pos) {
@@ -390,7 +390,7 @@ asi_status flush(std::vector<Program>& progs, hipStream_t st) {
             if (prof) {
                 (void)hipEventRecord(rec.e1, st);
                 // "phase|kernel instantiation:role", e.g. "core|k_ttm_mfma<float, false, 3, 0>:core"
-                rec.site = std::string(label) + (group[0]->role[0] ? std::string(":") + group[0]->role : std::string());
+                rec.site = std::string(phase) + "|" + label + (group[0]->role[0] ? std::string(":") + group[0]->role : std::string());
                 rec.bytes = rec.flops = rec.wgs = 0;
                 for (int j = 0; j < n; ++j) { rec.bytes += group[j]->bytes; rec.flops += group[j]->flops; rec.wgs += group[j]->nblocks; }
                 std::lock_guard<std::mutex> lk(g_prof_mu);
@@ -773,7 +773,7 @@ asi_status asi_compress_batch(int32_t count, const asi_tensor_desc* descs, const
     std::vector<Program> progs(count);
     for (int l = 0; l < count; ++l)
         ASI_TRYS(build_compress(&descs[l], A[l], U_prev[l], U_out[l], ws[l], ws_bytes[l], info ? info[l] : nullptr, progs[l]));
-    return flush(progs, static_cast<hipStream_t>(stream));
+    return flush(progs, static_cast<hipStream_t>(stream), "compress");
 }
 
 asi_status asi_core_project_batch(int32_t count, const asi_tensor_desc* descs, const void* const* A,
@@ -806,7 +806,7 @@ asi_status asi_core_project_batch(int32_t count, const asi_tensor_desc* descs, c
     std::vector<Program> progs(count);
     for (int l = 0; l < count; ++l)
         ASI_TRYS(build_core(&descs[l], A[l], U[l], S[l], ws[l], ws_bytes[l], have_common ? common : nullptr, progs[l]));
-    return flush(progs, static_cast<hipStream_t>(stream));
+    return flush(progs, static_cast<hipStream_t>(stream), "core");
 }
 
 asi_status asi_weight_grad_conv2d_batch(int32_t count, const asi_tensor_desc* descs, const float* const* S,
@@ -819,7 +819,7 @@ asi_status asi_weight_grad_conv2d_batch(int32_t count, const asi_tensor_desc* de
     for (int l = 0; l < count; ++l)
         ASI_TRYS(build_conv(&descs[l], S[l], U[l], grad_out[l], &convs[l], dW[l], accumulate ? accumulate[l] : 0, ws[l],
                             ws_bytes[l], progs[l]));
-    return flush(progs, static_cast<hipStream_t>(stream));
+    return flush(progs, static_cast<hipStream_t>(stream), "dW");
 }
 
 asi_status asi_weight_grad_linear_batch(int32_t count, const asi_tensor_desc* descs, const float* const* S,
@@ -832,7 +832,7 @@ asi_status asi_weight_grad_linear_batch(int32_t count, const asi_tensor_desc* de
     for (int l = 0; l < count; ++l)
         ASI_TRYS(build_linear(&descs[l], S[l], U[l], grad_out[l], dout[l], dW[l], accumulate ? accumulate[l] : 0, ws[l],
                               ws_bytes[l], progs[l]));
-    return flush(progs, static_cast<hipStream_t>(stream));
+    return flush(progs, static_cast<hipStream_t>(stream), "dW");
 }
 
 asi_status asi_compress(const asi_tensor_desc* desc, const void* A, const float* const* U_prev,
