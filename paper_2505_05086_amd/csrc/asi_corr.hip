@@ -11,6 +11,7 @@
 #include "asi_device.h"
 #include "asi_kernels.h"
 
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 
@@ -19,8 +20,15 @@ namespace asi {
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int CR_TO = 64;            // output channels per workgroup
-constexpr int CR_KC = 64;            // output positions per chunk
-constexpr int CR_ZMAX = 4096;        // floats of LDS for the Z slab
+// Output positions per chunk and the floats of LDS for the Z slab that goes with them.  Small output maps
+// (a few hundred positions) take chunks of 64.  On large maps a chunk of 64 is ~1 us of products between
+// two barriers and a round of loads that takes longer than that to arrive, so the products wait for
+// memory most of the time; chunks of 256 positions (whole output rows) give every round of loads ~4 us
+// of products to hide behind and a quarter of the barriers.
+constexpr int CR_KC_SMALL = 64, CR_ZMAX_SMALL = 4096;
+constexpr int CR_KC_BIG = 256, CR_ZMAX_BIG = 8192;
+constexpr int CR_BIG_MIN_POSITIONS = 1024;      // Ho * Wo from which the large chunks are used
+constexpr int CR_ZRMAX = 7;                     // most slab rows of a large chunk (its loader keeps 4 x 7 loads in flight per thread)
 // Waves per workgroup: 4 own 16 output channels each; with 8 the second four take every other
 // K step of a chunk on accumulators of their own (summed through LDS at the end).  One wave per
 // SIMD cannot overlap its operand reads and address arithmetic with its products (a step costs
@@ -30,6 +38,7 @@ constexpr int CR_NT = 64 * CR_NW;
 constexpr int CR_KG = CR_NW / 4;     // K-step groups
 
 struct CorrPlan {
+    int kc;          // output positions a chunk can hold (CR_KC_SMALL or CR_KC_BIG)
     int ry;          // output rows per chunk
     int nyc;         // chunks per core channel i
     int rows_in;     // Z rows a chunk touches
@@ -53,27 +62,37 @@ struct CorrJob {
 
 static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
     const int taps = g.kh * g.kw;
-    if (g.Wo > CR_KC || taps > 25) return false;
+    if (g.Wo > CR_KC_SMALL || taps > 25) return false;
     // the kernel indexes G1 and Z with 32-bit offsets
     if ((long long)g.r1 * g.cout * g.Ho * g.Wo >= (1LL << 31) || (long long)g.r1 * g.r2 * g.H * g.W >= (1LL << 31)) return false;
-    p->ry = CR_KC / g.Wo;
-    if (p->ry > g.Ho) p->ry = g.Ho;
-    p->nyc = (g.Ho + p->ry - 1) / p->ry;
-    p->rows_in = (p->ry - 1) * g.sh + (g.kh - 1) * g.dh + 1;
-    p->wp = (g.Wo - 1) * g.sw + (g.kw - 1) * g.dw + 1;
-    p->slab = p->rows_in * p->wp;
-    if ((long long)p->slab * 16 > CR_ZMAX) return false;
+    // large chunks for large maps with 3 x 3 taps and unit column dilation, if their slab fits; otherwise chunks of 64
+    int zmax = CR_ZMAX_SMALL;
+    for (int big = ((long long)g.Ho * g.Wo >= CR_BIG_MIN_POSITIONS && g.kh == 3 && g.kw == 3 && g.dw == 1) ? 1 : 0; big >= 0; --big) {
+        p->kc = big ? CR_KC_BIG : CR_KC_SMALL;
+        zmax = big ? CR_ZMAX_BIG : CR_ZMAX_SMALL;
+        p->ry = p->kc / g.Wo;
+        if (p->ry > g.Ho) p->ry = g.Ho;
+        p->nyc = (g.Ho + p->ry - 1) / p->ry;
+        p->rows_in = (p->ry - 1) * g.sh + (g.kh - 1) * g.dh + 1;
+        p->wp = (g.Wo - 1) * g.sw + (g.kw - 1) * g.dw + 1;
+        p->slab = p->rows_in * p->wp;
+        if ((long long)p->slab * 16 <= zmax && (!big || (p->rows_in <= CR_ZRMAX && p->wp <= 128))) break;
+        if (!big) return false;
+    }
     // In the multiply loop lane (j = l%16, k = l/16) reads slab j at the window origin of position k,
     // and the positions of a lane group are sw floats apart.  With unit stride a slab pitch of
     // 2 mod 32 puts the 32 lanes of a half wave on 32 different banks (a pitch that is a multiple
     // of 32, e.g. 6 rows x 16 columns, puts the 16 slabs on one bank); otherwise an odd pitch.
     p->zld = p->slab;
     while (g.sw == 1 ? (p->zld % 32 != 2) : (p->zld % 2 == 0)) ++p->zld;
-    if ((long long)p->zld * 16 > CR_ZMAX) p->zld = p->slab;
+    if ((long long)p->zld * 16 > zmax) p->zld = p->slab;
     p->nchunks = g.r1 * p->nyc;
     const long long base = (long long)((g.cout + CR_TO - 1) / CR_TO) * ((g.r2 + 15) / 16);
     long long target = 256;
     long long want = (target + base - 1) / base;
+    // With the large chunks a CU holds one workgroup (LDS), so a workgroup beyond the 256th waits for a whole
+    // round: round the split count down, not up.
+    if (p->kc == CR_KC_BIG) want = target / base;
     if (want > p->nchunks) want = p->nchunks;
     if (want < 1) want = 1;
     p->cps = (int)((p->nchunks + want - 1) / want);
@@ -81,7 +100,7 @@ static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
     // thousand output positions or more this way is better cut in three, so that three workgroups
     // per CU hide each other's rounds (measured on 64 x 64 planes: 252 -> 144 us; below that the extra
     // partial sums cost more than the overlap gains: 83 -> 96 us on 56 x 56 planes with twice the channels' splits).
-    if ((long long)p->cps * p->ry * g.Wo >= 1024) {
+    if (p->kc == CR_KC_SMALL && (long long)p->cps * p->ry * g.Wo >= 1024) {
         want = (3 * target + base - 1) / base;
         if (want > p->nchunks) want = p->nchunks;
         p->cps = (int)((p->nchunks + want - 1) / want);
@@ -91,13 +110,33 @@ static bool corr_plan(const CorrGeom& g, CorrPlan* p) {
 }
 
 
-template <int MAXT, bool EXACT>
+extern __shared__ float cr_dyn[];
+
+template <int MAXT>
+constexpr int corr_lds_floats(int kc, int zmax) {
+    // the G1 tile, the Z slabs and the table of window origins; afterwards the result tile
+    return (CR_TO * (16 * (MAXT < 9 ? MAXT : 9) + 1) > kc * (CR_TO + 2) + zmax) ? CR_TO * (16 * (MAXT < 9 ? MAXT : 9) + 1)
+                                                                                   : kc * (CR_TO + 2) + zmax;
+}
+
+// BIG (3 x 3 taps, unit column dilation, chunks of 256 positions): a wave owns TWO blocks of 16 output
+// channels and the eight waves form four K groups.  The matrix pipe and the vector ALU of a SIMD do not
+// overlap here (measured: a loop of independent 16x16x4 products runs at 33-36 cycles per product, and
+// every vector instruction placed between them adds its own ~4-8 cycles, whatever the number of waves),
+// so the loop carries as little else as possible: per K step one table read for the window origin,
+// three address additions (one per kernel row; the three taps of a row are immediate offsets), two A
+// reads and nine B reads feed eighteen products.
+template <int MAXT, bool EXACT, bool BIG>
 __global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
-    // As | Zs during the K loop; afterwards the 64 x (16 x up to 9 taps) result tile
+    constexpr int CR_KC = BIG ? CR_KC_BIG : CR_KC_SMALL, CR_ZMAX = BIG ? CR_ZMAX_BIG : CR_ZMAX_SMALL;
+    constexpr int OB = BIG ? 2 : 1;                      // blocks of 16 output channels per wave
+    constexpr int NWO = 4 / OB;                          // waves side by side along the output channels
+    constexpr int KG = CR_NW / NWO;                      // K groups: waves that share channels and split the K steps
+    static_assert(!BIG || (MAXT == 9 && EXACT), "the large-chunk form is written for 3 x 3 taps");
+    // As | Zs | korg during the K loop; afterwards the 64 x (16 x up to 9 taps) result tile
     constexpr int CR_TG = MAXT < 9 ? MAXT : 9;           // taps per pass of the result through LDS
     constexpr int CR_TS_LD = 16 * CR_TG + 1;
-    constexpr int CR_LDS = (CR_TO * CR_TS_LD > CR_KC * (CR_TO + 1) + CR_ZMAX) ? CR_TO * CR_TS_LD : CR_KC * (CR_TO + 1) + CR_ZMAX;
-    __shared__ float lds_raw[CR_LDS];
+    float* lds_raw = cr_dyn;                             // corr_lds_floats<MAXT>(CR_KC, CR_ZMAX) floats
     float (*As)[CR_TO + 1] = reinterpret_cast<float (*)[CR_TO + 1]>(lds_raw);
     float* Zs = lds_raw + CR_KC * (CR_TO + 1);
     int lb;
@@ -108,7 +147,8 @@ __global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
     const CorrGeom g = jb.g;
     const CorrPlan pl = jb.pl;
     const int bz = lb / (jb.gx * jb.gy), brem = lb - bz * (jb.gx * jb.gy), by = brem / jb.gx, bx = brem - by * jb.gx;
-    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kgrp = tid >> 8, lg = lane >> 4, ll = lane & 15;
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6, wo = wid % NWO, lg = lane >> 4, ll = lane & 15;
+    const int kgrp_s = __builtin_amdgcn_readfirstlane(wid / NWO);      // the same for a whole wave: a scalar
     const int taps = g.kh * g.kw;
     const int o0 = bx * CR_TO, j0 = by * 16, z = bz;
     const int HoWo = g.Ho * g.Wo;
@@ -119,99 +159,218 @@ __global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
         const int kh = t / g.kw, kw = t - kh * g.kw;
         tapofs[t] = (t < taps) ? kh * g.dh * pl.wp + kw * g.dw : 0;
     }
-    v4f acc[MAXT];
+    v4f acc[OB][MAXT];
 #pragma unroll
-    for (int t = 0; t < MAXT; ++t) acc[t] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int ob = 0; ob < OB; ++ob)
+#pragma unroll
+        for (int t = 0; t < MAXT; ++t) acc[ob][t] = (v4f){0.f, 0.f, 0.f, 0.f};
 
     const int ch_beg = z * pl.cps;
     const int ch_end = (ch_beg + pl.cps < pl.nchunks) ? ch_beg + pl.cps : pl.nchunks;
     const int ztotal = 16 * pl.slab;
     const float inv_slab = 1.0f / (float)pl.slab, inv_wp = 1.0f / (float)pl.wp, inv_wo = 1.0f / (float)g.Wo;
     const int row_step = g.sh * pl.wp;
-    constexpr int NA = CR_KC * CR_TO / CR_NT, NZ = CR_ZMAX / CR_NT;     // loads per thread and chunk
+    // loads per thread and chunk.  BIG: a thread serves one slab column of CR_ZRMAX rows of four slabs
+    constexpr int NA = CR_KC * CR_TO / CR_NT, NZ = BIG ? 4 * CR_ZRMAX : CR_ZMAX / CR_NT;
+    static_assert(NA <= 32 && NZ <= 32, "one mask bit per load");
     float a_t[NA], z_t[NZ];
-    // loads of one chunk into registers: the G1 tile (64 channels x kcv positions, contiguous
-    // along k) and the Z slab with its zero halo (rows ylo.., columns -pw..)
+    unsigned amask = 0, zmask = 0;     // which of the loaded values belong to the chunk (set by fetch, used by the next store)
+    // Loads of one chunk into registers: the G1 tile (64 channels x kcv positions, contiguous along k)
+    // and the Z slab with its zero halo (rows ylo.., columns -pw..).  Every load goes to an address
+    // that is valid whatever the lane (a lane outside the tile or in the halo reads a clamped position)
+    // and its result is only masked when it is stored to LDS: a load guarded by a test of its own is
+    // compiled into a conditional block that waits for it, and the loads of a chunk would then run one
+    // after the other instead of together.
+    // BIG: every quantity that depends on the row of the tile or slab a load belongs to is the same for
+    // a whole wave (rows are dealt out by tid / 256 resp. tid / 128), so it is kept in scalar registers
+    // and a load costs no vector arithmetic; what depends on the lane (position, slab column) is fixed
+    // for the kernel.  The vector instructions of fetch and store run at the expense of the products.
+    const int rga = __builtin_amdgcn_readfirstlane(tid / CR_KC);          // first tile row of this wave (BIG: 0 or 1)
+    const int rgz = __builtin_amdgcn_readfirstlane(tid >> 7);             // BIG: slabs 4 rgz .. 4 rgz + 3
+    const int zcc = tid & 127;                                            // BIG: slab column of this lane
+    const bool zc_in = zcc < pl.wp, zc_ok = zc_in & (zcc - g.pw >= 0) & (zcc - g.pw < g.W);
+    const int zcolc = min(max(zcc - g.pw, 0), g.W - 1);
+    int kcv_f = 0, ylo_f = 0;          // BIG: positions and first slab row of the chunk in the registers
+    auto fetch_big = [&](int ch) {
+        const int i = ch / pl.nyc, yc = ch - i * pl.nyc;
+        const int y0 = yc * pl.ry;
+        const int rows = (g.Ho - y0 < pl.ry) ? g.Ho - y0 : pl.ry;
+        kcv_f = rows * g.Wo;
+        ylo_f = y0 * g.sh - g.ph;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int j = j0 + 4 * rgz + jj, jc = j < g.r2 ? j : g.r2 - 1;
+#pragma unroll
+            for (int rr = 0; rr < CR_ZRMAX; ++rr) {
+                int row = ylo_f + rr;
+                row = row < 0 ? 0 : (row > g.H - 1 ? g.H - 1 : row);
+                const float* zrow = Z + (long long)(((i * g.r2 + jc) * g.H + row) * g.W);     // scalar
+                z_t[jj * CR_ZRMAX + rr] = zrow[zcolc];
+            }
+        }
+        const int k = tid & (CR_KC - 1);
+        const int kc = k < kcv_f ? k : 0;
+#pragma unroll
+        for (int u = 0; u < NA; ++u) {
+            int o = o0 + rga + (CR_NT / CR_KC) * u;
+            o = o < g.cout ? o : o0;
+            const float* arow = G1 + (long long)((i * g.cout + o) * HoWo + y0 * g.Wo);        // scalar
+            a_t[u] = arow[kc];
+        }
+    };
+    auto store_big = [&]() {
+        const int k = tid & (CR_KC - 1);
+        const bool kin = k < kcv_f;
+#pragma unroll
+        for (int u = 0; u < NA; ++u) {
+            const int ol = rga + (CR_NT / CR_KC) * u;
+            const bool oin = o0 + ol < g.cout;                                               // scalar
+            As[k][ol] = (kin & oin) ? a_t[u] : 0.f;
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int jl = 4 * rgz + jj;
+            const bool jin = j0 + jl < g.r2;                                                 // scalar
+#pragma unroll
+            for (int rr = 0; rr < CR_ZRMAX; ++rr) {
+                const int row = ylo_f + rr;
+                const bool rin = jin & (row >= 0) & (row < g.H);                             // scalar
+                if (rr < pl.rows_in && zc_in) Zs[jl * pl.zld + rr * pl.wp + zcc] = (rin & zc_ok) ? z_t[jj * CR_ZRMAX + rr] : 0.f;
+            }
+        }
+    };
     auto fetch = [&](int ch) {
+        if constexpr (BIG) { fetch_big(ch); return; }
         const int i = ch / pl.nyc, yc = ch - i * pl.nyc;
         const int y0 = yc * pl.ry;
         const int rows = (g.Ho - y0 < pl.ry) ? g.Ho - y0 : pl.ry;
         const int kcv = rows * g.Wo;
-        const int k = tid & 63;
-#pragma unroll
-        for (int u = 0; u < NA; ++u) {
-            const int o = o0 + (tid >> 6) + CR_NW * u;
-            a_t[u] = ldg_f32(G1, (i * g.cout + o) * HoWo + y0 * g.Wo + k, k < kcv && o < g.cout);
-        }
+        // Z slab first.  Row, column and core channel are clamped one by one (no select between two
+        // address expressions, no 64-bit multiply-add: both make the compiler wait for earlier loads).
         const int ylo = y0 * g.sh - g.ph;
+        const int zbase = i * g.r2;
+        zmask = 0;
 #pragma unroll
         for (int u = 0; u < NZ; ++u) {
             const int e = u * CR_NT + tid;
-            // e < 4096: the rounded float quotient is exact, no integer division needed
-            const int jl = (int)(((float)e + 0.5f) * inv_slab), rem = e - jl * pl.slab;
-            const int rr = (int)(((float)rem + 0.5f) * inv_wp), cc = rem - rr * pl.wp;
+            // e < 8192, slab <= 512: the rounded float quotient is exact, no integer division needed
+            const int jl = (int)(((float)e + 0.5f) * inv_slab), rem = e - __mul24(jl, pl.slab);
+            const int rr = (int)(((float)rem + 0.5f) * inv_wp), cc = rem - __mul24(rr, pl.wp);
             const int row = ylo + rr, col = cc - g.pw, j = j0 + jl;
-            const bool ok = e < ztotal && j < g.r2 && row >= 0 && row < g.H && col >= 0 && col < g.W;
-            const float v = ldg_f32(Z, ((i * g.r2 + j) * g.H + row) * g.W + col, ok);
-            z_t[u] = v;
+            const bool ok = (e < ztotal) & (j < g.r2) & (row >= 0) & (row < g.H) & (col >= 0) & (col < g.W);
+            const int jc = min(j, g.r2 - 1), rowc = min(max(row, 0), g.H - 1), colc = min(max(col, 0), g.W - 1);
+            z_t[u] = Z[__mul24(__mul24(zbase + jc, g.H) + rowc, g.W) + colc];
+            zmask |= ok ? (1u << u) : 0u;
+        }
+        // G1 tile: lane k of a wave walks the positions, the rows (channels) are CR_NT / CR_KC apart
+        const int k = tid & (CR_KC - 1);
+        const bool kin = k < kcv;
+        const int abase = __mul24(i, g.cout) * HoWo + y0 * g.Wo + (kin ? k : 0);
+        amask = 0;
+#pragma unroll
+        for (int u = 0; u < NA; ++u) {
+            const int o = o0 + tid / CR_KC + (CR_NT / CR_KC) * u;
+            const bool oin = o < g.cout;
+            a_t[u] = G1[abase + __mul24(oin ? o : o0, HoWo)];
+            amask |= (kin & oin) ? (1u << u) : 0u;
         }
     };
+    // korg[k]: offset of the window origin of output position k inside a slab, (k / Wo) * sh * wp + (k % Wo) * sw
+    // (0 for positions beyond the rows of a chunk; their A values are zero).  The same for every chunk.
+    int* korg = reinterpret_cast<int*>(lds_raw + CR_KC * (CR_TO + 1) + CR_ZMAX);
+    for (int k = tid; k < CR_KC; k += CR_NT) {
+        const int yl = (int)(((float)k + 0.5f) * inv_wo), x = k - yl * g.Wo;     // k < 2^14: exact
+        korg[k] = (yl < pl.ry) ? yl * row_step + x * g.sw : 0;
+    }
+    // per-lane constants of the operand reads: As[4 ks + lg][16 (OB wo + ob) + ll], slab ll of Zs
+    const int a_lane = lg * (CR_TO + 1) + 16 * OB * wo + ll, zlane = ll * pl.zld;
+    const int khstep = g.dh * pl.wp;                       // slab offset of one kernel row
     if (ch_beg < ch_end) fetch(ch_beg);
     for (int ch = ch_beg; ch < ch_end; ++ch) {
         const int i = ch / pl.nyc, yc = ch - i * pl.nyc;
         const int y0 = yc * pl.ry;
         const int rows = (g.Ho - y0 < pl.ry) ? g.Ho - y0 : pl.ry;
         const int kcv = rows * g.Wo;                       // valid positions in this chunk
+        (void)i;
         __syncthreads();                                   // previous chunk consumed
+        if constexpr (BIG) {
+            store_big();
+        } else {
 #pragma unroll
-        for (int u = 0; u < NA; ++u) As[tid & 63][(tid >> 6) + CR_NW * u] = a_t[u];
+            for (int u = 0; u < NA; ++u)
+                As[tid & (CR_KC - 1)][tid / CR_KC + (CR_NT / CR_KC) * u] = ((amask >> u) & 1u) ? a_t[u] : 0.f;
 #pragma unroll
-        for (int u = 0; u < NZ; ++u) {
-            const int e = u * CR_NT + tid;
-            const int jl = (int)(((float)e + 0.5f) * inv_slab);
-            if (e < ztotal) Zs[e + jl * (pl.zld - pl.slab)] = z_t[u];
+            for (int u = 0; u < NZ; ++u) {
+                const int e = u * CR_NT + tid;
+                const int jl = (int)(((float)e + 0.5f) * inv_slab);
+                if (e < ztotal) Zs[e + jl * (pl.zld - pl.slab)] = ((zmask >> u) & 1u) ? z_t[u] : 0.f;
+            }
         }
         __syncthreads();
         if (ch + 1 < ch_end) fetch(ch + 1);                // in flight while this chunk is multiplied
-        // operands of step ks: the A value and one B value per tap.  The loads of step ks + 1 are
-        // issued before the products of step ks, so that LDS latency is paid once per chunk and not
-        // once per product.  The step count is rounded up to even: positions past the chunk's end
-        // have zero A values (the loader's predicate) and read the slab origin, so they add nothing,
-        // and the loop body stays free of branches.
-        // steps of this wave's K group: ks = kgrp, kgrp + CR_KG, ...; their number is rounded up to even
-        const int nsteps = (((kcv + 3) >> 2) + CR_KG - 1) / CR_KG;
+        // Operands of step ks: one A value per channel block and one B value per tap.  The reads of step
+        // ks + 1 are issued before the products of step ks, so that LDS latency is paid once per chunk
+        // and not once per product.  The step count is rounded up to even: positions past the chunk's
+        // end have zero A values (the loader's mask) and read the slab origin, so they add nothing, and
+        // the loop body stays free of branches.  The step index is the same for a whole wave, so the A
+        // address is a per-lane constant plus a scalar, and the window origin of a position comes from
+        // the table korg: no vector multiply is left in the loop (besides their cost, the 64-bit
+        // multiply-add the compiler picks for some of them takes an unrelated register - one of the next
+        // chunk's pending loads - as its unused upper addend and waits for that load).
+        const int nsteps = (((kcv + 3) >> 2) + KG - 1) / KG;   // steps of this wave's K group: ks = kgrp, kgrp + KG, ...
         const int nst2 = (nsteps + 1) & ~1;
-        const int zbase = ll * pl.zld;
-        auto operands = [&](int st, float& a, float (&bq)[MAXT]) {
-            int ks = st * CR_KG + kgrp;
+        int org = korg[4 * kgrp_s + lg];                   // origin of this lane's position in step 0
+        auto operands = [&](int st, float (&a)[OB], float (&bq)[MAXT]) {
+            int ks = st * KG + kgrp_s;
             ks = ks < CR_KC / 4 ? ks : CR_KC / 4 - 1;          // only the read-ahead past the last step is clamped
-            const int k = 4 * ks + lg;
-            // window origin of position k inside the slab: (k / Wo) * sh * wp + (k % Wo) * sw
-            // (24-bit multiplies: one instruction each, and every factor here is far below 2^23)
-            const int yl = (int)(((float)k + 0.5f) * inv_wo), x = k - __mul24(yl, g.Wo);
-            // (a 24-bit multiply here too: the 64-bit multiply-add the compiler would pick takes a
-            // register of the next chunk's loads as its unused upper addend and waits for them)
-            a = lds_raw[__mul24(k, CR_TO + 1) + 16 * wave + ll];   // As[k][..]; rows past the chunk's end are zero
-            const int org = __mul24(yl, row_step) + __mul24(x, g.sw);
-            const int zo = zbase + ((yl < pl.ry) ? org : 0);
+            const float* ap = lds_raw + a_lane + ks * (4 * (CR_TO + 1));
 #pragma unroll
-            for (int t = 0; t < MAXT; ++t) bq[t] = (EXACT || t < taps) ? Zs[zo + tapofs[t]] : 0.f;
+            for (int ob = 0; ob < OB; ++ob) a[ob] = ap[16 * ob];   // rows past the chunk's end are zero
+            const int zo = zlane + org;
+            if constexpr (BIG) {
+                const float* z0 = Zs + zo;
+                const float* z1 = z0 + khstep;
+                const float* z2 = z1 + khstep;
+                bq[0] = z0[0]; bq[1] = z0[1]; bq[2] = z0[2];
+                bq[3] = z1[0]; bq[4] = z1[1]; bq[5] = z1[2];
+                bq[6] = z2[0]; bq[7] = z2[1]; bq[8] = z2[2];
+            } else {
+#pragma unroll
+                for (int t = 0; t < MAXT; ++t) bq[t] = (EXACT || t < taps) ? Zs[zo + tapofs[t]] : 0.f;
+            }
+            int kn = ks + KG;
+            kn = kn < CR_KC / 4 ? kn : CR_KC / 4 - 1;
+            org = korg[4 * kn + lg];                           // for the next step of this wave
         };
-        float a0, a1, b0[MAXT], b1[MAXT];
+        float a0[OB], a1[OB], b0[MAXT], b1[MAXT];
         operands(0, a0, b0);
+        // (scheduling fences: left alone, the compiler moves each read down next to the product that uses
+        // it, and the product then waits for the LDS round trip)
 #pragma unroll 1
         for (int st = 0; st < nst2; st += 2) {
             operands(st + 1, a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < MAXT; ++t)
-                if (EXACT || t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[t], acc[t], 0, 0, 0);
+                if (EXACT || t < taps) {
+#pragma unroll
+                    for (int ob = 0; ob < OB; ++ob)
+                        acc[ob][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[ob], b0[t], acc[ob][t], 0, 0, 0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
             operands(st + 2, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < MAXT; ++t)
-                if (EXACT || t < taps) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[t], acc[t], 0, 0, 0);
+                if (EXACT || t < taps) {
+#pragma unroll
+                    for (int ob = 0; ob < OB; ++ob)
+                        acc[ob][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[ob], b1[t], acc[ob][t], 0, 0, 0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    // lane holds o = o0 + 16w + 4*lg + v, j = j0 + ll
+    // lane holds o = o0 + 16 (OB wo + ob) + 4*lg + v, j = j0 + ll
     // The result goes through LDS, up to 9 taps at a time: the K groups add their tiles there, and
     // for one output channel the (j, tap) values of this workgroup are then one contiguous run of T
     // (stored straight from the accumulators every lane of a store would hit its own cache line:
@@ -225,18 +384,20 @@ __global__ __launch_bounds__(CR_NT) void k_corr_mfma(Batch<CorrJob> bt) {
             const int tg = (taps - t0 < CR_TG) ? taps - t0 : CR_TG;
             __syncthreads();                               // the tiles (or the previous pass) are no longer read
 #pragma unroll
-            for (int kg = CR_KG - 1; kg >= 0; --kg) {      // the K groups add their tiles one after the other
-                if (kgrp == kg) {
+            for (int kg = KG - 1; kg >= 0; --kg) {         // the K groups add their tiles one after the other
+                if (kgrp_s == kg) {
 #pragma unroll
-                    for (int tt = 0; tt < CR_TG; ++tt)
-                        if (t0 + tt < MAXT && tt < tg) {
+                    for (int ob = 0; ob < OB; ++ob)
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) {
-                                float* p = &Ts[(16 * wave + 4 * lg + v) * CR_TS_LD + ll * tg + tt];
-                                *p = (kg == CR_KG - 1) ? acc[(t0 + tt < MAXT) ? t0 + tt : 0][v]
-                                                       : *p + acc[(t0 + tt < MAXT) ? t0 + tt : 0][v];
+                        for (int tt = 0; tt < CR_TG; ++tt)
+                            if (t0 + tt < MAXT && tt < tg) {
+#pragma unroll
+                                for (int v = 0; v < 4; ++v) {
+                                    float* p = &Ts[(16 * (OB * wo + ob) + 4 * lg + v) * CR_TS_LD + ll * tg + tt];
+                                    const float mine = acc[ob][(t0 + tt < MAXT) ? t0 + tt : 0][v];
+                                    *p = (kg == KG - 1) ? mine : *p + mine;
+                                }
                             }
-                        }
                 }
                 __syncthreads();
             }
@@ -302,7 +463,8 @@ int corr_splits(const CorrGeom& g) {
     return (g.r1 + ips - 1) / ips;
 }
 
-// key: 0 = k_corr_mfma<1,true>, 1 = <9,true>, 2 = <9,false>, 3 = <25,false>; the fallback kernel has kind IT_CORR
+// key: 0 = k_corr_mfma<1,true,false>, 1 = <9,true,false>, 2 = <9,false,false>, 3 = <25,false,false>, 5 = <9,true,true> (chunks of 256 positions);
+// the fallback kernel has kind IT_CORR
 bool make_corr(const float* G1, const float* Z, float* Tpart, const CorrGeom& g, int nsplit, Item* out) {
     const long long total = (long long)g.cout * g.r2 * g.kh * g.kw;
     if (total <= 0 || nsplit <= 0 || !G1 || !Z || !Tpart) return false;
@@ -315,9 +477,10 @@ bool make_corr(const float* G1, const float* Z, float* Tpart, const CorrGeom& g,
         jb.gx = (g.cout + CR_TO - 1) / CR_TO; jb.gy = (g.r2 + 15) / 16; jb.gz = jb.pl.nsplit;
         const int taps = g.kh * g.kw;
         out->kind = IT_CORR_MFMA;
-        out->key = taps == 1 ? 0u : (taps == 9 ? 1u : (taps < 9 ? 2u : 3u));
-        std::snprintf(out->label, sizeof(out->label), "k_corr_mfma<%d, %s>", taps == 1 ? 1 : (taps <= 9 ? 9 : 25),
-                      (taps == 1 || taps == 9) ? "true" : "false");
+        const bool big = jb.pl.kc == CR_KC_BIG;
+        out->key = (taps == 1 ? 0u : (taps == 9 ? 1u : (taps < 9 ? 2u : 3u))) | (big ? 4u : 0u);
+        std::snprintf(out->label, sizeof(out->label), "k_corr_mfma<%d, %s, %s>", taps == 1 ? 1 : (taps <= 9 ? 9 : 25),
+                      (taps == 1 || taps == 9) ? "true" : "false", big ? "true" : "false");
     } else {
         jb.ips = (g.r1 + nsplit - 1) / nsplit;
         if ((total + 255) / 256 > 0x3fffffLL) return false;
@@ -340,12 +503,32 @@ hipError_t launch_corr_items(const Item* const* items, int n, hipStream_t st) {
         hipLaunchKernelGGL(k_corr, grid, 256, 0, st, b);
         return hipGetLastError();
     }
+    // LDS is dynamic: the large-chunk instantiations need more than the 64 KB a static array may take,
+    // which has to be allowed once per kernel (the flags are only ever set, so a race between threads is harmless)
+#define ASI_CORR_LAUNCH(MAXT, EXACT, BIG)                                                                          \
+    do {                                                                                                           \
+        constexpr size_t lds = sizeof(float) * corr_lds_floats<MAXT>(BIG ? CR_KC_BIG : CR_KC_SMALL,                \
+                                                                     BIG ? CR_ZMAX_BIG : CR_ZMAX_SMALL);           \
+        if (lds > 65536) {                                                                                         \
+            static std::atomic<bool> allowed{false};                                                               \
+            if (!allowed.load()) {                                                                                 \
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_corr_mfma<MAXT, EXACT, BIG>),   \
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
+                if (e != hipSuccess) return e;                                                                     \
+                allowed.store(true);                                                                               \
+            }                                                                                                      \
+        }                                                                                                          \
+        hipLaunchKernelGGL((k_corr_mfma<MAXT, EXACT, BIG>), grid, CR_NT, lds, st, b);                              \
+    } while (0)
     switch (items[0]->key) {
-        case 0: hipLaunchKernelGGL((k_corr_mfma<1, true>), grid, CR_NT, 0, st, b); break;
-        case 1: hipLaunchKernelGGL((k_corr_mfma<9, true>), grid, CR_NT, 0, st, b); break;
-        case 2: hipLaunchKernelGGL((k_corr_mfma<9, false>), grid, CR_NT, 0, st, b); break;
-        default: hipLaunchKernelGGL((k_corr_mfma<25, false>), grid, CR_NT, 0, st, b); break;
+        case 0: ASI_CORR_LAUNCH(1, true, false); break;
+        case 1: ASI_CORR_LAUNCH(9, true, false); break;
+        case 2: ASI_CORR_LAUNCH(9, false, false); break;
+        case 3: ASI_CORR_LAUNCH(25, false, false); break;
+        case 5: ASI_CORR_LAUNCH(9, true, true); break;
+        default: return hipErrorInvalidValue;
     }
+#undef ASI_CORR_LAUNCH
     return hipGetLastError();
 }
 

@@ -20,6 +20,7 @@
 #include "asi_device.h"
 #include "asi_kernels.h"
 
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 #include <type_traits>
@@ -1308,12 +1309,12 @@ hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st, ch
             // packed triangle, dinv, rdiag, pivot reciprocals, inverse block factor, row exchange buffer
             const size_t nb16 = (size_t)((rmax + 15) / 16) * 16;
             const size_t lds = sizeof(double) * ((size_t)rmax * (rmax + 1) / 2 + 2 * (size_t)rmax + nb16 + 16 * 17 + 2 * 64 * 4);
-            static size_t lds_allowed = 0;                 // the attribute only ever needs to grow
-            if (lds > lds_allowed) {
+            static std::atomic<size_t> lds_allowed{0};     // the attribute only ever needs to grow
+            if (lds > lds_allowed.load()) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_orthw_chol),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
                 if (e != hipSuccess) return e;
-                lds_allowed = lds;
+                lds_allowed.store(lds);
             }
             hipLaunchKernelGGL(k_orthw_chol, grid, OWC_NT, lds, st, b, aux & 1, (aux >> 1) & 1);
             break;

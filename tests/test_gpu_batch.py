@@ -52,3 +52,9 @@ def test_batch_equals_single_config5_linear_bf16():
 def test_batch_of_one_and_repeated_layer():
     _run_pair(1, [0])
     _run_pair(2, [1, 1, 2])
+
+
+def test_batch_of_eight_layers():
+    """The largest batch the ABI takes: every launch serves eight argument blocks."""
+    _run_pair(2, [0, 1, 2, 3, 3, 2, 1, 0], steps=1)
+    _run_pair(3, [0, 3, 0, 3, 1, 2, 0, 3], steps=1)

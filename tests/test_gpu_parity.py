@@ -79,11 +79,17 @@ def check_core_and_dw(run, lay, A_t, A64, U_or, dY_np, tol, tag, e2e_tol=None):
     dW_gpu = _np(run.weight_grad(dY_t, _dev(S_tf), U_tf_t))
     ew = O.max_rel_err(dW_gpu, dW_or)
     assert ew <= tol, f"{tag}: dW err {ew:.3e} > {tol}"
-    # end to end with the GPU's own factors: dW depends on the factors only through
-    # their projectors, so it is unique
-    run.core(A_t)
+    # end to end with the GPU's own factors: the reconstruction S x_m U_m (Eq. 3) and dW depend on
+    # the factors only through their projectors, so both are unique
+    S_own = _np(run.core(A_t))
+    S_ref = O.core_project(A64, U_or)
+    A_hat_gpu = O.reconstruct(S_own, [_np(u) for u in run.factors()])
+    A_hat_ref = O.reconstruct(S_ref, U_or)
+    ea = O.max_rel_err(A_hat_gpu, A_hat_ref)
+    assert ea <= tol, f"{tag}: reconstruction from the GPU's own (S, U) err {ea:.3e} > {tol}"
+    del A_hat_gpu, A_hat_ref
     dW_e2e = _np(run.weight_grad(dY_t))
-    dW_ref = _oracle_dw(lay, O.core_project(A64, U_or), U_or, dY64)
+    dW_ref = _oracle_dw(lay, S_ref, U_or, dY64)
     ee = O.max_rel_err(dW_e2e, dW_ref)
     assert ee <= (e2e_tol or tol), f"{tag}: end-to-end dW err {ee:.3e}"
     return dW_ref
@@ -107,8 +113,6 @@ def test_config1_exact_tucker_full_path():
 def _drift_config(ci, check_at, tol):
     cfg = CONFIGS[ci]
     for li, lay in enumerate(cfg.layers):
-        if ci == 2 and li == 3:
-            continue        # layers 1-3 of config 2 share one shape; two of them are enough here
         st = LayerStream(ci, li, lay, cfg.theta)
         run_tf, run_free = _runner(lay), _runner(lay)
         U_prev_or = [u.astype(F64) for u in st.u_prev0()]
@@ -125,10 +129,13 @@ def _drift_config(ci, check_at, tol):
             run_free.compress(A_t)
             U_prev_or = U_or
         torch.cuda.synchronize()
-        # after all steps both chains track the same subspace
+        # After all steps both chains track the same subspace, to the same bar as a single step: a
+        # difference between the two previous bases is contracted by (sigma_{r+1} / sigma_r)^2 per
+        # step (the noise floor sits far below the weakest kept direction), so nothing accumulates.
         for m, (ug, uo) in enumerate(zip(run_free.factors(), U_prev_or)):
             ep = O.max_rel_err(O.projector(_np(ug)), O.projector(uo))
-            assert ep <= 10 * tol, f"cfg{ci} layer{li} free-running mode {m}: {ep:.3e}"
+            print(f"cfg{ci} layer{li} free-running mode {m}: projector err {ep:.3e}")
+            assert ep <= tol, f"cfg{ci} layer{li} free-running mode {m}: {ep:.3e}"
 
 
 def test_config2_resnet18_tail_50_steps():
@@ -212,6 +219,16 @@ def test_edge_linear_shapes(case, dtype):
     check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), tol, f"edge {case}")
 
 
+def test_rank_above_192_takes_the_general_orthogonalisation():
+    """Ranks in (192, 1024] leave the blocked orthogonalisation kernels for the single-workgroup one and
+    need 13 or more rank tiles in the product kernels; the whole path is checked like any other shape."""
+    lay = Layer("edge", (8, 40, 600), (8, 40, 200), "f32", "linear", 9, alpha=0.3, noise=1e-2)
+    st = LayerStream(9, 4, lay)
+    run = _runner(lay)
+    A_t, A64, U_or = check_compress(run, lay, st.activation(0), st.u_prev0(), TOL["f32"], "rank 200")
+    check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), TOL["f32"], "rank 200")
+
+
 def test_accumulate_adds_to_dw_and_aliasing_factors_is_allowed():
     import paper_2505_05086_amd as asi
     lay = Layer("edge", (4, 6, 5, 5), (2, 3, 2, 2), "f32", "conv2d", 6, k=3, pad=1, alpha=0.5, noise=1e-2)
@@ -286,15 +303,35 @@ def _check_orthonormal_basis(lay, A, stream_id, tag):
     U_gpu = run.compress(run.upload(A))
     torch.cuda.synchronize()
     assert int(run.info.item()) == 0, tag
-    U_or = O.compress(A.astype(F64), [u.astype(F64) for u in st.u_prev0()])
+    A64 = A.astype(F64)
+    U0 = [u.astype(F64) for u in st.u_prev0()]
+    U_or = O.compress(A64, U0)
+    eps32 = 2.0 ** -24
+    compared = 0
     for m, (ug, uo) in enumerate(zip(U_gpu, U_or)):
         ug = _np(ug)
         assert np.all(np.isfinite(ug))
-        eo = np.max(np.abs(ug.T @ ug - np.eye(ug.shape[1])))
+        r = ug.shape[1]
+        eo = np.max(np.abs(ug.T @ ug - np.eye(r)))
         assert eo < 1e-5, f"{tag} mode {m}: U^T U - I = {eo:.2e}"
-        lead = uo[:, :2]                                           # QR keeps the column order of P
-        out = np.linalg.norm(lead - ug @ (ug.T @ lead))
-        assert out < 1e-3, f"{tag} mode {m}: dominant directions outside the basis by {out:.2e}"
+        # Gram-Schmidt keeps the column order of P, so the first k columns of the factor span the
+        # first k columns of P on both sides.  The library rounds V = A_m^T U_prev to fp32 (the fp32
+        # path's own arithmetic), which perturbs P by about eps32 ||A_m||^2 ||U_prev|| sqrt(b_m) at worst, and the span of
+        # P[:, :k] moves by that over sigma_min(P[:, :k]).  Each nested projector is therefore held to
+        #     8 eps32 sigma_max(P) / sigma_min(P[:, :k])    (plus the 1e-6 floor of the fp32 output),
+        # with the conditioning taken from the oracle's P; leading blocks whose bound exceeds 0.1 are
+        # not comparable in fp32 and are skipped.
+        Pm = O.subspace_P(A64, U0[m], m)
+        smax = np.linalg.svd(Pm, compute_uv=False)[0]
+        for k in range(1, r + 1):
+            smin_k = np.linalg.svd(Pm[:, :k], compute_uv=False)[-1]
+            bound = 8.0 * eps32 * smax / smin_k + 1e-6
+            if bound > 0.1:
+                break
+            ep = np.max(np.abs(O.projector(ug[:, :k]) - O.projector(uo[:, :k])))
+            assert ep <= bound, f"{tag} mode {m}: leading {k} columns, projector err {ep:.2e} > bound {bound:.2e}"
+            compared += 1
+    assert compared >= len(U_or), f"{tag}: only {compared} nested projectors were comparable"
 
 
 @pytest.mark.parametrize("ratio", [1e-1, 1e-2, 3e-3])
