@@ -85,6 +85,7 @@ struct CompressPlan {
     int nsplit[4] = {};
     int nblk[4] = {};
     bool fused[4] = {};
+    bool longm[4] = {};              // long fibres: V and P from one LDS tile of complete fibres (asi_long.hip)
     bool paired = false;             // the last two modes of a 4-mode tensor share one kernel
     bool tiny = false;               // ... the vector-ALU kernel for tiny planes
     bool fast_orth[4] = {};
@@ -98,7 +99,8 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
     size_t vmax = 0;
     for (int m = 0; m < s.d; ++m) {
         p.fused[m] = subspace_small_supported((int)s.n[m], s.r[m]);
-        if (!p.fused[m]) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
+        p.longm[m] = !p.fused[m] && subspace_long_supported(s.outer(m), (int)s.n[m], s.inner(m), s.r[m]);
+        if (!p.fused[m] && !p.longm[m]) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
     }
     p.V = c.take<float>(vmax);
     p.ctr8 = c.take<int32_t>(8);
@@ -108,6 +110,7 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
         const size_t n = (size_t)s.n[m], r = (size_t)s.r[m];
         if (p.tiny && m >= 2) p.nsplit[m] = subspace_tiny_nwg(s.n[0] * s.n[1]);
         else if (p.paired && m >= 2) p.nsplit[m] = subspace_pair_nwg(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3]);
+        else if (p.longm[m]) p.nsplit[m] = subspace_long_splits(s.outer(m), (int)n, s.inner(m), (int)r);
         else p.nsplit[m] = p.fused[m] ? subspace_small_nwg(s.outer(m), (int)n, s.inner(m))
                                       : pair_splits(s.outer(m), (int)n, s.inner(m), (int)r);
         p.part[m] = c.take<double>((size_t)p.nsplit[m] * n * r);
@@ -431,9 +434,9 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
     // the modes before it (independent work in extra workgroups), which saves a launch of its own.
     int order[4], nord = 0, last_two = -1;
     for (int m = 0; m < s.d; ++m)
-        if (p.fused[m] || (p.paired && m >= 2)) order[nord++] = m;
+        if (p.fused[m] || p.longm[m] || (p.paired && m >= 2)) order[nord++] = m;
     for (int m = 0; m < s.d; ++m)
-        if (!(p.fused[m] || (p.paired && m >= 2))) { order[nord++] = m; last_two = m; }
+        if (!(p.fused[m] || p.longm[m] || (p.paired && m >= 2))) { order[nord++] = m; last_two = m; }
     PresumJob prejob[4];
     bool preneed[4] = {false, false, false, false};
     for (int m = 0; m < s.d; ++m) {
@@ -461,6 +464,13 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
                                            p.part[3], p.nsplit[m], it__));
         } else if (p.paired && m == 3) {
             // done together with mode 3
+        } else if (p.longm[m]) {
+            // long fibres (64 < n <= 512): V and P from one LDS tile of complete fibres, V never stored
+            int32_t* zero = zero_given ? nullptr : p.ctr8;
+            zero_given = true;
+            const double cols = (double)outer * (double)inner;
+            ASI_ADD(pg, "", cols * n * esize(s.dt) + 4.0 * n * r + 8.0 * n * r * p.nsplit[m], 4.0 * cols * n * r,
+                    make_subspace_long(s.dt, A, outer, n, inner, U_prev[m], r, p.part[m], p.nsplit[m], zero, 8, it__));
         } else if (p.fused[m]) {
             // short fibres: V and P from one LDS tile of complete fibres, V never stored
             int32_t* zero = zero_given ? nullptr : p.ctr8;       // one early kernel clears the arrival counters
