@@ -88,6 +88,7 @@ struct CompressPlan {
     bool longm[4] = {};              // long fibres: V and P from one LDS tile of complete fibres (asi_long.hip)
     bool paired = false;             // the last two modes of a 4-mode tensor share one kernel
     bool tiny = false;               // ... the vector-ALU kernel for tiny planes
+    bool planes = false;             // ... the kernel for large planes (asi_planes.hip)
     bool fast_orth[4] = {};
     bool wide_orth[4] = {};
     size_t bytes = 0;
@@ -105,10 +106,12 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
     p.V = c.take<float>(vmax);
     p.ctr8 = c.take<int32_t>(8);
     p.tiny = s.d == 4 && subspace_tiny_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
-    p.paired = p.tiny || (s.d == 4 && subspace_pair_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]));
+    p.planes = s.d == 4 && subspace_planes_supported(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
+    p.paired = p.tiny || p.planes || (s.d == 4 && subspace_pair_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]));
     for (int m = 0; m < s.d; ++m) {
         const size_t n = (size_t)s.n[m], r = (size_t)s.r[m];
         if (p.tiny && m >= 2) p.nsplit[m] = subspace_tiny_nwg(s.n[0] * s.n[1]);
+        else if (p.planes && m >= 2) p.nsplit[m] = subspace_planes_nwg(s.n[0] * s.n[1]);
         else if (p.paired && m >= 2) p.nsplit[m] = subspace_pair_nwg(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3]);
         else if (p.longm[m]) p.nsplit[m] = subspace_long_splits(s.outer(m), (int)n, s.inner(m), (int)r);
         else p.nsplit[m] = p.fused[m] ? subspace_small_nwg(s.outer(m), (int)n, s.inner(m))
@@ -454,7 +457,11 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
         if (p.paired && m == 2) {
             // H and W modes: both subspace steps from one read of the activation's planes
             const double tot = (double)s.numel;
-            if (p.tiny)
+            if (p.planes)
+                ASI_ADD(pg, "", tot * esize(s.dt) + 8.0 * (n * r + (double)s.n[3] * s.r[3]) * p.nsplit[m], 4.0 * tot * (r + s.r[3]),
+                        make_subspace_planes(s.dt, A, s.n[0] * s.n[1], n, (int)s.n[3], U_prev[2], r, p.part[2], U_prev[3], s.r[3],
+                                             p.part[3], p.nsplit[m], nullptr, 0, it__));
+            else if (p.tiny)
                 ASI_ADD(pg, "", tot * esize(s.dt) + 8.0 * (n * r + (double)s.n[3] * s.r[3]) * p.nsplit[m], 4.0 * tot * (r + s.r[3]),
                         make_subspace_tiny(s.dt, A, s.n[0] * s.n[1], n, (int)s.n[3], U_prev[2], r, p.part[2], U_prev[3], s.r[3],
                                            p.part[3], p.nsplit[m], it__));

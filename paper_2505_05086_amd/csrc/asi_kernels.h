@@ -20,7 +20,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
     IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO,
-    IT_LONG
+    IT_LONG, IT_PLANES
 };
 
 struct Item {
@@ -205,6 +205,14 @@ int subspace_long_splits(long long outer, int n, long long inner, int r);
 bool make_subspace_long(DType xt, const void* X, long long outer, int n, long long inner, const float* U, int r,
                         double* part, int nsplit, int32_t* zero, int nzero, Item* out);
 
+// The last two modes of large planes (33..64 rows and columns, ranks up to 32, at least 1024 planes; asi_planes.hip):
+// part_rows is (nwg, rows, r_rows), part_cols (nwg, cols, r_cols).
+bool subspace_planes_supported(long long planes, int rows, int cols, int r_rows, int r_cols);
+int subspace_planes_nwg(long long planes);
+bool make_subspace_planes(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows, int r_rows,
+                          double* part_rows, const float* U_cols, int r_cols, double* part_cols, int nwg, int32_t* zero,
+                          int nzero, Item* out);
+
 // Both when rows, cols and both ranks are at most 8: vector-ALU kernel, no MFMA padding.
 bool subspace_tiny_supported(int rows, int cols, int r_rows, int r_cols);
 int subspace_tiny_nwg(long long planes);
@@ -279,6 +287,7 @@ hipError_t launch_expand_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_small_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_long_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_planes_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st, char* label_out);
 hipError_t launch_corr_items(const Item* const* items, int n, hipStream_t st);
 

@@ -181,6 +181,8 @@ EDGE_CONV = [
     ((40, 70, 33, 31), (4, 20, 6, 5), 6, 3, 1, 1, 1, 1),       # 40920 ragged columns for the 70-channel mode: more than 32 column splits, so a tree level
     ((8, 6, 128, 128), (4, 5, 12, 12), 16, 3, 1, 1, 1, 1),       # batch of 8 over 262144 columns of grad_out: the vector-ALU product for very short modes
     ((12, 5, 150, 150), (10, 4, 9, 9), 12, 3, 1, 1, 1, 1),       # the same with 9 to 16 entries, ragged planes
+    ((26, 40, 41, 45), (4, 10, 17, 9), 6, 3, 1, 1, 1, 1),        # 1040 ragged planes of three 16-blocks: the large-plane kernel, last tile partly empty
+    ((17, 61, 50, 63), (3, 8, 12, 16), 5, 3, 1, 1, 1, 1),        # 1037 planes of four 16-blocks, ranks within one block
 ]
 
 
