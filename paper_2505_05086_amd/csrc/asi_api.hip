@@ -71,6 +71,8 @@ bool parse_desc(const asi_tensor_desc* desc, Shape* s, asi_status* why) {
 // ---- compress ---------------------------------------------------------------
 struct CompressPlan {
     float* V = nullptr;
+    unsigned short* Ub = nullptr;    // a factor split into bf16 terms (bf16 tensors, product along the last mode)
+    bool bfv[4] = {};                // V of this mode comes from the bf16 MFMA kernel
     double* part[4] = {};
     double* part2[4] = {};          // first level of the partial-sum tree (nsplit > 32)
     int nsplit2[4] = {};
@@ -104,6 +106,13 @@ CompressPlan plan_compress(const Shape& s, void* ws) {
         if (!p.fused[m] && !p.longm[m]) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
     }
     p.V = c.take<float>(vmax);
+    size_t ubmax = 0;
+    for (int m = 0; m < s.d; ++m) {
+        p.bfv[m] = s.dt == BF16 && !p.fused[m] && !p.longm[m] && m == s.d - 1 &&
+                   gemm_bf16_supported(s.numel / s.n[m], (int)s.n[m], s.r[m]);
+        if (p.bfv[m]) ubmax = std::max(ubmax, split_bf16_elems((int)s.n[m], s.r[m]));
+    }
+    p.Ub = c.take<unsigned short>(ubmax);
     p.ctr8 = c.take<int32_t>(8);
     p.tiny = s.d == 4 && subspace_tiny_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
     p.planes = s.d == 4 && subspace_planes_supported(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
@@ -165,6 +174,8 @@ struct CorePlan {
     bool kron = false;               // the last super mode is (H, W) merged
     int order[4] = {0, 1, 2, 3};
     float* buf[2] = {};
+    unsigned short* Ub = nullptr;    // split factor of a first product along the last mode of a bf16 tensor
+    bool bf_last = false;            // such a product is available (bf16 MFMA kernel)
     size_t bytes = 0;
 };
 
@@ -186,7 +197,10 @@ double core_cost(const CorePlan& p, const int* perm) {
         double in = 1.0;
         for (int q = 0; q < p.d; ++q) in *= (double)cur[q];
         const double out = in / (double)cur[m] * p.r[m];
-        cost += in + out + in * p.r[m] / 64.0;
+        // first product along the last mode of a bf16 tensor: half the bytes per element, and the bf16 MFMA
+        // (two terms) multiplies at eight times the fp32 rate
+        if (k == 0 && p.bf_last && m == p.d - 1) cost += 0.5 * in + out + in * p.r[m] / 512.0;
+        else cost += in + out + in * p.r[m] / 64.0;
         cur[m] = p.r[m];
     }
     return cost;
@@ -197,6 +211,8 @@ void core_shape(const Shape& s, CorePlan* p) {
     p->d = p->kron ? 3 : s.d;
     for (int m = 0; m < p->d; ++m) { p->n[m] = s.n[m]; p->r[m] = s.r[m]; }
     if (p->kron) { p->n[2] = s.n[2] * s.n[3]; p->r[2] = s.r[2] * s.r[3]; }
+    p->bf_last = s.dt == BF16 && !p->kron &&
+                 gemm_bf16_supported(s.numel / s.n[s.d - 1], (int)s.n[s.d - 1], s.r[s.d - 1]);
 }
 
 // order: the order of the products, or null for the cheapest.  The two intermediate buffers are
@@ -223,6 +239,7 @@ CorePlan plan_core(const Shape& s, void* ws, const int* order = nullptr) {
     Carver c(ws);
     p.buf[0] = c.take<float>(need[0]);
     p.buf[1] = c.take<float>(need[1]);
+    p.Ub = c.take<unsigned short>(p.bf_last ? split_bf16_elems((int)s.n[s.d - 1], s.r[s.d - 1]) : 0);
     p.bytes = c.off;
     return p;
 }
@@ -489,7 +506,15 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
             int32_t* zero = zero_given ? nullptr : p.ctr8;
             zero_given = true;
             // V = A_m^T U_prev, kept as a tensor with mode m of size r
-            ASI_TRYS(add_ttm(pg, "V", s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0));
+            if (p.bfv[m]) {
+                const double cols = (double)outer;
+                ASI_ADD(pg, "V", 4.0 * n * r + 2.0 * (double)split_bf16_elems(n, r), 0.0,
+                        make_split_bf16(U_prev[m], r, 1, n, r, p.Ub, it__));
+                ASI_ADD(pg, "V", cols * n * 2.0 + 2.0 * (double)split_bf16_elems(n, r) + 4.0 * cols * r, 2.0 * cols * n * r,
+                        make_gemm_bf16(A, outer, n, p.Ub, r, p.V, nullptr, 0, it__));
+            } else {
+                ASI_TRYS(add_ttm(pg, "V", s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0));
+            }
             // P = A_m V, split over the unfolding's columns
             PresumArgs ride;
             std::memset(&ride, 0, sizeof(ride));
@@ -591,7 +616,15 @@ asi_status build_core(const asi_tensor_desc* desc, const void* A, const float* c
         for (int q = 0; q < m; ++q) outer *= cur[q];
         for (int q = m + 1; q < p.d; ++q) inner *= cur[q];
         float* dst = (k + 1 == p.d) ? S : p.buf[k & 1];
-        if (p.kron && m == 2) {
+        if (k == 0 && p.bf_last && m == p.d - 1) {
+            // the bf16 activation along its last mode: split factor, then the bf16 MFMA product
+            const int n = (int)cur[m], r = p.r[m];
+            const double cols = (double)outer;
+            ASI_ADD(pg, "core", 4.0 * n * r + 2.0 * (double)split_bf16_elems(n, r), 0.0,
+                    make_split_bf16(U[m], r, 1, n, r, p.Ub, it__));
+            ASI_ADD(pg, "core", cols * n * 2.0 + 2.0 * (double)split_bf16_elems(n, r) + 4.0 * cols * r, 2.0 * cols * n * r,
+                    make_gemm_bf16(src, outer, n, p.Ub, r, dst, nullptr, 0, it__));
+        } else if (p.kron && m == 2) {
             // (.., H, W) -> (.., r3, r4):  M(h*W + w, a*r4 + b) = U3[h,a] * U4[w,b]
             ASI_TRYS(add_ttm_kron(pg, "core", sdt, src, outer, (int)s.n[2], (int)s.n[3], U[2], s.r[2], 1, s.r[2], U[3],
                                   s.r[3], 1, s.r[3], dst));

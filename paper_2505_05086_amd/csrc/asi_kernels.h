@@ -20,7 +20,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
     IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO,
-    IT_LONG, IT_PLANES
+    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16
 };
 
 struct Item {
@@ -156,6 +156,15 @@ __device__ __forceinline__ void presum_block(const PresumJob* jobs, int njobs, i
 // if the items do not have these forms.
 bool make_ttm_duo(const Item& a, const Item& z, Item* out);
 
+// ---- product along the last mode of a bf16 tensor on the bf16 MFMA (asi_bf16.hip) -----------------------------
+// Y[c,q] = sum_i X[c,i] M[i,q]: X (ncols, n) bf16, Y (ncols, r) fp32.  The fp32 matrix is first split into two bf16
+// terms laid out in operand order (make_split_bf16 -> Mb of split_bf16_elems(n, r) 16-bit elements).
+bool gemm_bf16_supported(long long ncols, int n, int r);
+size_t split_bf16_elems(int n, int r);
+bool make_split_bf16(const float* M, long long ms_i, long long ms_q, int n, int r, unsigned short* Mb, Item* out);
+bool make_gemm_bf16(const void* X, long long ncols, int n, const unsigned short* Mb, int r, float* Y, int32_t* zero,
+                    int nzero, Item* out);
+
 // ---- pair: part[s][i][q] = sum_{c in split s} X[i,c] * Y[q,c]  over unfolding columns c = (o,j) -----
 // X: (outer, n, inner) dtype xt;  Y: (outer, r, inner) fp32;  part: (nsplit, n, r) fp64
 // (products of fp32 values are exact in fp64 and the sums are carried in fp64).
@@ -288,6 +297,7 @@ hipError_t launch_small_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_long_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_planes_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_bf16_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st, char* label_out);
 hipError_t launch_corr_items(const Item* const* items, int n, hipStream_t st);
 

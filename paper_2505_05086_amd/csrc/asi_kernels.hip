@@ -377,6 +377,7 @@ hipError_t launch_items(const Item* const* items, int n, hipStream_t st, char* l
         case IT_TINY: return launch_tiny_items(items, n, st);
         case IT_LONG: return launch_long_items(items, n, st);
         case IT_PLANES: return launch_planes_items(items, n, st);
+        case IT_SPLIT_BF16: case IT_GEMM_BF16: return launch_bf16_items(items, n, st);
         case IT_PRESUM: case IT_GRAM0: case IT_APPLY: case IT_ORTHW_GRAM: case IT_ORTHW_CHOL: case IT_ORTHW_APPLY:
         case IT_ORTH_BIG: case IT_INIT: return launch_orth_items(items, n, st, label_out);
         case IT_CORR_MFMA: case IT_CORR: return launch_corr_items(items, n, st);

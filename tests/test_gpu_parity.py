@@ -206,7 +206,11 @@ def test_edge_conv_shapes(case, dtype):
 
 EDGE_LINEAR = [((3, 5, 7), (2, 3, 4), 6), ((4, 9, 30), (4, 9, 30), 3), ((2, 33, 130), (1, 7, 20), 70),
                ((64, 1, 5), (3, 1, 2), 1), ((6, 50, 300), (3, 34, 100), 40),     # a rank above 64
-               ((3, 20, 600), (2, 8, 24), 50)]                                   # a last mode of 512 or more
+               ((3, 20, 600), (2, 8, 24), 50),                                   # a last mode of 512 or more
+               # 1024 or more tokens: with bf16 data the last-mode products run on the bf16 MFMA (split factor)
+               ((40, 30, 136), (5, 7, 20), 9),                                   # ragged: 1200 columns, last K chunk of 8, two output blocks
+               ((36, 32, 200), (6, 8, 70), 11),                                  # five output blocks over two waves
+               ((33, 32, 264), (4, 6, 100), 7)]                                  # seven output blocks over four waves
 
 
 @pytest.mark.parametrize("case", EDGE_LINEAR)
