@@ -21,6 +21,9 @@ Readings of ambiguous passages (each is also listed in the design notes):
     from the partially projected core, so the modes are independent.
   * "Orthogonalize" is Gram-Schmidt (App. A.1); the sign/rotation freedom is
     fixed by taking the Q factor of the thin QR with positive diagonal R.
+  * At t = 0 Alg. 1 draws V from a standard normal distribution; the draw is a
+    counter-based generator (Philox4x32-10 + Box-Muller, see gaussian_V) so that
+    both sides of a parity test produce the same V without storing it.
   * The backward formulation is given only as the cost sum C_ASI (Eq. 14); the
     contraction order is read off its five terms.
   * "FLOPs" in the paper are multiply-accumulates.
@@ -122,6 +125,72 @@ def subspace_P(A: np.ndarray, U_prev: np.ndarray, m: int) -> np.ndarray:
     """The un-orthogonalised iterate P = A_m (A_m^T U_prev) of Alg. 1 (for tests)."""
     Am = unfold(A, m)
     return Am @ (Am.T @ np.asarray(U_prev, dtype=F64))
+
+
+# --------------------------------------------------------------------------
+# Alg. 1, branch t = 0: V is drawn i.i.d. standard normal instead of A_m^T U_prev
+# --------------------------------------------------------------------------
+# The draw must be reproducible on both sides of a parity test without storing V (b_m x r_m values), so
+# it is a counter-based generator: Philox4x32-10 (Salmon et al., "Parallel random numbers: as easy as
+# 1, 2, 3", SC 2011) keyed by the 64-bit seed, one call per (unfolding column c, group of four rank
+# columns g, mode m) with counter (c mod 2^32, c div 2^32, g, m).  Its four 32-bit words give two pairs of
+# uniforms u = (top 24 bits + 0.5) / 2^24 and each pair one Box-Muller pair
+#     z0 = sqrt(-2 ln u1) cos(2 pi u2),  z1 = sqrt(-2 ln u1) sin(2 pi u2),
+# so V[c, 4 g + k] = (z0, z1 of words 0-1; z0, z1 of words 2-3)[k].  V is data in float32.
+_PH_M0, _PH_M1 = np.uint64(0xD2511F53), np.uint64(0xCD9E8D57)
+_PH_W0, _PH_W1 = np.uint64(0x9E3779B9), np.uint64(0xBB67AE85)
+_MASK32 = np.uint64(0xFFFFFFFF)
+
+
+def philox4x32_10(counter: Sequence[np.ndarray], key: Tuple[int, int]) -> List[np.ndarray]:
+    """Ten rounds of Philox-4x32: counter = four arrays of 32-bit words, key = two 32-bit words.
+
+    Round: (c0, c1, c2, c3) <- (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1, lo(M0 c0)); the key is
+    advanced by the Weyl constants (W0, W1) between rounds.
+    """
+    c = [np.asarray(x, dtype=np.uint64) & _MASK32 for x in counter]
+    k0, k1 = np.uint64(key[0]) & _MASK32, np.uint64(key[1]) & _MASK32
+    for _round in range(10):
+        p0, p1 = _PH_M0 * c[0], _PH_M1 * c[2]
+        c = [(p1 >> np.uint64(32)) ^ c[1] ^ k0, p1 & _MASK32, (p0 >> np.uint64(32)) ^ c[3] ^ k1, p0 & _MASK32]
+        k0, k1 = (k0 + _PH_W0) & _MASK32, (k1 + _PH_W1) & _MASK32
+    return c
+
+
+def _uniform24(x: np.ndarray) -> np.ndarray:
+    """(top 24 bits + 0.5) / 2^24: strictly inside (0, 1) and exact in float32."""
+    return ((x >> np.uint64(8)).astype(F64) + 0.5) / 16777216.0
+
+
+def gaussian_V(seed: int, m: int, b: int, r: int) -> np.ndarray:
+    """The standard-normal V (b x r) of Alg. 1's t = 0 branch for mode m (0-based), as float32 values."""
+    key = (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
+    ng = (r + 3) // 4
+    c = np.arange(b, dtype=np.uint64)[:, None]
+    g = np.arange(ng, dtype=np.uint64)[None, :]
+    shape = (b, ng)
+    w = philox4x32_10([np.broadcast_to(c & _MASK32, shape), np.broadcast_to(c >> np.uint64(32), shape),
+                       np.broadcast_to(g, shape), np.full(shape, m, dtype=np.uint64)], key)
+    u = [_uniform24(x) for x in w]
+    V = np.empty((b, ng, 4), dtype=F64)
+    for pair in range(2):
+        rad = np.sqrt(-2.0 * np.log(u[2 * pair]))
+        ang = 2.0 * math.pi * u[2 * pair + 1]
+        V[:, :, 2 * pair] = rad * np.cos(ang)
+        V[:, :, 2 * pair + 1] = rad * np.sin(ang)
+    return V.reshape(b, 4 * ng)[:, :r].astype(np.float32).astype(F64)
+
+
+def subspace_step_cold(A: np.ndarray, m: int, r: int, seed: int) -> np.ndarray:
+    """Alg. 1 at t = 0 for mode m: V i.i.d. standard normal (b_m x r), U = Orthogonalize(A_m V)."""
+    Am = unfold(A, m)
+    return orthogonalize(Am @ gaussian_V(seed, m, Am.shape[1], r))
+
+
+def compress_cold(A: np.ndarray, ranks: Sequence[int], seed: int) -> List[np.ndarray]:
+    """Alg. 1, t = 0 branch, for every mode of A.  Returns [U_1..U_d]."""
+    A = np.asarray(A, dtype=F64)
+    return [subspace_step_cold(A, m, int(ranks[m]), seed) for m in range(A.ndim)]
 
 
 def compress(A: np.ndarray, U_prev: Sequence[np.ndarray]) -> List[np.ndarray]:

@@ -476,3 +476,85 @@ def test_projector_is_the_orthogonal_projector():
     for i in range(7):
         for j in range(7):
             assert abs(Pm[i, j] - sum(U[i, k] * U[j, k] for k in range(3))) < 1e-15
+
+
+# ---------------------------------------------------------------- Alg. 1, t = 0: the Gaussian draw
+def test_philox4x32_10_known_answers():
+    """The known-answer vectors distributed with the published generator (tests/golden/philox4x32_10_kat.txt)."""
+    rows = [ln.split() for ln in open(os.path.join(os.path.dirname(GOLDEN), "philox4x32_10_kat.txt")) if ln.strip() and ln[0] != "#"]
+    assert len(rows) == 3
+    kat = [(tuple(int(x, 16) for x in r[0:4]), tuple(int(x, 16) for x in r[4:6]), tuple(int(x, 16) for x in r[6:10]))
+           for r in rows]
+    for ctr, key, want in kat:
+        got = O.philox4x32_10([np.array([c], dtype=np.uint64) for c in ctr], key)
+        assert tuple(int(x[0]) for x in got) == want
+    # vectorised over counters: every lane equals its own scalar call
+    c0 = np.array([0, 0xffffffff, 0x243f6a88, 7], dtype=np.uint64)
+    got = O.philox4x32_10([c0, c0 * 0 + 5, c0 * 0, c0 * 0 + 2], (11, 12))
+    for lane in range(4):
+        one = O.philox4x32_10([c0[lane:lane + 1], np.array([5], dtype=np.uint64), np.array([0], dtype=np.uint64),
+                               np.array([2], dtype=np.uint64)], (11, 12))
+        assert [int(x[lane]) for x in got] == [int(x[0]) for x in one]
+
+
+def test_gaussian_V_is_standard_normal_and_counter_addressed():
+    V = O.gaussian_V(seed=0x0123456789abcdef, m=1, b=200000, r=6)
+    assert V.shape == (200000, 6) and V.dtype == np.float64
+    assert np.array_equal(V, V.astype(np.float32).astype(np.float64))            # float32 data
+    # moments of N(0, 1): mean 0, variance 1, skewness 0, kurtosis 3 (1.2M samples: 5 sigma bounds)
+    x = V.ravel()
+    n = x.size
+    assert abs(x.mean()) < 5 / np.sqrt(n)
+    assert abs(x.var() - 1.0) < 5 * np.sqrt(2.0 / n)
+    assert abs(np.mean(x ** 3)) < 5 * np.sqrt(15.0 / n)
+    assert abs(np.mean(x ** 4) - 3.0) < 5 * np.sqrt(96.0 / n)
+    # tail mass beyond 3 sigma: 0.0027
+    assert abs(np.mean(np.abs(x) > 3.0) - 0.0026998) < 5 * np.sqrt(0.0027 / n)
+    # columns and rows are uncorrelated
+    C = np.corrcoef(V.T)
+    assert np.max(np.abs(C - np.eye(6))) < 5 / np.sqrt(200000)
+    assert abs(np.corrcoef(V[:-1, 0], V[1:, 0])[0, 1]) < 5 / np.sqrt(200000)
+    # counter addressing: an entry depends only on (seed, mode, column, rank column), not on b or r
+    W = O.gaussian_V(seed=0x0123456789abcdef, m=1, b=1000, r=3)
+    assert np.array_equal(W, V[:1000, :3])
+    assert not np.array_equal(O.gaussian_V(0x0123456789abcdef, 2, 1000, 3), W)      # another mode: another stream
+    assert not np.array_equal(O.gaussian_V(0x0123456789abcdee, 1, 1000, 3), W)      # another seed
+    # Box-Muller by hand for one entry: words -> 24-bit uniforms -> (radius, angle)
+    w = O.philox4x32_10([np.array([5], dtype=np.uint64), np.array([0], dtype=np.uint64), np.array([0], dtype=np.uint64),
+                         np.array([1], dtype=np.uint64)], (0x89abcdef, 0x01234567))
+    u1 = ((int(w[0][0]) >> 8) + 0.5) / 2 ** 24
+    u2 = ((int(w[1][0]) >> 8) + 0.5) / 2 ** 24
+    z0 = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    z1 = np.sqrt(-2.0 * np.log(u1)) * np.sin(2.0 * np.pi * u2)
+    assert V[5, 0] == np.float32(z0) and V[5, 1] == np.float32(z1)
+
+
+def test_cold_start_step_finds_the_range_of_an_exactly_low_rank_unfolding():
+    """t = 0 branch of Alg. 1: for an unfolding of exact rank r, range(A_m V) = range(A_m) for any V of
+    full column rank, so one cold step already gives the SVD's subspace; on a planted spectral gap the
+    cold step is at a finite angle and the warm steps that follow converge at the rate gamma^-2."""
+    rng = _rng(61)
+    dims, ranks = (5, 7, 6, 4), (2, 3, 2, 2)
+    A, Ut = _exact_tucker(rng, dims, ranks)
+    U = O.compress_cold(A, ranks, seed=2025)
+    for m in range(4):
+        assert np.max(np.abs(U[m].T @ U[m] - np.eye(ranks[m]))) < 1e-13
+        lead = np.linalg.svd(O.unfold(A, m), full_matrices=False)[0][:, :ranks[m]]
+        assert np.max(np.abs(O.projector(U[m]) - O.projector(lead))) < 1e-10
+    # the definition written out for one mode: U = Q of A_m V with V from the generator
+    Am = O.unfold(A, 1)
+    Q, R = np.linalg.qr(Am @ O.gaussian_V(2025, 1, Am.shape[1], 3))
+    assert np.max(np.abs(U[1] - Q * np.sign(np.diag(R)))) < 1e-12
+    # planted gap: tan(theta) shrinks by at least gamma^-2 per warm step after the cold one
+    n, b, r, gamma = 12, 40, 3, 4.0
+    Qa = _orth(rng, n, n)
+    Qb = _orth(rng, b, n)
+    sv = np.array([3.0, 2.5, 2.0] + [2.0 / gamma] * (n - r))
+    M = (Qa * sv) @ Qb.T
+    U0 = O.subspace_step_cold(M, 0, r, seed=7)
+    errs = []
+    Uk = U0
+    for _ in range(4):
+        errs.append(np.linalg.norm(Qa[:, r:].T @ Uk @ np.linalg.inv(Qa[:, :r].T @ Uk), 2))
+        Uk = O.subspace_step(M, Uk, 0)
+    assert errs[0] > 1e-2 and all(e1 <= e0 * gamma ** -2 * (1 + 1e-9) for e0, e1 in zip(errs, errs[1:]))
