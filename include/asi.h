@@ -91,6 +91,23 @@ asi_status asi_compress(const asi_tensor_desc* desc, const void* A,
                         const float* const* U_prev, float* const* U_out,
                         void* ws, size_t ws_bytes, int32_t* info, asi_stream_t stream);
 
+/* Alg. 1, first iteration (t = 0), for every mode m of A:
+ *     V ~ N(0, 1)^(b_m x ranks[m]);   P = A_m V;   U_out[m] = Orthogonalize(P)
+ * V is not stored: entry V[c, q] of mode m (0-based; c = column of the mode-m unfolding in the row-major
+ * order of the remaining modes) is a pure function of (seed, m, c, q).  With g = q / 4 and k = q % 4,
+ * Philox4x32-10 keyed by (seed mod 2^32, seed div 2^32) on the counter (c mod 2^32, c div 2^32, g, m) gives
+ * words x0..x3; u_i = ((x_i >> 9) + 0.5) / 2^23; V[c, 4g + {0,1}] = sqrt(-2 ln u0) * {cos, sin}(2 pi u1) and
+ * V[c, 4g + {2,3}] the same from (u2, u3), evaluated in fp64 and rounded to fp32.  Arguments, workspace (asi_workspace_bytes
+ * covers it) and error behaviour as asi_compress, without U_prev. */
+asi_status asi_compress_cold(const asi_tensor_desc* desc, const void* A, uint64_t seed,
+                             float* const* U_out, void* ws, size_t ws_bytes, int32_t* info,
+                             asi_stream_t stream);
+
+/* The V that asi_compress_cold multiplies by for one mode, written out for inspection:
+ *   V  out device fp32 (b_mode x ranks[mode]) row-major, b_mode = numel / dims[mode]. */
+asi_status asi_cold_start_matrix(const asi_tensor_desc* desc, int32_t mode, uint64_t seed, float* V,
+                            asi_stream_t stream);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): asi_compress with the library's own scratch memory in
  * place of `ws`.  The scratch is a static device array of ASI_STATIC_SCRATCH_BYTES that every GPU

@@ -134,7 +134,7 @@ def subspace_P(A: np.ndarray, U_prev: np.ndarray, m: int) -> np.ndarray:
 # it is a counter-based generator: Philox4x32-10 (Salmon et al., "Parallel random numbers: as easy as
 # 1, 2, 3", SC 2011) keyed by the 64-bit seed, one call per (unfolding column c, group of four rank
 # columns g, mode m) with counter (c mod 2^32, c div 2^32, g, m).  Its four 32-bit words give two pairs of
-# uniforms u = (top 24 bits + 0.5) / 2^24 and each pair one Box-Muller pair
+# uniforms u = (top 23 bits + 0.5) / 2^23 and each pair one Box-Muller pair
 #     z0 = sqrt(-2 ln u1) cos(2 pi u2),  z1 = sqrt(-2 ln u1) sin(2 pi u2),
 # so V[c, 4 g + k] = (z0, z1 of words 0-1; z0, z1 of words 2-3)[k].  V is data in float32.
 _PH_M0, _PH_M1 = np.uint64(0xD2511F53), np.uint64(0xCD9E8D57)
@@ -157,9 +157,9 @@ def philox4x32_10(counter: Sequence[np.ndarray], key: Tuple[int, int]) -> List[n
     return c
 
 
-def _uniform24(x: np.ndarray) -> np.ndarray:
-    """(top 24 bits + 0.5) / 2^24: strictly inside (0, 1) and exact in float32."""
-    return ((x >> np.uint64(8)).astype(F64) + 0.5) / 16777216.0
+def _uniform23(x: np.ndarray) -> np.ndarray:
+    """(top 23 bits + 0.5) / 2^23: strictly inside (0, 1) and exact in float32 (24 significant bits)."""
+    return ((x >> np.uint64(9)).astype(F64) + 0.5) / 8388608.0
 
 
 def gaussian_V(seed: int, m: int, b: int, r: int) -> np.ndarray:
@@ -171,7 +171,7 @@ def gaussian_V(seed: int, m: int, b: int, r: int) -> np.ndarray:
     shape = (b, ng)
     w = philox4x32_10([np.broadcast_to(c & _MASK32, shape), np.broadcast_to(c >> np.uint64(32), shape),
                        np.broadcast_to(g, shape), np.full(shape, m, dtype=np.uint64)], key)
-    u = [_uniform24(x) for x in w]
+    u = [_uniform23(x) for x in w]
     V = np.empty((b, ng, 4), dtype=F64)
     for pair in range(2):
         rad = np.sqrt(-2.0 * np.log(u[2 * pair]))

@@ -13,7 +13,9 @@ from .binding import (  # noqa: F401
     TensorDesc,
     alloc_workspace,
     asi_compress,
+    asi_cold_start_matrix,
     asi_compress_batch,
+    asi_compress_cold,
     asi_compress_static,
     asi_core_project,
     asi_core_project_batch,

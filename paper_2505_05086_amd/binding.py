@@ -22,7 +22,7 @@ ASI_F32, ASI_BF16 = 0, 1
 
 STATIC_SCRATCH_BYTES = 16 << 20      # ASI_STATIC_SCRATCH_BYTES of include/asi.h
 
-EXPORTS = ["asi_workspace_bytes", "asi_compress", "asi_compress_static", "asi_core_project", "asi_weight_grad_conv2d",
+EXPORTS = ["asi_workspace_bytes", "asi_compress", "asi_compress_cold", "asi_cold_start_matrix", "asi_compress_static", "asi_core_project", "asi_weight_grad_conv2d",
            "asi_weight_grad_linear", "asi_compress_batch", "asi_core_project_batch",
            "asi_weight_grad_conv2d_batch", "asi_weight_grad_linear_batch", "asi_status_string", "asi_version",
            "asi_profile_enable", "asi_profile_report"]
@@ -62,6 +62,11 @@ def lib() -> C.CDLL:
         L.asi_compress.restype = C.c_int
         L.asi_compress.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, pp, C.c_void_p, C.c_size_t,
                                    C.c_void_p, C.c_void_p]
+        L.asi_compress_cold.restype = C.c_int
+        L.asi_compress_cold.argtypes = [C.POINTER(TensorDesc), C.c_void_p, C.c_uint64, pp, C.c_void_p, C.c_size_t,
+                                        C.c_void_p, C.c_void_p]
+        L.asi_cold_start_matrix.restype = C.c_int
+        L.asi_cold_start_matrix.argtypes = [C.POINTER(TensorDesc), C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p]
         L.asi_compress_static.restype = C.c_int
         L.asi_compress_static.argtypes = [C.POINTER(TensorDesc), C.c_void_p, pp, pp, C.c_void_p, C.c_void_p]
         L.asi_core_project.restype = C.c_int
@@ -160,6 +165,21 @@ def asi_compress(desc: TensorDesc, A: torch.Tensor, U_prev: Sequence[torch.Tenso
     _check_dev(A, ws, info, *U_prev, *U_out)
     _check(lib().asi_compress(C.byref(desc), _ptr(A), _ptr_array(U_prev), _ptr_array(U_out), _ptr(ws),
                               ws.numel(), _ptr(info), _stream()), "asi_compress")
+
+
+def asi_compress_cold(desc: TensorDesc, A: torch.Tensor, seed: int, U_out: Sequence[torch.Tensor], ws: torch.Tensor,
+                      info: Optional[torch.Tensor] = None) -> None:
+    """Alg. 1's first iteration: V drawn from the counter-based generator keyed by `seed`."""
+    _check_dev(A, ws, info, *U_out)
+    _check(lib().asi_compress_cold(C.byref(desc), _ptr(A), int(seed) & (2 ** 64 - 1), _ptr_array(U_out), _ptr(ws),
+                                   ws.numel(), _ptr(info), _stream()), "asi_compress_cold")
+
+
+def asi_cold_start_matrix(desc: TensorDesc, mode: int, seed: int, V: torch.Tensor) -> None:
+    """The generated V of one mode written to V (numel / dims[mode], ranks[mode]) fp32."""
+    _check_dev(V)
+    _check(lib().asi_cold_start_matrix(C.byref(desc), int(mode), int(seed) & (2 ** 64 - 1), _ptr(V), _stream()),
+           "asi_cold_start_matrix")
 
 
 def asi_compress_static(desc: TensorDesc, A: torch.Tensor, U_prev: Sequence[torch.Tensor],

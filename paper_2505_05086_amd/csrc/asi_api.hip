@@ -96,27 +96,29 @@ struct CompressPlan {
     size_t bytes = 0;
 };
 
-CompressPlan plan_compress(const Shape& s, void* ws) {
+// cold: the first iteration of Alg. 1 (t = 0).  V is generated inside the P kernel of every mode, so no
+// mode takes a fused V/P kernel and no V is stored.
+CompressPlan plan_compress(const Shape& s, void* ws, bool cold = false) {
     CompressPlan p;
     Carver c(ws);
     size_t vmax = 0;
     for (int m = 0; m < s.d; ++m) {
-        p.fused[m] = subspace_small_supported((int)s.n[m], s.r[m]);
-        p.longm[m] = !p.fused[m] && subspace_long_supported(s.outer(m), (int)s.n[m], s.inner(m), s.r[m]);
-        if (!p.fused[m] && !p.longm[m]) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
+        p.fused[m] = !cold && subspace_small_supported((int)s.n[m], s.r[m]);
+        p.longm[m] = !cold && !p.fused[m] && subspace_long_supported(s.outer(m), (int)s.n[m], s.inner(m), s.r[m]);
+        if (!cold && !p.fused[m] && !p.longm[m]) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
     }
     p.V = c.take<float>(vmax);
     size_t ubmax = 0;
     for (int m = 0; m < s.d; ++m) {
-        p.bfv[m] = s.dt == BF16 && !p.fused[m] && !p.longm[m] && m == s.d - 1 &&
+        p.bfv[m] = !cold && s.dt == BF16 && !p.fused[m] && !p.longm[m] && m == s.d - 1 &&
                    gemm_bf16_supported(s.numel / s.n[m], (int)s.n[m], s.r[m]);
         if (p.bfv[m]) ubmax = std::max(ubmax, split_bf16_elems((int)s.n[m], s.r[m]));
     }
     p.Ub = c.take<unsigned short>(ubmax);
     p.ctr8 = c.take<int32_t>(8);
-    p.tiny = s.d == 4 && subspace_tiny_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
-    p.planes = s.d == 4 && subspace_planes_supported(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
-    p.paired = p.tiny || p.planes || (s.d == 4 && subspace_pair_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]));
+    p.tiny = !cold && s.d == 4 && subspace_tiny_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
+    p.planes = !cold && s.d == 4 && subspace_planes_supported(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
+    p.paired = p.tiny || p.planes || (!cold && s.d == 4 && subspace_pair_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]));
     for (int m = 0; m < s.d; ++m) {
         const size_t n = (size_t)s.n[m], r = (size_t)s.r[m];
         if (p.tiny && m >= 2) p.nsplit[m] = subspace_tiny_nwg(s.n[0] * s.n[1]);
@@ -379,6 +381,15 @@ asi_status add_pair(Program& pg, const char* role, DType xt, const void* X, long
             make_pair(xt, X, outer, n, inner, Y, r, part, nsplit, zero, nzero, ride, it__));
     return ASI_OK;
 }
+// P = A_m V with the generated V of Alg. 1's first iteration: nothing of V is read
+asi_status add_pair_gauss(Program& pg, const char* role, DType xt, const void* X, long long outer, int n, long long inner,
+                          unsigned long long seed, int mode, int r, double* part, int nsplit, int32_t* zero, int nzero,
+                          const PresumArgs* ride, double ride_bytes) {
+    const double cols = (double)outer * (double)inner;
+    ASI_ADD(pg, role, cols * n * esize(xt) + 8.0 * n * r * nsplit + ride_bytes, 2.0 * cols * n * r,
+            make_pair_gauss(xt, X, outer, n, inner, seed, mode, r, part, nsplit, zero, nzero, ride, it__));
+    return ASI_OK;
+}
 #define ASI_TRYS(expr)                                 \
     do {                                               \
         asi_status s__ = (expr);                       \
@@ -426,15 +437,17 @@ asi_status flush(std::vector<Program>& progs, hipStream_t st, const char* phase)
 }
 
 // ---- builders: validate one layer's arguments and append its launches -----------------------------
+// seed: null for the warm-start branch (U_prev given); else the first iteration, V drawn from *seed
 asi_status build_compress(const asi_tensor_desc* desc, const void* A, const float* const* U_prev, float* const* U_out,
-                          void* ws, size_t ws_bytes, int32_t* info, Program& pg) {
+                          void* ws, size_t ws_bytes, int32_t* info, const unsigned long long* seed, Program& pg) {
     Shape s;
     asi_status why;
     if (!parse_desc(desc, &s, &why)) return why;
-    if (!A || !U_prev || !U_out) return ASI_ERR_INVALID_ARG;
+    const bool cold = seed != nullptr;
+    if (!A || (!cold && !U_prev) || !U_out) return ASI_ERR_INVALID_ARG;
     for (int m = 0; m < s.d; ++m)
-        if (!U_prev[m] || !U_out[m]) return ASI_ERR_INVALID_ARG;
-    CompressPlan p = plan_compress(s, ws);
+        if ((!cold && !U_prev[m]) || !U_out[m]) return ASI_ERR_INVALID_ARG;
+    CompressPlan p = plan_compress(s, ws, cold);
     if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
 
     OrthArgs fast, wide, slow;
@@ -505,8 +518,9 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
         } else {
             int32_t* zero = zero_given ? nullptr : p.ctr8;
             zero_given = true;
-            // V = A_m^T U_prev, kept as a tensor with mode m of size r
-            if (p.bfv[m]) {
+            // V = A_m^T U_prev, kept as a tensor with mode m of size r (first iteration: generated, not kept)
+            if (cold) {
+            } else if (p.bfv[m]) {
                 const double cols = (double)outer;
                 ASI_ADD(pg, "V", 4.0 * n * r + 2.0 * (double)split_bf16_elems(n, r), 0.0,
                         make_split_bf16(U_prev[m], r, 1, n, r, p.Ub, it__));
@@ -527,8 +541,12 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
                     ride_b += 8.0 * s.n[m2] * s.r[m2] * (p.nsplit[m2] + p.nsplit2[m2]);
                     preneed[m2] = false;
                 }
-            ASI_TRYS(add_pair(pg, "P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], zero, 8,
-                              ride.njobs ? &ride : nullptr, ride_b));
+            if (cold)
+                ASI_TRYS(add_pair_gauss(pg, "P", s.dt, A, outer, n, inner, *seed, m, r, p.part[m], p.nsplit[m], zero, 8,
+                                        ride.njobs ? &ride : nullptr, ride_b));
+            else
+                ASI_TRYS(add_pair(pg, "P", s.dt, A, outer, n, inner, p.V, r, p.part[m], p.nsplit[m], zero, 8,
+                                  ride.njobs ? &ride : nullptr, ride_b));
         }
     }
     for (int m = 0; m < s.d; ++m)
@@ -803,6 +821,7 @@ size_t asi_workspace_bytes(const asi_tensor_desc* desc, const asi_conv2d_desc* c
     asi_status why;
     if (!parse_desc(desc, &s, &why)) return 0;
     size_t need = std::max(plan_compress(s, nullptr).bytes, plan_core(s, nullptr).bytes);
+    need = std::max(need, plan_compress(s, nullptr, true).bytes);
     if (conv) {
         ConvGeom cg;
         if (!parse_conv(s, conv, &cg)) return 0;
@@ -822,8 +841,28 @@ asi_status asi_compress_batch(int32_t count, const asi_tensor_desc* descs, const
     if (!descs || !A || !U_prev || !U_out || !ws || !ws_bytes) return ASI_ERR_INVALID_ARG;
     std::vector<Program> progs(count);
     for (int l = 0; l < count; ++l)
-        ASI_TRYS(build_compress(&descs[l], A[l], U_prev[l], U_out[l], ws[l], ws_bytes[l], info ? info[l] : nullptr, progs[l]));
+        ASI_TRYS(build_compress(&descs[l], A[l], U_prev[l], U_out[l], ws[l], ws_bytes[l], info ? info[l] : nullptr, nullptr,
+                                progs[l]));
     return flush(progs, static_cast<hipStream_t>(stream), "compress");
+}
+
+asi_status asi_compress_cold(const asi_tensor_desc* desc, const void* A, uint64_t seed, float* const* U_out, void* ws,
+                             size_t ws_bytes, int32_t* info, asi_stream_t stream) {
+    std::vector<Program> progs(1);
+    const unsigned long long sd = seed;
+    ASI_TRYS(build_compress(desc, A, nullptr, U_out, ws, ws_bytes, info, &sd, progs[0]));
+    return flush(progs, static_cast<hipStream_t>(stream), "cold");
+}
+
+asi_status asi_cold_start_matrix(const asi_tensor_desc* desc, int32_t mode, uint64_t seed, float* V, asi_stream_t stream) {
+    Shape s;
+    asi_status why;
+    if (!parse_desc(desc, &s, &why)) return why;
+    if (mode < 0 || mode >= s.d || !V) return ASI_ERR_INVALID_ARG;
+    std::vector<Program> progs(1);
+    const double cnt = (double)(s.numel / s.n[mode]) * s.r[mode];
+    ASI_ADD(progs[0], "", 4.0 * cnt, 0.0, make_gauss_fill(seed, mode, s.numel / s.n[mode], s.r[mode], V, it__));
+    return flush(progs, static_cast<hipStream_t>(stream), "cold");
 }
 
 asi_status asi_core_project_batch(int32_t count, const asi_tensor_desc* descs, const void* const* A,

@@ -37,4 +37,40 @@ struct ModeView {
     long long inner;
 };
 
+// ---------------------------------------------------------------------------
+// The standard-normal matrix V of Alg. 1's first iteration (t = 0), never stored: entry V[c, 4g + k] of
+// mode m is a pure function of (seed, m, c, g).  Philox4x32-10 (Salmon et al., SC 2011) keyed by the seed
+// is called on the counter (c mod 2^32, c div 2^32, g, m); each of its four words gives a uniform
+// u = (top 23 bits + 0.5) / 2^23, strictly inside (0, 1), and each pair of uniforms one Box-Muller pair
+// sqrt(-2 ln u1) * (cos 2 pi u2, sin 2 pi u2), evaluated in fp64 and rounded once to fp32: any correct
+// fp64 evaluation of the same formula then gives the same fp32 value (up to the rare tie within an fp64
+// rounding error), so V does not depend on a library's fp32 log / sin / cos.  The draw happens once per
+// training run, so its cost is of no account.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                              uint32_t out[4]) {
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0, hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+        k0 += W0; k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+__device__ __forceinline__ double uniform23(uint32_t x) { return ((double)(x >> 9) + 0.5) * 0x1p-23; }
+__device__ __forceinline__ void gauss4(uint32_t seed_lo, uint32_t seed_hi, int mode, long long c, uint32_t g, float z[4]) {
+    uint32_t w[4];
+    philox4x32_10((uint32_t)((unsigned long long)c & 0xffffffffu), (uint32_t)((unsigned long long)c >> 32), g, (uint32_t)mode,
+                  seed_lo, seed_hi, w);
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+        const double rad = sqrt(-2.0 * log(uniform23(w[2 * pr])));
+        double sn, cs;
+        sincospi(2.0 * uniform23(w[2 * pr + 1]), &sn, &cs);
+        z[2 * pr] = (float)(rad * cs);
+        z[2 * pr + 1] = (float)(rad * sn);
+    }
+}
+
 }  // namespace asi

@@ -20,7 +20,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
     IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO,
-    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16
+    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS
 };
 
 struct Item {
@@ -171,9 +171,11 @@ bool make_gemm_bf16(const void* X, long long ncols, int n, const unsigned short*
 struct PairJob {
     const void* X;
     long long outer, inner, cols_per_split;
-    const float* Y;
+    const float* Y;        // null in the generating variant: Y[., q, .] is the standard-normal V of Alg. 1's t = 0
     double* part;
     int n, r;
+    uint32_t seed_lo, seed_hi;   // generating variant: key of the counter-based generator, and the mode (0-based)
+    int mode;
     int gx, gy, gz;        // row tiles x output tiles x splits
     int32_t* zero;         // nullable: `nzero` int32 the kernel clears
     int nzero;
@@ -185,6 +187,11 @@ struct PairJob {
 int pair_splits(long long outer, int n, long long inner, int r);
 bool make_pair(DType xt, const void* X, long long outer, int n, long long inner, const float* Y, int r, double* part,
                int nsplit, int32_t* zero, int nzero, const PresumArgs* pre, Item* out);
+// the same with Y = the generated standard-normal V of mode `mode` (Alg. 1, t = 0)
+bool make_pair_gauss(DType xt, const void* X, long long outer, int n, long long inner, unsigned long long seed, int mode,
+                     int r, double* part, int nsplit, int32_t* zero, int nzero, const PresumArgs* pre, Item* out);
+// V itself, (ncols, r) row-major fp32, for inspection: the entries the generating variant multiplies by
+bool make_gauss_fill(unsigned long long seed, int mode, long long ncols, int r, float* V, Item* out);
 int presum_blocks(const PresumArgs& a);      // workgroups of the tree's first level, -1 if a is malformed
 
 // ---- out[e] = (beta ? out[e] : 0) + sum_s part[s*count + e] ---------------------------------------------

@@ -65,6 +65,13 @@ class LayerRunner:
         self.cur = 1 - self.cur
         return out
 
+    def compress_cold(self, A: torch.Tensor, seed: int) -> List[torch.Tensor]:
+        """U <- the first iteration of Alg. 1: the subspace step from a generated standard-normal V."""
+        out = self.U[1 - self.cur]
+        B.asi_compress_cold(self.desc, A, seed, out, self.ws, self.info)
+        self.cur = 1 - self.cur
+        return out
+
     def core(self, A: torch.Tensor, U: Optional[Sequence[torch.Tensor]] = None) -> torch.Tensor:
         B.asi_core_project(self.desc, A, U if U is not None else self.U[self.cur], self.S, self.ws)
         return self.S

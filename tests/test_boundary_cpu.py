@@ -78,6 +78,23 @@ def test_compress_rejects_bad_arguments_without_launching():
     assert call(asi.make_desc((8, 1, 1, 1), (2, 1, 1, 1)), FAKE, _arr(), _arr(), FAKE, 1 << 20) == 1
 
 
+def test_cold_start_rejects_bad_arguments_without_launching():
+    L = asi.lib()
+    good = asi.make_desc((8, 6, 5, 4), (2, 3, 2, 2))
+    need = asi.asi_workspace_bytes(good)
+    call = lambda d, A, uo, ws, n: L.asi_compress_cold(C.byref(d), A, C.c_uint64(7), uo, ws, n, None, None)
+    assert call(asi.make_desc((8, 6, 5, 4), (2, 3, 2, 5)), FAKE, _arr(), FAKE, need) == 1
+    assert call(asi.make_desc((8, 6, 5, 4), (2, 3, 2, 2), 7), FAKE, _arr(), FAKE, need) == 2
+    assert call(good, None, _arr(), FAKE, need) == 1
+    assert call(good, FAKE, _arr(3), FAKE, need) == 1
+    assert call(good, FAKE, None, FAKE, need) == 1
+    assert call(good, FAKE, _arr(), FAKE, 255) == 3
+    assert call(good, FAKE, _arr(), None, need) == 3
+    assert L.asi_cold_start_matrix(C.byref(good), 4, C.c_uint64(7), FAKE, None) == 1
+    assert L.asi_cold_start_matrix(C.byref(good), -1, C.c_uint64(7), FAKE, None) == 1
+    assert L.asi_cold_start_matrix(C.byref(good), 0, C.c_uint64(7), None, None) == 1
+
+
 def test_compress_static_rejects_before_touching_the_device():
     """The entry point that allocates nothing checks descriptor and size limit on the host first."""
     L = asi.lib()

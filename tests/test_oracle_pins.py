@@ -519,11 +519,11 @@ def test_gaussian_V_is_standard_normal_and_counter_addressed():
     assert np.array_equal(W, V[:1000, :3])
     assert not np.array_equal(O.gaussian_V(0x0123456789abcdef, 2, 1000, 3), W)      # another mode: another stream
     assert not np.array_equal(O.gaussian_V(0x0123456789abcdee, 1, 1000, 3), W)      # another seed
-    # Box-Muller by hand for one entry: words -> 24-bit uniforms -> (radius, angle)
+    # Box-Muller by hand for one entry: words -> 23-bit uniforms -> (radius, angle)
     w = O.philox4x32_10([np.array([5], dtype=np.uint64), np.array([0], dtype=np.uint64), np.array([0], dtype=np.uint64),
                          np.array([1], dtype=np.uint64)], (0x89abcdef, 0x01234567))
-    u1 = ((int(w[0][0]) >> 8) + 0.5) / 2 ** 24
-    u2 = ((int(w[1][0]) >> 8) + 0.5) / 2 ** 24
+    u1 = ((int(w[0][0]) >> 9) + 0.5) / 2 ** 23
+    u2 = ((int(w[1][0]) >> 9) + 0.5) / 2 ** 23
     z0 = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
     z1 = np.sqrt(-2.0 * np.log(u1)) * np.sin(2.0 * np.pi * u2)
     assert V[5, 0] == np.float32(z0) and V[5, 1] == np.float32(z1)
