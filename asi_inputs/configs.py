@@ -1,4 +1,4 @@
-"""The five benchmark workloads as tables of layers.
+"""The benchmark workloads as tables of layers (1-5: the headline set; 6: the language-model shape).
 
 Shapes follow the paper's fine-tuning workloads (ResNet-18 / MobileNetV2 tails
 of its ImageNet table, segmentation-sized maps, transformer linear layers);
@@ -90,6 +90,14 @@ CONFIGS: Dict[int, Config] = {
     5: Config(5, "vit-b-linear-bf16", (
         Layer("fc1", (64, 197, 768), (32, 64, 96), "bf16", "linear", 3072, alpha=1.2),
         Layer("fc2", (64, 197, 3072), (32, 64, 192), "bf16", "linear", 768, alpha=1.2)), steps=1),
+    # The paper's language-model experiment in shape (its TinyLlama table: batch 8, up to 512 tokens, rank 20
+    # on every mode, the batch mode capped by its size): the linear layers of one decoder block of a
+    # 2048-wide model with a 5632-wide feed-forward, tiny ranks against a huge unfolding.
+    6: Config(6, "llm-block-linear-bf16", (
+        Layer("attn.q", (8, 512, 2048), (8, 20, 20), "bf16", "linear", 2048, alpha=1.2),
+        Layer("attn.o", (8, 512, 2048), (8, 20, 20), "bf16", "linear", 2048, alpha=1.2),
+        Layer("mlp.up", (8, 512, 2048), (8, 20, 20), "bf16", "linear", 5632, alpha=1.2),
+        Layer("mlp.down", (8, 512, 5632), (8, 20, 20), "bf16", "linear", 2048, alpha=1.2)), steps=1),
 }
 
 

@@ -8,7 +8,7 @@ already resident in HBM.  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--no-cpu-baseline]
 
 Without --config the headline (`value`, `ms_per_step`, `roofline`, `cpu_baseline`) is the largest
-fp32 workload, config 4, and `per_config` carries the same figures for all five workloads.
+fp32 workload, config 4, and `per_config` carries the same figures for every workload (1-5: the headline set, 6: the language-model shape).
 With --config N only that workload is measured.
 """
 from __future__ import annotations
@@ -130,7 +130,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=0,
-                    help="measure only this workload (1-5); default: headline = config 4 plus per_config for all five")
+                    help="measure only this workload (1-6); default: headline = config 4 plus per_config for every workload")
     ap.add_argument("--distinct", type=int, default=8, help="distinct input steps kept in HBM and cycled")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams the layers are spread over (0 = one per layer)")
     ap.add_argument("--batch", type=int, default=0,

@@ -147,7 +147,7 @@ def test_config4_highres_20_steps():
 
 
 # ------------------------------------------------------------------ configs 3 and 5: one step, all layers
-@pytest.mark.parametrize("ci", [3, 5])
+@pytest.mark.parametrize("ci", [3, 5, 6])
 def test_single_step_configs(ci):
     cfg = CONFIGS[ci]
     for li, lay in enumerate(cfg.layers):
