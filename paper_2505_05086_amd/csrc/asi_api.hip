@@ -87,6 +87,7 @@ struct CompressPlan {
     int nsplit[4] = {};
     int nblk[4] = {};
     bool fused[4] = {};
+    bool gramm[4] = {};              // short mode, long inner extent: P = (A_m A_m^T) U_prev (asi_gram.hip)
     bool longm[4] = {};              // long fibres: V and P from one LDS tile of complete fibres (asi_long.hip)
     bool paired = false;             // the last two modes of a 4-mode tensor share one kernel
     bool tiny = false;               // ... the vector-ALU kernel for tiny planes
@@ -104,6 +105,7 @@ CompressPlan plan_compress(const Shape& s, void* ws, bool cold = false) {
     size_t vmax = 0;
     for (int m = 0; m < s.d; ++m) {
         p.fused[m] = !cold && subspace_small_supported((int)s.n[m], s.r[m]);
+        p.gramm[m] = p.fused[m] && subspace_gram_supported(s.outer(m), (int)s.n[m], s.inner(m), s.r[m]);
         p.longm[m] = !cold && !p.fused[m] && subspace_long_supported(s.outer(m), (int)s.n[m], s.inner(m), s.r[m]);
         if (!cold && !p.fused[m] && !p.longm[m]) vmax = std::max(vmax, (size_t)(s.numel / s.n[m]) * s.r[m]);
     }
@@ -124,6 +126,7 @@ CompressPlan plan_compress(const Shape& s, void* ws, bool cold = false) {
         if (p.tiny && m >= 2) p.nsplit[m] = subspace_tiny_nwg(s.n[0] * s.n[1]);
         else if (p.planes && m >= 2) p.nsplit[m] = subspace_planes_nwg(s.n[0] * s.n[1]);
         else if (p.paired && m >= 2) p.nsplit[m] = subspace_pair_nwg(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3]);
+        else if (p.gramm[m]) p.nsplit[m] = subspace_gram_nwg(s.outer(m), (int)n, s.inner(m));
         else if (p.longm[m]) p.nsplit[m] = subspace_long_splits(s.outer(m), (int)n, s.inner(m), (int)r);
         else p.nsplit[m] = p.fused[m] ? subspace_small_nwg(s.outer(m), (int)n, s.inner(m))
                                       : pair_splits(s.outer(m), (int)n, s.inner(m), (int)r);
@@ -508,6 +511,14 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
             const double cols = (double)outer * (double)inner;
             ASI_ADD(pg, "", cols * n * esize(s.dt) + 4.0 * n * r + 8.0 * n * r * p.nsplit[m], 4.0 * cols * n * r,
                     make_subspace_long(s.dt, A, outer, n, inner, U_prev[m], r, p.part[m], p.nsplit[m], zero, 8, it__));
+        } else if (p.gramm[m]) {
+            // short mode, long inner extent: the Gram matrix of the unfolding in one pass, then G U_prev
+            int32_t* zero = zero_given ? nullptr : p.ctr8;
+            zero_given = true;
+            const double cols = (double)outer * (double)inner;
+            // flops by the step's definition (two products of 2 cols n r), not the Gram matrix's own count
+            ASI_ADD(pg, "", cols * n * esize(s.dt) + 4.0 * n * r + 8.0 * n * r * p.nsplit[m], 4.0 * cols * n * r,
+                    make_subspace_gram(s.dt, A, outer, n, inner, U_prev[m], r, p.part[m], p.nsplit[m], zero, 8, it__));
         } else if (p.fused[m]) {
             // short fibres: V and P from one LDS tile of complete fibres, V never stored
             int32_t* zero = zero_given ? nullptr : p.ctr8;       // one early kernel clears the arrival counters

@@ -20,7 +20,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
     IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO,
-    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS
+    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE
 };
 
 struct Item {
@@ -203,6 +203,14 @@ struct SumJob {
 };
 bool make_sum_partials(const float* part, int nsplit, long long count, float* out, int beta, Item* it);
 bool make_sum_partials_f64(const double* part, int nsplit, long long count, float* out, int beta, Item* it);
+
+// ---- short mode with a long inner extent through its Gram matrix (asi_gram.hip): part is (nwg, n, r) fp64 ----
+// P = (A_m A_m^T) U_prev: one pass accumulates the n x n Gram matrix in fp64, V is never formed
+bool subspace_gram_supported(long long outer, int n, long long inner, int r);
+int subspace_gram_nwg(long long outer, int n, long long inner);
+bool make_subspace_gram(DType xt, const void* X, long long outer, int n, long long inner, const float* U, int r, double* part,
+                        int nwg, int32_t* zero, int nzero, Item* out);
+hipError_t launch_gram_items(const Item* const* items, int n, hipStream_t st);
 
 // ---- fused V/P step for modes with n <= 64 (asi_subspace.hip): part is (nwg, n, r) fp64 ---------------
 bool subspace_small_supported(int n, int r);

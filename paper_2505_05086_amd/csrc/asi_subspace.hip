@@ -87,66 +87,83 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
 
     const int n0 = jb.v[0].n;
     const int rowI = SS_TC + SS_PAD;
+    // Tiles of a long inner extent (!WHOLE_O): a short mode leaves most of the 64 LDS rows empty, so a tile
+    // takes To groups of 128 columns and stacks them: LDS row g * n + i holds mode index i of columns
+    // 128 g .. 128 g + 127.  The loads of a tile are issued (clamped, not branched, so that all stay in
+    // flight) while the previous tile is multiplied and stored to LDS when that is done.
+    T pre[WHOLE_O ? 1 : 32];
+    const float inv_n0 = 1.0f / (float)n0;
+    auto tile_origin = [&](long long tile, const T** src, int* vc) {
+        const int tcols = SS_TC * jb.To;
+        const long long o = tile / jb.tiles_per_o;
+        const long long j0 = (tile - o * jb.tiles_per_o) * tcols;
+        *vc = (int)((jb.inner - j0 < tcols) ? jb.inner - j0 : tcols);
+        *src = X + o * n0 * jb.inner + j0;
+    };
+    auto issue = [&](long long tile) {
+        const T* src;
+        int vc;
+        tile_origin(tile, &src, &vc);
+        const int c = tid & (SS_TC - 1);
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+            const int row = (tid >> 7) + 2 * u;
+            if constexpr (!STACK) {      // one group: LDS row = mode index
+                pre[u] = src[(c < vc && row < n0) ? (long long)row * jb.inner + c : 0];
+            } else {
+                const int g = (int)(((float)row + 0.5f) * inv_n0), i = row - g * n0, col = g * SS_TC + c;
+                pre[u] = src[(g < jb.To && col < vc) ? (long long)i * jb.inner + col : 0];
+            }
+        }
+    };
+    auto commit = [&](long long tile) -> int {
+        const T* src;
+        int vc;
+        tile_origin(tile, &src, &vc);
+        const int c = tid & (SS_TC - 1);
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+            const int row = (tid >> 7) + 2 * u;
+            if constexpr (!STACK) {
+                if (row < n0) smem[row * rowI + c] = (c < vc) ? to_f32(pre[u]) : 0.f;
+            } else {
+                const int g = (int)(((float)row + 0.5f) * inv_n0), col = g * SS_TC + c;
+                if (g < jb.To) smem[row * rowI + c] = (col < vc) ? to_f32(pre[u]) : 0.f;
+            }
+        }
+        return vc;
+    };
+    if constexpr (!WHOLE_O) {
+        if (lb < jb.ntiles) issue(lb);
+    }
     for (long long tile = lb; tile < jb.ntiles; tile += jb.nwg) {
         __syncthreads();   // everyone is done with the previous tile (and Us is written)
         int no_or_vc;
-        // the whole tile is requested before any of it is stored: one memory latency per tile
-        if (WHOLE_O) {
+        if constexpr (WHOLE_O) {
+            // the whole tile is requested before any of it is stored: one memory latency per tile
             const long long o0 = tile * jb.To;
             const int no = (int)((jb.outer - o0 < jb.To) ? jb.outer - o0 : jb.To);
             const int count = no * (int)jb.o_elems;
             const T* src = X + o0 * jb.o_elems;
-            T pre[SS_PRE];
+            T prw[SS_PRE];
 #pragma unroll
             for (int u = 0; u < SS_PRE; ++u) {
                 const int e = u * 256 + tid;
-                pre[u] = src[e < count ? e : 0];          // clamped, not branched: all loads stay in flight
+                prw[u] = src[e < count ? e : 0];          // clamped, not branched: all loads stay in flight
             }
 #pragma unroll
             for (int u = 0; u < SS_PRE; ++u) {
                 const int e = u * 256 + tid;
-                if (e < count) smem[e] = to_f32(pre[u]);
+                if (e < count) smem[e] = to_f32(prw[u]);
             }
             no_or_vc = no;
         } else {
-            // A short mode leaves most of the 64 LDS rows empty, so a tile takes To groups of 128 columns
-            // and stacks them: LDS row g * n + i holds mode index i of columns 128 g .. 128 g + 127.
-            const int G = jb.To, tcols = SS_TC * G;
-            const long long o = tile / jb.tiles_per_o;
-            const long long j0 = (tile - o * jb.tiles_per_o) * tcols;
-            const int vc = (int)((jb.inner - j0 < tcols) ? jb.inner - j0 : tcols);
-            const int c = tid & (SS_TC - 1);
-            const T* src = X + o * n0 * jb.inner + j0;
-            const float inv_n0 = 1.0f / (float)n0;
-            T pre[32];
-            if constexpr (!STACK) {  // one group: LDS row = mode index
-#pragma unroll
-                for (int u = 0; u < 32; ++u) {
-                    const int i = (tid >> 7) + 2 * u;
-                    pre[u] = src[(c < vc && i < n0) ? (long long)i * jb.inner + c : 0];
-                }
-#pragma unroll
-                for (int u = 0; u < 32; ++u) {
-                    const int i = (tid >> 7) + 2 * u;
-                    if (i < n0) smem[i * rowI + c] = (c < vc) ? to_f32(pre[u]) : 0.f;
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < 32; ++u) {
-                    const int row = (tid >> 7) + 2 * u;
-                    const int g = (int)(((float)row + 0.5f) * inv_n0), i = row - g * n0, col = g * SS_TC + c;
-                    pre[u] = src[(g < G && col < vc) ? (long long)i * jb.inner + col : 0];
-                }
-#pragma unroll
-                for (int u = 0; u < 32; ++u) {
-                    const int row = (tid >> 7) + 2 * u;
-                    const int g = (int)(((float)row + 0.5f) * inv_n0), col = g * SS_TC + c;
-                    if (g < G) smem[row * rowI + c] = (col < vc) ? to_f32(pre[u]) : 0.f;
-                }
-            }
-            no_or_vc = vc;
+            no_or_vc = commit(tile);
         }
         __syncthreads();
+        if constexpr (!WHOLE_O) {
+            if (tile + jb.nwg < jb.ntiles) issue(tile + jb.nwg);
+        }
 #pragma unroll
         for (int vi = 0; vi < NV; ++vi) {
             const SmallView& sv = jb.v[vi];
@@ -272,7 +289,10 @@ static void single_geometry(long long outer, int n, long long inner, SmallJob* j
 int subspace_small_nwg(long long outer, int n, long long inner) {
     SmallJob jb;
     single_geometry(outer, n, inner, &jb);
-    return (int)(jb.ntiles < SS_MAX_WG ? jb.ntiles : SS_MAX_WG);
+    // tiles of a long inner extent are prefetched behind the previous tile's products: two resident
+    // workgroups per CU, each walking several tiles, instead of further rounds of workgroups
+    const int cap = jb.whole_o ? SS_MAX_WG : SS_MAX_WG / 2;
+    return (int)(jb.ntiles < cap ? jb.ntiles : cap);
 }
 
 // The last two modes of a tensor (planes, rows, cols) can share tiles of whole planes.
@@ -305,8 +325,8 @@ static bool finish_small(DType xt, SmallJob& jb, int nbm, int nbr, int nwg, Item
     out->key = (xt == BF16 ? 1u : 0u) | (jb.nviews == 2 ? 2u : 0u) | (jb.whole_o ? 4u : 0u) | (stack ? 8u : 0u) |
                ((unsigned)nbm << 4) | ((unsigned)nbr << 8);
     out->nblocks = nwg;
-    std::snprintf(out->label, sizeof(out->label), "k_subspace_small<%s, %d, %d, %d, %s%s>", xt == F32 ? "float" : "asi::bf16_t",
-                  nbm, nbr, jb.nviews, jb.whole_o ? "true" : "false", stack ? ", true" : "");
+    std::snprintf(out->label, sizeof(out->label), "k_subspace_small<%s, %d, %d, %d, %s, %s>", xt == F32 ? "float" : "asi::bf16_t",
+                  nbm, nbr, jb.nviews, jb.whole_o ? "true" : "false", stack ? "true" : "false");
     static_assert(sizeof(SmallJob) <= kItemArgMax, "argument block");
     std::memcpy(out->arg, &jb, sizeof(jb));
     return true;

@@ -210,7 +210,11 @@ EDGE_LINEAR = [((3, 5, 7), (2, 3, 4), 6), ((4, 9, 30), (4, 9, 30), 3), ((2, 33, 
                # 1024 or more tokens: with bf16 data the last-mode products run on the bf16 MFMA (split factor)
                ((40, 30, 136), (5, 7, 20), 9),                                   # ragged: 1200 columns, last K chunk of 8, two output blocks
                ((36, 32, 200), (6, 8, 70), 11),                                  # five output blocks over two waves
-               ((33, 32, 264), (4, 6, 100), 7)]                                  # seven output blocks over four waves
+               ((33, 32, 264), (4, 6, 100), 7),                                  # seven output blocks over four waves
+               # short modes with a long inner extent (Gram-matrix route): one index (four stacked column
+               # ranges), five (two ranges, a ragged second one), 20 and 40 (one and three row blocks, odd extents)
+               ((1, 5, 161), (1, 3, 4), 3), ((5, 3, 700), (4, 2, 9), 5), ((20, 7, 33), (9, 3, 8), 4),
+               ((40, 6, 50), (32, 4, 10), 6)]
 
 
 @pytest.mark.parametrize("case", EDGE_LINEAR)
