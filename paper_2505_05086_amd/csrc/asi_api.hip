@@ -73,6 +73,8 @@ struct CompressPlan {
     float* V = nullptr;
     unsigned short* Ub = nullptr;    // a factor split into bf16 terms (bf16 tensors, product along the last mode)
     bool bfv[4] = {};                // V of this mode comes from the bf16 MFMA kernel
+    int bfks[4] = {1, 1, 1, 1};      // ... with the contraction split over this many workgroups per column tile
+    float* Vpart = nullptr;          // ... whose partial products are summed into V
     double* part[4] = {};
     double* part2[4] = {};          // first level of the partial-sum tree (nsplit > 32)
     int nsplit2[4] = {};
@@ -117,6 +119,13 @@ CompressPlan plan_compress(const Shape& s, void* ws, bool cold = false) {
         if (p.bfv[m]) ubmax = std::max(ubmax, split_bf16_elems((int)s.n[m], s.r[m]));
     }
     p.Ub = c.take<unsigned short>(ubmax);
+    size_t vpmax = 0;
+    for (int m = 0; m < s.d; ++m) {
+        if (!p.bfv[m]) continue;
+        p.bfks[m] = gemm_bf16_ksplit(s.numel / s.n[m], (int)s.n[m], s.r[m]);
+        if (p.bfks[m] > 1) vpmax = std::max(vpmax, (size_t)p.bfks[m] * (size_t)(s.numel / s.n[m]) * s.r[m]);
+    }
+    p.Vpart = c.take<float>(vpmax);
     p.ctr8 = c.take<int32_t>(8);
     p.tiny = !cold && s.d == 4 && subspace_tiny_supported((int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
     p.planes = !cold && s.d == 4 && subspace_planes_supported(s.n[0] * s.n[1], (int)s.n[2], (int)s.n[3], s.r[2], s.r[3]);
@@ -181,6 +190,8 @@ struct CorePlan {
     float* buf[2] = {};
     unsigned short* Ub = nullptr;    // split factor of a first product along the last mode of a bf16 tensor
     bool bf_last = false;            // such a product is available (bf16 MFMA kernel)
+    int bf_ks = 1;                   // ... with its contraction split over this many workgroups per column tile
+    float* part = nullptr;           // ... whose partial products are summed into the product's output
     size_t bytes = 0;
 };
 
@@ -245,6 +256,8 @@ CorePlan plan_core(const Shape& s, void* ws, const int* order = nullptr) {
     p.buf[0] = c.take<float>(need[0]);
     p.buf[1] = c.take<float>(need[1]);
     p.Ub = c.take<unsigned short>(p.bf_last ? split_bf16_elems((int)s.n[s.d - 1], s.r[s.d - 1]) : 0);
+    if (p.bf_last) p.bf_ks = gemm_bf16_ksplit(s.numel / s.n[s.d - 1], (int)s.n[s.d - 1], s.r[s.d - 1]);
+    p.part = c.take<float>(p.bf_ks > 1 ? (size_t)p.bf_ks * (size_t)(s.numel / s.n[s.d - 1]) * s.r[s.d - 1] : 0);
     p.bytes = c.off;
     return p;
 }
@@ -535,8 +548,12 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
                 const double cols = (double)outer;
                 ASI_ADD(pg, "V", 4.0 * n * r + 2.0 * (double)split_bf16_elems(n, r), 0.0,
                         make_split_bf16(U_prev[m], r, 1, n, r, p.Ub, it__));
-                ASI_ADD(pg, "V", cols * n * 2.0 + 2.0 * (double)split_bf16_elems(n, r) + 4.0 * cols * r, 2.0 * cols * n * r,
-                        make_gemm_bf16(A, outer, n, p.Ub, r, p.V, nullptr, 0, it__));
+                const int ks = p.bfks[m];
+                ASI_ADD(pg, "V", cols * n * 2.0 + 2.0 * (double)split_bf16_elems(n, r) + 4.0 * cols * r * ks, 2.0 * cols * n * r,
+                        make_gemm_bf16(A, outer, n, p.Ub, r, ks > 1 ? p.Vpart : p.V, ks, nullptr, 0, it__));
+                if (ks > 1)
+                    ASI_ADD(pg, "V", 4.0 * cols * r * (ks + 1), cols * r * ks,
+                            make_sum_partials(p.Vpart, ks, (long long)outer * r, p.V, 0, it__));
             } else {
                 ASI_TRYS(add_ttm(pg, "V", s.dt, A, outer, n, inner, U_prev[m], r, 1, r, p.V, 0));
             }
@@ -651,8 +668,12 @@ asi_status build_core(const asi_tensor_desc* desc, const void* A, const float* c
             const double cols = (double)outer;
             ASI_ADD(pg, "core", 4.0 * n * r + 2.0 * (double)split_bf16_elems(n, r), 0.0,
                     make_split_bf16(U[m], r, 1, n, r, p.Ub, it__));
-            ASI_ADD(pg, "core", cols * n * 2.0 + 2.0 * (double)split_bf16_elems(n, r) + 4.0 * cols * r, 2.0 * cols * n * r,
-                    make_gemm_bf16(src, outer, n, p.Ub, r, dst, nullptr, 0, it__));
+            const int ks = p.bf_ks;
+            ASI_ADD(pg, "core", cols * n * 2.0 + 2.0 * (double)split_bf16_elems(n, r) + 4.0 * cols * r * ks, 2.0 * cols * n * r,
+                    make_gemm_bf16(src, outer, n, p.Ub, r, ks > 1 ? p.part : dst, ks, nullptr, 0, it__));
+            if (ks > 1)
+                ASI_ADD(pg, "core", 4.0 * cols * r * (ks + 1), cols * r * ks,
+                        make_sum_partials(p.part, ks, (long long)outer * r, dst, 0, it__));
         } else if (p.kron && m == 2) {
             // (.., H, W) -> (.., r3, r4):  M(h*W + w, a*r4 + b) = U3[h,a] * U4[w,b]
             ASI_TRYS(add_ttm_kron(pg, "core", sdt, src, outer, (int)s.n[2], (int)s.n[3], U[2], s.r[2], 1, s.r[2], U[3],

@@ -38,9 +38,10 @@ struct SplitJob {
 struct GemmBfJob {
     const void* X;           // (ncols, n) bf16
     const unsigned short* Mb;
-    float* Y;                // (ncols, r)
+    float* Y;                // (ncols, r), or (ksplit, ncols, r) partial products when ksplit > 1
     long long ncols;
     int n, r, rpad, kchunks;
+    int ksplit, ntiles;      // workgroup lb: column tile lb % ntiles, K range lb / ntiles
     int32_t* zero;
     int nzero;
 };
@@ -107,7 +108,13 @@ __global__ __launch_bounds__(BG_NT) void k_gemm_bf16(Batch<GemmBfJob> bt) {
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wv / WN, wn = wv - wm * WN;
     if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
-    const long long c0 = (long long)lb * TCOLS;
+    // Few columns (a (tokens x hidden) activation of some thousand tokens) make few column tiles: the
+    // contraction is then split over `ksplit` workgroups per tile, each writing its partial product.
+    const int kpart = lb / jb.ntiles, ctile = lb - kpart * jb.ntiles;
+    const int ck_per = (nck + jb.ksplit - 1) / jb.ksplit;
+    const int ck_beg = kpart * ck_per, ck_end = (ck_beg + ck_per < nck) ? ck_beg + ck_per : nck;
+    float* __restrict__ Yout = jb.Y + (long long)kpart * ncols * r;
+    const long long c0 = (long long)ctile * TCOLS;
     const long long term_stride = (long long)kchunks * rpad * 32;            // bf16 elements per term
     constexpr int PPR = BG_KST * 4;                                          // 16-byte pieces per A row and chunk
 
@@ -160,15 +167,15 @@ __global__ __launch_bounds__(BG_NT) void k_gemm_bf16(Batch<GemmBfJob> bt) {
     // outputs of this wave that exist at all (uniform): blocks beyond rpad are skipped
     const int nb_live = (rpad - 16 * NBN * wn + 15) / 16;
 
-    fetch(0, a_r[0], b_r[0]);
-    if (nck > 1) fetch(1, a_r[1], b_r[1]);
-    for (int ck = 0; ck < nck; ck += 2) {
+    if (ck_beg < ck_end) fetch(ck_beg, a_r[0], b_r[0]);
+    if (ck_beg + 1 < ck_end) fetch(ck_beg + 1, a_r[1], b_r[1]);
+    for (int ck = ck_beg; ck < ck_end; ck += 2) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {                 // two chunks per trip: register set and LDS buffer h
-            if (ck + h < nck) {
+            if (ck + h < ck_end) {
                 stash(h, a_r[h], b_r[h]);
                 __syncthreads();   // chunk ck + h is in LDS; every wave has finished the chunk before it (its buffer is free again)
-                if (ck + h + 2 < nck) fetch(ck + h + 2, a_r[h], b_r[h]);
+                if (ck + h + 2 < ck_end) fetch(ck + h + 2, a_r[h], b_r[h]);
                 const unsigned char* base = bg_dyn + h * BUF;
                 const unsigned char* ap = base + (16 * CBW * wm + ll) * BG_APITCH_B + lg * 16;
                 const unsigned char* bp = base + A_BYTES + ((16 * NBN * wn + ll) * 4 + lg) * 16;
@@ -202,7 +209,7 @@ __global__ __launch_bounds__(BG_NT) void k_gemm_bf16(Batch<GemmBfJob> bt) {
             for (int v = 0; v < 4; ++v) {
                 const long long c = c0 + 16 * (CBW * wm + cb) + 4 * lg + v;
                 const int q = 16 * (NBN * wn + nb) + ll;
-                if (c < ncols && q < r) jb.Y[c * r + q] = acc[cb][nb][v];
+                if (c < ncols && q < r) Yout[c * r + q] = acc[cb][nb][v];
             }
 }
 
@@ -240,10 +247,29 @@ static void gemm_shape(int r, int* nbn, int* wn, int* cbw) {
     else { *nbn = 3; *wn = 4; *cbw = 2; }                     // 2 x 4 waves, 64 columns (128 columns, half the workgroups: 89 us against 69 for a 12608 x 3072 x 192 product)
 }
 
-// key: [4..5] NBN, [8..10] WN, [12..13] CBW
-bool make_gemm_bf16(const void* X, long long ncols, int n, const unsigned short* Mb, int r, float* Y, int32_t* zero,
-                    int nzero, Item* out) {
+static int gemm_tcols(int r) {
+    int nbn, wn, cbw;
+    gemm_shape(r, &nbn, &wn, &cbw);
+    return 16 * cbw * (8 / wn);
+}
+// Workgroups per column tile: enough to give every CU one when the columns alone make fewer tiles, while
+// each keeps at least four chunks of the contraction (a chunk is 64 elements long).
+int gemm_bf16_ksplit(long long ncols, int n, int r) {
+    const int tc = gemm_tcols(r);
+    const long long tiles = (ncols + tc - 1) / tc;
+    const int nck = (bf_kchunks(n) + BG_KST - 1) / BG_KST;
+    if (tiles >= 128) return 1;
+    long long ks = 256 / tiles;
+    if (ks > nck / 4) ks = nck / 4;
+    if (ks > 16) ks = 16;
+    return ks < 2 ? 1 : (int)ks;
+}
+
+// key: [4..5] NBN, [8..10] WN, [12..13] CBW.  ksplit > 1: Y takes ksplit partial products of (ncols, r), to be summed.
+bool make_gemm_bf16(const void* X, long long ncols, int n, const unsigned short* Mb, int r, float* Y, int ksplit,
+                    int32_t* zero, int nzero, Item* out) {
     if (!gemm_bf16_supported(ncols, n, r) || !X || !Mb || !Y || nzero < 0 || nzero > 256) return false;
+    if (ksplit < 1 || (ksplit != 1 && ksplit != gemm_bf16_ksplit(ncols, n, r))) return false;
     GemmBfJob jb;
     std::memset(&jb, 0, sizeof(jb));
     jb.X = X; jb.Mb = Mb; jb.Y = Y; jb.ncols = ncols; jb.n = n; jb.r = r; jb.rpad = bf_rpad(r); jb.kchunks = bf_kchunks(n);
@@ -251,8 +277,10 @@ bool make_gemm_bf16(const void* X, long long ncols, int n, const unsigned short*
     int nbn, wn, cbw;
     gemm_shape(r, &nbn, &wn, &cbw);
     const int tcols = 16 * cbw * (8 / wn);
-    const long long blocks = (ncols + tcols - 1) / tcols;
+    const long long tiles = (ncols + tcols - 1) / tcols;
+    const long long blocks = tiles * ksplit;
     if (blocks > 0x3fffffffLL) return false;
+    jb.ksplit = ksplit; jb.ntiles = (int)tiles;
     *out = Item();
     out->kind = IT_GEMM_BF16;
     out->key = ((unsigned)nbn << 4) | ((unsigned)wn << 8) | ((unsigned)cbw << 12);

@@ -162,8 +162,11 @@ bool make_ttm_duo(const Item& a, const Item& z, Item* out);
 bool gemm_bf16_supported(long long ncols, int n, int r);
 size_t split_bf16_elems(int n, int r);
 bool make_split_bf16(const float* M, long long ms_i, long long ms_q, int n, int r, unsigned short* Mb, Item* out);
-bool make_gemm_bf16(const void* X, long long ncols, int n, const unsigned short* Mb, int r, float* Y, int32_t* zero,
-                    int nzero, Item* out);
+// Few columns: the contraction is split over gemm_bf16_ksplit workgroups per column tile; Y then takes that
+// many partial products (ksplit, ncols, r), to be summed by make_sum_partials.
+int gemm_bf16_ksplit(long long ncols, int n, int r);
+bool make_gemm_bf16(const void* X, long long ncols, int n, const unsigned short* Mb, int r, float* Y, int ksplit,
+                    int32_t* zero, int nzero, Item* out);
 
 // ---- pair: part[s][i][q] = sum_{c in split s} X[i,c] * Y[q,c]  over unfolding columns c = (o,j) -----
 // X: (outer, n, inner) dtype xt;  Y: (outer, r, inner) fp32;  part: (nsplit, n, r) fp64

@@ -214,7 +214,10 @@ EDGE_LINEAR = [((3, 5, 7), (2, 3, 4), 6), ((4, 9, 30), (4, 9, 30), 3), ((2, 33, 
                # short modes with a long inner extent (Gram-matrix route): one index (four stacked column
                # ranges), five (two ranges, a ragged second one), 20 and 40 (one and three row blocks, odd extents)
                ((1, 5, 161), (1, 3, 4), 3), ((5, 3, 700), (4, 2, 9), 5), ((20, 7, 33), (9, 3, 8), 4),
-               ((40, 6, 50), (32, 4, 10), 6)]
+               ((40, 6, 50), (32, 4, 10), 6),
+               # few tokens against a long hidden mode: the bf16 product splits its contraction over two
+               # workgroups per column tile (nine chunks, the last one ragged) and sums the partial products
+               ((16, 64, 520), (4, 6, 20), 8)]
 
 
 @pytest.mark.parametrize("case", EDGE_LINEAR)
