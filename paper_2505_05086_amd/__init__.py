@@ -2,8 +2,10 @@
 
 Thin Python names over the C ABI of libasi_hip.so (see include/asi.h):
 asi_compress, asi_core_project, asi_weight_grad_conv2d, asi_weight_grad_linear and their
-*_batch forms, which serve several layers with every kernel launch.
+*_batch forms, which serve several layers with every kernel launch; asi_compress_cold for the first
+iteration; AsiConv2d / AsiLinear wire the calls into autograd (the layers keep (S, U), not the activation).
 """
+from .autograd import AsiConv2d, AsiLinear, AsiState  # noqa: F401
 from .binding import (  # noqa: F401
     ASI_BF16,
     ASI_F32,

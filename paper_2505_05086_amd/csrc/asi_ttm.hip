@@ -29,14 +29,21 @@ namespace asi {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int TM_TC = 64, TM_TQ = 64, TM_LD = TM_TC + 4;
+constexpr int TM_TC = 64, TM_TQ = 64;
+// Row pitch of the LDS tiles in floats.  An operand read takes rows 4ks + lane / 16 at columns lane % 16 of a
+// wave's block, so a pitch of 16 banks more than a multiple of 64 spreads the four rows over all 64 banks
+// (a pitch of 68 puts them 4 banks apart: up to four lanes per bank).  Along the last mode the tile is
+// stored transposed (lanes run along the mode index = the row), where a pitch of 80 would send 16 lanes to
+// one bank; there the rows stay 4 banks apart.
+template <bool LASTMODE> constexpr int tm_ld() { return LASTMODE ? TM_TC + 4 : TM_TC + 16; }
+constexpr int TM_LD_MAX = TM_TC + 16;
 constexpr int TM_KCMAX = 64;
 
 // KM: 0 = plain matrix, 1 = Kronecker product, 2 = Kronecker product with K chunks of 64 (long merged
 // modes with few columns; otherwise chunks of 32, which overlap across workgroups), 3 = plain matrix with
 // K chunks of 64 (a long last mode with at most one workgroup per CU: a chunk is a dependent round trip
 // to memory, and nothing else on the CU hides it)
-constexpr int TM_SMEM = 2 * TM_KCMAX * TM_LD;   // floats: Xs | Ms during the K loop, Ys (64 x TM_LD) afterwards
+constexpr int TM_SMEM = 2 * TM_KCMAX * TM_LD_MAX;   // floats: Xs | Ms during the K loop, Ys (64 x TM_LD) afterwards
 
 // one tile (workgroup lb of job jb); smem holds TM_SMEM floats
 template <typename T, bool LASTMODE, int NBR, int KM>
@@ -44,6 +51,7 @@ __device__ __forceinline__ void ttm_tile(const TtmJob& jb, int lb, float* smem) 
     constexpr bool KRON = KM == 1 || KM == 2;
     constexpr int TM_KC = KM >= 2 ? 64 : 32;
     constexpr int TM_LR = TM_KC / 4;      // loads per thread and operand for one chunk
+    constexpr int TM_LD = tm_ld<LASTMODE>();
     float (*Xs)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem);
     float (*Ms)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem + TM_KCMAX * TM_LD);
     float (*Ys)[TM_LD] = reinterpret_cast<float (*)[TM_LD]>(smem);

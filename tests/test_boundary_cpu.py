@@ -187,3 +187,18 @@ def test_batched_entry_points_reject_bad_arguments():
     dout = (C.c_int64 * 2)(7, 0)
     assert L.asi_weight_grad_linear_batch(2, descs(d3, d3), ptrs(2), up, ptrs(2), dout, ptrs(2), None, ptrs(2),
                                           sizes(big, big), None) == 1
+
+
+def test_autograd_layers_refuse_to_run_without_the_gpu_path():
+    """The training-loop wrappers have no CPU fallback: a CPU activation in training mode is an error."""
+    import torch
+    from paper_2505_05086_amd.autograd import AsiConv2d, AsiLinear
+    conv = AsiConv2d(3, 4, 3, padding=1, ranks=(2, 2, 2, 2)).train()
+    with pytest.raises(RuntimeError):
+        conv(torch.zeros(2, 3, 5, 5))
+    lin = AsiLinear(6, 4, ranks=(2, 2, 2)).train()
+    with pytest.raises(RuntimeError):
+        lin(torch.zeros(2, 3, 6))
+    with pytest.raises(ValueError):
+        lin(torch.zeros(3, 6))
+    assert conv.eval()(torch.zeros(2, 3, 5, 5)).shape == (2, 4, 5, 5)      # inference is the plain operator
