@@ -150,7 +150,7 @@ def parse_args():
     return ap.parse_args()
 
 
-def cpu_baseline(cfg, streams, budget_s):
+def cpu_baseline(cfg, streams, budget_s, extras=False):
     """The float64 oracle, as it stands, on the host cores: whole path per layer-step."""
     import numpy as np
     from oracle import asi_oracle as O
@@ -181,9 +181,56 @@ def cpu_baseline(cfg, streams, budget_s):
             done_bytes += lay.act_bytes
             n_ls += 1
         step += 1
-    return {"value": done_bytes / t_used / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n_ls} layer-step(s) of config {cfg.index} in layer order from step 0 "
-                      f"({t_used:.1f} s of float64 NumPy oracle time, input generation excluded)"}
+    out = {"value": done_bytes / t_used / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+           "sample": f"{n_ls} layer-step(s) of config {cfg.index} in layer order from step 0 "
+                     f"({t_used:.1f} s of float64 NumPy oracle time, input generation excluded)"}
+    if extras:
+        out["variants"] = cpu_variants(cfg, streams)
+    return out
+
+
+def cpu_variants(cfg, streams):
+    """Two more host figures on the first layer of the workload (step 0): the same oracle layer-step with the
+    BLAS pool limited to one thread, and the dense weight gradient (Eq. 1 on the activation itself, what
+    a trainer without compression computes) on all cores."""
+    import numpy as np
+    from oracle import asi_oracle as O
+    lay, st = cfg.layers[0], streams[0]
+    A = st.activation(0).astype(np.float64)
+    dY = st.grad_out(0).astype(np.float64)
+    U0 = [u.astype(np.float64) for u in st.u_prev0()]
+    cs = None
+    if lay.kind == "conv2d":
+        cs = O.Conv2dSpec(lay.cout, lay.k, lay.k, (lay.stride,) * 2, (lay.pad,) * 2, (lay.dil,) * 2, lay.groups)
+
+    def layer_step():
+        Un = O.compress(A, U0)
+        S = O.core_project(A, Un)
+        if cs is not None:
+            O.conv2d_weight_grad_lowrank(S, Un, dY, cs)
+        else:
+            O.linear_weight_grad_lowrank(S, Un, dY)
+
+    res = {}
+    try:
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            layer_step()
+            t1 = time.perf_counter() - t0
+        res["oracle_one_thread"] = {"value": lay.act_bytes / t1 / 1e9, "unit": "GB/s", "cores": 1,
+                                    "sample": f"one layer-step of layer {lay.name} ({t1:.1f} s)"}
+    except ImportError:
+        pass
+    t0 = time.perf_counter()
+    if cs is not None:
+        O.conv2d_weight_grad_dense(A, dY, cs)
+    else:
+        O.linear_weight_grad_dense(A, dY)
+    t2 = time.perf_counter() - t0
+    res["dense_weight_grad_only"] = {"value": lay.act_bytes / t2 / 1e9, "unit": "GB/s",
+                                     "sample": f"Eq. 1 on the uncompressed activation of layer {lay.name}, float64 NumPy, all cores ({t2:.1f} s)"}
+    return res
 
 
 def measure(cfg, args, cpu_seconds):
@@ -527,7 +574,7 @@ def measure(cfg, args, cpu_seconds):
         "gpu_ms_per_step_events": gpu_ms / args.steps,
     }
     if cpu_seconds > 0:
-        out["cpu_baseline"] = cpu_baseline(cfg, streams, cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(cfg, streams, cpu_seconds, extras=cpu_seconds >= 10)
     del A_dev, dY_dev, runners, batches, graphs, layer_graphs
     torch.cuda.empty_cache()
     return out
