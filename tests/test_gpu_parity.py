@@ -183,6 +183,12 @@ EDGE_CONV = [
     ((12, 5, 150, 150), (10, 4, 9, 9), 12, 3, 1, 1, 1, 1),       # the same with 9 to 16 entries, ragged planes
     ((26, 40, 41, 45), (4, 10, 17, 9), 6, 3, 1, 1, 1, 1),        # 1040 ragged planes of three 16-blocks: the large-plane kernel, last tile partly empty
     ((17, 61, 50, 63), (3, 8, 12, 16), 5, 3, 1, 1, 1, 1),        # 1037 planes of four 16-blocks, ranks within one block
+    # large maps, 3 x 3, Wo a multiple of 4: the double-buffered correlation.  37 output rows in chunks of two
+    # (ragged last chunk), 70 output channels (a ragged second tile), five core channels, 50-wide slab rows
+    ((2, 20, 37, 48), (2, 5, 6, 6), 70, 3, 1, 1, 1, 1),
+    ((1, 9, 32, 64), (1, 4, 5, 5), 10, 3, 1, 1, 1, 1),           # 66-wide slab rows (128 lanes per row), two rows per chunk, one batch entry
+    ((2, 6, 34, 32), (2, 3, 6, 5), 20, 3, 1, 1, 1, 1),           # four output rows per chunk: slabs of six rows, 34 rows in all (ragged)
+    ((2, 6, 40, 68), (2, 3, 6, 5), 20, 3, 1, 2, 2, 1),           # dilation 2 over 64 output columns: six slab rows of 68 columns
 ]
 
 
