@@ -21,6 +21,7 @@
 #include <atomic>
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 namespace asi {
 
@@ -44,7 +45,27 @@ struct PlanesJob {
 
 extern __shared__ __align__(16) float pn_dyn[];
 
-template <typename T, int NBM, int NBR>
+// pieces of a plane row as they travel from memory to LDS
+template <typename T, bool VEC> struct PlaneVec { typedef T type; };
+template <> struct PlaneVec<float, true> { typedef v4f type; };
+template <> struct PlaneVec<bf16_t, true> { typedef uint2 type; };
+template <typename T, bool VEC, typename P>
+__device__ __forceinline__ void plane_store(float* dst, const P& v, bool ok) {
+    if constexpr (!VEC) {
+        *dst = ok ? to_f32(v) : 0.f;
+    } else if constexpr (std::is_same<T, float>::value) {
+        const v4f z = {0.f, 0.f, 0.f, 0.f};
+        *reinterpret_cast<v4f*>(dst) = ok ? v : z;
+    } else {
+        v4f o;
+        o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+        o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+        const v4f z = {0.f, 0.f, 0.f, 0.f};
+        *reinterpret_cast<v4f*>(dst) = ok ? o : z;
+    }
+}
+
+template <typename T, int NBM, int NBR, bool VEC>
 __global__ __launch_bounds__(PN_NT) void k_subspace_planes(Batch<PlanesJob> bt) {
     constexpr int PF = 16 * NBM * PN_LD;              // floats of one plane in LDS
     constexpr int NLD = (PN_PL * 256 * NBM * NBM + PN_NT - 1) / PN_NT;    // elements per thread and tile (planes of up to 16 NBM squared)
@@ -82,32 +103,40 @@ __global__ __launch_bounds__(PN_NT) void k_subspace_planes(Batch<PlanesJob> bt) 
     // rows and columns beyond the plane stay zero for the whole kernel
     for (int e = tid; e < PN_PL * PF; e += PN_NT) Xs[e] = 0.f;
 
-    const float inv_pe = 1.0f / (float)pe, inv_cols = 1.0f / (float)cols;
-    T pre[NLD];
-    auto fetch = [&](long long t) {
+    // A tile is moved in pieces of W consecutive elements of a plane row: W = 4 (one 16-byte load, 8 bytes for
+    // bf16, and one 16-byte LDS store) when rows are a multiple of 4 long and X is aligned, else single
+    // elements.  The piece -> (plane, row, column) arithmetic is per piece, so the wide form needs a quarter of
+    // it, and a quarter of the load and store instructions; all of them are issued by the waves that also
+    // multiply, at the expense of the products.
+    constexpr int W = VEC ? 4 : 1;
+    constexpr int NLDW = (NLD + W - 1) / W;           // pieces per thread and tile
+    const int ppr = cols / W, ppp = rows * ppr;       // pieces per row and per plane (VEC: cols % 4 == 0)
+    const float inv_ppp = 1.0f / (float)ppp, inv_ppr = 1.0f / (float)ppr;
+    typename PlaneVec<T, VEC>::type pre[NLDW];
+    auto fetch = [&](long long t) __attribute__((always_inline)) {
         const long long p0 = t * PN_PL;
         const int np = (int)((jb.planes - p0 < PN_PL) ? jb.planes - p0 : PN_PL);
-        const int count = np * pe;
+        const int count = np * ppp;
         const T* src = X + p0 * pe;
 #pragma unroll
-        for (int u = 0; u < NLD; ++u) {
+        for (int u = 0; u < NLDW; ++u) {
             const int e = u * PN_NT + tid;
-            pre[u] = src[e < count ? e : 0];          // clamped, not branched: all loads stay in flight
+            pre[u] = *reinterpret_cast<const typename PlaneVec<T, VEC>::type*>(src + (e < count ? e * W : 0));   // clamped, not branched: all loads stay in flight
         }
     };
     if (lb < jb.ntiles) fetch(lb);
     for (long long t = lb; t < jb.ntiles; t += jb.nwg) {
         const long long p0 = t * PN_PL;
         const int np = (int)((jb.planes - p0 < PN_PL) ? jb.planes - p0 : PN_PL);
-        const int count = np * pe;
+        const int count = np * ppp;
         __syncthreads();                              // the previous tile is no longer read
 #pragma unroll
-        for (int u = 0; u < NLD; ++u) {
+        for (int u = 0; u < NLDW; ++u) {
             int e = u * PN_NT + tid;                  // e < 2^15: the rounded float quotients are exact
-            asm volatile("" : "+v"(e));               // (recomputed per tile: hoisted out of the loop, the 32 offsets cost 32 registers)
-            const int pl = (int)(((float)e + 0.5f) * inv_pe), rem = e - pl * pe;
-            const int i = (int)(((float)rem + 0.5f) * inv_cols), c = rem - i * cols;
-            if (e < PN_PL * pe) Xs[pl * PF + i * PN_LD + c] = (e < count) ? to_f32(pre[u]) : 0.f;
+            asm volatile("" : "+v"(e));               // (recomputed per tile: hoisted out of the loop, the offsets cost a register each)
+            const int pl = (int)(((float)e + 0.5f) * inv_ppp), rem = e - pl * ppp;
+            const int i = (int)(((float)rem + 0.5f) * inv_ppr), c = (rem - i * ppr) * W;
+            if (e < PN_PL * ppp) plane_store<T, VEC>(Xs + pl * PF + i * PN_LD + c, pre[u], e < count);
         }
         __syncthreads();
         if (t + jb.nwg < jb.ntiles) fetch(t + jb.nwg);    // in flight during the products of this tile
@@ -256,7 +285,7 @@ int subspace_planes_nwg(long long planes) {
     return (int)(ntiles < 256 ? ntiles : 256);
 }
 
-// key: [0] bf16, [4..6] NBM, [8..9] NBR
+// key: [0] bf16, [1] 16-byte pieces, [4..6] NBM, [8..9] NBR
 bool make_subspace_planes(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows, int r_rows,
                           double* part_rows, const float* U_cols, int r_cols, double* part_cols, int nwg, int32_t* zero,
                           int nzero, Item* out) {
@@ -273,28 +302,30 @@ bool make_subspace_planes(DType xt, const void* X, long long planes, int rows, i
     const int nbm = (rows + 15) / 16, nbr = ((r_rows > r_cols ? r_rows : r_cols) + 15) / 16;
     *out = Item();
     out->kind = IT_PLANES;
-    out->key = (xt == BF16 ? 1u : 0u) | ((unsigned)nbm << 4) | ((unsigned)nbr << 8);
+    const bool vec = cols % 4 == 0 && reinterpret_cast<uintptr_t>(X) % (xt == F32 ? 16 : 8) == 0;
+    out->key = (xt == BF16 ? 1u : 0u) | (vec ? 2u : 0u) | ((unsigned)nbm << 4) | ((unsigned)nbr << 8);
     out->nblocks = nwg;
-    std::snprintf(out->label, sizeof(out->label), "k_subspace_planes<%s, %d, %d>", xt == F32 ? "float" : "asi::bf16_t", nbm, nbr);
+    std::snprintf(out->label, sizeof(out->label), "k_subspace_planes<%s, %d, %d, %s>", xt == F32 ? "float" : "asi::bf16_t", nbm, nbr,
+                  vec ? "true" : "false");
     static_assert(sizeof(PlanesJob) <= kItemArgMax, "argument block");
     std::memcpy(out->arg, &jb, sizeof(jb));
     return true;
 }
 
-template <typename T, int NBM, int NBR>
+template <typename T, int NBM, int NBR, bool VEC>
 static hipError_t launch_planes_one(const Batch<PlanesJob>& b, dim3 grid, hipStream_t st) {
     constexpr size_t lds = sizeof(float) * ((size_t)PN_PL * 16 * NBM * PN_LD + 2 * 4 * NBM * NBR * 64);
     static_assert(lds >= sizeof(double) * 16 * NBM * 16 * NBR, "the reduction buffer fits the tile");
     if (lds > 65536) {                // more than a static array may take: allowed once per kernel
         static std::atomic<bool> allowed{false};
         if (!allowed.load()) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_subspace_planes<T, NBM, NBR>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_subspace_planes<T, NBM, NBR, VEC>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             allowed.store(true);
         }
     }
-    hipLaunchKernelGGL((k_subspace_planes<T, NBM, NBR>), grid, PN_NT, lds, st, b);
+    hipLaunchKernelGGL((k_subspace_planes<T, NBM, NBR, VEC>), grid, PN_NT, lds, st, b);
     return hipGetLastError();
 }
 
@@ -304,10 +335,12 @@ hipError_t launch_planes_items(const Item* const* items, int n, hipStream_t st) 
     if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
     const unsigned key = items[0]->key;
     const int nbm = (int)((key >> 4) & 7u), nbr = (int)((key >> 8) & 3u);
-    const bool bf = key & 1u;
-#define ASI_PLANES_CASE(M, R)                                                             \
-    if (nbm == M && nbr == R)                                                             \
-        return bf ? launch_planes_one<bf16_t, M, R>(b, grid, st) : launch_planes_one<float, M, R>(b, grid, st);
+    const bool bf = key & 1u, vec = key & 2u;
+#define ASI_PLANES_CASE(M, R)                                                                                               \
+    if (nbm == M && nbr == R) {                                                                                             \
+        if (vec) return bf ? launch_planes_one<bf16_t, M, R, true>(b, grid, st) : launch_planes_one<float, M, R, true>(b, grid, st);    \
+        return bf ? launch_planes_one<bf16_t, M, R, false>(b, grid, st) : launch_planes_one<float, M, R, false>(b, grid, st);           \
+    }
     ASI_PLANES_CASE(3, 1) ASI_PLANES_CASE(3, 2) ASI_PLANES_CASE(4, 1) ASI_PLANES_CASE(4, 2)
 #undef ASI_PLANES_CASE
     return hipErrorInvalidValue;
