@@ -27,6 +27,7 @@
 #include <atomic>
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 namespace asi {
 
@@ -61,14 +62,38 @@ struct LongShape {
     static constexpr size_t lds_bytes = sizeof(float) * (size_t)(XS + VP + VD);
 };
 
-template <typename T, int NRB, int NCB, int NBQ>
+// pieces of a tile row as they travel from memory to LDS (VEC: four consecutive columns)
+template <typename T, bool VEC> struct LongVec { typedef T type; };
+template <> struct LongVec<float, true> { typedef v4f type; };
+template <> struct LongVec<bf16_t, true> { typedef uint2 type; };
+template <typename T, bool VEC, typename P>
+__device__ __forceinline__ void long_store(float* dst, const P& v, bool ok) {
+    if constexpr (!VEC) {
+        *dst = ok ? to_f32(v) : 0.f;
+    } else {
+        v4f o;
+        if constexpr (std::is_same<T, float>::value) {
+            o = v;
+        } else {
+            o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+            o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+        }
+        const v4f z = {0.f, 0.f, 0.f, 0.f};
+        *reinterpret_cast<v4f*>(dst) = ok ? o : z;
+    }
+}
+
+// VEC: the inner extent is a multiple of 4 and X is aligned, so a thread moves four consecutive columns of a
+// row with one 16-byte load (8 bytes for bf16) and one 16-byte LDS store: a quarter of the loader's instructions.
+template <typename T, int NRB, int NCB, int NBQ, bool VEC>
 __global__ __launch_bounds__(LG_NT) void k_subspace_long(Batch<LongJob> bt) {
     using SH = LongShape<NRB, NCB, NBQ>;
     constexpr int TC = SH::TC, LD = SH::LD, VQ = SH::VQ, NROW = SH::NROW;
     constexpr int HC = NCB / 2;                       // column blocks of a wave in step A
     constexpr int KSA = 8 * NRB;                      // K steps of a wave in step A (32 NRB rows)
-    constexpr int NLD = NROW * TC / LG_NT;            // tile elements per thread
-    constexpr int RSTEP = LG_NT / TC;                 // rows between a thread's consecutive elements
+    constexpr int W = VEC ? 4 : 1;                    // columns per piece
+    constexpr int NLD = NROW * TC / W / LG_NT;        // tile pieces per thread
+    constexpr int RSTEP = LG_NT / (TC / W);           // rows between a thread's consecutive pieces
     static_assert(NCB % 2 == 0 && TC % 16 == 0 && LG_NT % TC == 0, "tile shape");
     float* Xs = lg_dyn;
     float* Vp = lg_dyn + SH::XS;
@@ -107,8 +132,8 @@ __global__ __launch_bounds__(LG_NT) void k_subspace_long(Batch<LongJob> bt) {
     for (int e = tid; e < SH::XS; e += LG_NT) Xs[e] = 0.f;
 
     // loader: this thread's column of the tile and its first row; element offsets are 32-bit (host check)
-    const int cl = tid & (TC - 1), r0 = tid / TC;
-    T pre[NLD];
+    const int cl = W * (tid & (TC / W - 1)), r0 = tid / (TC / W);
+    typename LongVec<T, VEC>::type pre[NLD];
     bool c_in = false;
     auto fetch = [&](int t) {
         const long long c = (long long)t * TC + cl;
@@ -123,7 +148,7 @@ __global__ __launch_bounds__(LG_NT) void k_subspace_long(Batch<LongJob> bt) {
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
             const int i = r0 + RSTEP * u;
-            pre[u] = X[base + (unsigned)(i < n ? i : n - 1) * istep];     // clamped, not branched: all loads stay in flight
+            pre[u] = *reinterpret_cast<const typename LongVec<T, VEC>::type*>(X + (base + (unsigned)(i < n ? i : n - 1) * istep));   // clamped, not branched: all loads stay in flight
         }
     };
     if (t_beg < t_end) fetch(t_beg);
@@ -132,7 +157,7 @@ __global__ __launch_bounds__(LG_NT) void k_subspace_long(Batch<LongJob> bt) {
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
             const int i = r0 + RSTEP * u;
-            if (i < n) Xs[i * LD + cl] = c_in ? to_f32(pre[u]) : 0.f;
+            if (i < n) long_store<T, VEC>(Xs + i * LD + cl, pre[u], c_in);
         }
         __syncthreads();
         if (t + 1 < t_end) fetch(t + 1);               // in flight during the products of this tile
@@ -255,7 +280,7 @@ int subspace_long_splits(long long outer, int n, long long inner, int r) {
     return jb.ncg;
 }
 
-// key: [0] bf16, [4..7] NRB, [8..11] NCB, [12..15] NBQ
+// key: [0] bf16, [1] 16-byte pieces, [4..7] NRB, [8..11] NCB, [12..15] NBQ
 bool make_subspace_long(DType xt, const void* X, long long outer, int n, long long inner, const float* U, int r,
                         double* part, int nsplit, int32_t* zero, int nzero, Item* out) {
     if (!subspace_long_supported(outer, n, inner, r) || !X || !U || !part || nzero < 0 || nzero > 256) return false;
@@ -269,35 +294,38 @@ bool make_subspace_long(DType xt, const void* X, long long outer, int n, long lo
     long_shape(n, r, &nrb, &ncb, &nbq);
     *out = Item();
     out->kind = IT_LONG;
-    out->key = (xt == BF16 ? 1u : 0u) | ((unsigned)nrb << 4) | ((unsigned)ncb << 8) | ((unsigned)nbq << 12);
+    const size_t piece = xt == F32 ? 16 : 8;
+    const bool vec = inner % 4 == 0 && reinterpret_cast<uintptr_t>(X) % piece == 0;
+    out->key = (xt == BF16 ? 1u : 0u) | (vec ? 2u : 0u) | ((unsigned)nrb << 4) | ((unsigned)ncb << 8) | ((unsigned)nbq << 12);
     out->nblocks = jb.ncg * jb.gy;
-    std::snprintf(out->label, sizeof(out->label), "k_subspace_long<%s, %d, %d, %d>", xt == F32 ? "float" : "asi::bf16_t",
-                  nrb, ncb, nbq);
+    std::snprintf(out->label, sizeof(out->label), "k_subspace_long<%s, %d, %d, %d, %s>", xt == F32 ? "float" : "asi::bf16_t",
+                  nrb, ncb, nbq, vec ? "true" : "false");
     static_assert(sizeof(LongJob) <= kItemArgMax, "argument block");
     std::memcpy(out->arg, &jb, sizeof(jb));
     return true;
 }
 
-template <typename T, int NRB, int NCB, int NBQ>
+template <typename T, int NRB, int NCB, int NBQ, bool VEC>
 static hipError_t launch_long_one(const Batch<LongJob>& b, dim3 grid, hipStream_t st) {
     constexpr size_t lds = LongShape<NRB, NCB, NBQ>::lds_bytes;
     static_assert(lds <= 160 * 1024, "LDS of a CU");
     if (lds > 65536) {                // more than a static array may take: allowed once per kernel
         static std::atomic<bool> allowed{false};
         if (!allowed.load()) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_subspace_long<T, NRB, NCB, NBQ>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_subspace_long<T, NRB, NCB, NBQ, VEC>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             allowed.store(true);
         }
     }
-    hipLaunchKernelGGL((k_subspace_long<T, NRB, NCB, NBQ>), grid, LG_NT, lds, st, b);
+    hipLaunchKernelGGL((k_subspace_long<T, NRB, NCB, NBQ, VEC>), grid, LG_NT, lds, st, b);
     return hipGetLastError();
 }
 
 template <typename T>
-static hipError_t launch_long_t(const Batch<LongJob>& b, dim3 grid, int nrb, int ncb, int nbq, hipStream_t st) {
-#define ASI_LONG_CASE(R, C, Q) if (nrb == R && ncb == C && nbq == Q) return launch_long_one<T, R, C, Q>(b, grid, st);
+static hipError_t launch_long_t(const Batch<LongJob>& b, dim3 grid, int nrb, int ncb, int nbq, bool vec, hipStream_t st) {
+#define ASI_LONG_CASE(R, C, Q) if (nrb == R && ncb == C && nbq == Q) \
+        return vec ? launch_long_one<T, R, C, Q, true>(b, grid, st) : launch_long_one<T, R, C, Q, false>(b, grid, st);
     ASI_LONG_CASE(1, 4, 1) ASI_LONG_CASE(1, 4, 2) ASI_LONG_CASE(1, 4, 3)
     ASI_LONG_CASE(2, 4, 1) ASI_LONG_CASE(2, 4, 2) ASI_LONG_CASE(2, 4, 3)
     ASI_LONG_CASE(4, 2, 1) ASI_LONG_CASE(4, 2, 2)
@@ -311,8 +339,9 @@ hipError_t launch_long_items(const Item* const* items, int n, hipStream_t st) {
     if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
     const unsigned key = items[0]->key;
     const int nrb = (int)((key >> 4) & 15u), ncb = (int)((key >> 8) & 15u), nbq = (int)((key >> 12) & 15u);
-    if (key & 1u) return launch_long_t<bf16_t>(b, grid, nrb, ncb, nbq, st);
-    return launch_long_t<float>(b, grid, nrb, ncb, nbq, st);
+    const bool vec = (key & 2u) != 0;
+    if (key & 1u) return launch_long_t<bf16_t>(b, grid, nrb, ncb, nbq, vec, st);
+    return launch_long_t<float>(b, grid, nrb, ncb, nbq, vec, st);
 }
 
 }  // namespace asi
