@@ -374,10 +374,10 @@ inline void tag(Program& pg, const char* role, double bytes, double flops) {
 
 // mode product with its accounting: reads X and M once, writes (or updates) Y once
 asi_status add_ttm(Program& pg, const char* role, DType xt, const void* X, long long outer, int n, long long inner,
-                   const float* Mp, long long ms_i, long long ms_q, int r, float* Y, int beta) {
+                   const float* Mp, long long ms_i, long long ms_q, int r, float* Y, int beta, bool stream_ok = true) {
     const double cols = (double)outer * (double)inner;
     ASI_ADD(pg, role, cols * n * esize(xt) + 4.0 * n * r + 4.0 * cols * r * (beta ? 2 : 1), 2.0 * cols * n * r,
-            make_ttm(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, it__));
+            make_ttm(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, it__, stream_ok));
     return ASI_OK;
 }
 // two trailing modes at once (Kronecker product of their matrices)
@@ -706,7 +706,9 @@ asi_status build_conv(const asi_tensor_desc* desc, const float* S, const float* 
     const int taps = g.kh * g.kw;
 
     // 1. G1 = grad_out x_1 U1^T                                   (r1, cout, Ho, Wo)
-    ASI_TRYS(add_ttm(pg, "G1", s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0));
+    // (where Z comes from one merged product it can share G1's launch: G1 then stays on the tiled kernel)
+    ASI_TRYS(add_ttm(pg, "G1", s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0,
+                     p.Z1 != nullptr));
     if (!p.Z1) {
         // 2+3. Z = S x_3 U3 x_4 U4 in one pass:  M(a*r4 + b, h*W + w) = U3[h,a] * U4[w,b]   (r1, r2, H, W)
         ASI_TRYS(add_ttm_kron(pg, "Z", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, U[3], 1, r4, g.W, p.Z));

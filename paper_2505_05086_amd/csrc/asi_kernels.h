@@ -19,7 +19,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
-    IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO,
+    IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO, IT_TTM_STREAM,
     IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE
 };
 
@@ -113,8 +113,15 @@ struct TtmJob {
     int32_t* zero;         // nullable: `nzero` int32 the kernel clears (arrival counters of later launches)
     int nzero;
 };
+// stream_ok = false keeps the product on the tiled kernels (which can share a launch with a second product, make_ttm_duo)
+constexpr long long kStreamMinElems = 1LL << 20;
 bool make_ttm(DType xt, const void* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
-              long long ms_q, int r, float* Y, int beta, Item* out);
+              long long ms_q, int r, float* Y, int beta, Item* out, bool stream_ok = true);
+// the same product by the streaming kernel (asi_ttm_stream.hip); make_ttm picks it where it is supported and faster
+bool ttm_stream_supported(DType xt, const void* X, long long outer, int n, long long inner, const float* Mp,
+                          long long ms_i, long long ms_q, int r, const float* Y);
+bool make_ttm_stream(DType xt, const void* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
+                     long long ms_q, int r, float* Y, int beta, Item* out);
 bool make_ttm_kron(DType xt, const void* X, long long cols, int n1, int n2, const float* M1, long long ms1_i,
                    long long ms1_q, int r1, const float* M2, long long ms2_i, long long ms2_q, int r2, float* Y,
                    int beta, Item* out);
@@ -307,6 +314,7 @@ bool make_expand_grouped(const float* T, const float* U2, float* dW, int cout, i
 
 // per-kind batch launchers (called by launch_items)
 hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, char* label_out);
+hipError_t launch_ttm_stream_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_ttm_duo_items(const Item* const* items, int n, hipStream_t st, char* label_out);
 hipError_t launch_pair_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_sum_items(const Item* const* items, int n, hipStream_t st);

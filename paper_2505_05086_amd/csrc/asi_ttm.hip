@@ -509,8 +509,13 @@ static bool fill_ttm(DType xt, const void* X, long long outer, int n, long long 
 }
 
 bool make_ttm(DType xt, const void* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
-              long long ms_q, int r, float* Y, int beta, Item* out) {
+              long long ms_q, int r, float* Y, int beta, Item* out, bool stream_ok) {
     const KronSpec none = {nullptr, 0, 0, 1, 1};
+    const long long ncols = outer * inner;
+    const bool thin = n <= 16 && r <= 16 && ncols >= (1LL << 18);
+    // the streaming kernel pays once the tensor is large enough to keep the chip busy with its loads
+    if (stream_ok && inner > 1 && !thin && ncols * n >= kStreamMinElems && !prefer_ksplit(ncols, n, inner) && ttm_stream_supported(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y))
+        return make_ttm_stream(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, out);
     return fill_ttm(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, none, out);
 }
 

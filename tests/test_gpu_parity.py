@@ -210,6 +210,43 @@ def test_edge_conv_shapes(case, dtype):
         assert O.max_rel_err(Ah, A64) <= (1e-5 if dtype == "f32" else 1e-5)
 
 
+# Tensors of a million elements or more whose contiguous extent is a multiple of four take the streaming
+# mode product (16-byte loads straight into the MFMA operands).  Each case names the instantiation
+# <NBR, KW> it is meant to reach: NBR blocks of 16 outputs, KW waves sharing a span of 64 columns.  (The core
+# chain starts with the mode that shrinks the tensor most, so the ranks keep H and W nearly whole.)
+STREAM_CONV = [
+    # a mode of 20 (two rounds, the second padded) over 144000 columns, 562.5 workgroups of 256 columns
+    ((20, 16, 100, 90), (8, 8, 12, 12), 8, "1, 1"),
+    # 80 channels (five rounds over four waves: one wave has one round, one has none), 42000 columns = 656.25 spans
+    ((5, 80, 100, 84), (4, 24, 60, 56), 12, "2, 4"),
+    # 56 channels, 40 outputs (three blocks, the last half empty), two waves per span with two rounds each
+    ((4, 56, 72, 76), (4, 40, 60, 68), 6, "3, 2"),
+]
+
+
+@pytest.mark.parametrize("case", STREAM_CONV)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_streaming_mode_product(case, dtype):
+    from paper_2505_05086_amd import binding as B
+    dims, ranks, cout, variant = case
+    lay = Layer("stream", dims, ranks, dtype, "conv2d", cout, k=3, stride=1, pad=1, dil=1, groups=1,
+                alpha=0.7, noise=1e-2)
+    st = LayerStream(9, 2, lay)
+    run = _runner(lay)
+    tol = TOL[dtype]
+    A_t, A64, U_or = check_compress(run, lay, st.activation(0), st.u_prev0(), tol, f"stream {case}")
+    B.asi_profile_enable(True)
+    try:
+        check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), tol, f"stream {case}")
+        sites = list(B.asi_profile_report())
+    finally:
+        B.asi_profile_enable(False)
+    # (a bf16 tensor may take its first product along the last mode on the bf16 MFMA; the streaming product
+    # then meets the fp32 intermediate)
+    want = ["k_ttm_stream<%s, %s>" % (t, variant) for t in (["float"] if dtype == "f32" else ["asi::bf16_t", "float"])]
+    assert any(w in s_ for s_ in sites for w in want), (want, [s_ for s_ in sites if "ttm" in s_])
+
+
 EDGE_LINEAR = [((3, 5, 7), (2, 3, 4), 6), ((4, 9, 30), (4, 9, 30), 3), ((2, 33, 130), (1, 7, 20), 70),
                ((64, 1, 5), (3, 1, 2), 1), ((6, 50, 300), (3, 34, 100), 40),     # a rank above 64
                ((3, 20, 600), (2, 8, 24), 50),                                   # a last mode of 512 or more
