@@ -80,29 +80,6 @@ __global__ __launch_bounds__(PN_NT) void k_subspace_planes(Batch<PlanesJob> bt) 
     const int role = wv >> 2, slot = wv & 3;          // role 0: mode H (rows), role 1: mode W (cols)
     if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
 
-    // The factor as B operands of step A, kept in LDS in the order the lanes read it (registers are needed
-    // for P): element [ks][nb][lane] is
-    //   role 0: K slot (ks, lg) is row 4 ks + lg:                          U_H[4 ks + lg][16 nb + ll]
-    //   role 1: K slot (v, lg) of block cb, ks = 4 cb + v, is column 16 cb + 4 lg + v:  U_W[16 cb + 4 lg + v][16 nb + ll]
-    float* Us = pn_dyn + PN_PL * PF;                  // [2][4 NBM][NBR][64]
-    for (int e = tid; e < 2 * 4 * NBM * NBR * 64; e += PN_NT) {
-        const int l = e & 63, nb = (e >> 6) % NBR, ks = ((e >> 6) / NBR) % (4 * NBM), ro = (e >> 6) / (NBR * 4 * NBM);
-        const int g = l >> 4, c = l & 15;
-        const int i = ro ? 16 * (ks >> 2) + 4 * g + (ks & 3) : 4 * ks + g, q = 16 * nb + c;
-        const int nn = ro ? cols : rows, rr = jb.r[ro];
-        const bool ok = (i < nn) & (q < rr);
-        const float u = jb.U[ro][ok ? i * rr + q : 0];
-        Us[e] = ok ? u : 0.f;
-    }
-    const float* ureg = Us + role * (4 * NBM * NBR * 64) + lane;      // ureg[(ks * NBR + nb) * 64]
-    v4d pacc[NBM][NBR];
-#pragma unroll
-    for (int mb = 0; mb < NBM; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NBR; ++nb) pacc[mb][nb] = (v4d){0.0, 0.0, 0.0, 0.0};
-    // rows and columns beyond the plane stay zero for the whole kernel
-    for (int e = tid; e < PN_PL * PF; e += PN_NT) Xs[e] = 0.f;
-
     // A tile is moved in pieces of W consecutive elements of a plane row: W = 4 (one 16-byte load, 8 bytes for
     // bf16, and one 16-byte LDS store) when rows are a multiple of 4 long and X is aligned, else single
     // elements.  The piece -> (plane, row, column) arithmetic is per piece, so the wide form needs a quarter of
@@ -124,7 +101,33 @@ __global__ __launch_bounds__(PN_NT) void k_subspace_planes(Batch<PlanesJob> bt) 
             pre[u] = *reinterpret_cast<const typename PlaneVec<T, VEC>::type*>(src + (e < count ? e * W : 0));   // clamped, not branched: all loads stay in flight
         }
     };
-    if (lb < jb.ntiles) fetch(lb);
+    if (lb < jb.ntiles) fetch(lb);                    // on its way while the factors are staged
+
+    // The factor as B operands of step A, kept in LDS in the order the lanes read it (registers are needed
+    // for P): element [ks][nb][lane] is
+    //   role 0: K slot (ks, lg) is row 4 ks + lg:                          U_H[4 ks + lg][16 nb + ll]
+    //   role 1: K slot (v, lg) of block cb, ks = 4 cb + v, is column 16 cb + 4 lg + v:  U_W[16 cb + 4 lg + v][16 nb + ll]
+    float* Us = pn_dyn + PN_PL * PF;                  // [2][4 NBM][NBR][64]
+    for (int e = tid; e < 2 * 4 * NBM * NBR * 64; e += PN_NT) {
+        const int l = e & 63, nb = (e >> 6) % NBR, ks = ((e >> 6) / NBR) % (4 * NBM), ro = (e >> 6) / (NBR * 4 * NBM);
+        const int g = l >> 4, c = l & 15;
+        const int i = ro ? 16 * (ks >> 2) + 4 * g + (ks & 3) : 4 * ks + g, q = 16 * nb + c;
+        const int nn = ro ? cols : rows, rr = jb.r[ro];
+        const bool ok = (i < nn) & (q < rr);
+        const float u = jb.U[ro][ok ? i * rr + q : 0];
+        Us[e] = ok ? u : 0.f;
+    }
+    const float* ureg = Us + role * (4 * NBM * NBR * 64) + lane;      // ureg[(ks * NBR + nb) * 64]
+    v4d pacc[NBM][NBR];
+#pragma unroll
+    for (int mb = 0; mb < NBM; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NBR; ++nb) pacc[mb][nb] = (v4d){0.0, 0.0, 0.0, 0.0};
+    // rows and columns beyond the plane stay zero for the whole kernel (a plane that fills its blocks has none:
+    // the pitch's spare columns are never read)
+    if (rows < 16 * NBM || cols < 16 * NBM)
+        for (int e = tid; e < PN_PL * PF; e += PN_NT) Xs[e] = 0.f;
+
     for (long long t = lb; t < jb.ntiles; t += jb.nwg) {
         const long long p0 = t * PN_PL;
         const int np = (int)((jb.planes - p0 < PN_PL) ? jb.planes - p0 : PN_PL);
@@ -243,24 +246,23 @@ __global__ __launch_bounds__(PN_NT) void k_subspace_planes(Batch<PlanesJob> bt) 
             }
         }
     }
-    // The four waves of a mode add their P through LDS, one after the other (fixed order), mode H first.
+    // The four waves of a mode put their P side by side in LDS (in the space of the tiles) and all threads add
+    // the four in a fixed order, mode H first.
     // fp64 MFMA result layout: lane holds row lg + 4 v, column ll of its 16 x 16 block.
-    double* red = reinterpret_cast<double*>(pn_dyn);  // (16 NBM) x (16 NBR) doubles
+    constexpr int RED = 16 * NBM * RQ;                // doubles of one wave's P
+    static_assert(sizeof(double) * 4 * RED <= sizeof(float) * PN_PL * PF, "four partial P fit the tiles");
+    double* red = reinterpret_cast<double*>(pn_dyn);
 #pragma unroll
     for (int md = 0; md < 2; ++md) {
-        for (int w = 0; w < 4; ++w) {
-            __syncthreads();
-            if (role == md && slot == w) {
+        __syncthreads();                              // the tiles (or the other mode's P) are no longer read
+        if (role == md) {
 #pragma unroll
-                for (int mb = 0; mb < NBM; ++mb)
+            for (int mb = 0; mb < NBM; ++mb)
 #pragma unroll
-                    for (int nb = 0; nb < NBR; ++nb)
+                for (int nb = 0; nb < NBR; ++nb)
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            double* p = red + (16 * mb + lg + 4 * v) * RQ + 16 * nb + ll;
-                            *p = (w == 0) ? pacc[mb][nb][v] : *p + pacc[mb][nb][v];
-                        }
-            }
+                    for (int v = 0; v < 4; ++v)
+                        red[slot * RED + (16 * mb + lg + 4 * v) * RQ + 16 * nb + ll] = pacc[mb][nb][v];
         }
         __syncthreads();
         const int n = md ? cols : rows, r = jb.r[md];
@@ -268,7 +270,8 @@ __global__ __launch_bounds__(PN_NT) void k_subspace_planes(Batch<PlanesJob> bt) 
         const float inv_r = 1.0f / (float)r;
         for (int e = tid; e < n * r; e += PN_NT) {    // e < 2^11: exact
             const int i = (int)(((float)e + 0.5f) * inv_r), q = e - i * r;
-            out[e] = red[i * RQ + q];
+            const double* p = red + i * RQ + q;
+            out[e] = ((p[0] + p[RED]) + p[2 * RED]) + p[3 * RED];
         }
     }
 }
@@ -315,7 +318,6 @@ bool make_subspace_planes(DType xt, const void* X, long long planes, int rows, i
 template <typename T, int NBM, int NBR, bool VEC>
 static hipError_t launch_planes_one(const Batch<PlanesJob>& b, dim3 grid, hipStream_t st) {
     constexpr size_t lds = sizeof(float) * ((size_t)PN_PL * 16 * NBM * PN_LD + 2 * 4 * NBM * NBR * 64);
-    static_assert(lds >= sizeof(double) * 16 * NBM * 16 * NBR, "the reduction buffer fits the tile");
     if (lds > 65536) {                // more than a static array may take: allowed once per kernel
         static std::atomic<bool> allowed{false};
         if (!allowed.load()) {
