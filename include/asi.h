@@ -41,7 +41,9 @@ typedef enum {
     ASI_ERR_UNSUPPORTED = 2,   /* unknown dtype, size beyond an implementation limit */
     ASI_ERR_WORKSPACE = 3,     /* ws null, misaligned or smaller than asi_workspace_bytes() */
     ASI_ERR_HIP = 4,           /* a HIP runtime call failed (launch error) */
-    ASI_ERR_NUMERIC = 5        /* reserved: numeric breakdown is reported through *info */
+    ASI_ERR_NUMERIC = 5,       /* an iteration did not converge (asi_mode_spectrum); elsewhere numeric
+                                  breakdown is reported through *info */
+    ASI_ERR_INFEASIBLE = 6     /* asi_rank_select: no choice of ranks fits the budget */
 } asi_status;
 
 typedef enum { ASI_F32 = 0, ASI_BF16 = 1 } asi_dtype;   /* element type of A and grad_out */
@@ -188,6 +190,55 @@ asi_status asi_weight_grad_linear_batch(int32_t count, const asi_tensor_desc* de
                                         const int64_t* dout, float* const* dW,
                                         const int32_t* accumulate, void* const* ws, const size_t* ws_bytes,
                                         asi_stream_t stream);
+
+/* ---- Rank selection (Sec. 3.3): measurements made once, before training, to choose the ranks ---- */
+
+/* Eq. 5: elements kept for one layer, prod_m ranks[m] + sum_m dims[m] * ranks[m]; -1 if desc is invalid. */
+int64_t asi_activation_memory(const asi_tensor_desc* desc);
+
+/* Scratch bytes of asi_mode_spectrum for this mode (desc->ranks is not read); 0 if the descriptor or
+ * the mode is invalid or dims[mode] exceeds the limit of 512. */
+size_t asi_mode_spectrum_workspace_bytes(const asi_tensor_desc* desc, int32_t mode);
+
+/* Spectrum of one mode (App. A.2; Sec. 3.3, Step 1): the eigenvalues of A_m A_m^T, i.e. the squared
+ * singular values of the mode-m unfolding, and its eigenvectors, the principal components of the mode.
+ *   A             in  device, dims per desc, dtype per desc (desc->ranks is not read)
+ *   eigenvalues   out device fp64 (dims[mode]), descending
+ *   eigenvectors  out device fp32 (dims[mode] x dims[mode]) row-major, column k = k-th principal component,
+ *                 nullable; its first r columns are the factor of a truncated HOSVD of rank r.  A column
+ *                 whose eigenvalue is below 1e-12 of the largest is returned as zeros.
+ *   sweeps        out HOST int32 (nullable): Jacobi sweeps used, -1 if 60 sweeps did not converge
+ * Unlike every other entry point this one WAITS for the stream: it iterates to convergence and reads
+ * the iteration's state after every sweep.  dims[mode] <= 512 (ASI_ERR_UNSUPPORTED beyond);
+ * ASI_ERR_NUMERIC if the iteration did not converge (the outputs then hold its last state). */
+asi_status asi_mode_spectrum(const asi_tensor_desc* desc, const void* A, int32_t mode, double* eigenvalues,
+                             float* eigenvectors, void* ws, size_t ws_bytes, int32_t* sweeps,
+                             asi_stream_t stream);
+
+/* Sec. 3.3, Step 1: for each threshold eps[j] (HOST array, 0 < eps <= 1, n_eps <= 16) the smallest
+ * r >= 1 with sum_{k <= r} lambda_k >= eps[j] * sum_k lambda_k.
+ *   eigenvalues in  device fp64 (n), descending (asi_mode_spectrum's output)
+ *   ranks       out device int32 (n_eps) */
+asi_status asi_explained_variance_ranks(const double* eigenvalues, int32_t n, const double* eps, int32_t n_eps,
+                                        int32_t* ranks, asi_stream_t stream);
+
+/* Eq. 7, the perplexity of a layer at one threshold: *out = || a - b ||_F in fp64.
+ *   a, b  in  device fp32 (count): the exact weight gradient and the one computed from the compressed
+ *             activation (asi_weight_grad_* on the truncated eigenvectors and their core)
+ *   out   out device fp64 (1)
+ *   ws    scratch of at least ASI_FROBENIUS_WS_BYTES bytes, 256-byte aligned */
+#define ASI_FROBENIUS_WS_BYTES 8192
+asi_status asi_frobenius_diff(const float* a, const float* b, int64_t count, double* out, void* ws,
+                              size_t ws_bytes, asi_stream_t stream);
+
+/* Eq. 8-9: one threshold index per layer, choice[i] in [0, n_eps), that minimises sum_i P[i, choice[i]]
+ * subject to sum_i M[i, choice[i]] <= budget, by recursive backtracking (exhaustive up to bounds that
+ * cannot change the result; among equal totals the lexicographically first choice).  HOST code on
+ * HOST arrays: P, M row-major (n_layers x n_eps), P >= 0 finite, M >= 0 (Eq. 5, in elements);
+ * n_layers <= 64, n_eps <= 16.  total (nullable) receives the minimum.  ASI_ERR_INFEASIBLE if no
+ * choice fits the budget (choice is then untouched). */
+asi_status asi_rank_select(int32_t n_layers, int32_t n_eps, const double* P, const int64_t* M, int64_t budget,
+                           int32_t* choice, double* total);
 
 /* Static, human-readable name of a status code. */
 const char* asi_status_string(asi_status s);

@@ -17,7 +17,7 @@ from .build import LIB_PATH
 
 ASI_OK = 0
 STATUS_NAMES = {0: "ASI_OK", 1: "ASI_ERR_INVALID_ARG", 2: "ASI_ERR_UNSUPPORTED",
-                3: "ASI_ERR_WORKSPACE", 4: "ASI_ERR_HIP", 5: "ASI_ERR_NUMERIC"}
+                3: "ASI_ERR_WORKSPACE", 4: "ASI_ERR_HIP", 5: "ASI_ERR_NUMERIC", 6: "ASI_ERR_INFEASIBLE"}
 ASI_F32, ASI_BF16 = 0, 1
 
 STATIC_SCRATCH_BYTES = 16 << 20      # ASI_STATIC_SCRATCH_BYTES of include/asi.h
@@ -25,7 +25,9 @@ STATIC_SCRATCH_BYTES = 16 << 20      # ASI_STATIC_SCRATCH_BYTES of include/asi.h
 EXPORTS = ["asi_workspace_bytes", "asi_compress", "asi_compress_cold", "asi_cold_start_matrix", "asi_compress_static", "asi_core_project", "asi_weight_grad_conv2d",
            "asi_weight_grad_linear", "asi_compress_batch", "asi_core_project_batch",
            "asi_weight_grad_conv2d_batch", "asi_weight_grad_linear_batch", "asi_status_string", "asi_version",
-           "asi_profile_enable", "asi_profile_report"]
+           "asi_profile_enable", "asi_profile_report", "asi_activation_memory", "asi_mode_spectrum_workspace_bytes",
+           "asi_mode_spectrum", "asi_explained_variance_ranks", "asi_frobenius_diff", "asi_rank_select"]
+FROBENIUS_WS_BYTES = 8192            # ASI_FROBENIUS_WS_BYTES of include/asi.h
 MAX_BATCH = 8
 
 
@@ -96,6 +98,20 @@ def lib() -> C.CDLL:
         L.asi_profile_enable.argtypes = [C.c_int32]
         L.asi_profile_report.restype = C.c_int64
         L.asi_profile_report.argtypes = [C.c_char_p, C.c_int64]
+        L.asi_activation_memory.restype = C.c_int64
+        L.asi_activation_memory.argtypes = [C.POINTER(TensorDesc)]
+        L.asi_mode_spectrum_workspace_bytes.restype = C.c_size_t
+        L.asi_mode_spectrum_workspace_bytes.argtypes = [C.POINTER(TensorDesc), C.c_int32]
+        L.asi_mode_spectrum.restype = C.c_int
+        L.asi_mode_spectrum.argtypes = [C.POINTER(TensorDesc), vp, C.c_int32, vp, vp, vp, C.c_size_t,
+                                        C.POINTER(C.c_int32), vp]
+        L.asi_explained_variance_ranks.restype = C.c_int
+        L.asi_explained_variance_ranks.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.c_int32, vp, vp]
+        L.asi_frobenius_diff.restype = C.c_int
+        L.asi_frobenius_diff.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_size_t, vp]
+        L.asi_rank_select.restype = C.c_int
+        L.asi_rank_select.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int64,
+                                      C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -301,6 +317,61 @@ def asi_status_string(status: int) -> str:
 
 def asi_version() -> int:
     return int(lib().asi_version())
+
+
+def asi_activation_memory(desc: TensorDesc) -> int:
+    """Eq. 5 in elements."""
+    v = int(lib().asi_activation_memory(C.byref(desc)))
+    if v < 0:
+        raise AsiError(1, "asi_activation_memory")
+    return v
+
+
+def asi_mode_spectrum_workspace_bytes(desc: TensorDesc, mode: int) -> int:
+    return int(lib().asi_mode_spectrum_workspace_bytes(C.byref(desc), int(mode)))
+
+
+def asi_mode_spectrum(desc: TensorDesc, A: torch.Tensor, mode: int, eigenvalues: torch.Tensor,
+                      eigenvectors: Optional[torch.Tensor], ws: torch.Tensor) -> int:
+    """Eigenvalues (fp64, descending) and eigenvectors (fp32, columns) of A_m A_m^T.  Waits for the stream.
+    Returns the number of Jacobi sweeps."""
+    _check_dev(A, eigenvalues, eigenvectors, ws)
+    if eigenvalues.dtype != torch.float64 or (eigenvectors is not None and eigenvectors.dtype != torch.float32):
+        raise ValueError("eigenvalues are fp64, eigenvectors fp32")
+    sweeps = C.c_int32(0)
+    _check(lib().asi_mode_spectrum(C.byref(desc), _ptr(A), int(mode), _ptr(eigenvalues), _ptr(eigenvectors), _ptr(ws),
+                                   ws.numel(), C.byref(sweeps), _stream()), "asi_mode_spectrum")
+    return int(sweeps.value)
+
+
+def asi_explained_variance_ranks(eigenvalues: torch.Tensor, eps: Sequence[float], ranks: torch.Tensor) -> None:
+    _check_dev(eigenvalues, ranks)
+    if eigenvalues.dtype != torch.float64 or ranks.dtype != torch.int32 or ranks.numel() < len(eps):
+        raise ValueError("eigenvalues are fp64, ranks int32 with one entry per threshold")
+    arr = (C.c_double * len(eps))(*[float(e) for e in eps])
+    _check(lib().asi_explained_variance_ranks(_ptr(eigenvalues), eigenvalues.numel(), arr, len(eps), _ptr(ranks),
+                                              _stream()), "asi_explained_variance_ranks")
+
+
+def asi_frobenius_diff(a: torch.Tensor, b: torch.Tensor, out: torch.Tensor, ws: torch.Tensor) -> None:
+    _check_dev(a, b, out, ws)
+    if a.dtype != torch.float32 or b.dtype != torch.float32 or out.dtype != torch.float64 or a.numel() != b.numel():
+        raise ValueError("two fp32 tensors of one size, fp64 result")
+    _check(lib().asi_frobenius_diff(_ptr(a), _ptr(b), a.numel(), _ptr(out), _ptr(ws), ws.numel(), _stream()),
+           "asi_frobenius_diff")
+
+
+def asi_rank_select(P, M, budget: int):
+    """Eq. 8-9 on host tables P, M (layers x thresholds, nested sequences).  Returns (choice per layer, total)."""
+    n, e = len(P), len(P[0])
+    if any(len(row) != e for row in P) or len(M) != n or any(len(row) != e for row in M):
+        raise ValueError("P and M are (layers x thresholds)")
+    Pa = (C.c_double * (n * e))(*[float(x) for row in P for x in row])
+    Ma = (C.c_int64 * (n * e))(*[int(x) for row in M for x in row])
+    choice = (C.c_int32 * n)()
+    total = C.c_double(0.0)
+    _check(lib().asi_rank_select(n, e, Pa, Ma, int(budget), choice, C.byref(total)), "asi_rank_select")
+    return [int(c) for c in choice], float(total.value)
 
 
 def asi_profile_enable(on: bool) -> bool:

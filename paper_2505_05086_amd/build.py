@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libasi_hip.so")
-SOURCES = ["asi_api.hip", "asi_kernels.hip", "asi_subspace.hip", "asi_long.hip", "asi_planes.hip", "asi_bf16.hip", "asi_gram.hip", "asi_orth.hip", "asi_ttm.hip", "asi_ttm_stream.hip", "asi_corr.hip"]
+SOURCES = ["asi_api.hip", "asi_kernels.hip", "asi_subspace.hip", "asi_long.hip", "asi_planes.hip", "asi_bf16.hip", "asi_gram.hip", "asi_orth.hip", "asi_ttm.hip", "asi_ttm_stream.hip", "asi_corr.hip", "asi_rank.hip"]
 # packed-fp32 VALU forms are switched off for every HIP translation unit
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

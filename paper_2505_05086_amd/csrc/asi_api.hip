@@ -801,7 +801,7 @@ asi_status static_scratch(void** out) {
 
 extern "C" {
 
-int32_t asi_version(void) { return 1001; }
+int32_t asi_version(void) { return 1002; }
 
 int32_t asi_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
@@ -846,6 +846,7 @@ const char* asi_status_string(asi_status s) {
         case ASI_ERR_WORKSPACE: return "ASI_ERR_WORKSPACE";
         case ASI_ERR_HIP: return "ASI_ERR_HIP";
         case ASI_ERR_NUMERIC: return "ASI_ERR_NUMERIC";
+        case ASI_ERR_INFEASIBLE: return "ASI_ERR_INFEASIBLE";
     }
     return "ASI_ERR_UNKNOWN";
 }
