@@ -10,13 +10,16 @@
 // Gram-Schmidt produces.  Its diagonal is the norm each column keeps after the earlier ones
 // are projected out; a column keeping less than 1e-12 ||P||_F is reported through *info.
 //
-// Fast path (r <= 64), five launches that serve all modes of a tensor at once:
-//   gram0 : row slices of 32 rows: sum the split partial sums of P -> P64, slice Gram (fp64 MFMA)
-//   chol  : one workgroup per mode: sum slice Grams (+ shift), Cholesky in LDS, invert the
-//           16x16 diagonal blocks of R
-//   apply : row slices: Q = P R^-1 by block forward substitution (fp64 MFMA), next slice Gram
-//   chol, apply (final: writes fp32 U)
-// Slow path (r > 64): one workgroup per mode, everything in global memory.
+// Fast path (r <= 64), two launches that serve all modes of a tensor at once:
+//   gram0 : row slices of 32 rows sum the split partial sums of P -> P64 and write their slice Gram
+//           (fp64 MFMA); the workgroup that arrives last at the mode's counter sums the slice Grams and
+//           factors: blocked Cholesky in LDS without a shift, with the shift only if a pivot is lost;
+//           it also inverts the 16x16 diagonal blocks of R
+//   apply : row slices: Q0 = P R^-1 by block forward substitution (fp64 MFMA), written in fp64 and as
+//           the fp32 result, plus the slice Gram of Q0; the last-arriving workgroup measures
+//           |Q0^T Q0 - I| and only if that exceeds OP_DONE_TOL runs the second pass by itself
+// Wide path (64 < r <= 192): separate Gram / Cholesky / apply launches on the packed triangle.
+// Slow path (r > 192): one workgroup per mode, everything in global memory.
 #include "asi_device.h"
 #include "asi_kernels.h"
 
