@@ -9,11 +9,14 @@
  *       (Alg. 1's core update; Eq. 3, Eq. 4),
  *   (3) in the backward pass computes the conv2d / linear weight gradient from
  *       core + factors without rebuilding the activation (App. A.3, Eq. 14).
+ * Before training, the ranks of every layer are chosen from measurements on a
+ * batch of activations (Sec. 3.3): the entry points at the end of this header.
  *
  * Conventions shared by every entry point
  *   - Every data pointer is caller-owned DEVICE memory on the current HIP
  *     device.  The library allocates nothing, keeps no state between calls and
- *     only enqueues kernels on `stream`; it never synchronises with the host.
+ *     only enqueues kernels on `stream`; it never synchronises with the host
+ *     (one exception, stated there: asi_mode_spectrum).
  *   - Activation `A` and output gradient `grad_out`: dense row-major, (B,C,H,W)
  *     or (B,N,D); element type given by asi_tensor_desc.dtype (fp32, or bf16
  *     with fp32 accumulation).

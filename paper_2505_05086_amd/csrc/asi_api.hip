@@ -292,6 +292,7 @@ bool parse_conv(const Shape& s, const asi_conv2d_desc* cv, ConvGeom* out) {
 
 struct ConvPlan {
     float *G1 = nullptr, *Z1 = nullptr, *Z = nullptr, *Tpart = nullptr, *T = nullptr;
+    float* S1 = nullptr;             // r1 = B: the core expanded along the batch mode (see build_conv)
     int nsplit = 1;
     size_t bytes = 0;
 };
@@ -301,6 +302,7 @@ ConvPlan plan_conv(const Shape& s, const ConvGeom& cg, void* ws) {
     const CorrGeom& g = cg.g;
     Carver c(ws);
     p.G1 = c.take<float>((size_t)g.r1 * g.cout * g.Ho * g.Wo);
+    if (g.r1 == cg.B) p.S1 = c.take<float>((size_t)cg.B * g.r2 * s.r[2] * s.r[3]);
     if ((long long)s.r[2] * s.r[3] > kKronMaxN || (long long)g.H * g.W > kKronMaxOut)
         p.Z1 = c.take<float>((size_t)g.r1 * g.r2 * g.H * s.r[3]);      // else Z comes from one merged pass
     p.Z = c.take<float>((size_t)g.r1 * g.r2 * g.H * g.W);
@@ -315,6 +317,7 @@ ConvPlan plan_conv(const Shape& s, const ConvGeom& cg, void* ws) {
 // ---- linear weight gradient --------------------------------------------------------
 struct LinPlan {
     float *G1 = nullptr, *G2 = nullptr, *T = nullptr;
+    float* S1 = nullptr;             // r1 = B: the core expanded along the batch mode (see build_linear)
     double* Tpart = nullptr;
     int nsplit = 1;
     size_t bytes = 0;
@@ -325,6 +328,7 @@ LinPlan plan_linear(const Shape& s, long long dout, void* ws) {
     Carver c(ws);
     p.G1 = c.take<float>((size_t)s.r[0] * s.n[1] * dout);
     p.G2 = c.take<float>((size_t)s.r[0] * s.r[1] * dout);
+    if (s.r[0] == s.n[0]) p.S1 = c.take<float>((size_t)s.n[0] * s.r[1] * s.r[2]);
     p.nsplit = pair_splits((long long)s.r[0] * s.r[1], (int)dout, 1, s.r[2]);
     p.T = c.take<float>((size_t)dout * s.r[2]);
     p.Tpart = c.take<double>((size_t)p.nsplit * dout * s.r[2]);
@@ -705,30 +709,44 @@ asi_status build_conv(const asi_tensor_desc* desc, const float* S, const float* 
     const int r3 = s.r[2], r4 = s.r[3];
     const int taps = g.kh * g.kw;
 
-    // 1. G1 = grad_out x_1 U1^T                                   (r1, cout, Ho, Wo)
-    // (where Z comes from one merged product it can share G1's launch: G1 then stays on the tiled kernel)
-    ASI_TRYS(add_ttm(pg, "G1", s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0,
-                     p.Z1 != nullptr));
+    // With r1 = B the batch factor is square: G1 would be as large as grad_out, and forming it saves the
+    // correlation nothing.  The same sum with the parentheses moved expands the small core instead,
+    //     T = sum_i (sum_b U1[b,i] dY[b]) * Z[i] = sum_b dY[b] * Z'[b],   Z' from S1 = S x_1 U1   (B, r2, r3, r4),
+    // and the correlation reads grad_out itself (fp32 data, aligned for its 16-byte loads).
+    const bool expand_core = p.S1 && s.dt == F32 && reinterpret_cast<uintptr_t>(grad_out) % 16 == 0;
+    const float* Sz = S;
+    const float* G1 = p.G1;
+    if (expand_core) {
+        // 1'. S1[b,...] = sum_i U1[b,i] S[i,...]
+        ASI_TRYS(add_ttm(pg, "S1", F32, S, 1, g.r1, (long long)g.r2 * r3 * r4, U[0], 1, g.r1, cg.B, p.S1, 0));
+        Sz = p.S1;
+        G1 = static_cast<const float*>(grad_out);
+    } else {
+        // 1. G1 = grad_out x_1 U1^T                                   (r1, cout, Ho, Wo)
+        // (where Z comes from one merged product it can share G1's launch: G1 then stays on the tiled kernel)
+        ASI_TRYS(add_ttm(pg, "G1", s.dt, grad_out, 1, cg.B, (long long)g.cout * g.Ho * g.Wo, U[0], g.r1, 1, g.r1, p.G1, 0,
+                         p.Z1 != nullptr));
+    }
     if (!p.Z1) {
         // 2+3. Z = S x_3 U3 x_4 U4 in one pass:  M(a*r4 + b, h*W + w) = U3[h,a] * U4[w,b]   (r1, r2, H, W)
-        ASI_TRYS(add_ttm_kron(pg, "Z", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, U[3], 1, r4, g.W, p.Z));
+        ASI_TRYS(add_ttm_kron(pg, "Z", F32, Sz, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, U[3], 1, r4, g.W, p.Z));
         // G1 and Z do not depend on each other: one launch for both when their kernels allow it
         Item duo;
         const size_t ni = pg.items.size();
-        if (make_ttm_duo(pg.items[ni - 2], pg.items[ni - 1], &duo)) {
+        if (!expand_core && make_ttm_duo(pg.items[ni - 2], pg.items[ni - 1], &duo)) {
             pg.items.pop_back();
             pg.items.back() = duo;
         }
     } else {
         // 2. Z1 = S x_3 U3                                        (r1, r2, H, r4)
-        ASI_TRYS(add_ttm(pg, "Z1", F32, S, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0));
+        ASI_TRYS(add_ttm(pg, "Z1", F32, Sz, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0));
         // 3. Z = Z1 x_4 U4                                        (r1, r2, H, W)
         ASI_TRYS(add_ttm(pg, "Z", F32, p.Z1, (long long)g.r1 * g.r2 * g.H, r4, 1, U[3], 1, r4, g.W, p.Z, 0));
     }
     // 4. T = correlation of Zpad with G1 over (r1, Ho, Wo)        (cout, r2, kh, kw)
     const double tsz = (double)g.cout * g.r2 * taps;
     ASI_ADD(pg, "", 4.0 * ((double)g.r1 * g.cout * g.Ho * g.Wo + (double)g.r1 * g.r2 * g.H * g.W + tsz * p.nsplit),
-            2.0 * g.r1 * g.Ho * g.Wo * tsz, make_corr(p.G1, p.Z, p.Tpart, g, p.nsplit, it__));
+            2.0 * g.r1 * g.Ho * g.Wo * tsz, make_corr(G1, p.Z, p.Tpart, g, p.nsplit, it__));
     if (p.nsplit > 1)
         ASI_ADD(pg, "", 4.0 * tsz * (p.nsplit + 1), tsz * p.nsplit,
                 make_sum_partials(p.Tpart, p.nsplit, (long long)g.cout * g.r2 * taps, p.T, 0, it__));
@@ -758,12 +776,21 @@ asi_status build_linear(const asi_tensor_desc* desc, const float* S, const float
     const int B = (int)s.n[0], N = (int)s.n[1], D = (int)s.n[2];
     const int r1 = s.r[0], r2 = s.r[1], r3 = s.r[2];
 
-    // 1. G1[i,n,o] = sum_b U1[b,i] dY[b,n,o]
-    ASI_TRYS(add_ttm(pg, "G1", s.dt, grad_out, 1, B, (long long)N * dout, U[0], r1, 1, r1, p.G1, 0));
-    // 2. G2[i,j,o] = sum_n U2[n,j] G1[i,n,o]
-    ASI_TRYS(add_ttm(pg, "G2", F32, p.G1, r1, N, dout, U[1], r2, 1, r2, p.G2, 0));
+    const float* Sz = S;
+    if (p.S1) {
+        // r1 = B: U1 is square and G1 would be as large as grad_out.  The sum over the batch mode is moved to
+        // the small core instead: S1[b,j,k] = sum_i U1[b,i] S[i,j,k], and step 2 reads grad_out itself.
+        ASI_TRYS(add_ttm(pg, "S1", F32, S, 1, r1, (long long)r2 * r3, U[0], 1, r1, B, p.S1, 0));
+        ASI_TRYS(add_ttm(pg, "G2", s.dt, grad_out, B, N, dout, U[1], r2, 1, r2, p.G2, 0));
+        Sz = p.S1;
+    } else {
+        // 1. G1[i,n,o] = sum_b U1[b,i] dY[b,n,o]
+        ASI_TRYS(add_ttm(pg, "G1", s.dt, grad_out, 1, B, (long long)N * dout, U[0], r1, 1, r1, p.G1, 0));
+        // 2. G2[i,j,o] = sum_n U2[n,j] G1[i,n,o]
+        ASI_TRYS(add_ttm(pg, "G2", F32, p.G1, r1, N, dout, U[1], r2, 1, r2, p.G2, 0));
+    }
     // 3. T[o,k] = sum_{i,j} G2[i,j,o] S[i,j,k]
-    ASI_TRYS(add_pair(pg, "T", F32, p.G2, (long long)r1 * r2, (int)dout, 1, S, r3, p.Tpart, p.nsplit, nullptr, 0));
+    ASI_TRYS(add_pair(pg, "T", F32, p.G2, (long long)r1 * r2, (int)dout, 1, Sz, r3, p.Tpart, p.nsplit, nullptr, 0));
     const double tsz = (double)dout * r3;
     ASI_ADD(pg, "", tsz * (8.0 * p.nsplit + 4.0), tsz * p.nsplit,
             make_sum_partials_f64(p.Tpart, p.nsplit, (long long)dout * r3, p.T, 0, it__));

@@ -381,6 +381,7 @@ asi_status asi_mode_spectrum(const asi_tensor_desc* desc, const void* A, int32_t
         hipLaunchKernelGGL(k_set_i32, dim3(1), 64, 0, st, rot, 0);
         for (int round = 0; round < n2 - 1; ++round)
             hipLaunchKernelGGL(k_jacobi_round, dim3((unsigned)npairs), 64, 0, st, W, n, round, tol, rot);
+        if (hipGetLastError() != hipSuccess) return ASI_ERR_HIP;
         int32_t h = -1;
         if (hipMemcpyAsync(&h, rot, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess) return ASI_ERR_HIP;
         if (hipStreamSynchronize(st) != hipSuccess) return ASI_ERR_HIP;

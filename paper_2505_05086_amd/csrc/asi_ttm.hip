@@ -514,7 +514,9 @@ bool make_ttm(DType xt, const void* X, long long outer, int n, long long inner, 
     const long long ncols = outer * inner;
     const bool thin = n <= 16 && r <= 16 && ncols >= (1LL << 18);
     // the streaming kernel pays once the tensor is large enough to keep the chip busy with its loads
-    if (stream_ok && inner > 1 && !thin && ncols * n >= kStreamMinElems && !prefer_ksplit(ncols, n, inner) && ttm_stream_supported(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y))
+    // (the split kernel's 16-column workgroups spread few columns further: it keeps the products below 256 spans)
+    if (stream_ok && inner > 1 && !thin && ncols * n >= kStreamMinElems && (ncols >= 256 * 64 || !prefer_ksplit(ncols, n, inner)) &&
+        ttm_stream_supported(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y))
         return make_ttm_stream(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, out);
     return fill_ttm(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y, beta, none, out);
 }

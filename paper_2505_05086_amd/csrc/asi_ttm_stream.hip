@@ -10,7 +10,7 @@
 // then hold, for output q = 16 nb + ll, the 16 consecutive columns 16 lg .. 16 lg + 15, which go to Y as
 // 16-byte stores in runs of 256 bytes.
 //
-// The matrix (n x r, at most 64 KB padded) is staged once per workgroup in LDS, permuted so that one
+// The matrix (n x r, at most 96 KB padded) is staged once per workgroup in LDS, permuted so that one
 // 16-byte read gives a lane its B operands of four K steps (a round of 16 rows).
 //
 // KW waves share a span and split the rounds between them (their partial tiles are added through LDS,
@@ -19,6 +19,7 @@
 #include "asi_device.h"
 #include "asi_kernels.h"
 
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 #include <type_traits>
@@ -28,7 +29,7 @@ namespace asi {
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int TS_RP = 68;                 // pitch of a partial tile's row (64 columns) in floats
-constexpr size_t TS_LDS_MAX = 64 * 1024;
+constexpr size_t TS_LDS_MAX = 96 * 1024;     // of the CU's 160 KB: a 512-long mode with 32 outputs takes 66 KB
 
 extern __shared__ __align__(16) float ts_dyn[];
 
@@ -247,19 +248,33 @@ bool make_ttm_stream(DType xt, const void* X, long long outer, int n, long long 
     return true;
 }
 
+template <typename T, int NBR, int KW>
+static hipError_t launch_stream_one(const Batch<TtmJob>& b, dim3 grid, size_t lds, hipStream_t st) {
+    if (lds > 65536) {                // more than a static array may take: allowed once per kernel
+        static std::atomic<bool> allowed{false};
+        if (!allowed.load()) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_ttm_stream<T, NBR, KW>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)TS_LDS_MAX);
+            if (e != hipSuccess) return e;
+            allowed.store(true);
+        }
+    }
+    hipLaunchKernelGGL((k_ttm_stream<T, NBR, KW>), grid, 256, lds, st, b);
+    return hipGetLastError();
+}
 template <typename T, int NBR>
-static void launch_stream_kw(int kw, const Batch<TtmJob>& b, dim3 grid, size_t lds, hipStream_t st) {
-    if (kw == 1) hipLaunchKernelGGL((k_ttm_stream<T, NBR, 1>), grid, 256, lds, st, b);
-    else if (kw == 2) hipLaunchKernelGGL((k_ttm_stream<T, NBR, 2>), grid, 256, lds, st, b);
-    else hipLaunchKernelGGL((k_ttm_stream<T, NBR, 4>), grid, 256, lds, st, b);
+static hipError_t launch_stream_kw(int kw, const Batch<TtmJob>& b, dim3 grid, size_t lds, hipStream_t st) {
+    if (kw == 1) return launch_stream_one<T, NBR, 1>(b, grid, lds, st);
+    if (kw == 2) return launch_stream_one<T, NBR, 2>(b, grid, lds, st);
+    return launch_stream_one<T, NBR, 4>(b, grid, lds, st);
 }
 template <typename T>
-static void launch_stream_t(int nbr, int kw, const Batch<TtmJob>& b, dim3 grid, size_t lds, hipStream_t st) {
+static hipError_t launch_stream_t(int nbr, int kw, const Batch<TtmJob>& b, dim3 grid, size_t lds, hipStream_t st) {
     switch (nbr) {
-        case 1: launch_stream_kw<T, 1>(kw, b, grid, lds, st); break;
-        case 2: launch_stream_kw<T, 2>(kw, b, grid, lds, st); break;
-        case 3: launch_stream_kw<T, 3>(kw, b, grid, lds, st); break;
-        default: launch_stream_kw<T, 4>(kw, b, grid, lds, st); break;
+        case 1: return launch_stream_kw<T, 1>(kw, b, grid, lds, st);
+        case 2: return launch_stream_kw<T, 2>(kw, b, grid, lds, st);
+        case 3: return launch_stream_kw<T, 3>(kw, b, grid, lds, st);
+        default: return launch_stream_kw<T, 4>(kw, b, grid, lds, st);
     }
 }
 
@@ -277,9 +292,8 @@ hipError_t launch_ttm_stream_items(const Item* const* items, int n, hipStream_t 
         lds = l > lds ? l : lds;
     }
     if (lds > TS_LDS_MAX) return hipErrorInvalidValue;
-    if (key & 1u) launch_stream_t<bf16_t>(nbr, kw, b, grid, lds, st);
-    else launch_stream_t<float>(nbr, kw, b, grid, lds, st);
-    return hipGetLastError();
+    if (key & 1u) return launch_stream_t<bf16_t>(nbr, kw, b, grid, lds, st);
+    return launch_stream_t<float>(nbr, kw, b, grid, lds, st);
 }
 
 }  // namespace asi
