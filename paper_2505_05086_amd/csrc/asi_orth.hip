@@ -253,27 +253,38 @@ __device__ bool chol_job(const OrthJob& jb, int pass, int last, int32_t* info, C
     const int n = jb.n, r = jb.r, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
     const int nb = (r + 15) / 16;
-    // sum of the slice Grams (packed upper triangles): ITS elements per thread, SB slices per
-    // round, all ITS * SB loads of a round in flight together
+    // sum of the slice Grams (packed upper triangles), slice after slice in their order: a round keeps up
+    // to 48 loads per thread in flight (a round is one dependent trip to memory, and a long mode has a
+    // hundred slices and more): IA elements per thread x SBX slices, IA = what the rank needs of the ITS
+    // elements the launch's largest rank would
     constexpr int ITS = (RM * (RM + 1) / 2 + 255) / 256;
-    constexpr int SB = (96 / ITS) > 16 ? 16 : (96 / ITS);
     const int T = (r * (r + 1)) / 2;
     double sum[ITS];
 #pragma unroll
     for (int it = 0; it < ITS; ++it) sum[it] = 0.0;
-    for (int b0 = 0; b0 < jb.nblk; b0 += SB) {
-        double t[SB][ITS];
+    auto sum_slices = [&](auto ia_c, auto sb_c) __attribute__((always_inline)) {
+        constexpr int IA = decltype(ia_c)::value, SBX = decltype(sb_c)::value;
+        for (int b0 = 0; b0 < jb.nblk; b0 += SBX) {
+            double t[SBX][IA];
 #pragma unroll
-        for (int u = 0; u < SB; ++u)
+            for (int u = 0; u < SBX; ++u)
 #pragma unroll
-            for (int it = 0; it < ITS; ++it) {
-                const int e = tid + 256 * it;
-                t[u][it] = ldg_f64(jb.Gpart, (long long)(b0 + u) * T + e, e < T && b0 + u < jb.nblk);
-            }
+                for (int it = 0; it < IA; ++it) {
+                    const int e = tid + 256 * it;
+                    t[u][it] = ldg_f64(jb.Gpart, (long long)(b0 + u) * T + e, e < T && b0 + u < jb.nblk);
+                }
 #pragma unroll
-        for (int u = 0; u < SB; ++u)
+            for (int u = 0; u < SBX; ++u)
 #pragma unroll
-            for (int it = 0; it < ITS; ++it) sum[it] += t[u][it];
+                for (int it = 0; it < IA; ++it) sum[it] += t[u][it];
+        }
+    };
+    {
+        const int ia = (T + 255) / 256;
+        constexpr int SB = (96 / ITS) > 16 ? 16 : (96 / ITS);
+        if (ia == 1) sum_slices(std::integral_constant<int, 1>{}, std::integral_constant<int, 48>{});
+        else if (ITS >= 2 && ia == 2) sum_slices(std::integral_constant<int, (ITS >= 2 ? 2 : 1)>{}, std::integral_constant<int, 24>{});
+        else sum_slices(std::integral_constant<int, ITS>{}, std::integral_constant<int, SB>{});
     }
     // Gs = the summed Gram matrix, padded with the identity up to a multiple of 16
     auto scatter = [&]() {
