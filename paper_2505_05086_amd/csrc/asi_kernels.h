@@ -19,7 +19,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
-    IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO, IT_TTM_STREAM,
+    IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO, IT_TTM_STREAM, IT_TTM_EXPAND,
     IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE
 };
 
@@ -315,6 +315,7 @@ bool make_expand_grouped(const float* T, const float* U2, float* dW, int cout, i
 // per-kind batch launchers (called by launch_items)
 hipError_t launch_ttm_items(const Item* const* items, int n, hipStream_t st, char* label_out);
 hipError_t launch_ttm_stream_items(const Item* const* items, int n, hipStream_t st);
+hipError_t launch_ttm_expand_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_ttm_duo_items(const Item* const* items, int n, hipStream_t st, char* label_out);
 hipError_t launch_pair_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_sum_items(const Item* const* items, int n, hipStream_t st);

@@ -442,6 +442,93 @@ __global__ __launch_bounds__(256) void k_ttm_thin(Batch<TtmJob> bt) {
             }
 }
 
+// ---- a short last mode expanded to many outputs, on the vector ALU ------------------------------
+// Y[c, q] (+)= sum_k X[c, k] M(k, q) with at most 32 terms and 256 or more outputs per column: the last
+// step of the linear weight gradient (dW = T U_3^T: rank 20, thousands of features).  The output is the
+// only large tensor, so the kernel is built around its stores: a workgroup owns 32 columns x 256 outputs,
+// lane l holds the four consecutive outputs 4 l .. 4 l + 3 of eight columns, and every store instruction of
+// a wave writes 1 KB of one output row.  M's tile sits in LDS as Ms[k][q] (one 16-byte read per term), X's
+// tile as Xs[c][k] (every lane of a wave reads the same word).
+constexpr int EX_C = 32, EX_Q = 256, EX_K = 32;
+__global__ __launch_bounds__(256) void k_ttm_expand(Batch<TtmJob> bt) {
+    __shared__ __align__(16) float Ms[EX_K][EX_Q + 4];
+    __shared__ float Xs[EX_C][EX_K + 1];
+    int lb;
+    const TtmJob& jb = bt.job[locate(bt, &lb)];
+    const float* __restrict__ X = static_cast<const float*>(jb.X);
+    const float* __restrict__ Mp = jb.Mp;
+    float* __restrict__ Y = jb.Y;
+    const long long ncols = jb.outer, ms_i = jb.ms_i, ms_q = jb.ms_q;
+    const int n = jb.n, r = jb.r, beta = jb.beta;
+    const int bx = lb / jb.gy, by = lb - bx * jb.gy;
+    const long long c0 = (long long)bx * EX_C;
+    const int q0 = by * EX_Q;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
+    // tiles: consecutive threads along the index that is contiguous in memory; every load of the workgroup is
+    // issued before the first is stored (clamped addresses, masks at the store: nothing waits in between)
+    const bool k_fast = ms_i == 1;
+    const float inv_n = 1.0f / (float)n;             // e < 2^13: the rounded float quotients are exact
+    float mt[EX_K], xt[EX_C * EX_K / 256];
+#pragma unroll
+    for (int u = 0; u < EX_K; ++u) {
+        const int e = tid + 256 * u;
+        const int eq = (int)(((float)e + 0.5f) * inv_n);
+        const int k = k_fast ? e - eq * n : u, q = k_fast ? eq : tid;       // (e / 256 = u, e % 256 = tid)
+        const bool ok = e < EX_Q * n && q0 + q < r;
+        mt[u] = Mp[ok ? (long long)k * ms_i + (long long)(q0 + q) * ms_q : 0LL];
+    }
+#pragma unroll
+    for (int u = 0; u < EX_C * EX_K / 256; ++u) {
+        const int e = tid + 256 * u;
+        const int c = (int)(((float)e + 0.5f) * inv_n), k = e - c * n;
+        const bool ok = e < EX_C * n && c0 + c < ncols;
+        xt[u] = X[ok ? (c0 + c) * n + k : 0LL];
+    }
+#pragma unroll
+    for (int u = 0; u < EX_K; ++u) {
+        const int e = tid + 256 * u;
+        const int eq = (int)(((float)e + 0.5f) * inv_n);
+        const int k = k_fast ? e - eq * n : u, q = k_fast ? eq : tid;
+        if (e < EX_Q * n) Ms[k][q] = (q0 + q < r) ? mt[u] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < EX_C * EX_K / 256; ++u) {
+        const int e = tid + 256 * u;
+        const int c = (int)(((float)e + 0.5f) * inv_n), k = e - c * n;
+        if (e < EX_C * n) Xs[c][k] = (c0 + c < ncols) ? xt[u] : 0.f;
+    }
+    __syncthreads();
+    v4f acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < n; ++k) {
+        const v4f m = *reinterpret_cast<const v4f*>(&Ms[k][4 * lane]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float x = Xs[8 * wave + j][k];
+            acc[j][0] = fmaf(x, m[0], acc[j][0]); acc[j][1] = fmaf(x, m[1], acc[j][1]);
+            acc[j][2] = fmaf(x, m[2], acc[j][2]); acc[j][3] = fmaf(x, m[3], acc[j][3]);
+        }
+    }
+    const int q = q0 + 4 * lane;
+    if (q < r) {                                      // r is a multiple of four (host check): a piece is whole
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const long long c = c0 + 8 * wave + j;
+            if (c < ncols) {
+                v4f* yp = reinterpret_cast<v4f*>(Y + c * r + q);
+                v4f out = acc[j];
+                if (beta) out += *yp;
+                *yp = out;
+            }
+        }
+    }
+}
+static bool ttm_expand_supported(DType xt, long long inner, int n, int r, const float* Y) {
+    return xt == F32 && inner == 1 && n <= EX_K && r >= EX_Q && r % 4 == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0;
+}
+
 // ---- host side -----------------------------------------------------------------------------------
 // key bits: [0] bf16 input, [1] LASTMODE, [2] KRON, [3] split kernel, [4..6] NBR-1, [8..12] KS,
 // [13] split kernel with several column blocks per workgroup (4 up to NBR = 3, else 2),
@@ -470,7 +557,13 @@ static bool fill_ttm(DType xt, const void* X, long long outer, int n, long long 
     jb.kr = kr; jb.n = n; jb.r = r; jb.beta = beta;
     const char* tn = xt == F32 ? "float" : "asi::bf16_t";
     *out = Item();
-    if (!kron && !last && n <= 16 && r <= 16 && ncols >= (1LL << 18)) {
+    if (!kron && ttm_expand_supported(xt, inner, n, r, Y)) {
+        const long long gx = (ncols + EX_C - 1) / EX_C;
+        jb.gx = (int)gx; jb.gy = (r + EX_Q - 1) / EX_Q;
+        if (gx * jb.gy > 0x3fffffffLL) return false;
+        out->kind = IT_TTM_EXPAND; out->key = 0;
+        std::snprintf(out->label, sizeof(out->label), "k_ttm_expand");
+    } else if (!kron && !last && n <= 16 && r <= 16 && ncols >= (1LL << 18)) {
         const long long gx = (ncols + TH_COLS - 1) / TH_COLS;
         if (gx > 0x3fffffffLL) return false;
         jb.gx = (int)gx; jb.gy = 1;
@@ -596,6 +689,14 @@ hipError_t launch_ttm_duo_items(const Item* const* items, int n, hipStream_t st,
     }
     if (!bf16) { ASI_DUO(float) } else { ASI_DUO(bf16_t) }
 #undef ASI_DUO
+    return hipGetLastError();
+}
+
+hipError_t launch_ttm_expand_items(const Item* const* items, int n, hipStream_t st) {
+    Batch<TtmJob> b;
+    dim3 grid;
+    if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_ttm_expand, grid, 256, 0, st, b);
     return hipGetLastError();
 }
 

@@ -275,6 +275,25 @@ def test_edge_linear_shapes(case, dtype):
     check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), tol, f"edge {case}")
 
 
+def test_full_rank_batch_mode_and_the_expansion_kernel_are_taken():
+    """A linear layer whose batch rank equals the batch (the core is expanded along the batch mode and no G1 is
+    formed) and whose last step expands rank 24 to 600 features (the vector-ALU expansion kernel: three output
+    tiles, the last one ragged; 50 columns in two tiles): parity as everywhere, and the launch record shows both."""
+    from paper_2505_05086_amd import binding as B
+    lay = Layer("edge", (3, 20, 600), (3, 8, 24), "f32", "linear", 50, alpha=0.7, noise=1e-2)
+    st = LayerStream(9, 3, lay)
+    run = _runner(lay)
+    A_t, A64, U_or = check_compress(run, lay, st.activation(0), st.u_prev0(), TOL["f32"], "expand")
+    B.asi_profile_enable(True)
+    try:
+        check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), TOL["f32"], "expand")
+        sites = list(B.asi_profile_report())
+    finally:
+        B.asi_profile_enable(False)
+    assert any("k_ttm_expand" in s_ for s_ in sites), sites
+    assert any(s_.endswith(":S1") for s_ in sites) and not any(s_.endswith(":G1") for s_ in sites), sites
+
+
 def test_rank_above_192_takes_the_general_orthogonalisation():
     """Ranks in (192, 1024] leave the blocked orthogonalisation kernels for the single-workgroup one and
     need 13 or more rank tiles in the product kernels; the whole path is checked like any other shape."""
