@@ -76,6 +76,20 @@ __global__ __launch_bounds__(SG_NT, 2) void k_subspace_gram(Batch<GramJob> bt) {
     const long long inner = jb.inner;
     if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
     for (int e = tid; e < ROWS * PITCH; e += SG_NT) Xs[e] = 0.f;      // rows >= n stay zero for good
+    // U_prev for the product at the end: fetched now (all loads of the workgroup together, addresses valid for
+    // every lane), so that the last step reads it from LDS instead of one word at a time from memory
+    __shared__ float Us[ROWS * 64];
+    {
+        constexpr int NU = ROWS * 64 / SG_NT;
+        float ut[NU];
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int e = tid + SG_NT * u;
+            ut[u] = jb.U[e < n * r ? e : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < NU; ++u) Us[tid + SG_NT * u] = ut[u];
+    }
 
     // a thread's share of a tile: NL pieces (VEC: of four columns) in rows (piece / pieces per row)
     constexpr int W = VEC ? 4 : 1, PPR = TC / W, NL = ROWS * PPR / SG_NT;
@@ -191,7 +205,7 @@ __global__ __launch_bounds__(SG_NT, 2) void k_subspace_gram(Batch<GramJob> bt) {
             } else {
                 g = ((i >> 4) <= (k >> 4)) ? G[i * ROWS + k] : G[k * ROWS + i];
             }
-            sum = fma(g, (double)jb.U[k * r + q], sum);
+            sum = fma(g, (double)Us[k * r + q], sum);
         }
         out[e] = sum;
     }

@@ -108,14 +108,28 @@ __global__ __launch_bounds__(PN_NT) void k_subspace_planes(Batch<PlanesJob> bt) 
     //   role 0: K slot (ks, lg) is row 4 ks + lg:                          U_H[4 ks + lg][16 nb + ll]
     //   role 1: K slot (v, lg) of block cb, ks = 4 cb + v, is column 16 cb + 4 lg + v:  U_W[16 cb + 4 lg + v][16 nb + ll]
     float* Us = pn_dyn + PN_PL * PF;                  // [2][4 NBM][NBR][64]
-    for (int e = tid; e < 2 * 4 * NBM * NBR * 64; e += PN_NT) {
-        const int l = e & 63, nb = (e >> 6) % NBR, ks = ((e >> 6) / NBR) % (4 * NBM), ro = (e >> 6) / (NBR * 4 * NBM);
-        const int g = l >> 4, c = l & 15;
-        const int i = ro ? 16 * (ks >> 2) + 4 * g + (ks & 3) : 4 * ks + g, q = 16 * nb + c;
-        const int nn = ro ? cols : rows, rr = jb.r[ro];
-        const bool ok = (i < nn) & (q < rr);
-        const float u = jb.U[ro][ok ? i * rr + q : 0];
-        Us[e] = ok ? u : 0.f;
+    // (all loads first, from addresses valid for every lane, then the stores: written as a loop of load and
+    // store, every element paid its own round trip to memory)
+    {
+        constexpr int NU = 2 * 4 * NBM * NBR * 64 / PN_NT;
+        static_assert(NU * PN_NT == 2 * 4 * NBM * NBR * 64, "whole passes");
+        const float* U0 = jb.U[0];
+        const float* U1 = jb.U[1];
+        const int r0 = jb.r[0], r1 = jb.r[1];
+        float ut[NU];
+        bool uok[NU];
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int e = tid + PN_NT * u;
+            const int l = e & 63, nb = (e >> 6) % NBR, ks = ((e >> 6) / NBR) % (4 * NBM), ro = (e >> 6) / (NBR * 4 * NBM);
+            const int g = l >> 4, c = l & 15;
+            const int i = ro ? 16 * (ks >> 2) + 4 * g + (ks & 3) : 4 * ks + g, q = 16 * nb + c;
+            const int nn = ro ? cols : rows, rr = ro ? r1 : r0;
+            uok[u] = (i < nn) & (q < rr);
+            ut[u] = (ro ? U1 : U0)[uok[u] ? i * rr + q : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < NU; ++u) Us[tid + PN_NT * u] = uok[u] ? ut[u] : 0.f;
     }
     const float* ureg = Us + role * (4 * NBM * NBR * 64) + lane;      // ureg[(ks * NBR + nb) * 64]
     v4d pacc[NBM][NBR];

@@ -70,11 +70,28 @@ __global__ __launch_bounds__(256, 2) void k_subspace_small(Batch<SmallJob> bt) {
     const T* __restrict__ X = static_cast<const T*>(jb.X);
     if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
 
-    for (int e = tid; e < NV * NBM * 16 * NBR * 16; e += 256) {
-        const int vi = e / (NBM * 16 * NBR * 16), rem = e - vi * (NBM * 16 * NBR * 16);
-        const int i = rem / (NBR * 16), q = rem - i * (NBR * 16);
-        const SmallView& sv = jb.v[vi];
-        Us[vi][i][q] = ldg_f32(sv.U, (long long)i * sv.r + q, i < sv.n && q < sv.r);
+    // the factors: all loads first (addresses valid for every lane), then the stores; written as a loop of
+    // load and store, every element paid its own round trip to memory
+    {
+        constexpr int PV = NBM * 16 * NBR * 16, NU = PV / 256;
+        static_assert(NU * 256 == PV, "whole passes");
+        float ut[NV][NU];
+        bool uok[NV][NU];
+#pragma unroll
+        for (int vi = 0; vi < NV; ++vi) {
+            const float* Uv = jb.v[vi].U;
+            const int nv = jb.v[vi].n, rv = jb.v[vi].r;
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int rem = tid + 256 * u, i = rem / (NBR * 16), q = rem - i * (NBR * 16);
+                uok[vi][u] = i < nv && q < rv;
+                ut[vi][u] = Uv[uok[vi][u] ? (long long)i * rv + q : 0LL];
+            }
+        }
+#pragma unroll
+        for (int vi = 0; vi < NV; ++vi)
+#pragma unroll
+            for (int u = 0; u < NU; ++u) (&Us[vi][0][0])[tid + 256 * u] = uok[vi][u] ? ut[vi][u] : 0.f;
     }
 
     v4d pacc[NV][NBM][NBR];
