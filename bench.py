@@ -35,7 +35,7 @@ PEAK_TFLOPS = {"mfma_f32": 157.3, "mfma_f64": 78.6, "mfma_bf16": 2500.0, "valu_f
 # which arithmetic unit each kernel symbol runs its contraction on; a symbol that is not listed is an error
 KERNEL_UNIT = {"k_subspace_small": "mfma_f32+f64", "k_subspace_tiny": "valu_f32+f64", "k_subspace_long": "mfma_f32+f64", "k_subspace_planes": "mfma_f32+f64",
                "k_subspace_gram": "mfma_f64", "k_gauss_fill": "valu_f64",
-               "k_ttm_mfma": "mfma_f32", "k_ttm_ksplit": "mfma_f32", "k_ttm_stream": "mfma_f32", "k_ttm_expand": "valu_f32", "k_ttm_duo": "mfma_f32", "k_ttm_thin": "valu_f32",
+               "k_ttm_mfma": "mfma_f32", "k_ttm_ksplit": "mfma_f32", "k_ttm_stream": "mfma_f32", "k_ttm_stream_short": "mfma_f32", "k_ttm_expand": "valu_f32", "k_ttm_duo": "mfma_f32", "k_ttm_thin": "valu_f32",
                "k_gemm_bf16": "mfma_bf16", "k_split_bf16": "valu_f32", "k_pair": "mfma_f64",
                "k_corr_mfma": "mfma_f32", "k_corr": "valu_f32",
                "k_orth_gram0": "mfma_f64", "k_orth_apply": "mfma_f64",

@@ -16,6 +16,12 @@
 // KW waves share a span and split the rounds between them (their partial tiles are added through LDS,
 // in the space of the matrix); 4 / KW spans make a workgroup.  KW = 1 suits short modes over very many
 // columns, KW = 4 long modes or few columns.
+//
+// k_ttm_stream_short: modes of 17..32 entries over very many columns (the batch mode of grad_out, G1 of
+// Eq. 14).  A wave's whole fibre block is two rounds, and a lane's matrix operands are 8 words per block of
+// 16 outputs, which it reads straight from memory (every wave of the launch reads the same few KB): no LDS,
+// no barrier, a third of the registers, so four times as many waves stay resident per CU.  Such a launch
+// has nothing but its loads to wait for, and the resident waves are what keeps them in flight.
 #include "asi_device.h"
 #include "asi_kernels.h"
 
@@ -201,6 +207,93 @@ __global__ __launch_bounds__(256, 2) void k_ttm_stream(Batch<TtmJob> bt) {
     }
 }
 
+template <typename T, int NBR>
+__global__ __launch_bounds__(256, NBR <= 2 ? 4 : 2) void k_ttm_stream_short(Batch<TtmJob> bt) {
+    typedef typename StreamPiece<T>::type P;
+    int lb;
+    const TtmJob& jb = bt.job[locate_xcd(bt, &lb)];
+    const T* __restrict__ X = static_cast<const T*>(jb.X);
+    const float* __restrict__ Mp = jb.Mp;
+    float* __restrict__ Y = jb.Y;
+    const unsigned inner = (unsigned)jb.inner, ncols = (unsigned)(jb.outer * jb.inner);   // below 2^31 (host check)
+    const int n = jb.n, r = jb.r, beta = jb.beta, msi = (int)jb.ms_i;                      // 32 ms_i below 2^31 (host check)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
+    if (jb.zero && lb == 0 && tid < jb.nzero) jb.zero[tid] = 0;
+
+    const unsigned cs = ((unsigned)lb * 4u + wave) * 64u;
+    const unsigned c = cs + 4u * ll;
+    const unsigned cc = c < ncols ? c : 0u;             // past the end: the first piece (valid), dropped at the store
+    const unsigned o = cc / inner, j = cc - o * inner;
+    const T* __restrict__ xp = X + ((size_t)o * n * inner + j);
+
+    // B operands: step s of round S multiplies row i = 16 S + 4 s + lg of the mode; this lane's output is 16 nb + ll.
+    // Requested before X (loads return in order), from addresses valid for every lane, masked afterwards.
+    float bm[2][NBR][4];
+#pragma unroll
+    for (int S = 0; S < 2; ++S)
+#pragma unroll
+        for (int nb = 0; nb < NBR; ++nb)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int i = 16 * S + 4 * s + lg, q = 16 * nb + ll;
+                bm[S][nb][s] = Mp[(i < n && q < r) ? i * msi + q : 0];
+            }
+    P x[2][4];
+#pragma unroll
+    for (int S = 0; S < 2; ++S)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int i = 16 * S + 4 * s + lg;
+            // a row past n is read as row n - 1 and meets a zero of the matrix
+            x[S][s] = *reinterpret_cast<const P*>(xp + (unsigned)(i < n ? i : n - 1) * inner);
+        }
+#pragma unroll
+    for (int S = 0; S < 2; ++S)
+#pragma unroll
+        for (int nb = 0; nb < NBR; ++nb)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int i = 16 * S + 4 * s + lg, q = 16 * nb + ll;
+                bm[S][nb][s] = (i < n && q < r) ? bm[S][nb][s] : 0.f;
+            }
+
+    v4f acc[4][NBR];
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+        for (int nb = 0; nb < NBR; ++nb) acc[v][nb] = (v4f){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int S = 0; S < 2; ++S)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const v4f a = stream_widen(x[S][s]);
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int nb = 0; nb < NBR; ++nb)
+                    acc[v][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[v], bm[S][nb][s], acc[v][nb], 0, 0, 0);
+        }
+
+    // acc[v][nb][e]: column cs + 16 lg + 4 e + v, output 16 nb + ll
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const unsigned ce = cs + 16u * lg + 4u * e;
+        if (ce < ncols) {
+            const unsigned oe = ce / inner, je = ce - oe * inner;
+#pragma unroll
+            for (int nb = 0; nb < NBR; ++nb) {
+                const int q = 16 * nb + ll;
+                if (q < r) {
+                    v4f* yp = reinterpret_cast<v4f*>(Y + (((size_t)oe * r + q) * inner + je));
+                    v4f out = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
+                    if (beta) out += *yp;
+                    *yp = out;
+                }
+            }
+        }
+    }
+}
+
 // ---- host side -----------------------------------------------------------------------------------
 static size_t stream_lds(int n, int nbr, int kw) {
     const size_t ms = sizeof(float) * (size_t)(16 * nbr) * (size_t)(16 * ((n + 15) / 16) + 4);
@@ -226,7 +319,7 @@ bool ttm_stream_supported(DType xt, const void* X, long long outer, int n, long 
     return stream_lds(n, nbr, 4) <= TS_LDS_MAX;
 }
 
-// key: [0] bf16, [4..6] NBR - 1, [8..10] KW
+// key: [0] bf16, [4..6] NBR - 1, [8..10] KW, [12] k_ttm_stream_short
 bool make_ttm_stream(DType xt, const void* X, long long outer, int n, long long inner, const float* Mp, long long ms_i,
                      long long ms_q, int r, float* Y, int beta, Item* out) {
     if (!X || !Mp || !Y || !ttm_stream_supported(xt, X, outer, n, inner, Mp, ms_i, ms_q, r, Y)) return false;
@@ -240,9 +333,11 @@ bool make_ttm_stream(DType xt, const void* X, long long outer, int n, long long 
     jb.gx = (int)((ncols + wcols - 1) / wcols); jb.gy = 1;
     *out = Item();
     out->kind = IT_TTM_STREAM;
-    out->key = (xt == BF16 ? 1u : 0u) | ((unsigned)(nbr - 1) << 4) | ((unsigned)kw << 8);
+    const bool shrt = kw == 1 && n > 16 && n <= 32 && ms_i < (1LL << 25);
+    out->key = (xt == BF16 ? 1u : 0u) | ((unsigned)(nbr - 1) << 4) | ((unsigned)kw << 8) | (shrt ? 1u << 12 : 0u);
     out->nblocks = jb.gx;
-    std::snprintf(out->label, sizeof(out->label), "k_ttm_stream<%s, %d, %d>", xt == F32 ? "float" : "asi::bf16_t", nbr, kw);
+    if (shrt) std::snprintf(out->label, sizeof(out->label), "k_ttm_stream_short<%s, %d>", xt == F32 ? "float" : "asi::bf16_t", nbr);
+    else std::snprintf(out->label, sizeof(out->label), "k_ttm_stream<%s, %d, %d>", xt == F32 ? "float" : "asi::bf16_t", nbr, kw);
     static_assert(sizeof(TtmJob) <= kItemArgMax, "argument block");
     std::memcpy(out->arg, &jb, sizeof(jb));
     return true;
@@ -269,6 +364,16 @@ static hipError_t launch_stream_kw(int kw, const Batch<TtmJob>& b, dim3 grid, si
     return launch_stream_one<T, NBR, 4>(b, grid, lds, st);
 }
 template <typename T>
+static hipError_t launch_stream_short_t(int nbr, const Batch<TtmJob>& b, dim3 grid, hipStream_t st) {
+    switch (nbr) {
+        case 1: hipLaunchKernelGGL((k_ttm_stream_short<T, 1>), grid, 256, 0, st, b); break;
+        case 2: hipLaunchKernelGGL((k_ttm_stream_short<T, 2>), grid, 256, 0, st, b); break;
+        case 3: hipLaunchKernelGGL((k_ttm_stream_short<T, 3>), grid, 256, 0, st, b); break;
+        default: hipLaunchKernelGGL((k_ttm_stream_short<T, 4>), grid, 256, 0, st, b); break;
+    }
+    return hipGetLastError();
+}
+template <typename T>
 static hipError_t launch_stream_t(int nbr, int kw, const Batch<TtmJob>& b, dim3 grid, size_t lds, hipStream_t st) {
     switch (nbr) {
         case 1: return launch_stream_kw<T, 1>(kw, b, grid, lds, st);
@@ -284,6 +389,15 @@ hipError_t launch_ttm_stream_items(const Item* const* items, int n, hipStream_t 
     if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
     const unsigned key = items[0]->key;
     const int nbr = (int)((key >> 4) & 7u) + 1, kw = (int)((key >> 8) & 7u);
+    if ((key >> 12) & 1u) {                             // the short form holds exactly two rounds of a mode
+        for (int j = 0; j < n; ++j) {
+            TtmJob tj;
+            std::memcpy(&tj, items[j]->arg, sizeof(tj));
+            if (tj.n <= 16 || tj.n > 32 || tj.ms_i >= (1LL << 25)) return hipErrorInvalidValue;
+        }
+        if (key & 1u) return launch_stream_short_t<bf16_t>(nbr, b, grid, st);
+        return launch_stream_short_t<float>(nbr, b, grid, st);
+    }
     size_t lds = 0;
     for (int j = 0; j < n; ++j) {                       // items of one launch share the instantiation; the largest matrix sizes the LDS
         TtmJob tj;

@@ -212,11 +212,11 @@ def test_edge_conv_shapes(case, dtype):
 
 # Tensors of a million elements or more whose contiguous extent is a multiple of four take the streaming
 # mode product (16-byte loads straight into the MFMA operands).  Each case names the instantiation
-# <NBR, KW> it is meant to reach: NBR blocks of 16 outputs, KW waves sharing a span of 64 columns.  (The core
+# <NBR, KW> it is meant to reach: NBR blocks of 16 outputs, KW waves sharing a span of 64 columns ("short": the form for modes of 17..32).  (The core
 # chain starts with the mode that shrinks the tensor most, so the ranks keep H and W nearly whole.)
 STREAM_CONV = [
     # a mode of 20 (two rounds, the second padded) over 144000 columns, 562.5 workgroups of 256 columns
-    ((20, 16, 100, 90), (8, 8, 12, 12), 8, "1, 1"),
+    ((20, 16, 100, 90), (8, 8, 12, 12), 8, "short"),
     # 80 channels (five rounds over four waves: one wave has one round, one has none), 42000 columns = 656.25 spans
     ((5, 80, 100, 84), (4, 24, 60, 56), 12, "2, 4"),
     # 56 channels, 40 outputs (three blocks, the last half empty), two waves per span with two rounds each
@@ -243,7 +243,11 @@ def test_streaming_mode_product(case, dtype):
         B.asi_profile_enable(False)
     # (a bf16 tensor may take its first product along the last mode on the bf16 MFMA; the streaming product
     # then meets the fp32 intermediate)
-    want = ["k_ttm_stream<%s, %s>" % (t, variant) for t in (["float"] if dtype == "f32" else ["asi::bf16_t", "float"])]
+    types = ["float"] if dtype == "f32" else ["asi::bf16_t", "float"]
+    if variant == "short":          # a mode of 17..32 with one wave per span: the form without LDS
+        want = ["k_ttm_stream_short<%s, 1>" % t for t in types]
+    else:
+        want = ["k_ttm_stream<%s, %s>" % (t, variant) for t in types]
     assert any(w in s_ for s_ in sites for w in want), (want, [s_ for s_ in sites if "ttm" in s_])
 
 
