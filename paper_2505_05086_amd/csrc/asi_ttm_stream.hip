@@ -160,26 +160,10 @@ __global__ __launch_bounds__(256, 2) void k_ttm_stream(Batch<TtmJob> bt) {
         }
     }
 
-    // acc[v][nb][e]: column cs + 16 lg + 4 e + v, output 16 nb + ll
-    if (KW == 1) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const unsigned ce = cs + 16u * lg + 4u * e;
-            if (ce < ncols) {
-                const unsigned oe = ce / inner, je = ce - oe * inner;
-#pragma unroll
-                for (int nb = 0; nb < NBR; ++nb) {
-                    const int q = 16 * nb + ll;
-                    if (q < r) {
-                        v4f* yp = reinterpret_cast<v4f*>(Y + (((size_t)oe * r + q) * inner + je));
-                        v4f out = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
-                        if (beta) out += *yp;
-                        *yp = out;
-                    }
-                }
-            }
-        }
-    } else {
+    // acc[v][nb][e]: column cs + 16 lg + 4 e + v, output 16 nb + ll: a lane owns 64 contiguous bytes of one output
+    // row, and a store from there would write 16-byte pieces 64 bytes apart in 16 rows.  The tiles go through
+    // LDS (for KW > 1 the partial tiles meet there anyway) and a store instruction writes whole runs of a row.
+    {
         __syncthreads();                                // every wave has read its last matrix operand
 #pragma unroll
         for (int nb = 0; nb < NBR; ++nb)
@@ -210,6 +194,7 @@ __global__ __launch_bounds__(256, 2) void k_ttm_stream(Batch<TtmJob> bt) {
 template <typename T, int NBR>
 __global__ __launch_bounds__(256, NBR <= 2 ? 4 : 2) void k_ttm_stream_short(Batch<TtmJob> bt) {
     typedef typename StreamPiece<T>::type P;
+    __shared__ __align__(16) float ss_tile[4 * 16 * NBR * TS_RP];       // a result tile per wave
     int lb;
     const TtmJob& jb = bt.job[locate_xcd(bt, &lb)];
     const T* __restrict__ X = static_cast<const T*>(jb.X);
@@ -274,21 +259,30 @@ __global__ __launch_bounds__(256, NBR <= 2 ? 4 : 2) void k_ttm_stream_short(Batc
                     acc[v][nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[v], bm[S][nb][s], acc[v][nb], 0, 0, 0);
         }
 
-    // acc[v][nb][e]: column cs + 16 lg + 4 e + v, output 16 nb + ll
+    // acc[v][nb][e]: column cs + 16 lg + 4 e + v, output 16 nb + ll: a lane owns 64 contiguous bytes of one output
+    // row.  Stored from there, an instruction would write 16-byte pieces 64 bytes apart in 16 rows; the tile goes
+    // through the wave's own LDS block instead (LDS serves a wave's accesses in order: no barrier), and every
+    // store instruction then writes four whole rows of the span, 256 contiguous bytes each, like the loads.
+    float* tile = ss_tile + wave * (16 * NBR * TS_RP);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const unsigned ce = cs + 16u * lg + 4u * e;
-        if (ce < ncols) {
-            const unsigned oe = ce / inner, je = ce - oe * inner;
+    for (int nb = 0; nb < NBR; ++nb)
 #pragma unroll
-            for (int nb = 0; nb < NBR; ++nb) {
-                const int q = 16 * nb + ll;
-                if (q < r) {
-                    v4f* yp = reinterpret_cast<v4f*>(Y + (((size_t)oe * r + q) * inner + je));
-                    v4f out = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
-                    if (beta) out += *yp;
-                    *yp = out;
-                }
+        for (int e = 0; e < 4; ++e) {
+            const v4f out = {acc[0][nb][e], acc[1][nb][e], acc[2][nb][e], acc[3][nb][e]};
+            *reinterpret_cast<v4f*>(tile + (16 * nb + ll) * TS_RP + 16 * lg + 4 * e) = out;
+        }
+    const unsigned ce = cs + 4u * ll;                   // this lane's piece of every row
+    if (ce < ncols) {
+        const unsigned oe = ce / inner, je = ce - oe * inner;
+        float* yb = Y + ((size_t)oe * r * inner + je);
+#pragma unroll
+        for (int k = 0; k < 4 * NBR; ++k) {
+            const int q = 4 * k + lg;
+            if (q < r) {
+                v4f out = *reinterpret_cast<const v4f*>(tile + q * TS_RP + 4 * ll);
+                v4f* yp = reinterpret_cast<v4f*>(yb + (size_t)q * inner);
+                if (beta) out += *yp;
+                *yp = out;
             }
         }
     }
@@ -297,7 +291,8 @@ __global__ __launch_bounds__(256, NBR <= 2 ? 4 : 2) void k_ttm_stream_short(Batc
 // ---- host side -----------------------------------------------------------------------------------
 static size_t stream_lds(int n, int nbr, int kw) {
     const size_t ms = sizeof(float) * (size_t)(16 * nbr) * (size_t)(16 * ((n + 15) / 16) + 4);
-    const size_t rd = kw > 1 ? sizeof(float) * 4u * (size_t)(16 * nbr) * TS_RP : 0;
+    const size_t rd = sizeof(float) * 4u * (size_t)(16 * nbr) * TS_RP;       // the four waves' result tiles
+    (void)kw;
     return ms > rd ? ms : rd;
 }
 

@@ -217,6 +217,8 @@ def test_edge_conv_shapes(case, dtype):
 STREAM_CONV = [
     # a mode of 20 (two rounds, the second padded) over 144000 columns, 562.5 workgroups of 256 columns
     ((20, 16, 100, 90), (8, 8, 12, 12), 8, "short"),
+    # a mode of 40 (three rounds, the last half empty) over the same columns: one wave per span in the general form
+    ((40, 16, 100, 90), (8, 8, 12, 12), 16, "1, 1"),
     # 80 channels (five rounds over four waves: one wave has one round, one has none), 42000 columns = 656.25 spans
     ((5, 80, 100, 84), (4, 24, 60, 56), 12, "2, 4"),
     # 56 channels, 40 outputs (three blocks, the last half empty), two waves per span with two rounds each
