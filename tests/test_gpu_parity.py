@@ -300,6 +300,26 @@ def test_full_rank_batch_mode_and_the_expansion_kernel_are_taken():
     assert any(s_.endswith(":S1") for s_ in sites) and not any(s_.endswith(":G1") for s_ in sites), sites
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_wide_output_tiles_of_the_last_mode_pair_product(dtype):
+    """P = A_m V along a last mode longer than 512 with a rank above 32 over 4096 columns: the pair product
+    takes 64 outputs per workgroup (rank 40: the second block of 16 is half empty, the fourth empty; 520 rows:
+    nine row tiles, the last one ragged).  Parity as everywhere, and the launch record shows the instantiation."""
+    from paper_2505_05086_amd import binding as B
+    lay = Layer("edge", (16, 256, 520), (4, 6, 40), dtype, "linear", 8, alpha=0.7, noise=1e-2)
+    st = LayerStream(9, 5, lay)
+    run = _runner(lay)
+    B.asi_profile_enable(True)
+    try:
+        A_t, A64, U_or = check_compress(run, lay, st.activation(0), st.u_prev0(), TOL[dtype], "wide pair")
+        sites = list(B.asi_profile_report())
+    finally:
+        B.asi_profile_enable(False)
+    xt = "float" if dtype == "f32" else "asi::bf16_t"
+    assert any("k_pair<%s, true, false, 64>" % xt in s_ for s_ in sites), sites
+    check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), TOL[dtype], "wide pair")
+
+
 def test_rank_above_192_takes_the_general_orthogonalisation():
     """Ranks in (192, 1024] leave the blocked orthogonalisation kernels for the single-workgroup one and
     need 13 or more rank tiles in the product kernels; the whole path is checked like any other shape."""
