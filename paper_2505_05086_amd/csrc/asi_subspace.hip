@@ -22,6 +22,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 namespace asi {
 
@@ -406,6 +407,14 @@ __device__ __forceinline__ double dpp_move(double x) {
     const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xF, 0xF, false);
     return __hiloint2double(hi, lo);
 }
+typedef float v4f_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ v4f_t tiny_widen(const v4f_t& p) { return p; }
+__device__ __forceinline__ v4f_t tiny_widen(const uint2& p) {
+    v4f_t o;
+    o[0] = __uint_as_float(p.x << 16); o[1] = __uint_as_float(p.x & 0xffff0000u);
+    o[2] = __uint_as_float(p.y << 16); o[3] = __uint_as_float(p.y & 0xffff0000u);
+    return o;
+}
 struct TinyJob {
     const void* X;
     long long planes, ntiles;
@@ -415,9 +424,18 @@ struct TinyJob {
     int nwg;
 };
 
-template <typename T, int RP>
+template <typename T, bool VEC> struct TinyPiece { typedef T type; };
+template <> struct TinyPiece<float, true> { typedef v4f_t type; };
+template <> struct TinyPiece<bf16_t, true> { typedef uint2 type; };
+template <typename T, bool VEC, typename PC>
+__device__ __forceinline__ void tiny_store(float* dst, const PC& v) {
+    if constexpr (VEC) *reinterpret_cast<v4f_t*>(dst) = tiny_widen(v);
+    else *dst = to_f32(v);
+}
+
+template <typename T, int RP, bool VEC>
 __global__ __launch_bounds__(256) void k_subspace_tiny(Batch<TinyJob> bt) {
-    __shared__ float tile[TY_PL * 64];
+    __shared__ __align__(16) float tile[TY_PL * 64];
     __shared__ float Us[2][8][RP];
     __shared__ double red[4][2][8 * RP];
     int lb;
@@ -428,10 +446,38 @@ __global__ __launch_bounds__(256) void k_subspace_tiny(Batch<TinyJob> bt) {
     const int n_v = view ? cols : rows;          // length of this view's fibres (the mode size)
     const int m_v = view ? rows : cols;          // fibres per plane
     const int sI = view ? 1 : cols, sC = view ? cols : 1;    // element (i, c) of the plane at i*sI + c*sC
-    for (int e = tid; e < 2 * 8 * RP; e += 256) {
-        const int vi = e / (8 * RP), rem = e - vi * (8 * RP), i = rem / RP, q = rem - i * RP;
-        const int nn = vi ? cols : rows;
-        Us[vi][i][q] = ldg_f32(jb.U[vi], (long long)i * jb.r[vi] + q, i < nn && q < jb.r[vi]);
+    // A tile (TY_PL consecutive planes, one contiguous run of X) travels in pieces of W elements.  VEC (X is
+    // aligned, so every tile of 128 planes is): W = 4, one 16-byte load (8 bytes for bf16) and one 16-byte LDS
+    // store; the up to three elements after the last whole piece of a ragged last tile go one by one.
+    // The first tile is requested before the factors are staged, and a workgroup with a further tile requests it
+    // before it multiplies: a tile's round trip to memory costs as much as its arithmetic.
+    typedef typename TinyPiece<T, VEC>::type Piece;
+    constexpr int W = VEC ? 4 : 1;
+    constexpr int NPC = TY_PL * 64 / W / 256;                // pieces per thread
+    Piece pre[NPC];
+    T pre_tail;
+    auto fetch = [&](long long t) __attribute__((always_inline)) {
+        const long long p0 = t * TY_PL;
+        const int np = (int)((jb.planes - p0 < TY_PL) ? jb.planes - p0 : TY_PL);
+        const int count = np * pe;
+        const T* src = X + p0 * pe;
+#pragma unroll
+        for (int k = 0; k < NPC; ++k) {
+            const int e = W * (k * 256 + tid);
+            pre[k] = *reinterpret_cast<const Piece*>(src + (e + W - 1 < count ? e : 0));      // clamped, not branched: all loads stay in flight
+        }
+        const int et = (count & ~(W - 1)) + (tid & 3);
+        pre_tail = src[et < count ? et : 0];
+    };
+    if (lb < jb.ntiles) fetch(lb);
+    {
+        float ut = 0.f;                                      // 2 * 8 * RP <= 128 elements: one per thread
+        const int e = tid, vi = e / (8 * RP), rem = e - vi * (8 * RP), i = rem / RP, q = rem - i * RP;
+        const bool in = e < 2 * 8 * RP;
+        const int nn = vi ? cols : rows, rr = in ? jb.r[vi] : 1;
+        const bool ok = in && i < nn && q < rr;
+        ut = jb.U[in ? vi : 0][ok ? (long long)i * rr + q : 0];
+        if (in) Us[vi][i][q] = ok ? ut : 0.f;
     }
     __syncthreads();
     float u[8][RP];
@@ -449,19 +495,17 @@ __global__ __launch_bounds__(256) void k_subspace_tiny(Batch<TinyJob> bt) {
         const long long p0 = t * TY_PL;
         const int np = (int)((jb.planes - p0 < TY_PL) ? jb.planes - p0 : TY_PL);
         const int count = np * pe;
-        const T* src = X + p0 * pe;
         __syncthreads();                          // previous tile consumed
-        T pre[TY_PL * 64 / 256];
 #pragma unroll
-        for (int k = 0; k < TY_PL * 64 / 256; ++k) {
-            const int e = k * 256 + tid;
-            pre[k] = src[e < count ? e : 0];      // clamped, not branched: all loads stay in flight
+        for (int k = 0; k < NPC; ++k) {
+            const int e = W * (k * 256 + tid);
+            if (e + W - 1 < count) tiny_store<T, VEC>(tile + e, pre[k]);
         }
-#pragma unroll
-        for (int k = 0; k < TY_PL * 64 / 256; ++k) {
-            const int e = k * 256 + tid;
-            if (e < count) tile[e] = to_f32(pre[k]);
+        {
+            const int et = (count & ~(W - 1)) + (tid & 3);
+            if (tid < 4 && et < count) tile[et] = to_f32(pre_tail);
         }
+        if (t + jb.nwg < jb.ntiles) fetch(t + jb.nwg);       // on its way during this tile's arithmetic
         __syncthreads();
         if (pl < np) {
             const float* xp = tile + pl * pe;
@@ -525,9 +569,15 @@ __global__ __launch_bounds__(256) void k_subspace_tiny(Batch<TinyJob> bt) {
 bool subspace_tiny_supported(int rows, int cols, int r_rows, int r_cols) {
     return rows <= 8 && cols <= 8 && r_rows <= 8 && r_cols <= 8 && r_rows <= rows && r_cols <= cols;
 }
+// Two workgroups are resident per CU (a thread holds its P in ~100 fp64 registers), and a workgroup's fixed costs
+// (factor staging, the first tile's round trip, the sum over its lanes and waves) are several times a tile's
+// arithmetic: no more workgroups than are resident, every one walking the same number of tiles, the next
+// tile on its way while the current one is multiplied.
+constexpr int TY_MAX_WG = 512;
 int subspace_tiny_nwg(long long planes) {
     const long long ntiles = (planes + TY_PL - 1) / TY_PL;
-    return (int)(ntiles < SS_MAX_WG ? ntiles : SS_MAX_WG);
+    const long long per = (ntiles + TY_MAX_WG - 1) / TY_MAX_WG;
+    return (int)((ntiles + per - 1) / per);
 }
 bool make_subspace_tiny(DType xt, const void* X, long long planes, int rows, int cols, const float* U_rows, int r_rows,
                         double* part_rows, const float* U_cols, int r_cols, double* part_cols, int nwg, Item* out) {
@@ -543,9 +593,11 @@ bool make_subspace_tiny(DType xt, const void* X, long long planes, int rows, int
     const int rp = rmax <= 4 ? 4 : (rmax <= 6 ? 6 : 8);
     *out = Item();
     out->kind = IT_TINY;
-    out->key = (xt == BF16 ? 1u : 0u) | ((unsigned)rp << 4);
+    const bool vec = reinterpret_cast<uintptr_t>(X) % (xt == F32 ? 16 : 8) == 0;
+    out->key = (xt == BF16 ? 1u : 0u) | (vec ? 2u : 0u) | ((unsigned)rp << 4);
     out->nblocks = nwg;
-    std::snprintf(out->label, sizeof(out->label), "k_subspace_tiny<%s, %d>", xt == F32 ? "float" : "asi::bf16_t", rp);
+    std::snprintf(out->label, sizeof(out->label), "k_subspace_tiny<%s, %d, %s>", xt == F32 ? "float" : "asi::bf16_t", rp,
+                  vec ? "true" : "false");
     static_assert(sizeof(TinyJob) <= kItemArgMax, "argument block");
     std::memcpy(out->arg, &jb, sizeof(jb));
     return true;
@@ -556,16 +608,21 @@ hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st) {
     if (!gather(items, n, &b, &grid)) return hipErrorInvalidValue;
     const unsigned key = items[0]->key;
     const int rp = (int)(key >> 4);
-    if (!(key & 1u)) {
-        if (rp == 4) hipLaunchKernelGGL((k_subspace_tiny<float, 4>), grid, 256, 0, st, b);
-        else if (rp == 6) hipLaunchKernelGGL((k_subspace_tiny<float, 6>), grid, 256, 0, st, b);
-        else hipLaunchKernelGGL((k_subspace_tiny<float, 8>), grid, 256, 0, st, b);
-    } else {
-        if (rp == 4) hipLaunchKernelGGL((k_subspace_tiny<bf16_t, 4>), grid, 256, 0, st, b);
-        else if (rp == 6) hipLaunchKernelGGL((k_subspace_tiny<bf16_t, 6>), grid, 256, 0, st, b);
-        else hipLaunchKernelGGL((k_subspace_tiny<bf16_t, 8>), grid, 256, 0, st, b);
+    const bool bf = key & 1u, vec = key & 2u;
+#define ASI_TINY_CASE(R)                                                                                  \
+    if (rp == R) {                                                                                        \
+        if (bf) {                                                                                         \
+            if (vec) hipLaunchKernelGGL((k_subspace_tiny<bf16_t, R, true>), grid, 256, 0, st, b);         \
+            else hipLaunchKernelGGL((k_subspace_tiny<bf16_t, R, false>), grid, 256, 0, st, b);            \
+        } else {                                                                                          \
+            if (vec) hipLaunchKernelGGL((k_subspace_tiny<float, R, true>), grid, 256, 0, st, b);          \
+            else hipLaunchKernelGGL((k_subspace_tiny<float, R, false>), grid, 256, 0, st, b);             \
+        }                                                                                                 \
+        return hipGetLastError();                                                                         \
     }
-    return hipGetLastError();
+    ASI_TINY_CASE(4) ASI_TINY_CASE(6) ASI_TINY_CASE(8)
+#undef ASI_TINY_CASE
+    return hipErrorInvalidValue;
 }
 
 template <typename T, int NV>

@@ -320,6 +320,44 @@ def test_wide_output_tiles_of_the_last_mode_pair_product(dtype):
     check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), TOL[dtype], "wide pair")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_activation_aligned_to_its_element_only(dtype):
+    """The activation may start at any element of a buffer: the tile loaders that move 16-byte pieces need an
+    aligned start and have element-wise forms for the rest.  A 7 x 7 conv activation (the small-plane kernel;
+    300 planes: two full tiles of 128 and a ragged third) one element into its allocation, against the oracle
+    and against the same call on an aligned copy."""
+    from paper_2505_05086_amd import binding as B
+    lay = Layer("edge", (6, 50, 7, 7), (3, 8, 5, 5), dtype, "conv2d", 12, k=3, stride=1, pad=1, dil=1, groups=1,
+                alpha=0.7, noise=1e-2)
+    st = LayerStream(9, 6, lay)
+    run = _runner(lay)
+    A_np, U0 = st.activation(0), st.u_prev0()
+    U_or = O.compress(A_np.astype(F64), [u.astype(F64) for u in U0])
+    A_al = run.upload(A_np)
+    buf = torch.empty(A_al.numel() + 8, dtype=A_al.dtype, device=A_al.device)
+    A_off = buf[1:1 + A_al.numel()].view(A_al.shape)
+    A_off.copy_(A_al)
+    assert A_off.data_ptr() % 8 != 0 and A_off.is_contiguous()
+    got = []
+    for A_t, want in ((A_al, "true"), (A_off, "false")):
+        run.set_factors(U0)
+        B.asi_profile_enable(True)
+        try:
+            U_gpu = [_np(u).copy() for u in run.compress(A_t)]
+            torch.cuda.synchronize()
+            sites = list(B.asi_profile_report())
+        finally:
+            B.asi_profile_enable(False)
+        assert int(run.info.item()) == 0
+        assert any("k_subspace_tiny<" in s_ and s_.rstrip().endswith(want + ">") for s_ in sites), sites
+        for m, (ug, uo) in enumerate(zip(U_gpu, U_or)):
+            ep = O.max_rel_err(O.projector(ug), O.projector(uo))
+            assert ep <= TOL[dtype], f"mode {m} ({want}): projector err {ep:.3e}"
+        got.append(U_gpu)
+    for ua, ub in zip(*got):      # the two loaders feed the same arithmetic in the same order
+        assert np.array_equal(ua, ub)
+
+
 def test_rank_above_192_takes_the_general_orthogonalisation():
     """Ranks in (192, 1024] leave the blocked orthogonalisation kernels for the single-workgroup one and
     need 13 or more rank tiles in the product kernels; the whole path is checked like any other shape."""
