@@ -3,6 +3,8 @@ array in place of a caller workspace) against asi_compress on the same inputs, t
 C ABI: two calls in a row, the second on a smaller layer, so that what the first call left in
 the shared array must not matter.  The two entry points run the same kernels, so the factors
 must agree bit for bit (the parity bar of the fp32 path, 1e-4 on projectors, is implied)."""
+import gc
+
 import numpy as np
 import pytest
 import torch
@@ -28,10 +30,13 @@ def _compress_both(lay, stream_id):
     prev = [torch.from_numpy(np.ascontiguousarray(u, dtype=np.float32)).cuda() for u in U0]
     out = [torch.full_like(u, float("nan")) for u in ref]
     info = torch.full((1,), 77, dtype=torch.int32, device="cuda")
-    before = torch.cuda.memory_allocated()
+    # no allocation through torch's allocator during the call: the cumulative count of allocations stands still
+    # (the bytes in use may drop meanwhile, when Python collects what earlier tests left behind)
+    gc.collect()
+    before = torch.cuda.memory_stats()["allocation.all.allocated"]
     asi.asi_compress_static(run.desc, A_t, prev, out, info)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
     assert int(info.item()) == 0
     for m, (a, b) in enumerate(zip(out, ref)):
         assert torch.equal(a, b), f"mode {m}: static-scratch result differs from the workspace result"
