@@ -244,7 +244,7 @@ static void gemm_shape(int r, int* nbn, int* wn, int* cbw) {
     if (nb <= 2) { *nbn = nb; *wn = 1; *cbw = 1; }            // 8 waves x 16 columns
     else if (nb <= 3) { *nbn = 3; *wn = 1; *cbw = 1; }
     else if (nb <= 6) { *nbn = 3; *wn = 2; *cbw = 1; }        // 4 x 2 waves, 64 columns
-    else { *nbn = 3; *wn = 4; *cbw = 2; }                     // 2 x 4 waves, 64 columns (128 columns, half the workgroups: 89 us against 69 for a 12608 x 3072 x 192 product)
+    else { *nbn = 3; *wn = 4; *cbw = 4; }                     // 2 x 4 waves, 128 columns
 }
 
 static int gemm_tcols(int r) {
@@ -324,7 +324,7 @@ hipError_t launch_bf16_items(const Item* const* items, int n, hipStream_t st) {
     if (wn == 1 && cbw == 1 && nbn == 2) return launch_gemm_one<2, 1, 1>(b, grid, st);
     if (wn == 1 && cbw == 1 && nbn == 3) return launch_gemm_one<3, 1, 1>(b, grid, st);
     if (wn == 2 && cbw == 1 && nbn == 3) return launch_gemm_one<3, 2, 1>(b, grid, st);
-    if (wn == 4 && cbw == 2 && nbn == 3) return launch_gemm_one<3, 4, 2>(b, grid, st);
+    if (wn == 4 && cbw == 4 && nbn == 3) return launch_gemm_one<3, 4, 4>(b, grid, st);
     return hipErrorInvalidValue;
 }
 
