@@ -202,3 +202,13 @@ def test_autograd_layers_refuse_to_run_without_the_gpu_path():
     with pytest.raises(ValueError):
         lin(torch.zeros(3, 6))
     assert conv.eval()(torch.zeros(2, 3, 5, 5)).shape == (2, 4, 5, 5)      # inference is the plain operator
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on exactly one GPU: bench.py says so and exits before it touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 2
+    assert "one GPU" in res.stderr and res.stdout.strip() == ""
