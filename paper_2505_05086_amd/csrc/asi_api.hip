@@ -747,10 +747,21 @@ asi_status build_conv(const asi_tensor_desc* desc, const float* S, const float* 
     const double tsz = (double)g.cout * g.r2 * taps;
     ASI_ADD(pg, "", 4.0 * ((double)g.r1 * g.cout * g.Ho * g.Wo + (double)g.r1 * g.r2 * g.H * g.W + tsz * p.nsplit),
             2.0 * g.r1 * g.Ho * g.Wo * tsz, make_corr(G1, p.Z, p.Tpart, g, p.nsplit, it__));
+    // 5. dW = T x_(r2) U2, per group                              (cout, C/groups, kh, kw)
+    // An ungrouped convolution with 1 or 9 taps and r2 <= 64 sums the partial T's and expands the result in one
+    // launch (T itself is then never written); anything else sums first and multiplies in a second launch.
+    if (cg.groups == 1) {
+        pg.items.emplace_back();
+        if (make_dw_fold(p.Tpart, p.nsplit, U[1], dW, g.cout, cg.C, g.r2, taps, accumulate ? 1 : 0, &pg.items.back())) {
+            tag(pg, "dW", 4.0 * (tsz * p.nsplit + (double)cg.C * g.r2 + (double)g.cout * cg.C * taps * (accumulate ? 2 : 1)),
+                2.0 * (double)g.cout * taps * g.r2 * cg.C + tsz * p.nsplit);
+            return ASI_OK;
+        }
+        pg.items.pop_back();
+    }
     if (p.nsplit > 1)
         ASI_ADD(pg, "", 4.0 * tsz * (p.nsplit + 1), tsz * p.nsplit,
                 make_sum_partials(p.Tpart, p.nsplit, (long long)g.cout * g.r2 * taps, p.T, 0, it__));
-    // 5. dW = T x_(r2) U2, per group                              (cout, C/groups, kh, kw)
     if (cg.groups == 1) {
         ASI_TRYS(add_ttm(pg, "dW", F32, p.T, g.cout, g.r2, taps, U[1], 1, g.r2, cg.C, dW, accumulate ? 1 : 0));
     } else {

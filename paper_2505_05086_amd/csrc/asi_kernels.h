@@ -20,7 +20,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
     IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO, IT_TTM_STREAM, IT_TTM_EXPAND,
-    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE
+    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE, IT_DW_FOLD
 };
 
 struct Item {
@@ -320,6 +320,14 @@ hipError_t launch_ttm_duo_items(const Item* const* items, int n, hipStream_t st,
 hipError_t launch_pair_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_sum_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_expand_items(const Item* const* items, int n, hipStream_t st);
+
+// ---- step 5 of Eq. 14 for an ungrouped convolution with a small core (asi_kernels.hip) ------------------------
+// dW[o, c, t] (+)= sum_j T[o, j, t] U2[c, j] with T given as nsplit >= 1 partial tensors of (cout, r2, taps): one
+// launch adds up the partial sums of the correlation and expands the result, and T is never written.  taps is
+// 1 or 9, r2 <= 64.  False for anything else (the caller then sums and multiplies in two launches).
+bool make_dw_fold(const float* Tpart, int nsplit, const float* U2, float* dW, int cout, int C, int r2, int taps, int beta,
+                  Item* out);
+hipError_t launch_dw_fold_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_small_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_long_items(const Item* const* items, int n, hipStream_t st);

@@ -189,6 +189,11 @@ EDGE_CONV = [
     ((1, 9, 32, 64), (1, 4, 5, 5), 10, 3, 1, 1, 1, 1),           # 66-wide slab rows (128 lanes per row), two rows per chunk, one batch entry
     ((2, 6, 34, 32), (2, 3, 6, 5), 20, 3, 1, 1, 1, 1),           # four output rows per chunk: slabs of six rows, 34 rows in all (ragged)
     ((2, 6, 40, 68), (2, 3, 6, 5), 20, 3, 1, 2, 2, 1),           # dilation 2 over 64 output columns: six slab rows of 68 columns
+    # step 5 with the sum of the partial T's in the same launch: 300 input channels (a full block of 256 and a ragged
+    # one of 44), 131 output channels in pairs (the last workgroup has one), rank 40 (three K blocks, the last half empty)
+    ((4, 300, 9, 9), (3, 40, 5, 5), 131, 3, 1, 1, 1, 1),
+    # the same for a pointwise convolution: 1100 output channels in groups of eight (the last group has four), 130 input channels
+    ((4, 130, 8, 8), (3, 24, 4, 4), 1100, 1, 1, 0, 1, 1),
 ]
 
 
@@ -356,6 +361,26 @@ def test_activation_aligned_to_its_element_only(dtype):
         got.append(U_gpu)
     for ua, ub in zip(*got):      # the two loaders feed the same arithmetic in the same order
         assert np.array_equal(ua, ub)
+
+
+def test_conv_weight_gradient_sums_the_partial_products_in_its_last_launch():
+    """Ungrouped 3 x 3 and 1 x 1 convolutions: the split partial sums of the correlation (step 4 of Eq. 14) are added
+    up by the launch that expands them to dW (step 5); no pass writes T out.  A 5 x 5 kernel keeps the two launches."""
+    from paper_2505_05086_amd import binding as B
+    for k, want_fold in ((3, True), (1, True), (5, False)):
+        lay = Layer("edge", (16, 64, 14, 14), (8, 16, 7, 7), "f32", "conv2d", 64, k=k, stride=1, pad=k // 2, dil=1, groups=1,
+                    alpha=0.7, noise=1e-2)
+        st = LayerStream(9, 7, lay)
+        run = _runner(lay)
+        A_t, A64, U_or = check_compress(run, lay, st.activation(0), st.u_prev0(), TOL["f32"], f"fold k={k}")
+        B.asi_profile_enable(True)
+        try:
+            check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), TOL["f32"], f"fold k={k}")
+            sites = list(B.asi_profile_report())
+        finally:
+            B.asi_profile_enable(False)
+        assert any("k_dw_fold<%d," % (k * k) in s_ for s_ in sites) == want_fold, sites
+        assert any(s_.startswith("dW|k_sum_partials") for s_ in sites) == (not want_fold), sites
 
 
 def test_rank_above_192_takes_the_general_orthogonalisation():
