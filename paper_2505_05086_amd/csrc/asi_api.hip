@@ -737,7 +737,14 @@ asi_status build_conv(const asi_tensor_desc* desc, const float* S, const float* 
             pg.items.pop_back();
             pg.items.back() = duo;
         }
+    } else if (pg.items.emplace_back(),
+               make_z_planes(Sz, (long long)g.r1 * g.r2, r3, r4, U[2], g.H, U[3], g.W, p.Z, &pg.items.back())) {
+        // 2+3. Z[p] = U3 S[p] U4^T plane by plane, both products in one launch (planes of up to 64 x 64, ranks up to 32)
+        const double planes = (double)g.r1 * g.r2;
+        tag(pg, "Z", 4.0 * (planes * ((double)r3 * r4 + (double)g.H * g.W) + (double)g.H * r3 + (double)g.W * r4),
+            2.0 * planes * ((double)g.H * r3 * r4 + (double)g.H * g.W * r4));
     } else {
+        pg.items.pop_back();
         // 2. Z1 = S x_3 U3                                        (r1, r2, H, r4)
         ASI_TRYS(add_ttm(pg, "Z1", F32, Sz, (long long)g.r1 * g.r2, r3, r4, U[2], 1, r3, g.H, p.Z1, 0));
         // 3. Z = Z1 x_4 U4                                        (r1, r2, H, W)

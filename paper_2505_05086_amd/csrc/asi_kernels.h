@@ -20,7 +20,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
     IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO, IT_TTM_STREAM, IT_TTM_EXPAND,
-    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE, IT_DW_FOLD
+    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE, IT_DW_FOLD, IT_Z_PLANES
 };
 
 struct Item {
@@ -328,6 +328,14 @@ hipError_t launch_expand_items(const Item* const* items, int n, hipStream_t st);
 bool make_dw_fold(const float* Tpart, int nsplit, const float* U2, float* dW, int cout, int C, int r2, int taps, int beta,
                   Item* out);
 hipError_t launch_dw_fold_items(const Item* const* items, int n, hipStream_t st);
+
+// ---- steps 2 and 3 of Eq. 14 for large planes in one launch (asi_kernels.hip) ----------------------------------
+// Z[p] = U3 S[p] U4^T for every plane p of the core: S (planes, r3, r4), U3 (H, r3), U4 (W, r4), Z (planes, H, W);
+// H, W <= 64, r3, r4 <= 32 and multiples of 4, W a multiple of 4, 16-byte aligned pointers.  False otherwise (the
+// caller then takes the two mode products one after the other).
+bool make_z_planes(const float* S, long long planes, int r3, int r4, const float* U3, int H, const float* U4, int W, float* Z,
+                   Item* out);
+hipError_t launch_z_planes_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_small_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_long_items(const Item* const* items, int n, hipStream_t st);

@@ -194,6 +194,11 @@ EDGE_CONV = [
     ((4, 300, 9, 9), (3, 40, 5, 5), 131, 3, 1, 1, 1, 1),
     # the same for a pointwise convolution: 1100 output channels in groups of eight (the last group has four), 130 input channels
     ((4, 130, 8, 8), (3, 24, 4, 4), 1100, 1, 1, 0, 1, 1),
+    # steps 2 and 3 plane by plane in one launch: 40 x 36 planes (three 16-blocks each way, the last ones ragged),
+    # ranks 12 and 8 (one K block each, partly filled); 15 planes of the core, three waves each
+    ((3, 6, 40, 36), (3, 5, 12, 8), 5, 3, 1, 1, 1, 1),
+    # 64 x 64 planes, ranks 32 and 20: two K blocks, the second one of the last mode a quarter full
+    ((2, 5, 64, 64), (2, 3, 32, 20), 4, 3, 1, 1, 1, 1),
 ]
 
 
@@ -381,6 +386,25 @@ def test_conv_weight_gradient_sums_the_partial_products_in_its_last_launch():
             B.asi_profile_enable(False)
         assert any("k_dw_fold<%d," % (k * k) in s_ for s_ in sites) == want_fold, sites
         assert any(s_.startswith("dW|k_sum_partials") for s_ in sites) == (not want_fold), sites
+
+
+def test_large_planes_take_steps_2_and_3_in_one_launch():
+    """Z = S x_3 U3 x_4 U4 for planes beyond 16 x 16 with ranks that are multiples of four: one launch, a wave per plane
+    of the core (48 x 52 planes, ranks 16 and 24); with a rank that is not a multiple of four, the two mode products."""
+    from paper_2505_05086_amd import binding as B
+    for ranks, fused in (((3, 4, 16, 24), True), ((3, 4, 16, 22), False)):
+        lay = Layer("edge", (4, 6, 48, 52), ranks, "f32", "conv2d", 7, k=3, stride=1, pad=1, dil=1, groups=1, alpha=0.7, noise=1e-2)
+        st = LayerStream(9, 8, lay)
+        run = _runner(lay)
+        A_t, A64, U_or = check_compress(run, lay, st.activation(0), st.u_prev0(), TOL["f32"], f"z planes {ranks}")
+        B.asi_profile_enable(True)
+        try:
+            check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), TOL["f32"], f"z planes {ranks}")
+            sites = list(B.asi_profile_report())
+        finally:
+            B.asi_profile_enable(False)
+        assert any("k_z_planes<4>" in s_ for s_ in sites) == fused, sites
+        assert any(s_.endswith(":Z1") for s_ in sites) == (not fused), sites
 
 
 def test_rank_above_192_takes_the_general_orthogonalisation():
