@@ -660,12 +660,30 @@ asi_status build_core(const asi_tensor_desc* desc, const void* A, const float* c
     for (int m = 0; m < 4; ++m) cur[m] = p.n[m];
     const void* src = A;
     DType sdt = s.dt;
+    int pp = 0;                                         // which of the two buffers the next intermediate goes to
     for (int k = 0; k < p.d; ++k) {
         const int m = p.order[k];
         long long outer = 1, inner = 1;
         for (int q = 0; q < m; ++q) outer *= cur[q];
         for (int q = m + 1; q < p.d; ++q) inner *= cur[q];
-        float* dst = (k + 1 == p.d) ? S : p.buf[k & 1];
+        // The H and W products of an fp32 intermediate with large planes, when the order has them side by side:
+        // one launch, plane by plane (the intermediate is a few MB and each product alone is a chain of round trips).
+        if (!p.kron && p.d == 4 && k >= 1 && k + 1 < p.d && sdt == F32 && m + p.order[k + 1] == 5 && m >= 2 && p.order[k + 1] >= 2) {
+            float* dst2 = (k + 2 == p.d) ? S : p.buf[pp];
+            pg.items.emplace_back();
+            if (make_core_planes(static_cast<const float*>(src), cur[0] * cur[1], (int)cur[2], (int)cur[3], U[2], p.r[2], U[3],
+                                 p.r[3], dst2, &pg.items.back())) {
+                const double planes = (double)cur[0] * (double)cur[1], H = (double)cur[2], W = (double)cur[3];
+                tag(pg, "core", 4.0 * (planes * (H * W + (double)p.r[2] * p.r[3]) + H * p.r[2] + W * p.r[3]),
+                    2.0 * planes * (H * W * p.r[3] + H * p.r[2] * p.r[3]));
+                cur[2] = p.r[2]; cur[3] = p.r[3];
+                src = dst2; pp ^= 1; ++k;
+                continue;
+            }
+            pg.items.pop_back();
+        }
+        float* dst = (k + 1 == p.d) ? S : p.buf[pp];
+        pp ^= 1;
         if (k == 0 && p.bf_last && m == p.d - 1) {
             // the bf16 activation along its last mode: split factor, then the bf16 MFMA product
             const int n = (int)cur[m], r = p.r[m];

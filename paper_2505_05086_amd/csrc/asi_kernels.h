@@ -20,7 +20,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
     IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO, IT_TTM_STREAM, IT_TTM_EXPAND,
-    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE, IT_DW_FOLD, IT_Z_PLANES
+    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE, IT_DW_FOLD, IT_Z_PLANES, IT_CORE_PLANES
 };
 
 struct Item {
@@ -336,6 +336,13 @@ hipError_t launch_dw_fold_items(const Item* const* items, int n, hipStream_t st)
 bool make_z_planes(const float* S, long long planes, int r3, int r4, const float* U3, int H, const float* U4, int W, float* Z,
                    Item* out);
 hipError_t launch_z_planes_items(const Item* const* items, int n, hipStream_t st);
+
+// ---- the H and W products of the core projection for large planes in one launch (asi_kernels.hip) -----------
+// Y[p] = U3^T X[p] U4 for every plane p: X (planes, H, W) fp32, U3 (H, r3), U4 (W, r4), Y (planes, r3, r4); H, W <= 64,
+// r3, r4 <= 32, W a multiple of 4, X 16-byte aligned.  False otherwise (the caller takes the two mode products).
+bool make_core_planes(const float* X, long long planes, int H, int W, const float* U3, int r3, const float* U4, int r4, float* Y,
+                      Item* out);
+hipError_t launch_core_planes_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_small_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_tiny_items(const Item* const* items, int n, hipStream_t st);
 hipError_t launch_long_items(const Item* const* items, int n, hipStream_t st);

@@ -407,6 +407,24 @@ def test_large_planes_take_steps_2_and_3_in_one_launch():
         assert any(s_.endswith(":Z1") for s_ in sites) == (not fused), sites
 
 
+def test_core_projection_takes_the_two_plane_modes_in_one_launch():
+    """The H and W products of the core projection on an fp32 intermediate with 48 x 52 planes (three and four
+    16-blocks, both ragged; ranks 16 and 24): one launch, a workgroup per plane, after the channel mode has shrunk the
+    tensor; the core, the reconstruction and the weight gradient are checked like anywhere else."""
+    from paper_2505_05086_amd import binding as B
+    lay = Layer("edge", (4, 24, 48, 52), (3, 6, 16, 24), "f32", "conv2d", 7, k=3, stride=1, pad=1, dil=1, groups=1, alpha=0.7, noise=1e-2)
+    st = LayerStream(9, 9, lay)
+    run = _runner(lay)
+    A_t, A64, U_or = check_compress(run, lay, st.activation(0), st.u_prev0(), TOL["f32"], "core planes")
+    B.asi_profile_enable(True)
+    try:
+        check_core_and_dw(run, lay, A_t, A64, U_or, st.grad_out(0), TOL["f32"], "core planes")
+        sites = list(B.asi_profile_report())
+    finally:
+        B.asi_profile_enable(False)
+    assert any("k_core_planes<4>" in s_ for s_ in sites), sites
+
+
 def test_rank_above_192_takes_the_general_orthogonalisation():
     """Ranks in (192, 1024] leave the blocked orthogonalisation kernels for the single-workgroup one and
     need 13 or more rank tiles in the product kernels; the whole path is checked like any other shape."""
