@@ -40,7 +40,7 @@ KERNEL_UNIT = {"k_subspace_small": "mfma_f32+f64", "k_subspace_tiny": "valu_f32+
                "k_corr_mfma": "mfma_f32", "k_corr": "valu_f32",
                "k_orth_gram0": "mfma_f64", "k_orth_apply": "mfma_f64",
                "k_orthw_gram": "mfma_f64", "k_orthw_apply": "mfma_f64", "k_orthw_chol": "valu_f64",
-               "k_orth_big": "valu_f64", "k_orth_presum": "valu_f64", "k_sum_partials": "valu_f64",
+               "k_orth_big": "valu_f64", "k_orth_presum": "valu_f64", "k_orthw_gsum": "valu_f64", "k_sum_partials": "valu_f64",
                "k_expand_grouped": "valu_f32", "k_dw_fold": "mfma_f32", "k_z_planes": "mfma_f32", "k_core_planes": "mfma_f32", "k_init_ctrl": "valu_f32"}
 
 

@@ -159,8 +159,8 @@ CompressPlan plan_compress(const Shape& s, void* ws, bool cold = false) {
             // The factorisation is one workgroup; summing megabytes of slice Grams there runs at the
             // bandwidth of one CU (110 us for 24 slices of 192 x 192), so a tree level does it first.
             if ((size_t)p.nblk[m] * r * r >= (size_t)1 << 16) {
-                p.ngsum[m] = (p.nblk[m] + 31) / 32;
-                p.Gsum[m] = c.take<double>((size_t)p.ngsum[m] * r * r);
+                p.ngsum[m] = 1;                       // one summed matrix (k_orthw_gsum)
+                p.Gsum[m] = c.take<double>((size_t)r * r);
             }
             p.R[m] = c.take<double>(r * r);
             p.Dinv[m] = c.take<double>(((r + 15) / 16) * 256);
@@ -471,7 +471,7 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
     if (!ws_ok(ws, ws_bytes, p.bytes)) return ASI_ERR_WORKSPACE;
 
     OrthArgs fast, wide, slow;
-    PresumArgs gsum;                 // wide modes with many slices: tree level over the slice Grams
+    GsumArgs gsum;                   // wide modes with many slices: tree level over the slice Grams
     std::memset(&gsum, 0, sizeof(gsum));
     double gsum_b = 0;
     std::memset(&fast, 0, sizeof(fast));
@@ -596,10 +596,12 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
         j.nblk = p.nblk[m]; j.Gpart = p.Gpart[m]; j.R = p.R[m]; j.Dinv = p.Dinv[m]; j.scal = p.scal[m];
         j.ctr = p.ctr8 + 2 * m;
         if (p.wide_orth[m] && p.Gsum[m]) {
-            PresumJob& gj = gsum.job[gsum.njobs++];
-            gj.in = p.Gpart[m]; gj.out = p.Gsum[m]; gj.cnt = (long long)r * r; gj.nsplit = p.nblk[m];
-            gj.nchunks = (int)((gj.cnt + 255) / 256); gj.ngroups = p.ngsum[m];
-            gsum_b += 8.0 * r * r * (p.nblk[m] + p.ngsum[m]);
+            GsumJob& gj = gsum.job[gsum.njobs++];
+            gj.in = p.Gpart[m]; gj.out = p.Gsum[m]; gj.nblk = p.nblk[m]; gj.r = r;
+            gj.nchunks = (r * r + 255) / 256;
+            gj.devbits = reinterpret_cast<unsigned long long*>(p.scal[m] + 196);     // (the wide path's bookkeeping ends at 194)
+            j.devbits = gj.devbits;
+            gsum_b += 8.0 * r * r * (p.nblk[m] + 1);
         }
         if (p.wide_orth[m]) {
             PresumJob& pj = pre2.job[pre2.njobs++];
@@ -633,11 +635,11 @@ asi_status build_compress(const asi_tensor_desc* desc, const void* A, const floa
             if (p.Gsum[m]) { wchol.job[j].Gpart = p.Gsum[m]; wchol.job[j].nblk = p.ngsum[m]; }
         }
         ASI_ADD(pg, "", wide_b, wide_f, make_orthw_gram(wide, it__));
-        if (gsum.njobs) ASI_ADD(pg, "", gsum_b, gsum_b / 8.0, make_orth_presum(gsum, it__));
+        if (gsum.njobs) ASI_ADD(pg, "", gsum_b, gsum_b / 8.0, make_orthw_gsum(gsum, it__));
         ASI_ADD(pg, "", wchol_b, wchol_f, make_orthw_chol(wchol, 0, 0, it__));
         ASI_ADD(pg, "", 2 * wide_b, wide_f, make_orthw_apply(wide, 0, it__));
         ASI_ADD(pg, "", wide_b, wide_f, make_orthw_gram(wide, it__));
-        if (gsum.njobs) ASI_ADD(pg, "", gsum_b, gsum_b / 8.0, make_orth_presum(gsum, it__));
+        if (gsum.njobs) ASI_ADD(pg, "", gsum_b, gsum_b / 8.0, make_orthw_gsum(gsum, it__));
         ASI_ADD(pg, "", wchol_b, wchol_f, make_orthw_chol(wchol, 1, 1, it__));
         ASI_ADD(pg, "", 1.5 * wide_b, wide_f, make_orthw_apply(wide, 1, it__));
     }

@@ -20,7 +20,7 @@ constexpr int kItemArgMax = 640;     // bytes of the largest per-layer argument 
 enum ItemKind {
     IT_TTM = 1, IT_KSPLIT, IT_PAIR, IT_SMALL, IT_PRESUM, IT_GRAM0, IT_APPLY, IT_ORTHW_GRAM, IT_ORTHW_CHOL,
     IT_ORTHW_APPLY, IT_ORTH_BIG, IT_CORR_MFMA, IT_CORR, IT_SUM_F32, IT_SUM_F64, IT_EXPAND, IT_INIT, IT_TINY, IT_TTM_DUO, IT_TTM_STREAM, IT_TTM_EXPAND,
-    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE, IT_DW_FOLD, IT_Z_PLANES, IT_CORE_PLANES
+    IT_LONG, IT_PLANES, IT_SPLIT_BF16, IT_GEMM_BF16, IT_GAUSS, IT_GRAM_MODE, IT_DW_FOLD, IT_Z_PLANES, IT_CORE_PLANES, IT_ORTHW_GSUM
 };
 
 struct Item {
@@ -270,12 +270,27 @@ struct OrthJob {
     int mode1;           // 1-based mode number for *info
     int nblk;            // row slices = orth_slices(n) (wide path: orth_wide_gram_blocks(n))
     int pad_;
+    unsigned long long* devbits;   // wide path with a summed Gram matrix (make_orthw_gsum): bits of max |G - I|; else null
 };
 struct OrthArgs {        // the modes of one tensor that share a path
     OrthJob job[4];
     int njobs;
 };
 bool make_orth_presum(const PresumArgs& a, Item* out);
+// Wide path, many slices: the slice Gram matrices of a mode added up into ONE matrix (slice after slice, in their
+// order), and the largest deviation of its upper triangle from the identity raised into *devbits (the bit pattern of
+// a non-negative double, so that an integer atomic maximum orders it; the first factorisation clears it).
+struct GsumJob {
+    const double* in;    // (nblk, r, r), upper triangles valid
+    double* out;         // (r, r)
+    unsigned long long* devbits;
+    int nblk, r, nchunks;   // nchunks = ceil(r r / 256)
+};
+struct GsumArgs {
+    GsumJob job[4];
+    int njobs;
+};
+bool make_orthw_gsum(const GsumArgs& a, Item* out);
 bool orth_fast_supported(int r);
 int orth_slices(int n);
 // gram0: sums the partial sums of P, slice Grams; the last workgroup of a mode factors (shifted pass)

@@ -763,6 +763,39 @@ __global__ __launch_bounds__(256) void k_orthw_gram(OrthBatch a) {
     }
 }
 
+// Sum of the slice Gram matrices of a mode and its distance from the identity, spread over the chip: the
+// factorisation is one workgroup, and what it reads right after other workgroups wrote it costs it 3-5 us per
+// dependent round of loads (five rounds for two partial sums of a 192 x 192 matrix: 28 us of the second pass went
+// into a sum whose only use was the check that the first pass had been enough).
+struct GsumBatch {
+    GsumJob job[kMaxOrthJobs];
+    int njobs;
+};
+__global__ __launch_bounds__(256) void k_orthw_gsum(GsumBatch a) {
+    int j = 0, b = blockIdx.x;
+    while (j + 1 < a.njobs && b >= a.job[j].nchunks) { b -= a.job[j].nchunks; ++j; }
+    const GsumJob& jb = a.job[j];
+    const int r = jb.r, cnt = r * r;
+    const int e = b * 256 + threadIdx.x;
+    double s = 0.0;
+    for (int b0 = 0; b0 < jb.nblk; b0 += 32) {               // 32 slices' loads in flight, added in slice order
+        double t[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) t[u] = jb.in[(long long)(b0 + u < jb.nblk ? b0 + u : jb.nblk - 1) * cnt + (e < cnt ? e : 0)];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) s += (b0 + u < jb.nblk) ? t[u] : 0.0;
+    }
+    double dev = 0.0;
+    if (e < cnt) {
+        jb.out[e] = s;
+        const int ga = e / r, gb = e - ga * r;
+        if (ga <= gb) dev = fabs(s - (ga == gb ? 1.0 : 0.0));   // (only the upper triangles of the slices are written)
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) dev = fmax(dev, __shfl_xor(dev, m));
+    if ((threadIdx.x & 63) == 0 && dev > 0.0) atomicMax(jb.devbits, (unsigned long long)__double_as_longlong(dev));
+}
+
 extern __shared__ double ow_dyn[];
 
 // 512 threads: with 1024 a thread may hold 128 registers, and the diagonal-block factorisation (a column
@@ -833,9 +866,18 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
     double (*rowbuf)[64][4] = reinterpret_cast<double (*)[64][4]>(pinvs + nb * 16 + 16 * 17);
     const GramPacked G{Gp, r};
     const int lane = tid & 63, wave = tid >> 6, lg = lane >> 4, ll = lane & 15;
-    double dev = sum_gram();
-    __syncthreads();
+    // Second pass with a summed Gram matrix: its distance from the identity has been measured by the launch that
+    // summed it, and the matrix itself is read only if the pass has to be carried out.
+    const bool measured = pass != 0 && jb.devbits != nullptr;
+    double dev = 0.0;
+    if (measured) {
+        dev = __longlong_as_double((long long)*jb.devbits);
+    } else {
+        dev = sum_gram();
+        __syncthreads();
+    }
     if (pass == 0) {
+        if (tid == 0 && jb.devbits) *jb.devbits = 0ull;     // the second Gram sum starts from zero
         if (tid < r) rdiag[tid] = Gp[pidx(tid, tid)];
         __syncthreads();
         if (wave == 0) {                 // trace: lanes sum every 64th diagonal entry, then a fixed-order butterfly
@@ -849,25 +891,41 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
     } else {
         // Second pass: if Q0 is orthonormal to 1e-7 already, its fp32 copy (written by the first solve)
         // is the result and the final solve returns at once.
+        if (!measured) {
 #pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) dev = fmax(dev, __shfl_xor(dev, m));
-        if ((tid & 63) == 0) s_red[tid >> 6] = dev;
-        __syncthreads();
-        dev = 0.0;
-        for (int w = 0; w < OWC_NW; ++w) dev = fmax(dev, s_red[w]);
+            for (int m = 32; m >= 1; m >>= 1) dev = fmax(dev, __shfl_xor(dev, m));
+            if ((tid & 63) == 0) s_red[tid >> 6] = dev;
+            __syncthreads();
+            dev = 0.0;
+            for (int w = 0; w < OWC_NW; ++w) dev = fmax(dev, s_red[w]);
+        }
         const bool done = dev <= OP_DONE_TOL;
         if (tid == 0) {
             jb.scal[2 + OW_RMAX] = done ? 1.0 : 0.0;
             s_trace = jb.scal[0];
-            if (done && last && jb.info) {
+        }
+        if (done && last && jb.info) {
+            // first column whose accumulated diagonal fell to the noise floor: every thread looks at one column (one
+            // thread walking all of them paid a round trip to memory per column: 29 us for 192 of them)
+            const double floor_ = 1e-12 * sqrt(jb.scal[0]);
+            const bool low = tid < r && !(jb.scal[1 + tid] > floor_);
+            if (tid == 0) s_lost = 0x7fffffff;
+            __syncthreads();
+            if (low) atomicMin(&s_lost, tid);
+            __syncthreads();
+            if (tid == 0) {
                 const double bad = jb.scal[1 + OW_RMAX];
                 if (bad != 0.0) flag_info(jb.info, jb.mode1, (int)bad);
-                const double floor_ = 1e-12 * sqrt(s_trace);
-                for (int k = 0; k < r; ++k)
-                    if (!(jb.scal[1 + k] > floor_)) { flag_info(jb.info, jb.mode1, k + 1); break; }
+                if (s_lost != 0x7fffffff) flag_info(jb.info, jb.mode1, s_lost + 1);
             }
         }
         if (done) return;
+        __syncthreads();
+        if (tid == 0) s_lost = 0;
+        if (measured) {
+            sum_gram();
+            __syncthreads();
+        }
         if (tid < r) rdiag[tid] = Gp[pidx(tid, tid)];
         __syncthreads();
     }
@@ -993,15 +1051,18 @@ __global__ __launch_bounds__(OWC_NT) void k_orthw_chol(OrthBatch a, int pass, in
 #pragma unroll
         for (int j = 0; j < 16; ++j) jb.Dinv[(b * 16 + i) * 16 + j] = x[j];
     }
+    __syncthreads();                                      // (the pivot flags are no longer read)
+    if (tid == 0) s_lost = 0x7fffffff;
+    __syncthreads();
+    if (last && jb.info && tid < r && !(rdiag[tid] > 1e-12 * sqrt(s_trace))) atomicMin(&s_lost, tid);
+    __syncthreads();
     if (tid == 0) {
         double bad = (pass == 0) ? 0.0 : jb.scal[1 + OW_RMAX];
         if (bad == 0.0 && s_bad) bad = (double)s_bad;
         jb.scal[1 + OW_RMAX] = bad;
         if (last && jb.info) {
             if (bad != 0.0) flag_info(jb.info, jb.mode1, (int)bad);
-            const double floor_ = 1e-12 * sqrt(s_trace);
-            for (int k = 0; k < r; ++k)
-                if (!(rdiag[k] > floor_)) { flag_info(jb.info, jb.mode1, k + 1); break; }
+            if (s_lost != 0x7fffffff) flag_info(jb.info, jb.mode1, s_lost + 1);
         }
     }
 }
@@ -1222,6 +1283,22 @@ bool make_orth_presum(const PresumArgs& a, Item* out) {
     std::memcpy(out->arg, &a, sizeof(a));
     return true;
 }
+bool make_orthw_gsum(const GsumArgs& a, Item* out) {
+    if (a.njobs <= 0 || a.njobs > 4) return false;
+    long long blocks = 0;
+    for (int j = 0; j < a.njobs; ++j) {
+        const GsumJob& jb = a.job[j];
+        if (!jb.in || !jb.out || !jb.devbits || jb.nblk < 1 || !orth_wide_supported(jb.r)) return false;
+        if (jb.nchunks != (jb.r * jb.r + 255) / 256) return false;
+        blocks += jb.nchunks;
+    }
+    *out = Item();
+    out->kind = IT_ORTHW_GSUM; out->nblocks = (int)blocks;
+    std::snprintf(out->label, sizeof(out->label), "k_orthw_gsum");
+    static_assert(sizeof(GsumArgs) <= kItemArgMax, "argument block");
+    std::memcpy(out->arg, &a, sizeof(a));
+    return true;
+}
 bool make_orth_gram0(const OrthArgs& a, Item* out) {
     return fast_args_ok(a) && put_orth(IT_GRAM0, 0, "k_orth_gram0", a, total_blocks(a), out);
 }
@@ -1287,6 +1364,17 @@ hipError_t launch_orth_items(const Item* const* items, int n, hipStream_t st, ch
             for (int k = 0; k < a.njobs; ++k) b.job[b.njobs++] = a.job[k];
         }
         hipLaunchKernelGGL(k_orth_presum, grid, 256, 0, st, b);
+        return hipGetLastError();
+    }
+    if (kind == IT_ORTHW_GSUM) {
+        GsumBatch b;
+        b.njobs = 0;
+        for (int j = 0; j < n; ++j) {
+            GsumArgs a;
+            std::memcpy(&a, items[j]->arg, sizeof(a));
+            for (int k = 0; k < a.njobs; ++k) b.job[b.njobs++] = a.job[k];
+        }
+        hipLaunchKernelGGL(k_orthw_gsum, grid, 256, 0, st, b);
         return hipGetLastError();
     }
     OrthBatch b;
